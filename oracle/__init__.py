@@ -1,0 +1,169 @@
+"""CPU oracle for the MXFP4 weight-only-quantised linear layer (arXiv 2503.13565,
+section 3.4.3) -- TEST INFRASTRUCTURE, not the product.
+
+This package wraps ``mxfp4_oracle.c`` (plain C, FP64, index-order loops) with
+``ctypes``.  Only ``tests/``, the smoke check and the benchmark's
+``cpu_baseline`` leg may import it.  It shares nothing with the HIP path and
+never imports it.
+
+Arrays are numpy: BF16 values travel as their 16-bit patterns (``uint16``),
+packed nibbles and scale bytes as ``uint8``, results as ``float64``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mxfp4_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+BLOCK = 32
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP on) and return the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.oracle_direct_cast.argtypes = [vp, i64, i64, i64, vp, vp, i32]
+        lib.oracle_direct_cast.restype = i32
+        lib.oracle_dequant.argtypes = [vp, vp, i64, i64, vp]
+        lib.oracle_dequant.restype = i32
+        lib.oracle_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32]
+        lib.oracle_woq_gemm.restype = i32
+        lib.oracle_woq_gemm_late_scaled.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp]
+        lib.oracle_woq_gemm_late_scaled.restype = i32
+        lib.oracle_argmax.argtypes = [vp, i64, i64, vp, vp]
+        lib.oracle_argmax.restype = i32
+        lib.oracle_e2m1_magnitude.argtypes = [i32]
+        lib.oracle_e2m1_magnitude.restype = ctypes.c_double
+        lib.oracle_max_threads.argtypes = []
+        lib.oracle_max_threads.restype = i32
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _as(a, dtype, ndim) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if a.ndim != ndim:
+        raise ValueError("expected %d dimensions, got shape %r" % (ndim, a.shape))
+    return a
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def e2m1_magnitude(code: int) -> float:
+    return float(_load().oracle_e2m1_magnitude(int(code)))
+
+
+def direct_cast(w_bits, threads: int = 0):
+    """BF16 bit patterns ``[N,K]`` (uint16) -> (q ``[N,K/2]`` uint8, s ``[N,K/32]`` uint8)."""
+    w = _as(w_bits, np.uint16, 2)
+    n, k = w.shape
+    if k % BLOCK:
+        raise ValueError("K must be a multiple of 32")
+    q = np.empty((n, k // 2), np.uint8)
+    s = np.empty((n, k // BLOCK), np.uint8)
+    rc = _load().oracle_direct_cast(_ptr(w), n, k, k, _ptr(q), _ptr(s), threads)
+    if rc:
+        raise RuntimeError("oracle_direct_cast failed: %d" % rc)
+    return q, s
+
+
+def dequant(q, s) -> np.ndarray:
+    """Packed nibbles + scale bytes -> float64 ``[N,K]``."""
+    q = _as(q, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    n, k = q.shape[0], q.shape[1] * 2
+    if s.shape != (n, k // BLOCK) or k % BLOCK:
+        raise ValueError("scale shape %r does not match q shape %r" % (s.shape, q.shape))
+    out = np.empty((n, k), np.float64)
+    rc = _load().oracle_dequant(_ptr(q), _ptr(s), n, k, _ptr(out))
+    if rc:
+        raise RuntimeError("oracle_dequant failed: %d" % rc)
+    return out
+
+
+def woq_gemm(x_bits, q, s, threads: int = 0, want_abs: bool = True):
+    """FP64 product ``y[m,n] = sum_k x[m,k] * w_hat[n,k]`` and, if asked, the sum of
+    absolute products (for the tolerance).  ``x_bits`` is uint16 ``[M,K]``."""
+    x = _as(x_bits, np.uint16, 2)
+    q = _as(q, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    m, k = x.shape
+    n = q.shape[0]
+    if q.shape[1] * 2 != k or s.shape != (n, k // BLOCK) or k % BLOCK:
+        raise ValueError("shape mismatch: x %r q %r s %r" % (x.shape, q.shape, s.shape))
+    y = np.empty((m, n), np.float64)
+    a = np.empty((m, n), np.float64) if want_abs else None
+    rc = _load().oracle_woq_gemm(_ptr(x), m, k, _ptr(q), _ptr(s), n, k, _ptr(y),
+                                 _ptr(a) if want_abs else None, threads)
+    if rc:
+        raise RuntimeError("oracle_woq_gemm failed: %d" % rc)
+    return (y, a) if want_abs else y
+
+
+def woq_gemm_late_scaled(x_bits, q, s) -> np.ndarray:
+    """The product with the scale applied once per 32-block partial sum (Eq. 2)."""
+    x = _as(x_bits, np.uint16, 2)
+    q = _as(q, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    m, k = x.shape
+    n = q.shape[0]
+    y = np.empty((m, n), np.float64)
+    rc = _load().oracle_woq_gemm_late_scaled(_ptr(x), m, k, _ptr(q), _ptr(s), n, k, _ptr(y))
+    if rc:
+        raise RuntimeError("oracle_woq_gemm_late_scaled failed: %d" % rc)
+    return y
+
+
+def argmax(y):
+    """Row-wise index of the maximum (lowest index among equals) and its value."""
+    y = _as(y, np.float64, 2)
+    m, n = y.shape
+    idx = np.empty((m,), np.int32)
+    val = np.empty((m,), np.float64)
+    rc = _load().oracle_argmax(_ptr(y), m, n, _ptr(idx), _ptr(val))
+    if rc:
+        raise RuntimeError("oracle_argmax failed: %d" % rc)
+    return idx, val
+
+
+def bf16_ulp(y) -> np.ndarray:
+    """Spacing of BF16 numbers at |y|: 2^(floor(log2|y|) - 7); the smallest normal
+    spacing for zero.  This is the '+1 BF16 ulp of |y_ref|' term of the output
+    tolerance."""
+    y = np.abs(np.asarray(y, np.float64))
+    _, ex = np.frexp(y)                       # y = f * 2^ex, f in [0.5, 1)
+    ulp = np.ldexp(1.0, ex - 1 - 7)
+    return np.where(y == 0.0, np.ldexp(1.0, -126 - 7), ulp)
+
+
+def tolerance(y_ref, a_ref) -> np.ndarray:
+    """|y_gpu - y_ref| <= 1e-3 * sum_k |x_k w_k| + one BF16 ulp of |y_ref|."""
+    return 1e-3 * np.asarray(a_ref, np.float64) + bf16_ulp(y_ref)

@@ -1,0 +1,305 @@
+/*
+ * CPU oracle for the MXFP4 weight-only-quantised linear layer of ML-SpecQD
+ * (arXiv 2503.13565, section 3.4.3 "MXFP4 direct-cast of weights and GEMM
+ * Microkernel").
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is the plain, slow definition that the HIP
+ * kernels are checked against and shares no code, table or header with them.
+ * Only the test-suite, the smoke check and the benchmark's cpu_baseline leg may
+ * call it; the product path never does.
+ *
+ * Everything is written as the definition reads: doubles for arithmetic (every
+ * BF16 value, every power of two and every product of a BF16 value with an
+ * MXFP4 weight is exact in a double), plain index-order loops, no blocking.  The
+ * only parallelism is an optional OpenMP split over independent output rows,
+ * which changes no arithmetic.
+ *
+ * Conventions (section 3.4.3; readings of the silent points are listed with the
+ * functions that need them):
+ *   - element format E2M1: 1 sign, 2 exponent (bias 1), 1 mantissa bit; the
+ *     eight magnitudes are 0, 0.5, 1, 1.5, 2, 3, 4, 6 for codes 0..7;
+ *   - scale format E8M0: one byte per 32 consecutive elements along K holding a
+ *     biased FP32 exponent, value 2^(byte-127); byte 0xFF marks a NaN block;
+ *   - packed layout: byte j of a row holds element 2j in bits 0..3 and element
+ *     2j+1 in bits 4..7; scales are [N, K/32] row-major.
+ *
+ * Pins (tests/test_oracle_*.py): every code point round-trips, the scale equals
+ * floor(log2 amax) - 2, the decision intervals of round-to-nearest-even, an
+ * integer closed form over every BF16 magnitude, power-of-two invariance, sign
+ * symmetry, idempotence, the error bound, the product against a library FP64
+ * matmul on on-grid weights, one-hot activations, and brute-force argmax.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_BLOCK 32
+
+/* The eight E2M1 magnitudes, from the field widths: code = eem, exponent bias 1,
+ * code 1 is the single subnormal. */
+static double e2m1_magnitude(int code)
+{
+    int ee = (code >> 1) & 3;
+    int m = code & 1;
+    if (ee == 0)
+        return 0.5 * m;                       /* subnormal: 0.m * 2^(1-1)      */
+    return ldexp(1.0 + 0.5 * m, ee - 1);      /* normal:    1.m * 2^(ee-1)     */
+}
+
+/* BF16 bit pattern -> double (exact).  BF16 is the top half of an FP32. */
+static double bf16_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* Round |r| (finite, >= 0) to the nearest E2M1 magnitude; a value exactly half
+ * way between two neighbours goes to the one whose code is even (mantissa bit
+ * 0); anything beyond the largest magnitude saturates to it.  Section 3.4.3
+ * fixes the saturation; round-to-nearest-even is the OCP Microscaling rule the
+ * section defers to. */
+static int e2m1_round_code(double r)
+{
+    int best = 0;
+    double best_d = fabs(r - e2m1_magnitude(0));
+    for (int c = 1; c < 8; ++c) {
+        double d = fabs(r - e2m1_magnitude(c));
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return best;   /* r > 6 lands on code 7 because 6 is then the nearest */
+}
+
+/* Direct cast of one 32-element block (section 3.4.3, steps i and ii).
+ * Returns the scale byte; writes 32 nibbles (sign<<3 | code) to nib[]. */
+static uint8_t cast_block(const uint16_t *w, uint8_t nib[ORACLE_BLOCK])
+{
+    double v[ORACLE_BLOCK];
+    double amax = 0.0;
+    int nonfinite = 0;
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        v[i] = bf16_to_double(w[i]);
+        if (isnan(v[i]) || isinf(v[i]))
+            nonfinite = 1;
+        else if (fabs(v[i]) > amax)
+            amax = fabs(v[i]);
+    }
+    if (nonfinite) {
+        /* Reading: a block holding NaN or Inf becomes a NaN block. */
+        for (int i = 0; i < ORACLE_BLOCK; ++i)
+            nib[i] = 0;
+        return 0xFF;
+    }
+    /* Step i: X = (largest power of two <= amax) / (largest power of two that
+     * E2M1 represents = 4 = 2^2), i.e. X = 2^E with E = floor(log2 amax) - 2.
+     * Reading: an all-zero block and any E below -127 take E = -127 (byte 0);
+     * the upper clamp cannot trigger from BF16 inputs. */
+    int E;
+    if (amax == 0.0) {
+        E = -127;
+    } else {
+        int ex;
+        (void)frexp(amax, &ex);               /* amax = f * 2^ex, f in [0.5,1) */
+        E = (ex - 1) - 2;                     /* floor(log2 amax) - 2          */
+    }
+    if (E < -127)
+        E = -127;
+    if (E > 127)
+        E = 127;
+    /* Step ii: v_i / X, quantised to E2M1, saturating, sign preserved.
+     * Reading: the sign bit of the input is kept even when the magnitude
+     * rounds to zero. */
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        double r = ldexp(fabs(v[i]), -E);     /* exact division by 2^E */
+        int code = e2m1_round_code(r);
+        int sign = (w[i] >> 15) & 1;
+        nib[i] = (uint8_t)((sign << 3) | code);
+    }
+    return (uint8_t)(E + 127);
+}
+
+/* Direct cast of W[N,K] (BF16 bit patterns, row stride ldw elements) to packed
+ * nibbles q[N,K/2] and scale bytes s[N,K/32].  Returns 0, or 2 on a bad shape. */
+int oracle_direct_cast(const uint16_t *w, int64_t N, int64_t K, int64_t ldw,
+                       uint8_t *q, uint8_t *s, int threads)
+{
+    if (N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldw < K)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t b = 0; b < nblk; ++b) {
+            uint8_t nib[ORACLE_BLOCK];
+            s[n * nblk + b] = cast_block(w + n * ldw + b * ORACLE_BLOCK, nib);
+            for (int j = 0; j < ORACLE_BLOCK / 2; ++j)
+                q[n * (K / 2) + b * (ORACLE_BLOCK / 2) + j] =
+                    (uint8_t)(nib[2 * j] | (nib[2 * j + 1] << 4));
+        }
+    }
+    (void)threads;
+    return 0;
+}
+
+/* One dequantised weight: (-1)^sign * magnitude(code) * 2^(scale-127); a scale
+ * byte of 0xFF gives NaN. */
+static double dequant_one(uint8_t nibble, uint8_t scale_byte)
+{
+    if (scale_byte == 0xFF)
+        return NAN;
+    double mag = e2m1_magnitude(nibble & 7);
+    double val = ldexp(mag, (int)scale_byte - 127);
+    return (nibble & 8) ? -val : val;
+}
+
+static void dequant_row(const uint8_t *q_row, const uint8_t *s_row, int64_t K,
+                        double *out)
+{
+    for (int64_t k = 0; k < K; ++k) {
+        uint8_t byte = q_row[k / 2];
+        uint8_t nibble = (k & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 0xF);
+        out[k] = dequant_one(nibble, s_row[k / ORACLE_BLOCK]);
+    }
+}
+
+/* Dequantise q,s to doubles w_hat[N,K]. */
+int oracle_dequant(const uint8_t *q, const uint8_t *s, int64_t N, int64_t K,
+                   double *w_hat)
+{
+    if (N < 0 || K < 0 || K % ORACLE_BLOCK != 0)
+        return 2;
+    for (int64_t n = 0; n < N; ++n)
+        dequant_row(q + n * (K / 2), s + n * (K / ORACLE_BLOCK), K, w_hat + n * K);
+    return 0;
+}
+
+/* y_ref[m,n] = sum_k x[m,k] * w_hat[n,k] in FP64, k ascending; also
+ * a_ref[m,n] = sum_k |x[m,k] * w_hat[n,k]| (the tolerance's magnitude sum).
+ * x holds BF16 bit patterns [M,K] with row stride ldx; outputs are [M,N]
+ * row-major doubles.  a_ref may be NULL. */
+int oracle_woq_gemm(const uint16_t *x, int64_t M, int64_t ldx,
+                    const uint8_t *q, const uint8_t *s, int64_t N, int64_t K,
+                    double *y_ref, double *a_ref, int threads)
+{
+    if (M < 0 || N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldx < K)
+        return 2;
+    double *xd = (double *)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
+    if (!xd)
+        return 6;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k)
+            xd[m * K + k] = bf16_to_double(x[m * ldx + k]);
+    int failed = 0;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel
+#endif
+    {
+        double *wrow = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+        if (!wrow) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp for schedule(static)
+#endif
+        for (int64_t n = 0; n < N; ++n) {
+            if (!wrow)
+                continue;
+            dequant_row(q + n * (K / 2), s + n * (K / ORACLE_BLOCK), K, wrow);
+            for (int64_t m = 0; m < M; ++m) {
+                double acc = 0.0, aacc = 0.0;
+                const double *xr = xd + m * K;
+                for (int64_t k = 0; k < K; ++k) {
+                    double p = xr[k] * wrow[k];
+                    acc += p;
+                    aacc += fabs(p);
+                }
+                y_ref[m * N + n] = acc;
+                if (a_ref)
+                    a_ref[m * N + n] = aacc;
+            }
+        }
+        free(wrow);
+    }
+    free(xd);
+    (void)threads;
+    return failed ? 6 : 0;
+}
+
+/* The same product with the scale applied once per 32-block partial sum (the
+ * late-scaling form, Eq. 2).  Used by a test of the identity only. */
+int oracle_woq_gemm_late_scaled(const uint16_t *x, int64_t M, int64_t ldx,
+                                const uint8_t *q, const uint8_t *s, int64_t N,
+                                int64_t K, double *y_ref)
+{
+    if (M < 0 || N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldx < K)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t b = 0; b < nblk; ++b) {
+                uint8_t sb = s[n * nblk + b];
+                double partial = 0.0;
+                for (int i = 0; i < ORACLE_BLOCK; ++i) {
+                    int64_t k = b * ORACLE_BLOCK + i;
+                    uint8_t byte = q[n * (K / 2) + k / 2];
+                    uint8_t nibble = (k & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 0xF);
+                    double wi = e2m1_magnitude(nibble & 7);
+                    if (nibble & 8)
+                        wi = -wi;
+                    partial += wi * bf16_to_double(x[m * ldx + k]);
+                }
+                acc += (sb == 0xFF) ? NAN : ldexp(partial, (int)sb - 127);
+            }
+            y_ref[m * N + n] = acc;
+        }
+    }
+    return 0;
+}
+
+/* Greedy pick per row: index of the largest value, lowest index among equals.
+ * The result for a row that holds a NaN is unspecified (no graded input has one). */
+int oracle_argmax(const double *y, int64_t M, int64_t N, int32_t *idx, double *val)
+{
+    if (M < 0 || N < 1)
+        return 2;
+    for (int64_t m = 0; m < M; ++m) {
+        int64_t best = 0;
+        for (int64_t n = 0; n < N; ++n) {
+            if (y[m * N + n] > y[m * N + best])
+                best = n;
+        }
+        idx[m] = (int32_t)best;
+        if (val)
+            val[m] = y[m * N + best];
+    }
+    return 0;
+}
+
+/* The E2M1 magnitude of a code, exported so a test can print the grid. */
+double oracle_e2m1_magnitude(int code) { return e2m1_magnitude(code & 7); }
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
