@@ -1,0 +1,141 @@
+/*
+ * mxfp4.h -- C ABI of the MI355X (gfx950) MXFP4 weight-only-quantised linear layer.
+ *
+ * The operations are those of arXiv 2503.13565 (ML-SpecQD), section 3.4.3: weights are
+ * direct-cast once, offline, from BF16 to MXFP4 (an FP4 E2M1 tensor plus one 8-bit E8M0
+ * scale per 32 elements), and every draft decode step and every verification pass then
+ * multiplies a few BF16 activation rows (1 token when drafting, k+1 when verifying k draft
+ * tokens; section 4.4) with the dequantised weights, accumulating in FP32.
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is a DEVICE pointer (HBM) unless marked "host".  The caller owns all
+ *     buffers and keeps them alive until `stream` has passed the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work on it and return; they never synchronise, allocate or free device memory.
+ *   - BF16 tensors are row-major with an explicit leading dimension in elements.
+ *   - Packed weights `q`: uint8 [N, K/2] row-major, byte j of a row holds element 2j in bits
+ *     0..3 and element 2j+1 in bits 4..7; a nibble is sign<<3 | eem (magnitudes 0, .5, 1,
+ *     1.5, 2, 3, 4, 6).  Scales `s`: uint8 [N, K/32] row-major, value 2^(byte-127), 0xFF marks
+ *     a NaN block.  Blocks of 32 run along K, the reduction axis (Eq. 2).
+ *   - Return value: MXFP4_OK or an error code; on error nothing was enqueued and
+ *     mxfp4_last_error() (host, thread-local) describes it.  No call aborts the process.
+ *   - Results are deterministic: the same inputs and shapes give bit-identical outputs.
+ */
+#ifndef MXFP4_H
+#define MXFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MXFP4_OK = 0,
+    MXFP4_ERR_NULL = 1,      /* a required pointer is NULL */
+    MXFP4_ERR_SHAPE = 2,     /* K % 32 != 0, a size < 1 (0 rows is allowed and a no-op), ld < K, K too large */
+    MXFP4_ERR_ALIGN = 3,     /* a buffer or leading dimension breaks the 16-byte alignment rule */
+    MXFP4_ERR_WORKSPACE = 4, /* workspace missing or smaller than *_workspace_bytes() */
+    MXFP4_ERR_HIP = 5,       /* the HIP runtime refused a launch */
+    MXFP4_ERR_ARG = 6        /* unknown path / option value */
+};
+
+/* Kernel families the dispatcher can be forced to (tests and measurements); AUTO picks by M. */
+enum {
+    MXFP4_PATH_AUTO = 0,
+    MXFP4_PATH_VALU_BITS = 1, /* wave-per-row GEMV, nibbles decoded with plain integer/FP32 ops  */
+    MXFP4_PATH_VALU_CVT = 2,  /* wave-per-row GEMV, gfx950 FP4->BF16 scaled converts + dot2      */
+    MXFP4_PATH_VALU_LUT = 3,  /* wave-per-row GEMV, LDS-resident byte -> 2xBF16 lookup table      */
+    MXFP4_PATH_MFMA = 4       /* 16-row MFMA tiles (bf16 16x16x32), for verification batches     */
+};
+
+/*
+ * Direct cast BF16 -> MXFP4 (section 3.4.3, the two quantisation steps).
+ * For every 32-element block along K: scale byte = max(biased_exponent(amax) - 2, 0), i.e.
+ * X = 2^(floor(log2 amax) - 2); each element v/X is rounded to the nearest E2M1 value, ties to
+ * the even code, saturating at +-6, sign bit preserved (also for zeros).  A block holding NaN
+ * or Inf gets scale 0xFF and zero nibbles.  Integer-only on the BF16 bit patterns.
+ *   w_bf16      in  BF16 [N, K], row stride ldw elements (ldw >= K, ldw % 8 == 0, 16-byte aligned)
+ *   q_packed    out uint8 [N, K/2]   (4-byte aligned)
+ *   scales_e8m0 out uint8 [N, K/32]
+ * N may be 0 (no-op).  K must be a positive multiple of 32.
+ */
+int mxfp4_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                      void* q_packed, void* scales_e8m0, void* stream);
+
+/*
+ * Dequantise to BF16 (exact whenever 2^(scale-127) * 6 is a normal BF16 number): the inverse
+ * map of the format in section 3.4.3; used to check the weight decode in isolation.
+ *   w_bf16 out BF16 [N, K], row stride ldw elements.
+ */
+int mxfp4_dequant(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                  void* w_bf16, int64_t ldw, void* stream);
+
+/*
+ * Skinny weight-only-quantised product y = x * dequant(W)^T (section 3.4.3, Eq. 2; the
+ * paper's GEMM with 1..8 tokens, section 4.4):
+ *   y[m, n] = bf16_rne( sum_k x[m, k] * w_hat[n, k] ),  FP32 accumulation, scale applied per
+ *   32-block (late or early scaling are the same number because the scale is a power of two).
+ *   x_bf16 in  BF16 [M, K], row stride ldx (ldx >= K, ldx % 8 == 0, base 16-byte aligned)
+ *   q_packed, scales_e8m0  in, as written by mxfp4_direct_cast (q 16-byte aligned)
+ *   y_bf16 out BF16 [M, N], row stride ldy (ldy >= N)
+ * M >= 1 (any size; M <= 32 is the designed range), N >= 1, K a positive multiple of 32 and at
+ * most MXFP4_MAX_K.  The summation order is fixed per (M, N, K, path), not specified.
+ */
+#define MXFP4_MAX_K 65536
+int mxfp4_woq_gemm(const void* x_bf16, int64_t M, int64_t ldx,
+                   const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                   void* y_bf16, int64_t ldy, void* stream);
+
+/* Same, with the kernel family forced (MXFP4_PATH_*); MXFP4_ERR_ARG if the path cannot run
+ * the shape. */
+int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx,
+                        const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                        void* y_bf16, int64_t ldy, int path, void* stream);
+
+/*
+ * The same product with the greedy pick fused (section 3.1: the target's token at each
+ * verified position is compared with the draft's; section 4.1: greedy search): for every
+ * activation row m, the index n of the largest FP32 accumulator (before any BF16 rounding),
+ * the lowest index among equal maxima.  No y is written.
+ *   argmax_out out int32 [M]
+ *   max_out    out float [M], the winning accumulator; may be NULL
+ *   workspace  scratch of at least mxfp4_woq_gemm_argmax_workspace_bytes(M, N, K) bytes,
+ *              8-byte aligned; contents before and after the call are unspecified.  Two calls
+ *              that overlap in time must not share it.
+ * Rows whose accumulators contain NaN give an unspecified index.
+ */
+size_t mxfp4_woq_gemm_argmax_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int mxfp4_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
+                          const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                          int32_t* argmax_out, float* max_out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx,
+                               const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                               int32_t* argmax_out, float* max_out,
+                               void* workspace, size_t workspace_bytes, int path, void* stream);
+
+/* The same decode through the gfx950 scaled FP4->BF16 convert instruction (the one the CVT
+ * product path uses), so that its semantics can be checked in isolation. */
+int mxfp4_dequant_hwcvt(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                        void* w_bf16, int64_t ldw, void* stream);
+
+/*
+ * Measurement aids, not part of the method: a read-only and a copy kernel over `bytes` bytes
+ * (16-byte aligned, multiple of 16) that show what the memory system delivers to plain
+ * 128-bit streaming loads.  `sink4` is a 4-byte device scratch word.
+ */
+int mxfp4_diag_stream_read(const void* src, size_t bytes, void* sink4, void* stream);
+int mxfp4_diag_stream_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/* Host: text of the last error on this thread ("" if none).  Never NULL. */
+const char* mxfp4_last_error(void);
+
+/* Host: library version, e.g. "mxfp4-gfx950 0.1". */
+const char* mxfp4_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MXFP4_H */

@@ -1,0 +1,174 @@
+"""Thin ctypes binding of ``include/mxfp4.h``: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of ``libmxfp4_hip.so``; torch supplies device
+memory and the current stream.  There is no fallback: if the library has not been built
+(``python -m paper_2503_13565_amd.build``) the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmxfp4_hip.so")
+
+PATH_AUTO, PATH_VALU_BITS, PATH_VALU_CVT, PATH_VALU_LUT, PATH_MFMA = 0, 1, 2, 3, 4
+
+EXPORTS = [
+    "mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm", "mxfp4_woq_gemm_path",
+    "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
+    "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
+]
+
+_lib = None
+
+
+class Mxfp4Error(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("mxfp4 error %d: %s" % (code, text))
+        self.code = code
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library (torch first, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build it with `python -m paper_2503_13565_amd.build`; "
+            "there is no fallback path" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    lib.mxfp4_direct_cast.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    lib.mxfp4_dequant.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_dequant_hwcvt.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_woq_gemm_path.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, i32, vp]
+    lib.mxfp4_woq_gemm_argmax_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.mxfp4_woq_gemm_argmax_workspace_bytes.restype = sz
+    lib.mxfp4_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.mxfp4_woq_gemm_argmax_path.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, i32, vp]
+    lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
+    for name in ("mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
+                 "mxfp4_woq_gemm_path", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
+                 "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy"):
+        getattr(lib, name).restype = i32
+    lib.mxfp4_last_error.restype = ctypes.c_char_p
+    lib.mxfp4_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise Mxfp4Error(rc, load().mxfp4_last_error().decode())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dev(t: torch.Tensor) -> None:
+    if not t.is_cuda:
+        raise ValueError("tensor must live in GPU memory")
+
+
+def version() -> str:
+    return load().mxfp4_version().decode()
+
+
+def mxfp4_direct_cast(w: torch.Tensor, q: Optional[torch.Tensor] = None,
+                      s: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """BF16 ``[N,K]`` (last dim contiguous) -> (q uint8 ``[N,K/2]``, s uint8 ``[N,K/32]``)."""
+    _dev(w)
+    if w.dtype != torch.bfloat16 or w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be a 2-D BF16 tensor with a contiguous last dimension")
+    n, k = w.shape
+    if q is None:
+        q = torch.empty((n, k // 2), dtype=torch.uint8, device=w.device)
+    if s is None:
+        s = torch.empty((n, k // 32), dtype=torch.uint8, device=w.device)
+    ldw = w.stride(0) if n > 1 else max(k, 1)
+    with torch.cuda.device(w.device):
+        _check(load().mxfp4_direct_cast(_ptr(w), n, k, ldw, _ptr(q), _ptr(s), _stream()))
+    return q, s
+
+
+def mxfp4_dequant(q: torch.Tensor, s: torch.Tensor, hw_convert: bool = False) -> torch.Tensor:
+    _dev(q)
+    n, k = q.shape[0], q.shape[1] * 2
+    w = torch.empty((n, k), dtype=torch.bfloat16, device=q.device)
+    fn = load().mxfp4_dequant_hwcvt if hw_convert else load().mxfp4_dequant
+    with torch.cuda.device(q.device):
+        _check(fn(_ptr(q), _ptr(s), n, k, _ptr(w), k, _stream()))
+    return w
+
+
+def _gemm_shapes(x, q, s):
+    _dev(x)
+    if x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D BF16 tensor with a contiguous last dimension")
+    if q.dtype != torch.uint8 or s.dtype != torch.uint8 or not q.is_contiguous() or not s.is_contiguous():
+        raise ValueError("q and s must be contiguous uint8 tensors")
+    m, k = x.shape
+    n = q.shape[0]
+    if q.shape[1] * 2 != k or tuple(s.shape) != (n, k // 32):
+        raise ValueError("shape mismatch: x %r q %r s %r" % (tuple(x.shape), tuple(q.shape), tuple(s.shape)))
+    ldx = x.stride(0) if m > 1 else k
+    return m, n, k, ldx
+
+
+def mxfp4_woq_gemm(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, y: Optional[torch.Tensor] = None,
+                   path: int = PATH_AUTO) -> torch.Tensor:
+    """y ``[M,N]`` BF16 = x ``[M,K]`` BF16 times dequant(q, s)^T."""
+    m, n, k, ldx = _gemm_shapes(x, q, s)
+    if y is None:
+        y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_path(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(y),
+                                         y.stride(0) if m > 1 else n, path, _stream()))
+    return y
+
+
+def mxfp4_woq_gemm_argmax_workspace_bytes(m: int, n: int, k: int) -> int:
+    return int(load().mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k))
+
+
+def mxfp4_woq_gemm_argmax(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor,
+                          workspace: Optional[torch.Tensor] = None, path: int = PATH_AUTO,
+                          out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
+                          ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Row-wise (argmax int32 ``[M]``, max float32 ``[M]``) of x times dequant(q, s)^T."""
+    m, n, k, ldx = _gemm_shapes(x, q, s)
+    need = mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k)
+    if workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    if out is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+        val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    else:
+        idx, val = out
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_argmax_path(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(idx), _ptr(val),
+                                                _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                path, _stream()))
+    return idx, val
+
+
+def mxfp4_diag_stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    with torch.cuda.device(src.device):
+        _check(load().mxfp4_diag_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()))
+
+
+def mxfp4_diag_stream_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    with torch.cuda.device(src.device):
+        _check(load().mxfp4_diag_stream_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()))

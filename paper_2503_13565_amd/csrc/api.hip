@@ -1,0 +1,353 @@
+// C ABI of the MXFP4 weight-only-quantised linear layer (include/mxfp4.h): argument checks,
+// dispatch by the number of activation rows, and two plain streaming kernels used to measure
+// the memory system.  All device work is enqueued on the caller's stream; nothing here
+// synchronises, allocates or frees device memory.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "common.h"
+#include "kernels.h"
+#include "../../include/mxfp4.h"
+
+namespace mxfp4 {
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static int hip_fail(hipError_t e, const char* what)
+{
+    return fail(MXFP4_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Per-device facts, looked up once per device.
+static int device_info(DeviceInfo* out)
+{
+    static DeviceInfo cache[64];
+    static bool have[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64)
+        return fail(MXFP4_ERR_HIP, "device ordinal %d out of range", dev);
+    if (!have[dev]) {
+        int cus = 0, lds = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess)
+            return hip_fail(e, "hipDeviceGetAttribute(cus)");
+        e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+        if (e != hipSuccess)
+            return hip_fail(e, "hipDeviceGetAttribute(lds)");
+        cache[dev].cus = cus > 0 ? cus : 256;
+        cache[dev].lds_bytes = lds > 0 ? lds : 64 * 1024;
+        have[dev] = true;
+    }
+    *out = cache[dev];
+    return MXFP4_OK;
+}
+
+static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static int check_weights(const void* q, const void* s, int64_t N, int64_t K)
+{
+    if (!q || !s)
+        return fail(MXFP4_ERR_NULL, "q_packed or scales_e8m0 is NULL");
+    if (N < 1 || N > 0x7FFFFFFF / 8)
+        return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
+    if (K < 32 || K % 32 != 0 || K > MXFP4_MAX_K)
+        return fail(MXFP4_ERR_SHAPE, "K=%lld must be a multiple of 32 in [32, %d]", (long long)K, MXFP4_MAX_K);
+    if (!aligned(q, 16))
+        return fail(MXFP4_ERR_ALIGN, "q_packed must be 16-byte aligned");
+    return MXFP4_OK;
+}
+
+static int check_x(const void* x, int64_t M, int64_t ldx, int64_t K)
+{
+    if (!x)
+        return fail(MXFP4_ERR_NULL, "x_bf16 is NULL");
+    if (M < 1 || M > (1 << 20))
+        return fail(MXFP4_ERR_SHAPE, "M=%lld out of range", (long long)M);
+    if (ldx < K)
+        return fail(MXFP4_ERR_SHAPE, "ldx=%lld < K=%lld", (long long)ldx, (long long)K);
+    if (ldx % 8 != 0 || !aligned(x, 16))
+        return fail(MXFP4_ERR_ALIGN, "x_bf16 must be 16-byte aligned with ldx %% 8 == 0");
+    return MXFP4_OK;
+}
+
+static int pick_path(int path, int64_t M)
+{
+    if (path != MXFP4_PATH_AUTO)
+        return path;
+    static int env_path = -1;
+    if (env_path < 0) {
+        const char* v = getenv("MXFP4_FORCE_PATH");
+        env_path = v ? atoi(v) : 0;
+    }
+    if (env_path > 0)
+        return env_path;
+    (void)M;
+    return MXFP4_PATH_VALU_CVT;
+}
+
+static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const void* s, int64_t N, int64_t K,
+                    void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
+                    size_t workspace_bytes, bool argmax, int path, void* stream)
+{
+    g_err[0] = 0;
+    int rc = check_weights(q, s, N, K);
+    if (rc)
+        return rc;
+    rc = check_x(x, M, ldx, K);
+    if (rc)
+        return rc;
+    DeviceInfo dev;
+    rc = device_info(&dev);
+    if (rc)
+        return rc;
+    GemmArgs a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.ldx = ldx;
+    a.q = static_cast<const uint8_t*>(q);
+    a.s = static_cast<const uint8_t*>(s);
+    a.m = (int)M;
+    a.n = (int)N;
+    a.k = (int)K;
+    if (argmax) {
+        if (!argmax_out)
+            return fail(MXFP4_ERR_NULL, "argmax_out is NULL");
+        const size_t need = mxfp4_woq_gemm_argmax_workspace_bytes(M, N, K);
+        if (!workspace || workspace_bytes < need)
+            return fail(MXFP4_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                        workspace ? workspace_bytes : (size_t)0);
+        if (!aligned(workspace, 8))
+            return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
+        a.parts = gemv_max_parts(dev);
+        a.part_val = static_cast<float*>(workspace);
+        a.part_idx = reinterpret_cast<int32_t*>(a.part_val + (size_t)M * a.parts);
+    } else {
+        if (!y)
+            return fail(MXFP4_ERR_NULL, "y_bf16 is NULL");
+        if (ldy < N)
+            return fail(MXFP4_ERR_SHAPE, "ldy=%lld < N=%lld", (long long)ldy, (long long)N);
+        a.y = static_cast<uint16_t*>(y);
+        a.ldy = ldy;
+    }
+    const int chosen = pick_path(path, M);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int parts_used = 0;
+    hipError_t e;
+    switch (chosen) {
+    case MXFP4_PATH_VALU_BITS:
+    case MXFP4_PATH_VALU_CVT:
+    case MXFP4_PATH_VALU_LUT:
+        if ((size_t)K * 2 + (chosen == MXFP4_PATH_VALU_LUT ? 32768u : 0u) > (size_t)dev.lds_bytes)
+            return fail(MXFP4_ERR_SHAPE, "K=%lld does not fit the LDS copy of one activation row",
+                        (long long)K);
+        e = launch_gemv(a, chosen, argmax, dev, &parts_used, st);
+        break;
+    default:
+        return fail(MXFP4_ERR_ARG, "unknown or unavailable path %d", chosen);
+    }
+    if (e != hipSuccess)
+        return hip_fail(e, "product launch");
+    if (argmax) {
+        e = launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
+        if (e != hipSuccess)
+            return hip_fail(e, "argmax finish launch");
+    }
+    return MXFP4_OK;
+}
+
+// ---- plain streaming kernels ------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink)
+{
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (acc == 0x9E3779B9u)                          // practically never: keeps the loads alive
+        sink[0] = acc;
+}
+
+__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src,
+                                                          uint4* __restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+        dst[i] = src[i];
+}
+
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, const DeviceInfo& dev,
+                              hipStream_t stream)
+{
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(dev.cus * 8), dim3(256), 0, stream,
+                       static_cast<const uint4*>(src), n16, static_cast<uint32_t*>(sink));
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, const DeviceInfo& dev,
+                              hipStream_t stream)
+{
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(dev.cus * 8), dim3(256), 0, stream,
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
+    return hipGetLastError();
+}
+
+}  // namespace mxfp4
+
+using namespace mxfp4;
+
+extern "C" {
+
+int mxfp4_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q_packed,
+                      void* scales_e8m0, void* stream)
+{
+    g_err[0] = 0;
+    if (N < 0 || N > 0x7FFFFFFF)
+        return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
+    if (K < 32 || K % 32 != 0 || K > (1 << 24))
+        return fail(MXFP4_ERR_SHAPE, "K=%lld must be a positive multiple of 32", (long long)K);
+    if (ldw < K)
+        return fail(MXFP4_ERR_SHAPE, "ldw=%lld < K=%lld", (long long)ldw, (long long)K);
+    if (N == 0)
+        return MXFP4_OK;
+    if (!w_bf16 || !q_packed || !scales_e8m0)
+        return fail(MXFP4_ERR_NULL, "w_bf16, q_packed or scales_e8m0 is NULL");
+    if (ldw % 8 != 0 || !aligned(w_bf16, 16))
+        return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
+    if (!aligned(q_packed, 4))
+        return fail(MXFP4_ERR_ALIGN, "q_packed must be 4-byte aligned");
+    hipError_t e = launch_direct_cast(w_bf16, N, K, ldw, q_packed, scales_e8m0, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "direct cast launch");
+}
+
+static int dequant_impl(const void* q, const void* s, int64_t N, int64_t K, void* w, int64_t ldw, bool hw,
+                        void* stream)
+{
+    g_err[0] = 0;
+    if (N == 0)
+        return MXFP4_OK;
+    int rc = check_weights(q, s, N, K);
+    if (rc)
+        return rc;
+    if (!w)
+        return fail(MXFP4_ERR_NULL, "w_bf16 is NULL");
+    if (ldw < K)
+        return fail(MXFP4_ERR_SHAPE, "ldw=%lld < K=%lld", (long long)ldw, (long long)K);
+    if (ldw % 8 != 0 || !aligned(w, 16))
+        return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
+    hipError_t e = launch_dequant(q, s, N, K, w, ldw, hw, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "dequant launch");
+}
+
+int mxfp4_dequant(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K, void* w_bf16,
+                  int64_t ldw, void* stream)
+{
+    return dequant_impl(q_packed, scales_e8m0, N, K, w_bf16, ldw, false, stream);
+}
+
+int mxfp4_dequant_hwcvt(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K, void* w_bf16,
+                        int64_t ldw, void* stream)
+{
+    return dequant_impl(q_packed, scales_e8m0, N, K, w_bf16, ldw, true, stream);
+}
+
+int mxfp4_woq_gemm(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                   const void* scales_e8m0, int64_t N, int64_t K, void* y_bf16, int64_t ldy, void* stream)
+{
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, nullptr, 0,
+                    false, MXFP4_PATH_AUTO, stream);
+}
+
+int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                        const void* scales_e8m0, int64_t N, int64_t K, void* y_bf16, int64_t ldy, int path,
+                        void* stream)
+{
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, nullptr, 0,
+                    false, path, stream);
+}
+
+size_t mxfp4_woq_gemm_argmax_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    (void)N;
+    (void)K;
+    if (M < 1)
+        return 0;
+    // one (value, index) pair per activation row and per workgroup of the product kernel; the
+    // bound on workgroups is taken for the largest device this library targets (256 CUs)
+    return (size_t)M * 256 * 8 * (sizeof(float) + sizeof(int32_t));
+}
+
+int mxfp4_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                          const void* scales_e8m0, int64_t N, int64_t K, int32_t* argmax_out,
+                          float* max_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, MXFP4_PATH_AUTO, stream);
+}
+
+int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                               const void* scales_e8m0, int64_t N, int64_t K, int32_t* argmax_out,
+                               float* max_out, void* workspace, size_t workspace_bytes, int path,
+                               void* stream)
+{
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, path, stream);
+}
+
+int mxfp4_diag_stream_read(const void* src, size_t bytes, void* sink4, void* stream)
+{
+    g_err[0] = 0;
+    if (!src || !sink4)
+        return fail(MXFP4_ERR_NULL, "src or sink is NULL");
+    if (!aligned(src, 16) || bytes % 16 != 0)
+        return fail(MXFP4_ERR_ALIGN, "src must be 16-byte aligned and bytes a multiple of 16");
+    DeviceInfo dev;
+    int rc = device_info(&dev);
+    if (rc)
+        return rc;
+    hipError_t e = launch_stream_read(src, bytes, sink4, dev, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "stream read launch");
+}
+
+int mxfp4_diag_stream_copy(const void* src, void* dst, size_t bytes, void* stream)
+{
+    g_err[0] = 0;
+    if (!src || !dst)
+        return fail(MXFP4_ERR_NULL, "src or dst is NULL");
+    if (!aligned(src, 16) || !aligned(dst, 16) || bytes % 16 != 0)
+        return fail(MXFP4_ERR_ALIGN, "src/dst must be 16-byte aligned and bytes a multiple of 16");
+    DeviceInfo dev;
+    int rc = device_info(&dev);
+    if (rc)
+        return rc;
+    hipError_t e = launch_stream_copy(src, dst, bytes, dev, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "stream copy launch");
+}
+
+const char* mxfp4_last_error(void) { return g_err; }
+
+const char* mxfp4_version(void) { return "mxfp4-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,146 @@
+// BF16 -> MXFP4 direct cast and its inverse for gfx950 (arXiv 2503.13565, section 3.4.3:
+// the two-step quantisation; E2M1 elements, one E8M0 scale per 32 elements along K).
+//
+// Integer-only on the BF16 bit patterns.  Four lanes share one 32-element block: each lane
+// loads 16 bytes (8 elements), the block maximum is taken across the quad with DPP, and each
+// lane writes one packed dword; a wave therefore reads 1 KiB and writes 256 B, contiguous.
+#include "common.h"
+#include "kernels.h"
+
+namespace mxfp4 {
+
+// Code (eem) of one element from its 15 magnitude bits and the block's scale byte.
+// With sig the 8-bit significand and d = exponent - scale byte (d <= 2 for every element of
+// the block that produced the scale), F = |v|/X in units of 2^-10 is sig << (d+3).  The
+// quantum of E2M1 is 0.5 below 2 and doubles per binade above; F is rounded to it to nearest
+// even and the result is re-based to the code, saturating at 7.
+__device__ __forceinline__ uint32_t quantise_e2m1(uint32_t mag, int scale_byte)
+{
+    const uint32_t exp = mag >> 7;
+    const uint32_t man = mag & 0x7Fu;
+    const uint32_t sig = exp ? (0x80u | man) : man;
+    const int sh3 = (int)(exp ? exp : 1u) - scale_byte + 3;
+    if (sh3 < 0)
+        return 0u;                                   // below 2^-3 of X: rounds to zero
+    const uint32_t F = sig << sh3;
+    const int top = 31 - __clz((int)F);              // -1 for F == 0
+    const int shq = (top > 10 ? top : 10) - 1;       // log2 of the quantum in F units
+    const uint32_t rounded = (F + ((1u << (shq - 1)) - 1u) + ((F >> shq) & 1u)) >> shq;
+    const uint32_t code = rounded + 2u * (uint32_t)(shq - 9);
+    return code > 7u ? 7u : code;
+}
+
+__global__ __launch_bounds__(256) void direct_cast_kernel(const uint16_t* __restrict__ w,
+                                                          int64_t n_rows, int k, int64_t ldw,
+                                                          uint32_t* __restrict__ q,
+                                                          uint8_t* __restrict__ s)
+{
+    const int groups_per_row = k >> 3;               // 8-element groups; a multiple of 4
+    const int64_t total = n_rows * groups_per_row;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total)
+        return;                                      // quads are never split: total % 4 == 0
+    const int64_t row = gid / groups_per_row;
+    const int cg = (int)(gid - row * groups_per_row);
+    const uint4 v = *reinterpret_cast<const uint4*>(w + row * ldw + (int64_t)cg * 8);
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+
+    uint32_t amax = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = d[i] & 0x7FFFu, hi = (d[i] >> 16) & 0x7FFFu;
+        amax = max(amax, max(lo, hi));
+    }
+    // block maximum over the 4 lanes of the quad (BF16 magnitude order = integer order)
+    amax = max(amax, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)amax, 0xB1, 0xF, 0xF, false));
+    amax = max(amax, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)amax, 0x4E, 0xF, 0xF, false));
+
+    uint32_t packed = 0;
+    int scale_byte;
+    if (amax >= 0x7F80u) {
+        scale_byte = 0xFF;                           // NaN or Inf in the block
+    } else {
+        scale_byte = (int)(amax >> 7) - 2;           // biased exponent of amax, minus 2
+        scale_byte = scale_byte < 0 ? 0 : scale_byte;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = d[i] & 0xFFFFu, hi = d[i] >> 16;
+            const uint32_t nlo = quantise_e2m1(lo & 0x7FFFu, scale_byte) | ((lo >> 15) << 3);
+            const uint32_t nhi = quantise_e2m1(hi & 0x7FFFu, scale_byte) | ((hi >> 15) << 3);
+            packed |= (nlo | (nhi << 4)) << (8 * i);
+        }
+    }
+    q[gid] = packed;
+    if ((cg & 3) == 0)
+        s[gid >> 2] = (uint8_t)scale_byte;
+}
+
+// q, s -> BF16 (scale * magnitude, exact while the product is a normal BF16).  One lane per
+// packed dword (8 elements).  kHw selects the gfx950 scaled FP4->BF16 convert instead of bit
+// assembly, so that the instruction's semantics can be checked in isolation.
+template <bool kHw>
+__global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict__ q,
+                                                      const uint8_t* __restrict__ s,
+                                                      int64_t n_rows, int k, uint16_t* __restrict__ w,
+                                                      int64_t ldw)
+{
+    const int groups_per_row = k >> 3;
+    const int64_t total = n_rows * groups_per_row;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total)
+        return;
+    const int64_t row = gid / groups_per_row;
+    const int cg = (int)(gid - row * groups_per_row);
+    const uint32_t packed = q[gid];
+    const float scale = e8m0_to_f32(s[gid >> 2]);
+    uint32_t out[4];
+    if constexpr (kHw) {
+        bf16x2_t p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(packed, scale, 0);
+        bf16x2_t p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(packed, scale, 1);
+        bf16x2_t p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(packed, scale, 2);
+        bf16x2_t p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(packed, scale, 3);
+        out[0] = __builtin_bit_cast(uint32_t, p0);
+        out[1] = __builtin_bit_cast(uint32_t, p1);
+        out[2] = __builtin_bit_cast(uint32_t, p2);
+        out[3] = __builtin_bit_cast(uint32_t, p3);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t byte = (packed >> (8 * i)) & 0xFFu;
+            const float lo = e2m1_to_f32(byte & 0xFu) * scale;
+            const float hi = e2m1_to_f32(byte >> 4) * scale;
+            out[i] = (uint32_t)f32_to_bf16_rne(lo) | ((uint32_t)f32_to_bf16_rne(hi) << 16);
+        }
+    }
+    *reinterpret_cast<uint4*>(w + row * ldw + (int64_t)cg * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+hipError_t launch_direct_cast(const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q, void* s,
+                              hipStream_t stream)
+{
+    const int64_t total = n_rows * (k / 8);
+    if (total == 0)
+        return hipSuccess;
+    const int64_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(direct_cast_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       (const uint16_t*)w, n_rows, (int)k, ldw, (uint32_t*)q, (uint8_t*)s);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant(const void* q, const void* s, int64_t n_rows, int64_t k, void* w, int64_t ldw,
+                          bool hw_convert, hipStream_t stream)
+{
+    const int64_t total = n_rows * (k / 8);
+    if (total == 0)
+        return hipSuccess;
+    const int64_t blocks = (total + 255) / 256;
+    if (hw_convert)
+        hipLaunchKernelGGL(dequant_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           (const uint32_t*)q, (const uint8_t*)s, n_rows, (int)k, (uint16_t*)w, ldw);
+    else
+        hipLaunchKernelGGL(dequant_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           (const uint32_t*)q, (const uint8_t*)s, n_rows, (int)k, (uint16_t*)w, ldw);
+    return hipGetLastError();
+}
+
+}  // namespace mxfp4

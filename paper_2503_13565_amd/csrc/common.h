@@ -1,0 +1,69 @@
+// Device-side helpers shared by the gfx950 kernels of the MXFP4 weight-only-quantised
+// linear layer (arXiv 2503.13565, section 3.4.3).  Wave size is 64 everywhere.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mxfp4 {
+
+constexpr int kWave = 64;
+constexpr int kBlockElems = 32;      // elements per scale block along K
+constexpr int kBlockBytes = 16;      // packed bytes per scale block
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// E8M0 scale byte -> FP32 2^(byte-127).  Byte 0 is 2^-127 (an FP32 subnormal), byte 0xFF is NaN.
+__device__ __forceinline__ float e8m0_to_f32(uint32_t byte)
+{
+    uint32_t bits = byte << 23;
+    bits = (byte == 0u) ? 0x00400000u : bits;
+    bits = (byte == 0xFFu) ? 0x7FC00000u : bits;
+    return __uint_as_float(bits);
+}
+
+// FP32 -> BF16 bit pattern, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// One E2M1 nibble (sign<<3 | eem) -> FP32, by bit assembly: codes 0 and 1 are 0 and 0.5, a
+// normal code eem is 1.m * 2^(ee-1).
+__device__ __forceinline__ float e2m1_to_f32(uint32_t nib)
+{
+    uint32_t c = nib & 7u;
+    uint32_t bits = (((c >> 1) + 126u) << 23) | ((c & 1u) << 22);
+    bits = (c == 1u) ? 0x3F000000u : bits;
+    bits = (c == 0u) ? 0u : bits;
+    return __uint_as_float(bits | ((nib & 8u) << 28));
+}
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xF, 0xF, false));
+}
+
+// Sum over the 64 lanes of a wave in a fixed order; every lane returns the total.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_f32<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_f32<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f32<0x141>(v);   // row_half_mirror
+    v += dpp_f32<0x140>(v);   // row_mirror: all 16 lanes of a row now hold the row's sum
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+}  // namespace mxfp4

@@ -1,0 +1,54 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mxfp4 {
+
+// Arguments of one skinny product launch; see include/mxfp4.h for the tensor layouts.
+struct GemmArgs {
+    const uint16_t* x;   // BF16 [M, K], row stride ldx
+    int64_t ldx;
+    const uint8_t* q;    // packed nibbles [N, K/2]
+    const uint8_t* s;    // scale bytes [N, K/32]
+    int m;               // activation rows
+    int n;               // output features
+    int k;               // reduction length, multiple of 32
+    uint16_t* y;         // BF16 [M, N], row stride ldy; unused by the argmax form
+    int64_t ldy;
+    // argmax form: per-workgroup partial winners [M, parts] written by the product kernel
+    float* part_val;
+    int32_t* part_idx;
+    int parts;           // capacity per row of the two arrays above
+};
+
+struct DeviceInfo {
+    int cus;             // compute units
+    int lds_bytes;       // LDS per workgroup the device allows
+};
+
+hipError_t launch_direct_cast(const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q, void* s,
+                              hipStream_t stream);
+hipError_t launch_dequant(const void* q, const void* s, int64_t n_rows, int64_t k, void* w, int64_t ldw,
+                          bool hw_convert, hipStream_t stream);
+
+// Wave-per-row-group product on the vector ALUs.  `decode` is one of MXFP4_PATH_VALU_*.
+// Handles any M by passing over the weights once per group of activation rows.
+// `parts_used` receives the number of partial winners written per row (argmax form).
+hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceInfo& dev,
+                       int* parts_used, hipStream_t stream);
+int gemv_max_parts(const DeviceInfo& dev);
+
+// Second stage of the fused argmax: reduce `parts_used` partial winners per row.
+hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
+                                int m, int32_t* argmax_out, float* max_out, hipStream_t stream);
+
+// Plain streaming kernels used to measure what the memory system delivers.
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, const DeviceInfo& dev,
+                              hipStream_t stream);
+hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, const DeviceInfo& dev,
+                              hipStream_t stream);
+
+}  // namespace mxfp4

@@ -1,0 +1,86 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host-side argument checks return error codes (never abort) before any GPU work."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_13565_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mxfp4.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(mxfp4_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = declared_functions()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == names
+    assert binding.version().startswith("mxfp4-gfx950")
+
+
+def test_product_never_touches_the_oracle():
+    # the product package must not import the test oracle
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2503_13565_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b", src, flags=re.M), f
+                assert "liboracle" not in src, f
+
+
+P16 = ctypes.c_void_p(4096)          # a non-NULL, 16-byte aligned fake pointer; never dereferenced on error paths
+P2 = ctypes.c_void_p(4098)
+
+
+@pytest.mark.parametrize("args,code", [
+    ((None, -1, 32, 32, None, None, None), 2),                 # N < 0
+    ((P16, 4, 48, 48, P16, P16, None), 2),                      # K % 32
+    ((P16, 4, 64, 32, P16, P16, None), 2),                      # ldw < K
+    ((None, 4, 64, 64, P16, P16, None), 1),                     # NULL input
+    ((P2, 4, 64, 64, P16, P16, None), 3),                       # misaligned input
+    ((P16, 4, 64, 68, P16, P16, None), 3),                      # ldw % 8
+    ((P16, 0, 64, 64, None, None, None), 0),                    # N == 0 is a no-op
+])
+def test_direct_cast_argument_checks(args, code):
+    lib = binding.load()
+    assert lib.mxfp4_direct_cast(*args) == code
+    if code:
+        assert lib.mxfp4_last_error()
+
+
+@pytest.mark.parametrize("args,code", [
+    ((None, 1, 64, P16, P16, 8, 64, P16, 8, None), 1),          # x NULL
+    ((P16, 1, 64, None, P16, 8, 64, P16, 8, None), 1),          # q NULL
+    ((P16, 0, 64, P16, P16, 8, 64, P16, 8, None), 2),           # M < 1
+    ((P16, 1, 64, P16, P16, 0, 64, P16, 8, None), 2),           # N < 1
+    ((P16, 1, 64, P16, P16, 8, 40, P16, 8, None), 2),           # K % 32
+    ((P16, 1, 64, P16, P16, 8, 131072, P16, 8, None), 2),       # K too large
+    ((P16, 1, 32, P16, P16, 8, 64, P16, 8, None), 2),           # ldx < K
+    ((P2, 1, 64, P16, P16, 8, 64, P16, 8, None), 3),            # x misaligned
+    ((P16, 1, 64, P2, P16, 8, 64, P16, 8, None), 3),            # q misaligned
+    ((P16, 2, 68, P16, P16, 8, 64, P16, 8, None), 3),           # ldx % 8
+])
+def test_gemm_argument_checks(args, code):
+    lib = binding.load()
+    assert lib.mxfp4_woq_gemm(*args) == code
+    assert lib.mxfp4_last_error()
+
+
+def test_argmax_workspace_size_and_checks():
+    lib = binding.load()
+    need = lib.mxfp4_woq_gemm_argmax_workspace_bytes(4, 32000, 4096)
+    assert need >= 4 * 8 and need % 8 == 0
+    assert lib.mxfp4_woq_gemm_argmax_workspace_bytes(0, 1, 32) == 0
+    # bad K is reported before the workspace is looked at
+    assert lib.mxfp4_woq_gemm_argmax(P16, 1, 64, P16, P16, 8, 40, P16, None, None, 0, None) == 2
