@@ -81,7 +81,7 @@ int mxfp4_dequant(const void* q_packed, const void* scales_e8m0, int64_t N, int6
  *   q_packed, scales_e8m0  in, as written by mxfp4_direct_cast (q 16-byte aligned)
  *   y_bf16 out BF16 [M, N], row stride ldy (ldy >= N)
  * M >= 1 (any size; M <= 32 is the designed range), N >= 1, K a positive multiple of 32 and at
- * most MXFP4_MAX_K.  The summation order is fixed per (M, N, K, path), not specified.
+ * most MXFP4_MAX_K; the packed weights of one call stay below 2 GiB.  The summation order is fixed per (M, N, K, path), not specified.
  */
 #define MXFP4_MAX_K 65536
 int mxfp4_woq_gemm(const void* x_bf16, int64_t M, int64_t ldx,

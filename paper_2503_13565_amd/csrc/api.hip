@@ -66,6 +66,8 @@ static int check_weights(const void* q, const void* s, int64_t N, int64_t K)
         return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
     if (K < 32 || K % 32 != 0 || K > MXFP4_MAX_K)
         return fail(MXFP4_ERR_SHAPE, "K=%lld must be a multiple of 32 in [32, %d]", (long long)K, MXFP4_MAX_K);
+    if (N * (K / 2) > 0x7FFFFFFF)
+        return fail(MXFP4_ERR_SHAPE, "N*K/2=%lld bytes of packed weights exceed 2 GiB - 1", (long long)(N * (K / 2)));
     if (!aligned(q, 16))
         return fail(MXFP4_ERR_ALIGN, "q_packed must be 16-byte aligned");
     return MXFP4_OK;

@@ -15,6 +15,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 // E8M0 scale byte -> FP32 2^(byte-127).  Byte 0 is 2^-127 (an FP32 subnormal), byte 0xFF is NaN.
 __device__ __forceinline__ float e8m0_to_f32(uint32_t byte)

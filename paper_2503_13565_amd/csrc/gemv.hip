@@ -19,6 +19,9 @@
 //           every lane reads its own bank; the scale is applied to the 32-element partial
 //           sum (late scaling, Eq. 2).
 //   kBits - plain integer/FP32 bit assembly; slow, kept as the in-library cross-check.
+#include <stdio.h>
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 #include "../../include/mxfp4.h"
@@ -29,10 +32,11 @@ enum { kBits = MXFP4_PATH_VALU_BITS, kCvt = MXFP4_PATH_VALU_CVT, kLut = MXFP4_PA
 
 constexpr int kLutBytes = 256 * 32 * 4;   // 256 byte values x 32 banks x one dword
 
-template <int R>
+template <int R, bool kScaleDword>
 struct Item {
-    uint4 q[R];         // packed nibbles of this lane's block, one per row of the group
-    uint32_t s[R];      // scale bytes
+    u32x4_t q[R];                   // packed nibbles of this lane's block, one per row of the group
+    uint32_t s[kScaleDword ? 1 : R];  // scale bytes: this lane's own (one per row), or, in the dword
+                                    // scheme, four consecutive scales of row (lane / 16) % R
 };
 
 struct Pos {
@@ -40,54 +44,46 @@ struct Pos {
     int t;              // step along K (64 blocks per step)
 };
 
-template <int MT, int R, int kDecode, bool kTail, bool kArgmax>
-__global__ __launch_bounds__(256) void gemv_kernel(GemmArgs a, int m0)
+// Workgroup barrier that waits for LDS traffic only.  __syncthreads() would also drain the
+// vector-memory counter and with it the weight loads that are deliberately in flight.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Wait until every vector-memory operation of this wave has completed (s_waitcnt vmcnt(0),
+// other counters untouched; gfx9 encoding).  A real waitcnt instruction rather than inline
+// assembly, so that the compiler's own wait insertion knows nothing is pending afterwards.
+__device__ __forceinline__ void drain_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+constexpr int kXRegChunks = 4;    // activation chunks a thread can hold while the weights start
+
+// MT activation rows per pass, R weight rows per group, D register buffers of one step each
+// (D-1 steps of loads stay in flight while one is computed), NW waves per workgroup.
+template <int MT, int R, int D, int NW, int kDecode, bool kScaleDword>
+__global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmArgs a, int m0)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    uint4* xs = reinterpret_cast<uint4*>(smem);                      // [MT][4][nblk] chunks
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                  // [MT][4][nblk] chunks
     uint32_t* lut = reinterpret_cast<uint32_t*>(smem + (size_t)MT * a.k * 2);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform, kept scalar
     const int nblk = a.k >> 5;
-
-    // Stage the activation rows: chunk c (8 elements) of row m goes to [m][c & 3][c >> 2].
-    {
-        const int chunks = a.k >> 3;
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            const int msrc = min(m0 + m, a.m - 1);                   // ragged M: repeat the last row
-            const uint4* xr = reinterpret_cast<const uint4*>(a.x + (int64_t)msrc * a.ldx);
-            for (int c = tid; c < chunks; c += 256)
-                xs[(m * 4 + (c & 3)) * nblk + (c >> 2)] = xr[c];
-        }
-        if constexpr (kDecode == kLut) {
-            for (int e = tid; e < 256 * 32; e += 256) {
-                const uint32_t byte = (uint32_t)e >> 5;
-                const uint32_t lo = __float_as_uint(e2m1_to_f32(byte & 0xFu)) >> 16;
-                const uint32_t hi = __float_as_uint(e2m1_to_f32(byte >> 4)) >> 16;
-                lut[e] = lo | (hi << 16);
-            }
-        }
-    }
-    __syncthreads();
-
     const int steps = (nblk + 63) >> 6;
+    const int tail_blocks = nblk - (steps - 1) * 64;                 // blocks in the last step (1..64)
     const int n_groups = (a.n + R - 1) / R;
-    const int total_waves = gridDim.x * 4;
-    const int64_t q_row_bytes = a.k >> 1;
+    const int total_waves = gridDim.x * NW;
+    const int first_group = (int)blockIdx.x * NW + wave;
+    const int q_row_bytes = a.k >> 1;
+    const bool argmax = a.part_val != nullptr;
 
-    float best_val[MT];
-    int best_idx[MT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-        best_val[m] = -INFINITY;
-        best_idx[m] = 0x7FFFFFFF;
-    }
-    float acc[R][MT];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int m = 0; m < MT; ++m)
-            acc[r][m] = 0.f;
+    // Buffer descriptors: all addressing is a scalar offset (row, step) plus lane * 16.
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(a.q), 0, a.n * q_row_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(a.s), 0, a.n * nblk, 0x00020000);
 
     auto valid = [&](const Pos& p) { return p.g < n_groups; };
     auto advance = [&](Pos& p) {
@@ -96,54 +92,173 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs a, int m0)
             p.g += total_waves;
         }
     };
-    auto issue = [&](const Pos& p, Item<R>& it) {
-        const int b = p.t * 64 + lane;
-        const int bc = kTail ? min(b, nblk - 1) : b;
+    // the lane's block within step t; lanes past the end of a ragged last step re-read its last block
+    auto lane_block = [&](int t) { return (t == steps - 1 && lane >= tail_blocks) ? tail_blocks - 1 : lane; };
+    // Always the same number of loads, so that the hardware's in-order load counter can be
+    // waited on precisely.  Past the wave's last position the lane offset is pushed beyond the
+    // descriptor's range: such loads touch no memory and return zero.
+    //
+    // Scales.  Byte scheme: one byte load per row, the lane's own block.  Dword scheme (needs
+    // K % 128 == 0 so that every dword is aligned and inside its row): the 64 scale bytes of a
+    // step are 16 dwords per row; lane l loads dword (l % 16) of row (l / 16) % R, so ONE load
+    // brings all R rows' scales of the step, and compute() fetches each row's byte from the lane
+    // that holds it with ds_bpermute.
+    const int srow = (lane >> 4) % R;
+    auto issue = [&](const Pos& p, Item<R, kScaleDword>& it) {
+        const bool live = valid(p);
+        const int lb = lane_block(p.t);
+        const int voff_q = live ? lb * 16 : 0x7FFFFFF0;
+        const int g = live ? p.g : 0;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int row = min(p.g * R + r, a.n - 1);                // ragged N: re-read the last row
-            it.q[r] = *reinterpret_cast<const uint4*>(a.q + row * q_row_bytes + (int64_t)bc * 16);
-            it.s[r] = a.s[(int64_t)row * nblk + bc];
+            const int row = min(g * R + r, a.n - 1);                  // ragged N: re-read the last row
+            it.q[r] = __builtin_amdgcn_raw_buffer_load_b128(rq, voff_q, row * q_row_bytes + p.t * 1024, 2);
+            if constexpr (!kScaleDword) {
+                const int voff_s = live ? lb : 0x7FFFFFF0;
+                it.s[r] = __builtin_amdgcn_raw_buffer_load_b8(rs, voff_s, row * nblk + p.t * 64, 2);
+            }
+        }
+        if constexpr (kScaleDword) {
+            const int row = min(g * R + srow, a.n - 1);
+            const int voff_s = live ? row * nblk + (lane & 15) * 4 : 0x7FFFFFF0;
+            it.s[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff_s, p.t * 64, 2);
         }
     };
-    auto compute = [&](const Pos& p, Item<R>& it) {
-        const int b = p.t * 64 + lane;
-        const int bc = kTail ? min(b, nblk - 1) : b;
-        uint4 xv[MT][4];
+
+    // Prologue.  The activation loads go out first and the first D steps of weight loads right
+    // behind them; only the activations are waited for before the LDS copy, so the weights stay
+    // in flight across the barrier.  Chunk c (8 elements) of row m goes to [m][c & 3][c >> 2].
+    Item<R, kScaleDword> buf[D];
+    Pos pos[D];
+    Pos load{first_group, 0};
+    {
+        const int chunks = a.k >> 3;
+        constexpr int T = NW * 64;
+        u32x4_t xr[MT][kXRegChunks];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            const int msrc = min(m0 + m, a.m - 1);                   // ragged M: repeat the last row
+            const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx);
+#pragma unroll
+            for (int i = 0; i < kXRegChunks; ++i)
+                xr[m][i] = xp[min(tid + i * T, chunks - 1)];
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            pos[d] = load;
+            issue(load, buf[d]);
+            advance(load);
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+#pragma unroll
+            for (int i = 0; i < kXRegChunks; ++i) {
+                const int c = min(tid + i * T, chunks - 1);          // clamped duplicates rewrite the same data
+                xs[(m * 4 + (c & 3)) * nblk + (c >> 2)] = xr[m][i];
+            }
+            if (chunks > kXRegChunks * T) {                          // long rows: the rest, the slow way
+                const int msrc = min(m0 + m, a.m - 1);
+                const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx);
+                for (int c = tid + kXRegChunks * T; c < chunks; c += T)
+                    xs[(m * 4 + (c & 3)) * nblk + (c >> 2)] = xp[c];
+            }
+        }
+        if constexpr (kDecode == kLut) {
+            for (int e = tid; e < 256 * 32; e += NW * 64) {
+                const uint32_t byte = (uint32_t)e >> 5;
+                const uint32_t lo = __float_as_uint(e2m1_to_f32(byte & 0xFu)) >> 16;
+                const uint32_t hi = __float_as_uint(e2m1_to_f32(byte >> 4)) >> 16;
+                lut[e] = lo | (hi << 16);
+            }
+        }
+    }
+    lds_barrier();
+
+    float best_val[MT];
+    int best_idx[MT];
+    float res[MT];               // finished outputs, one per lane: slot i = i-th finished row of this wave
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        best_val[m] = -INFINITY;
+        best_idx[m] = 0x7FFFFFFF;
+        res[m] = 0.f;
+    }
+    int slots = 0;               // outputs held in res[]
+    int flushed_groups = 0;      // row groups of this wave already written
+    float acc[R][MT];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+            acc[r][m] = 0.f;
+
+    // Write the held outputs: lane i owns the i-th row finished since the last flush.  Stores
+    // and loads share one completion counter but complete out of order with respect to each
+    // other, so the counter is drained here; the main loop then only ever sees loads in flight.
+    auto flush = [&]() {
+        if (lane < slots) {
+            const int j = lane / R, r = lane - j * R;
+            const int row = (first_group + (flushed_groups + j) * total_waves) * R + r;
+            if (row < a.n) {
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    if (m0 + m < a.m)
+                        a.y[(int64_t)(m0 + m) * a.ldy + row] = f32_to_bf16_rne(res[m]);
+            }
+        }
+        flushed_groups += slots / R;
+        slots = 0;
+        drain_vmem();
+    };
+
+    auto compute = [&](const Pos& p, Item<R, kScaleDword>& it) {
+        const int lb = lane_block(p.t);
+        const int bc = p.t * 64 + lb;
+        u32x4_t xv[MT][4];
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 xv[m][j] = xs[(m * 4 + j) * nblk + bc];
-        if (kTail && b >= nblk) {
+        if (p.t == steps - 1 && lane >= tail_blocks) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                it.q[r] = make_uint4(0, 0, 0, 0);                     // all nibbles +0
+                it.q[r] = u32x4_t{0, 0, 0, 0};                        // all nibbles +0
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const float sc = e8m0_to_f32(it.s[r]);
-            const uint32_t qd[4] = {it.q[r].x, it.q[r].y, it.q[r].z, it.q[r].w};
+            uint32_t sbyte;
+            if constexpr (kScaleDword) {
+                // the dword with this lane's scale of row r sits in lane r*16 + lb/4, byte lb%4
+                const uint32_t dw = (uint32_t)__builtin_amdgcn_ds_bpermute((r * 16 + (lb >> 2)) * 4, (int)it.s[0]);
+                sbyte = (dw >> ((lb & 3) * 8)) & 0xFFu;
+            } else {
+                sbyte = it.s[r];
+            }
+            // The scaled convert reads only the exponent field of its scale operand and treats it
+            // as E8M0 (0 is 2^-127, 255 is NaN), so byte << 23 is the whole conversion there.
+            const float sc = kDecode == kCvt ? __uint_as_float(sbyte << 23) : e8m0_to_f32(sbyte);
             float part[MT];
 #pragma unroll
             for (int m = 0; m < MT; ++m)
                 part[m] = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                const uint32_t qd = it.q[r][j];
                 uint32_t xd[MT][4];
 #pragma unroll
                 for (int m = 0; m < MT; ++m) {
-                    xd[m][0] = xv[m][j].x;
-                    xd[m][1] = xv[m][j].y;
-                    xd[m][2] = xv[m][j].z;
-                    xd[m][3] = xv[m][j].w;
+                    xd[m][0] = xv[m][j][0];
+                    xd[m][1] = xv[m][j][1];
+                    xd[m][2] = xv[m][j][2];
+                    xd[m][3] = xv[m][j][3];
                 }
                 if constexpr (kDecode == kCvt) {
                     bf16x2_t w[4];
-                    w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd[j], sc, 0);
-                    w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd[j], sc, 1);
-                    w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd[j], sc, 2);
-                    w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd[j], sc, 3);
+                    w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0);
+                    w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1);
+                    w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2);
+                    w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3);
 #pragma unroll
                     for (int p4 = 0; p4 < 4; ++p4)
 #pragma unroll
@@ -154,7 +269,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs a, int m0)
                     const uint32_t* bank = lut + (lane & 31);
 #pragma unroll
                     for (int p4 = 0; p4 < 4; ++p4) {
-                        const uint32_t byte = (qd[j] >> (8 * p4)) & 0xFFu;
+                        const uint32_t byte = (qd >> (8 * p4)) & 0xFFu;
                         const uint32_t w2 = bank[byte * 32];
 #pragma unroll
                         for (int m = 0; m < MT; ++m)
@@ -165,7 +280,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs a, int m0)
                 } else {
 #pragma unroll
                     for (int p4 = 0; p4 < 4; ++p4) {
-                        const uint32_t byte = (qd[j] >> (8 * p4)) & 0xFFu;
+                        const uint32_t byte = (qd >> (8 * p4)) & 0xFFu;
                         const float wlo = e2m1_to_f32(byte & 0xFu), whi = e2m1_to_f32(byte >> 4);
 #pragma unroll
                         for (int m = 0; m < MT; ++m) {
@@ -182,7 +297,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs a, int m0)
             }
         }
         if (p.t == steps - 1) {
-            // end of the row group: sum the lanes' partials, write or compare
+            // end of the row group: sum the lanes' partials, then hold or compare the totals
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int row = p.g * R + r;
@@ -190,49 +305,47 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs a, int m0)
                 for (int m = 0; m < MT; ++m) {
                     const float v = wave_sum(acc[r][m]);
                     acc[r][m] = 0.f;
-                    if (row < a.n && m0 + m < a.m) {
-                        if constexpr (kArgmax) {
-                            if (v > best_val[m]) {                    // rows ascend: lowest index wins ties
-                                best_val[m] = v;
-                                best_idx[m] = row;
-                            }
-                        } else if (lane == 0) {
-                            a.y[(int64_t)(m0 + m) * a.ldy + row] = f32_to_bf16_rne(v);
+                    if (argmax) {
+                        if (row < a.n && v > best_val[m]) {           // rows ascend: lowest index wins ties
+                            best_val[m] = v;
+                            best_idx[m] = row;
                         }
+                    } else {
+                        res[m] = (lane == slots + r) ? v : res[m];
                     }
                 }
+            }
+            if (!argmax) {
+                slots += R;
+                if (slots + R > 64)
+                    flush();
             }
         }
     };
 
-    Item<R> buf_a, buf_b;
-    Pos load{(int)blockIdx.x * 4 + wave, 0};
-    Pos cur = load;
-    if (valid(load))
-        issue(load, buf_a);
-    advance(load);
-    while (valid(cur)) {
-        Pos next = load;
-        if (valid(load))
-            issue(load, buf_b);
-        advance(load);
-        compute(cur, buf_a);
-        cur = next;
-        if (!valid(cur))
-            break;
-        next = load;
-        if (valid(load))
-            issue(load, buf_a);
-        advance(load);
-        compute(cur, buf_b);
-        cur = next;
+    // Positions only grow, so the first exhausted buffer ends the walk.  The exit is a direct
+    // jump: an exit path that rejoined the loop's back edge would make the compiler's load
+    // counting assume the shorter queue of the exiting path on every iteration.
+    for (;;) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (!valid(pos[d]))
+                goto walk_done;
+            compute(pos[d], buf[d]);
+            pos[d] = load;
+            issue(load, buf[d]);
+            advance(load);
+        }
     }
+walk_done:
+    if (!argmax && slots > 0)
+        flush();
 
-    if constexpr (kArgmax) {
-        // combine the 4 waves of the workgroup, then publish one partial winner per row
+    if (argmax) {
+        // combine the waves of the workgroup, then publish one partial winner per row
         __syncthreads();
         float* wv = reinterpret_cast<float*>(smem);
-        int* wi = reinterpret_cast<int*>(smem) + 4 * MT;
+        int* wi = reinterpret_cast<int*>(smem) + NW * MT;
         if (lane == 0) {
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
@@ -244,7 +357,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs a, int m0)
         if (tid < MT && m0 + tid < a.m) {
             float bv = wv[tid];
             int bi = wi[tid];
-            for (int w = 1; w < 4; ++w) {
+            for (int w = 1; w < NW; ++w) {
                 const float v = wv[w * MT + tid];
                 const int i = wi[w * MT + tid];
                 if (v > bv || (v == bv && i < bi)) {
@@ -303,10 +416,46 @@ int gemv_max_parts(const DeviceInfo& dev) { return dev.cus * 8; }
 
 namespace {
 
-template <int MT, int R, int kDecode, bool kTail, bool kArgmax>
+// Launch shape: rows per group, register buffers, waves per workgroup, workgroups per CU.
+struct Tune {
+    int r, d, nw, wgs_per_cu;
+    bool byte_scales;       // force the byte scale loads even when K allows the dword scheme
+};
+
+// Rows per group: enough groups that every SIMD gets a few waves even for short matrices.
+Tune default_tune(int n_rows, int cus)
+{
+    const int want_groups = cus * 16;
+    int r = 4;
+    while (r > 1 && (n_rows + r - 1) / r < want_groups)
+        r >>= 1;
+    return Tune{r, 2, 4, 4, false};
+}
+
+// MXFP4_GEMV_TUNE="R,D,NW,WGS[,B]" overrides the launch shape (measurement only; R = 0 keeps
+// the default rows per group, B = 1 forces byte scale loads).
+bool env_tune(Tune* out)
+{
+    static Tune t;
+    static const bool have = [] {
+        if (const char* e = getenv("MXFP4_GEMV_TUNE")) {
+            int r, d, nw, w, b = 0;
+            if (sscanf(e, "%d,%d,%d,%d,%d", &r, &d, &nw, &w, &b) >= 4) {
+                t = Tune{r, d, nw, w, b != 0};
+                return true;
+            }
+        }
+        return false;
+    }();
+    if (have)
+        *out = t;
+    return have;
+}
+
+template <int MT, int R, int D, int NW, int kDecode, bool kScaleDword>
 hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
-    auto kern = gemv_kernel<MT, R, kDecode, kTail, kArgmax>;
+    auto kern = gemv_kernel<MT, R, D, NW, kDecode, kScaleDword>;
     static bool attr_set = false;                   // per instantiation; racing writers set the same value
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -315,46 +464,68 @@ hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max
             return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, stream, a, m0);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0);
     return hipGetLastError();
 }
 
-template <int MT, int kDecode, bool kArgmax>
-hipError_t launch_mt(const GemmArgs& a, int m0, bool tail, int blocks, size_t lds, int max_lds,
-                     hipStream_t stream)
+template <int MT, int kDecode>
+hipError_t launch_shape(const GemmArgs& a, int m0, const Tune& t, int blocks, size_t lds, int max_lds,
+                        hipStream_t stream)
 {
-    constexpr int R = 4;
-    if (tail)
-        return launch_one<MT, R, kDecode, true, kArgmax>(a, m0, blocks, lds, max_lds, stream);
-    return launch_one<MT, R, kDecode, false, kArgmax>(a, m0, blocks, lds, max_lds, stream);
+    const bool sd = (a.k % 128 == 0) && !t.byte_scales;
+#define MXFP4_CASE(R_, D_, NW_)                                                                      \
+    if (t.r == R_ && t.d == D_ && t.nw == NW_)                                                       \
+        return sd ? launch_one<MT, R_, D_, NW_, kDecode, true>(a, m0, blocks, lds, max_lds, stream)  \
+                  : launch_one<MT, R_, D_, NW_, kDecode, false>(a, m0, blocks, lds, max_lds, stream);
+    MXFP4_CASE(4, 2, 4)
+    MXFP4_CASE(2, 2, 4)
+    MXFP4_CASE(1, 2, 4)
+    if constexpr (kDecode == kCvt) {
+        MXFP4_CASE(4, 3, 4)
+        MXFP4_CASE(2, 3, 4)
+        MXFP4_CASE(2, 4, 4)
+        MXFP4_CASE(1, 3, 4)
+        MXFP4_CASE(1, 4, 4)
+        MXFP4_CASE(4, 2, 8)
+        MXFP4_CASE(2, 2, 8)
+        MXFP4_CASE(2, 4, 8)
+        MXFP4_CASE(1, 4, 8)
+    }
+#undef MXFP4_CASE
+    return hipErrorInvalidValue;
 }
 
-template <int kDecode, bool kArgmax>
+template <int kDecode>
 hipError_t launch_decode(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
 {
-    constexpr int R = 4;
-    const int nblk = a.k / 32;
-    const bool tail = (nblk % 64) != 0;
+    Tune t = default_tune(a.n, dev.cus);
+    if constexpr (kDecode == kCvt) {
+        Tune e;
+        if (env_tune(&e)) {
+            if (e.r == 0)
+                e.r = t.r;
+            t = e;
+        }
+    }
     const size_t extra = kDecode == kLut ? (size_t)kLutBytes : 0;
     // two activation rows per pass when their LDS copy fits, else one
     const bool two_fit = (size_t)2 * a.k * 2 + extra <= (size_t)dev.lds_bytes;
-    const int n_groups = (a.n + R - 1) / R;
-    int blocks_per_cu = 4;
-    int blocks = (n_groups + 3) / 4;
-    if (blocks > dev.cus * blocks_per_cu)
-        blocks = dev.cus * blocks_per_cu;
+    const int n_groups = (a.n + t.r - 1) / t.r;
+    int blocks = (n_groups + t.nw - 1) / t.nw;
+    if (blocks > dev.cus * t.wgs_per_cu)
+        blocks = dev.cus * t.wgs_per_cu;
+    if (blocks > gemv_max_parts(dev))
+        blocks = gemv_max_parts(dev);
     if (parts_used)
         *parts_used = blocks;
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
         hipError_t e;
         if (left >= 2 && two_fit) {
-            e = launch_mt<2, kDecode, kArgmax>(a, m0, tail, blocks, (size_t)2 * a.k * 2 + extra,
-                                                dev.lds_bytes, stream);
+            e = launch_shape<2, kDecode>(a, m0, t, blocks, (size_t)2 * a.k * 2 + extra, dev.lds_bytes, stream);
             m0 += 2;
         } else {
-            e = launch_mt<1, kDecode, kArgmax>(a, m0, tail, blocks, (size_t)a.k * 2 + extra, dev.lds_bytes,
-                                                stream);
+            e = launch_shape<1, kDecode>(a, m0, t, blocks, (size_t)a.k * 2 + extra, dev.lds_bytes, stream);
             m0 += 1;
         }
         if (e != hipSuccess)
@@ -368,16 +539,14 @@ hipError_t launch_decode(const GemmArgs& a, const DeviceInfo& dev, int* parts_us
 hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceInfo& dev, int* parts_used,
                        hipStream_t stream)
 {
+    (void)argmax;                                   // the kernels look at a.part_val
     switch (decode) {
     case kBits:
-        return argmax ? launch_decode<kBits, true>(a, dev, parts_used, stream)
-                      : launch_decode<kBits, false>(a, dev, parts_used, stream);
+        return launch_decode<kBits>(a, dev, parts_used, stream);
     case kCvt:
-        return argmax ? launch_decode<kCvt, true>(a, dev, parts_used, stream)
-                      : launch_decode<kCvt, false>(a, dev, parts_used, stream);
+        return launch_decode<kCvt>(a, dev, parts_used, stream);
     case kLut:
-        return argmax ? launch_decode<kLut, true>(a, dev, parts_used, stream)
-                      : launch_decode<kLut, false>(a, dev, parts_used, stream);
+        return launch_decode<kLut>(a, dev, parts_used, stream);
     default:
         return hipErrorInvalidValue;
     }
