@@ -1,0 +1,272 @@
+#!/usr/bin/env python3
+"""Benchmark of the MXFP4 weight-only-quantised decode linears on one MI355X.
+
+Workload (the second benchmark configuration): the five Llama-7B-shaped decode linears at
+M = 1 -- fused QKV [12288x4096], O [4096x4096], gate+up [22016x4096], down [4096x11008] and
+the LM head [32000x4096] with the fused argmax -- on seeded synthetic data (Student-t(4)*0.02
+weights direct-cast to MXFP4 on the GPU, N(0,1) activations with 8 outlier channels x50).
+
+One step = one pass over the five linears (6 kernel launches).  To keep the 256 MB Infinity
+Cache out of the picture every step uses a different one of `--sets` weight sets (>= 2 GB in
+total), so each launch streams its weights from HBM.  The timed region replays HIP graphs
+(one per weight set) on one stream; inputs are resident in HBM before it starts.
+
+Prints ONE JSON line: value = algorithmic bytes per step / time per step (GB/s), with the
+roofline of the dominant kernel and the CPU oracle timed on this machine's host cores beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "MXFP4 WOQ GEMV effective HBM GB/s (% peak) at M=1; us per 7B-shaped decode step"
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(m: int, n: int, k: int) -> float:
+    """Packed nibbles + scales, read once; activations in; outputs out (BF16)."""
+    return n * k * 0.53125 + 2.0 * m * k + 2.0 * m * n
+
+
+def build_sets(n_sets: int, m: int, dev):
+    import torch
+    from paper_2503_13565_amd import binding, synth
+    shape = synth.LLAMA_7B
+    sets = []
+    cast_bytes = 0.0
+    cast_ms = 0.0
+    for layer in range(n_sets):
+        lin = {}
+        for li, (name, n, k) in enumerate(shape.linears()):
+            seed = synth.tensor_seed(0, layer, li)
+            w = synth.weights_student_t(n, k, seed=seed, device=dev)
+            x = synth.activations_outlier_channels(m, k, seed=seed + 8, device=dev)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            q, s = binding.mxfp4_direct_cast(w)
+            e1.record()
+            torch.cuda.synchronize()
+            if layer > 0:                              # the first layer's casts pay one-time costs
+                cast_ms += e0.elapsed_time(e1)
+                cast_bytes += n * k * 2.53125
+            del w
+            lin[name] = dict(n=n, k=k, q=q, s=s, x=x,
+                             y=torch.empty((m, n), dtype=torch.bfloat16, device=dev))
+        lin["lm_head"]["idx"] = torch.empty((m,), dtype=torch.int32, device=dev)
+        lin["lm_head"]["val"] = torch.empty((m,), dtype=torch.float32, device=dev)
+        sets.append(lin)
+    return sets, (cast_bytes / (cast_ms * 1e-3) / 1e9 if cast_ms > 0 else None)
+
+
+def run_step(lin, ws):
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up", "down"):
+        t = lin[name]
+        binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+    t = lin["lm_head"]
+    binding.mxfp4_woq_gemm_argmax(t["x"], t["q"], t["s"], workspace=ws, out=(t["idx"], t["val"]))
+
+
+def run_dominant(lin, ws):
+    """The two launches of a step that use the dominant kernel instance (4 rows per wave step)."""
+    from paper_2503_13565_amd import binding
+    t = lin["gate_up"]
+    binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+    t = lin["lm_head"]                                  # same kernel instance as the fused-argmax call
+    binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+
+
+def capture(fn, sets, ws, stream):
+    """One HIP graph holding one step per weight set, in order; None if capture is unavailable."""
+    import torch
+    try:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for lin in sets:
+                fn(lin, ws)
+    except Exception as exc:                            # plain launches still measure the kernels
+        print("bench: graph capture failed (%s); timing plain launches" % exc, file=sys.stderr)
+        return None
+    return g
+
+
+def runner(graph, fn, sets, ws):
+    """run(n): execute n steps, weight sets in rotation -- whole rotations as graph replays, the
+    remainder (and everything, without a graph) as plain launches on the current stream."""
+    def run(n):
+        done = 0
+        if graph is not None:
+            while n - done >= len(sets):
+                graph.replay()
+                done += len(sets)
+        while done < n:
+            fn(sets[done % len(sets)], ws)
+            done += 1
+    return run
+
+
+def timed(run, n, stream):
+    """Time run(n) on `stream` with HIP events; returns milliseconds in total."""
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        e0.record(stream)
+        run(n)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1)
+
+
+def cpu_baseline(m: int):
+    """The CPU oracle, as it stands, on the same five linears (weight set 0), all host threads."""
+    import numpy as np
+    import oracle
+    from paper_2503_13565_amd import synth
+    shape = synth.LLAMA_7B
+    threads = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    threads = max(1, min(threads, oracle.max_threads()))
+    t_cast = t_gemm = 0.0
+    nbytes = 0.0
+    for li, (name, n, k) in enumerate(shape.linears()):
+        seed = synth.tensor_seed(0, 0, li)
+        w = synth.weights_student_t(n, k, seed=seed)
+        x = synth.activations_outlier_channels(m, k, seed=seed + 8)
+        wb, xb = synth.to_bits(w), synth.to_bits(x)
+        t0 = time.perf_counter()
+        q, s = oracle.direct_cast(wb, threads=threads)
+        t1 = time.perf_counter()
+        y, _ = oracle.woq_gemm(xb, q, s, threads=threads)
+        if name == "lm_head":
+            oracle.argmax(y)
+        t2 = time.perf_counter()
+        t_cast += t1 - t0
+        t_gemm += t2 - t1
+        nbytes += algorithmic_bytes(m, n, k)
+    return {
+        "value": nbytes / t_gemm / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": "one full step: the five 7B decode linears at M=%d (FP64 product + argmax), "
+                  "%.2f s; the oracle's direct cast of the same weights took %.2f s more "
+                  "(not in value)" % (m, t_gemm, t_cast),
+        "seconds_per_step": t_gemm,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=240)
+    ap.add_argument("--warmup", type=int, default=24)
+    ap.add_argument("--sets", type=int, default=12, help="distinct weight sets rotated over (12 = 2.1 GB)")
+    ap.add_argument("--m", type=int, default=1, help="activation rows (1 = decode)")
+    ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of graph replays")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X: this build has no multi-GPU path (the linears shard by "
+              "output rows without collectives; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2503_13565_amd import binding, synth
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    binding.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    m = args.m
+    sets, cast_gbps = build_sets(args.sets, m, dev)
+    ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(m, 32000, 4096),), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    shape = synth.LLAMA_7B
+    step_bytes = sum(algorithmic_bytes(m, n, k) for _, n, k in shape.linears())
+    weight_bytes = sum(n * k * 0.53125 for _, n, k in shape.linears())
+
+    # warm every kernel instance outside any capture (first launches set function attributes)
+    with torch.cuda.stream(stream):
+        for lin in sets:
+            run_step(lin, ws)
+    torch.cuda.synchronize()
+
+    graph = None if args.no_graph else capture(run_step, sets, ws, stream)
+    run_steps = runner(graph, run_step, sets, ws)
+    timed(run_steps, args.warmup, stream)
+    ms = timed(run_steps, args.steps, stream)
+    ms_per_step = ms / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # the same steps as plain stream launches (host launch cost included), for the record
+    n_plain = max(len(sets), args.steps // 4)
+    plain_ms = timed(runner(None, run_step, sets, ws), n_plain, stream) / n_plain
+
+    # dominant kernel: the instance that runs gate+up and the LM head (2 of the 6 launches,
+    # 66 % of the bytes); average launch duration from events around graph replays of these two
+    # launches only, rotating over the weight sets
+    dgraph = None if args.no_graph else capture(run_dominant, sets, ws, stream)
+    run_dom = runner(dgraph, run_dominant, sets, ws)
+    timed(run_dom, len(sets), stream)
+    reps = len(sets) * max(2, args.steps // (2 * len(sets)))
+    dom_ms = timed(run_dom, reps, stream) / reps
+    dom_launch_us = dom_ms * 1e3 / 2.0
+    dom_bytes = (algorithmic_bytes(m, 22016, 4096) + algorithmic_bytes(m, 32000, 4096)) / 2.0
+    achieved = dom_bytes / (dom_launch_us * 1e-6) / 1e9
+
+    # what a plain 128-bit read stream gets on this device, over 4 GiB (context for frac)
+    buf = torch.empty(4 << 30, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    def run_read(n):
+        for _ in range(n):
+            binding.mxfp4_diag_stream_read(buf, sink)
+    timed(run_read, 1, stream)
+    read_ms = timed(run_read, 5, stream) / 5
+    stream_read_gbps = buf.numel() / (read_ms * 1e-3) / 1e9
+    del buf
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("gemv_m1_dominant_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-7B-shaped decode linears at M=%d "
+                               "(qkv 12288x4096, o 4096x4096, gate_up 22016x4096, down 4096x11008, "
+                               "lm_head 32000x4096 + argmax), %d weight sets rotated (%.2f GB)"
+                               % (m, len(sets), len(sets) * weight_bytes / 1e9),
+                   "M": m, "launch": "hip graph replay" if graph is not None else "stream launches"},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "us_per_step": round(ms_per_step * 1e3, 2),
+        "us_per_step_plain_launches": round(plain_ms * 1e3, 2),
+        "bytes_per_step": step_bytes,
+        "tflops": round(2.0 * m * sum(n * k for _, n, k in shape.linears()) / (ms_per_step * 1e-3) / 1e12, 3),
+        "stream_read_GBps": round(stream_read_gbps, 1),
+        "direct_cast_GBps": None if cast_gbps is None else round(cast_gbps, 1),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel": "mxfp4::gemv_kernel<1,4,2,4,2,true> (gate_up and lm_head launches)",
+                     "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_launch_us, 3)},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(m)
+        for key in ("value", "seconds_per_step"):
+            out["cpu_baseline"][key] = round(out["cpu_baseline"][key], 4)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
