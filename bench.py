@@ -228,15 +228,23 @@ def main() -> int:
     timed(run_read, 1, stream)
     read_ms = timed(run_read, 5, stream) / 5
     stream_read_gbps = buf.numel() / (read_ms * 1e-3) / 1e9
+    # one plain copy of known size (1 GiB read + 1 GiB written): the reference against which
+    # the profiler's FETCH_SIZE / WRITE_SIZE counters are scaled
+    half = buf.numel() // 4
+    with torch.cuda.stream(stream):
+        binding.mxfp4_diag_stream_copy(buf[:half], buf[2 * half:3 * half])
+    torch.cuda.synchronize()
     del buf
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "traffic.txt")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("gemv_m1_dominant_bytes_per_launch")
-        except Exception:
-            traffic = None
+        for line in open(tpath):
+            if line.startswith("gemv_m1_dominant_bytes_per_launch"):
+                try:
+                    traffic = int(line.split("=")[1])
+                except ValueError:
+                    traffic = None
 
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
