@@ -86,7 +86,10 @@ static int check_x(const void* x, int64_t M, int64_t ldx, int64_t K)
     return MXFP4_OK;
 }
 
-static int pick_path(int path, int64_t M)
+// AUTO: the vector-ALU GEMV for one or two activation rows, MFMA tiles from three rows on (each
+// extra row costs the GEMV half an instruction per weight; the tiles' cost does not grow up to
+// 16 rows), unless the shape cannot run there.
+static int pick_path(int path, int64_t M, bool mfma_ok)
 {
     if (path != MXFP4_PATH_AUTO)
         return path;
@@ -97,8 +100,7 @@ static int pick_path(int path, int64_t M)
     }
     if (env_path > 0)
         return env_path;
-    (void)M;
-    return MXFP4_PATH_VALU_CVT;
+    return (M >= 3 && mfma_ok) ? MXFP4_PATH_MFMA : MXFP4_PATH_VALU_CVT;
 }
 
 static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const void* s, int64_t N, int64_t K,
@@ -144,7 +146,7 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         a.y = static_cast<uint16_t*>(y);
         a.ldy = ldy;
     }
-    const int chosen = pick_path(path, M);
+    const int chosen = pick_path(path, M, mfma_can_run(a, dev));
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
     hipError_t e;
@@ -156,6 +158,12 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
             return fail(MXFP4_ERR_SHAPE, "K=%lld does not fit the LDS copy of one activation row",
                         (long long)K);
         e = launch_gemv(a, chosen, argmax, dev, &parts_used, st);
+        break;
+    case MXFP4_PATH_MFMA:
+        if (!mfma_can_run(a, dev))
+            return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and K <= %d here",
+                        (dev.lds_bytes - 16384) / 8);
+        e = launch_mfma(a, dev, &parts_used, st);
         break;
     default:
         return fail(MXFP4_ERR_ARG, "unknown or unavailable path %d", chosen);

@@ -41,6 +41,11 @@ hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceI
                        int* parts_used, hipStream_t stream);
 int gemv_max_parts(const DeviceInfo& dev);
 
+// 16-row MFMA tiles (bf16 16x16x32) for verification batches; passes of up to 16 activation rows.
+// mfma_can_run: K % 128 == 0 and the LDS copy of 4 activation rows fits.
+bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev);
+hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+
 // Second stage of the fused argmax: reduce `parts_used` partial winners per row.
 hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
                                 int m, int32_t* argmax_out, float* max_out, hipStream_t stream);

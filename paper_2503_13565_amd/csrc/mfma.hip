@@ -1,0 +1,283 @@
+// Skinny product y = x * dequant(W)^T on the matrix cores of gfx950, for verification batches
+// (arXiv 2503.13565, section 4.4: k+1 rows are verified in one pass and the pass has to cost
+// about as much as one decode step; section 3.4.3, Eq. 2 for the arithmetic).
+//
+// Why matrix cores for so few rows: on the vector ALUs every extra activation row costs half an
+// instruction per weight, which exhausts the ALU budget of a memory-speed kernel at 3 to 4 rows.
+// Here a weight costs half a vector instruction (the scaled FP4->BF16 convert) whatever the
+// number of rows, and v_mfma_f32_16x16x32_bf16 does the multiply-adds for up to 16 rows at once.
+// K = 32 of the instruction is one MX scale block per lane group.
+//
+// Mapping.  A tile is 16 weight rows.  Lane (i = lane % 16, g = lane / 16) loads, per step T,
+// the 16 bytes of block 4T + g of row i: 32 weights that feed four MFMAs (dword j = the lane's
+// 8 k-slots of MFMA j) after 16 converts; the block's scale goes into the converts.  The
+// activation operand of MFMA j for lane (col = lane % 16, g) is x[col][32 (4T + g) + 8 j .. + 8],
+// one 128-bit LDS read; activations are staged once per workgroup as [chunk][MP] so that the 16
+// columns of a chunk are contiguous.  The NW waves of a workgroup split K, every wave
+// accumulates a 16 x 16 FP32 tile over its K slice, the partial tiles are summed through LDS in
+// a fixed order, wave 0 rounds and stores (or tracks the argmax).  Workgroups are persistent
+// over tiles; loads run one item (4 steps) ahead in a second register buffer.
+#include "common.h"
+#include "kernels.h"
+#include "../../include/mxfp4.h"
+
+namespace mxfp4 {
+
+namespace {
+
+constexpr int kCh = 4;             // steps (16-byte loads per lane) per pipeline item
+constexpr int kSentinel = 0x7FFFFFF0;   // lane offset beyond any descriptor: the load returns zero
+
+__device__ __forceinline__ void lds_barrier_mfma()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+struct MItem {
+    u32x4_t q[kCh];
+    uint32_t s[kCh];
+};
+
+struct MPos {
+    int tile;
+    int c;          // item within the tile
+};
+
+// MP: activation rows held per pass (4, 8 or 16); NW: waves per workgroup (they split K).
+template <int MP, int NW>
+__global__ __launch_bounds__(NW * 64) void mfma_kernel(GemmArgs a, int m0)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                          // [K/8][MP] chunks of 8 elements
+    f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + (size_t)a.k * 2 * MP);  // [2][NW][64] partial tiles
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int nblk = a.k >> 5;
+    const int q_row_bytes = a.k >> 1;
+    const int t_total = a.k >> 7;                                 // steps of 4 blocks along K
+    const int steps_w = (t_total + NW - 1) / NW;                  // steps per wave and tile
+    const int items = (steps_w + kCh - 1) / kCh;
+    const int n_tiles = (a.n + 15) >> 4;
+    const bool argmax = a.part_val != nullptr;
+    const int m_valid = min(MP, a.m - m0);
+
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(a.q), 0, a.n * q_row_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(a.s), 0, a.n * nblk, 0x00020000);
+
+    // Stage the activations: chunk c of row m goes to xs[c * MP + m]; rows past M repeat the last.
+    {
+        const int chunks = a.k >> 3;
+        for (int e = tid; e < chunks * MP; e += NW * 64) {
+            const int m = e % MP, c = e / MP;
+            const int msrc = min(m0 + m, a.m - 1);
+            xs[c * MP + m] = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx)[c];
+        }
+    }
+
+    auto valid = [&](const MPos& p) { return p.tile < n_tiles; };
+    auto advance = [&](MPos& p) {
+        if (++p.c == items) {
+            p.c = 0;
+            p.tile += gridDim.x;
+        }
+    };
+    // Step T of this wave for slot u of item c, and whether it exists (wave-uniform).
+    auto step_of = [&](const MPos& p, int u, bool* ok) {
+        const int local = p.c * kCh + u;
+        const int t = wave * steps_w + local;
+        *ok = valid(p) && local < steps_w && t < t_total;
+        return t;
+    };
+    // Always kCh + kCh loads per item (absent steps read nothing and return zero), so that the
+    // in-order load counter can be waited on exactly.
+    auto issue = [&](const MPos& p, MItem& it) {
+        const int tile = valid(p) ? p.tile : 0;
+        const int row = min(tile * 16 + li, a.n - 1);             // ragged N: repeat the last row
+        const int vq = row * q_row_bytes + lg * 16;
+        const int vs = row * nblk + lg;
+#pragma unroll
+        for (int u = 0; u < kCh; ++u) {
+            bool ok;
+            const int t = step_of(p, u, &ok);
+            it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? t * 64 : 0, 2);
+            it.s[u] = __builtin_amdgcn_raw_buffer_load_b8(rs, ok ? vs : kSentinel, ok ? t * 4 : 0, 2);
+        }
+    };
+
+    MItem buf[2];
+    MPos pos[2];
+    MPos load{(int)blockIdx.x, 0};
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+        pos[d] = load;
+        issue(load, buf[d]);
+        advance(load);
+        __builtin_amdgcn_sched_barrier(0);                        // keep the buffers' loads in issue order
+    }
+    lds_barrier_mfma();
+
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    float best_val = -INFINITY;       // wave 0: running winner of column li over rows 4 lg + r of all tiles
+    int best_idx = 0x7FFFFFFF;
+    int tiles_done = 0;
+    const int col = li % MP;
+
+    auto compute = [&](const MPos& p, const MItem& it) {
+#pragma unroll
+        for (int u = 0; u < kCh; ++u) {
+            bool ok;
+            const int t = step_of(p, u, &ok);
+            const int tc = ok ? t : 0;                            // absent steps: zero weights, any finite x
+            const float sc = __uint_as_float(it.s[u] << 23);      // the convert reads the exponent field as E8M0
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t qd = it.q[u][j];
+                u32x4_t w;
+                w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0));
+                w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1));
+                w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2));
+                w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3));
+                const u32x4_t xb = xs[(16 * tc + 4 * lg + j) * MP + col];
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
+                                                              __builtin_bit_cast(bf16x8_t, xb), acc, 0, 0, 0);
+            }
+        }
+        if (p.c == items - 1) {
+            // end of the tile: sum the NW partial tiles in wave order, then store or compare
+            f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
+            slot[wave * 64 + lane] = acc;
+            acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            lds_barrier_mfma();
+            if (wave == 0) {
+                f32x4_t sum = slot[lane];
+#pragma unroll
+                for (int w = 1; w < NW; ++w)
+                    sum += slot[w * 64 + lane];
+                // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
+                if (li < m_valid) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = p.tile * 16 + 4 * lg + r;
+                        if (row < a.n) {
+                            if (argmax) {
+                                if (sum[r] > best_val) {          // rows ascend: lowest index wins ties
+                                    best_val = sum[r];
+                                    best_idx = row;
+                                }
+                            } else {
+                                a.y[(int64_t)(m0 + li) * a.ldy + row] = f32_to_bf16_rne(sum[r]);
+                            }
+                        }
+                    }
+                }
+                if (!argmax)
+                    __builtin_amdgcn_s_waitcnt(0x0F70);           // stores done: only loads stay in flight
+            }
+            ++tiles_done;
+        }
+    };
+
+    for (;;) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            if (!valid(pos[d]))
+                goto walk_done;
+            compute(pos[d], buf[d]);
+            pos[d] = load;
+            issue(load, buf[d]);
+            advance(load);
+        }
+    }
+walk_done:
+
+    if (argmax && wave == 0) {
+        // combine the four lane groups of each column (value desc, index asc), publish one partial
+#pragma unroll
+        for (int off = 16; off < 64; off <<= 1) {
+            const float v = __shfl_xor(best_val, off);
+            const int i = __shfl_xor(best_idx, off);
+            if (v > best_val || (v == best_val && i < best_idx)) {
+                best_val = v;
+                best_idx = i;
+            }
+        }
+        if (lane < m_valid) {
+            a.part_val[(int64_t)(m0 + lane) * a.parts + blockIdx.x] = best_val;
+            a.part_idx[(int64_t)(m0 + lane) * a.parts + blockIdx.x] = best_idx;
+        }
+    }
+}
+
+template <int MP, int NW>
+hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
+{
+    auto kern = mfma_kernel<MP, NW>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0);
+    return hipGetLastError();
+}
+
+size_t lds_need(int k, int mp, int nw) { return (size_t)k * 2 * mp + (size_t)2 * nw * 64 * 16; }
+
+}  // namespace
+
+bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev)
+{
+    return a.k % 128 == 0 && lds_need(a.k, 4, 8) <= (size_t)dev.lds_bytes;
+}
+
+hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+{
+    if (!mfma_can_run(a, dev))
+        return hipErrorInvalidValue;
+    constexpr int NW = 8;
+    const int n_tiles = (a.n + 15) / 16;
+    int first_blocks = 0;
+    for (int m0 = 0; m0 < a.m;) {
+        const int left = a.m - m0;
+        // the widest pass whose activation copy fits the LDS, but no wider than needed
+        int mp = left > 8 ? 16 : (left > 4 ? 8 : 4);
+        while (mp > 4 && lds_need(a.k, mp, NW) > (size_t)dev.lds_bytes)
+            mp >>= 1;
+        const size_t lds = lds_need(a.k, mp, NW);
+        int per_cu = (int)((size_t)dev.lds_bytes / lds);
+        per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+        int blocks = n_tiles < dev.cus * per_cu ? n_tiles : dev.cus * per_cu;
+        if (blocks > gemv_max_parts(dev))
+            blocks = gemv_max_parts(dev);
+        if (m0 == 0)
+            first_blocks = blocks;
+        // the argmax partial arrays are indexed by workgroup: keep the grid the same for all passes
+        if (a.part_val != nullptr)
+            blocks = first_blocks < blocks ? first_blocks : blocks;
+        hipError_t e;
+        if (mp == 16)
+            e = launch_one<16, NW>(a, m0, blocks, lds, dev.lds_bytes, stream);
+        else if (mp == 8)
+            e = launch_one<8, NW>(a, m0, blocks, lds, dev.lds_bytes, stream);
+        else
+            e = launch_one<4, NW>(a, m0, blocks, lds, dev.lds_bytes, stream);
+        if (e != hipSuccess)
+            return e;
+        if (a.part_val != nullptr && blocks != first_blocks)
+            return hipErrorInvalidValue;                           // cannot happen: LDS need only shrinks
+        m0 += mp;
+    }
+    if (parts_used)
+        *parts_used = first_blocks;
+    return hipSuccess;
+}
+
+}  // namespace mxfp4

@@ -52,6 +52,37 @@ def test_edge_shapes(n, k, m):
     run_gemm_case(w, x, paths, "N=%d K=%d M=%d" % (n, k, m), argmax=True)
 
 
+MFMA = binding.PATH_MFMA
+
+
+@pytest.mark.parametrize("n,k", [(1, 128), (16, 128), (17, 256), (33, 2048), (250, 11008), (1000, 4096),
+                                 (48, 8192), (31, 16384)])
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 9, 16, 17, 33])
+def test_mfma_tiles_edge_shapes(n, k, m):
+    w = synth.weights_student_t(n, k, seed=3000 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=4000 + m + k)
+    run_gemm_case(w, x, [MFMA], "MFMA N=%d K=%d M=%d" % (n, k, m), argmax=True)
+
+
+def test_mfma_needs_k_multiple_of_128():
+    x = torch.zeros((4, 96), dtype=torch.bfloat16, device=DEV)
+    q = torch.zeros((8, 48), dtype=torch.uint8, device=DEV)
+    s = torch.zeros((8, 3), dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.Mxfp4Error) as e:
+        binding.mxfp4_woq_gemm(x, q, s, path=MFMA)
+    assert e.value.code == 6
+    y = binding.mxfp4_woq_gemm(x, q, s)                    # AUTO falls back to the vector path
+    assert not y.float().abs().sum().item()
+
+
+def test_mfma_config0_and_llama_shapes():
+    data = synth.config0()
+    run_gemm_case(data["w"], data["x"], [MFMA], "config0 MFMA")
+    for linear in ("down", "o"):
+        d = synth.llama_linear(synth.LLAMA_7B, linear, m=8, seed=0)
+        run_gemm_case(d["w"], d["x"], [MFMA], "7B %s M=8 MFMA" % linear)
+
+
 @pytest.mark.parametrize("m", [17, 33])
 def test_many_rows(m):
     w = synth.weights_student_t(260, 1024, seed=5)
@@ -90,7 +121,7 @@ def test_on_grid_weights_and_one_hot_rows():
     x[3, 65] = 1.0
     xt = torch.from_numpy(x).to(torch.bfloat16)
     qd, sd = torch.from_numpy(q).to(DEV), torch.from_numpy(sb).to(DEV)
-    for p in ALL_VALU:
+    for p in ALL_VALU + [binding.PATH_MFMA]:
         y = binding.mxfp4_woq_gemm(xt.to(DEV), qd, sd, path=p).double().cpu().numpy()
         assert np.array_equal(y[0], wh[:, 0]), p
         assert np.array_equal(y[1], -2.0 * wh[:, 33]), p
@@ -109,7 +140,7 @@ def test_argmax_exact_ties_pick_lowest_index():
         q, s, q_ref, s_ref = assert_cast_bit_exact(wt)
         y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref)
         assert oracle.argmax(y_ref)[0][0] == rows[0]
-        for p in ALL_VALU:
+        for p in ALL_VALU + [binding.PATH_MFMA]:
             idx, val = binding.mxfp4_woq_gemm_argmax(x.to(DEV), q, s, path=p)
             assert int(idx[0]) == rows[0], (rows, p, int(idx[0]))
             assert_argmax_ok(idx, val, y_ref, a_ref)
@@ -132,7 +163,7 @@ def test_argmax_near_tie_accepts_either_within_tolerance():
     q = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8)
     y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q, sb)
     assert oracle.argmax(y_ref)[0][0] == 10 and y_ref[0, 10] - y_ref[0, 40] < 1e-6 * a_ref[0, 10]
-    for p in ALL_VALU:
+    for p in ALL_VALU + [binding.PATH_MFMA]:
         idx, val = binding.mxfp4_woq_gemm_argmax(x.to(DEV), torch.from_numpy(q).to(DEV),
                                                  torch.from_numpy(sb).to(DEV), path=p)
         got = assert_argmax_ok(idx, val, y_ref, a_ref)
