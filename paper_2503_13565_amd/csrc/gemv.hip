@@ -323,21 +323,20 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmArgs a, int m0)
         }
     };
 
-    // Positions only grow, so the first exhausted buffer ends the walk.  The exit is a direct
-    // jump: an exit path that rejoined the loop's back edge would make the compiler's load
-    // counting assume the shorter queue of the exiting path on every iteration.
-    for (;;) {
+    // Positions only grow, so the walk ends when buffer 0 runs dry.  Every trip issues the same
+    // loads whether or not the later buffers still had work: every path into the loop head then
+    // carries the same queue of outstanding loads and the compiler's counter waits stay exact
+    // (an exit path that rejoins the back edge with a shorter queue makes it wait for everything).
+    while (valid(pos[0])) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            if (!valid(pos[d]))
-                goto walk_done;
-            compute(pos[d], buf[d]);
+            if (d == 0 || valid(pos[d]))
+                compute(pos[d], buf[d]);
             pos[d] = load;
             issue(load, buf[d]);
             advance(load);
         }
     }
-walk_done:
     if (!argmax && slots > 0)
         flush();
 

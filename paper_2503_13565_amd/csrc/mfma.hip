@@ -13,10 +13,12 @@
 // 8 k-slots of MFMA j) after 16 converts; the block's scale goes into the converts.  The
 // activation operand of MFMA j for lane (col = lane % 16, g) is x[col][32 (4T + g) + 8 j .. + 8],
 // one 128-bit LDS read; activations are staged once per workgroup as [chunk][MP] so that the 16
-// columns of a chunk are contiguous.  The NW waves of a workgroup split K, every wave
-// accumulates a 16 x 16 FP32 tile over its K slice, the partial tiles are summed through LDS in
-// a fixed order, wave 0 rounds and stores (or tracks the argmax).  Workgroups are persistent
-// over tiles; loads run one item (4 steps) ahead in a second register buffer.
+// columns of a chunk are contiguous.  NW compute waves of a workgroup split K, each accumulates
+// a 16 x 16 FP32 tile over its K slice and leaves it in LDS; one more wave, which never loads
+// weights, sums the partial tiles in a fixed order, rounds and stores (or tracks the argmax), so
+// that the compute waves only ever have loads in flight and their load counter stays exact.
+// Workgroups are persistent over tiles; loads run one item (4 steps) ahead in a second register
+// buffer.
 #include "common.h"
 #include "kernels.h"
 #include "../../include/mxfp4.h"
@@ -45,15 +47,17 @@ struct MPos {
     int c;          // item within the tile
 };
 
-// MP: activation rows held per pass (4, 8 or 16); NW: waves per workgroup (they split K).
+// MP: activation rows held per pass (4, 8 or 16); NW: compute waves per workgroup (they split K);
+// the workgroup has NW + 1 waves, wave 0 is the epilogue wave.
 template <int MP, int NW>
-__global__ __launch_bounds__(NW * 64) void mfma_kernel(GemmArgs a, int m0)
+__global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                          // [K/8][MP] chunks of 8 elements
     f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + (size_t)a.k * 2 * MP);  // [2][NW][64] partial tiles
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kw = wave - 1;                                      // K slice of a compute wave
     const int li = lane & 15, lg = lane >> 4;
     const int nblk = a.k >> 5;
     const int q_row_bytes = a.k >> 1;
@@ -70,12 +74,28 @@ __global__ __launch_bounds__(NW * 64) void mfma_kernel(GemmArgs a, int m0)
         const_cast<uint8_t*>(a.s), 0, a.n * nblk, 0x00020000);
 
     // Stage the activations: chunk c of row m goes to xs[c * MP + m]; rows past M repeat the last.
+    // Consecutive threads read consecutive chunks of one row (coalesced); eight independent loads
+    // per thread are in flight at a time (one latency per batch, not per load).
     {
         const int chunks = a.k >> 3;
-        for (int e = tid; e < chunks * MP; e += NW * 64) {
-            const int m = e % MP, c = e / MP;
-            const int msrc = min(m0 + m, a.m - 1);
-            xs[c * MP + m] = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx)[c];
+        const int entries = chunks * MP;
+        constexpr int kBatch = 8;
+        constexpr int kThreads = (NW + 1) * 64;
+        for (int e0 = tid; e0 < entries; e0 += kBatch * kThreads) {
+            u32x4_t v[kBatch];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const int e = min(e0 + b * kThreads, entries - 1);
+                const int m = e / chunks, c = e - m * chunks;
+                const int msrc = min(m0 + m, a.m - 1);
+                v[b] = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx)[c];
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const int e = min(e0 + b * kThreads, entries - 1);   // clamped duplicates rewrite the same data
+                const int m = e / chunks, c = e - m * chunks;
+                xs[c * MP + m] = v[b];
+            }
         }
     }
 
@@ -89,7 +109,7 @@ __global__ __launch_bounds__(NW * 64) void mfma_kernel(GemmArgs a, int m0)
     // Step T of this wave for slot u of item c, and whether it exists (wave-uniform).
     auto step_of = [&](const MPos& p, int u, bool* ok) {
         const int local = p.c * kCh + u;
-        const int t = wave * steps_w + local;
+        const int t = kw * steps_w + local;
         *ok = valid(p) && local < steps_w && t < t_total;
         return t;
     };
@@ -105,95 +125,103 @@ __global__ __launch_bounds__(NW * 64) void mfma_kernel(GemmArgs a, int m0)
             bool ok;
             const int t = step_of(p, u, &ok);
             it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? t * 64 : 0, 2);
-            it.s[u] = __builtin_amdgcn_raw_buffer_load_b8(rs, ok ? vs : kSentinel, ok ? t * 4 : 0, 2);
+            it.s[u] = __builtin_amdgcn_raw_buffer_load_b8(rs, ok ? vs : kSentinel, ok ? t * 4 : 0, 0);   // scale lines are shared by the waves: cached
         }
     };
 
-    MItem buf[2];
-    MPos pos[2];
-    MPos load{(int)blockIdx.x, 0};
-#pragma unroll
-    for (int d = 0; d < 2; ++d) {
-        pos[d] = load;
-        issue(load, buf[d]);
-        advance(load);
-        __builtin_amdgcn_sched_barrier(0);                        // keep the buffers' loads in issue order
-    }
-    lds_barrier_mfma();
-
-    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const int col = li % MP;
     float best_val = -INFINITY;       // wave 0: running winner of column li over rows 4 lg + r of all tiles
     int best_idx = 0x7FFFFFFF;
-    int tiles_done = 0;
-    const int col = li % MP;
 
-    auto compute = [&](const MPos& p, const MItem& it) {
+    if (wave == 0) {
+        // Epilogue wave: one barrier per tile, like the compute waves; no weight loads of its own.
+        lds_barrier_mfma();                                       // activations staged
+        int tiles_done = 0;
+        for (int tile = (int)blockIdx.x; tile < n_tiles; tile += gridDim.x, ++tiles_done) {
+            const f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
+            lds_barrier_mfma();                                   // partial tiles of `tile` are in LDS
+            f32x4_t sum = slot[lane];
 #pragma unroll
-        for (int u = 0; u < kCh; ++u) {
-            bool ok;
-            const int t = step_of(p, u, &ok);
-            const int tc = ok ? t : 0;                            // absent steps: zero weights, any finite x
-            const float sc = __uint_as_float(it.s[u] << 23);      // the convert reads the exponent field as E8M0
+            for (int w = 1; w < NW; ++w)
+                sum += slot[w * 64 + lane];
+            // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
+            if (li < m_valid) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t qd = it.q[u][j];
-                u32x4_t w;
-                w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0));
-                w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1));
-                w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2));
-                w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3));
-                const u32x4_t xb = xs[(16 * tc + 4 * lg + j) * MP + col];
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
-                                                              __builtin_bit_cast(bf16x8_t, xb), acc, 0, 0, 0);
-            }
-        }
-        if (p.c == items - 1) {
-            // end of the tile: sum the NW partial tiles in wave order, then store or compare
-            f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
-            slot[wave * 64 + lane] = acc;
-            acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            lds_barrier_mfma();
-            if (wave == 0) {
-                f32x4_t sum = slot[lane];
-#pragma unroll
-                for (int w = 1; w < NW; ++w)
-                    sum += slot[w * 64 + lane];
-                // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
-                if (li < m_valid) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int row = p.tile * 16 + 4 * lg + r;
-                        if (row < a.n) {
-                            if (argmax) {
-                                if (sum[r] > best_val) {          // rows ascend: lowest index wins ties
-                                    best_val = sum[r];
-                                    best_idx = row;
-                                }
-                            } else {
-                                a.y[(int64_t)(m0 + li) * a.ldy + row] = f32_to_bf16_rne(sum[r]);
+                for (int r = 0; r < 4; ++r) {
+                    const int row = tile * 16 + 4 * lg + r;
+                    if (row < a.n) {
+                        if (argmax) {
+                            if (sum[r] > best_val) {              // rows ascend: lowest index wins ties
+                                best_val = sum[r];
+                                best_idx = row;
                             }
+                        } else {
+                            a.y[(int64_t)(m0 + li) * a.ldy + row] = f32_to_bf16_rne(sum[r]);
                         }
                     }
                 }
-                if (!argmax)
-                    __builtin_amdgcn_s_waitcnt(0x0F70);           // stores done: only loads stay in flight
             }
-            ++tiles_done;
         }
-    };
-
-    for (;;) {
+    } else {
+        MItem buf[2];
+        MPos pos[2];
+        MPos load{(int)blockIdx.x, 0};
 #pragma unroll
         for (int d = 0; d < 2; ++d) {
-            if (!valid(pos[d]))
-                goto walk_done;
-            compute(pos[d], buf[d]);
             pos[d] = load;
             issue(load, buf[d]);
             advance(load);
+            __builtin_amdgcn_sched_barrier(0);                    // keep the buffers' loads in issue order
+        }
+        lds_barrier_mfma();                                       // activations staged
+
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        int tiles_done = 0;
+        auto compute = [&](const MPos& p, const MItem& it) {
+#pragma unroll
+            for (int u = 0; u < kCh; ++u) {
+                bool ok;
+                const int t = step_of(p, u, &ok);
+                const int tc = ok ? t : 0;                        // absent steps: zero weights, any finite x
+                const float sc = __uint_as_float(it.s[u] << 23);  // the convert reads the exponent field as E8M0
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t qd = it.q[u][j];
+                    u32x4_t w;
+                    w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0));
+                    w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1));
+                    w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2));
+                    w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3));
+                    const u32x4_t xb = xs[(16 * tc + 4 * lg + j) * MP + col];
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
+                                                                  __builtin_bit_cast(bf16x8_t, xb), acc, 0, 0, 0);
+                }
+            }
+            if (p.c == items - 1) {
+                // end of the tile: leave the partial tile for the epilogue wave
+                f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
+                slot[kw * 64 + lane] = acc;
+                acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                lds_barrier_mfma();
+                ++tiles_done;
+            }
+        };
+
+        // Positions only grow, so the walk ends when buffer 0 runs dry.  Every trip issues the
+        // same loads whether or not buffer 1 still had work: every path into the loop head then
+        // carries the same queue of outstanding loads and the compiler's counter waits stay exact.
+        while (valid(pos[0])) {
+            compute(pos[0], buf[0]);
+            pos[0] = load;
+            issue(load, buf[0]);
+            advance(load);
+            if (valid(pos[1]))
+                compute(pos[1], buf[1]);
+            pos[1] = load;
+            issue(load, buf[1]);
+            advance(load);
         }
     }
-walk_done:
 
     if (argmax && wave == 0) {
         // combine the four lane groups of each column (value desc, index asc), publish one partial
@@ -225,7 +253,7 @@ hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max
             return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a, m0);
     return hipGetLastError();
 }
 
@@ -253,7 +281,7 @@ hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, int* parts_used
             mp >>= 1;
         const size_t lds = lds_need(a.k, mp, NW);
         int per_cu = (int)((size_t)dev.lds_bytes / lds);
-        per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+        per_cu = per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu);          // 9 waves each: a third one would not fit the SIMDs evenly
         int blocks = n_tiles < dev.cus * per_cu ? n_tiles : dev.cus * per_cu;
         if (blocks > gemv_max_parts(dev))
             blocks = gemv_max_parts(dev);
