@@ -78,7 +78,7 @@ int mxfp4_dequant(const void* q_packed, const void* scales_e8m0, int64_t N, int6
  *   y[m, n] = bf16_rne( sum_k x[m, k] * w_hat[n, k] ),  FP32 accumulation, scale applied per
  *   32-block (late or early scaling are the same number because the scale is a power of two).
  *   x_bf16 in  BF16 [M, K], row stride ldx (ldx >= K, ldx % 8 == 0, base 16-byte aligned)
- *   q_packed, scales_e8m0  in, as written by mxfp4_direct_cast (q 16-byte aligned)
+ *   q_packed, scales_e8m0  in, as written by mxfp4_direct_cast (q 16-byte, scales 4-byte aligned)
  *   y_bf16 out BF16 [M, N], row stride ldy (ldy >= N)
  * M >= 1 (any size; M <= 32 is the designed range), N >= 1, K a positive multiple of 32 and at
  * most MXFP4_MAX_K; the packed weights of one call stay below 2 GiB.  The summation order is fixed per (M, N, K, path), not specified.

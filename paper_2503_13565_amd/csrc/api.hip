@@ -70,6 +70,8 @@ static int check_weights(const void* q, const void* s, int64_t N, int64_t K)
         return fail(MXFP4_ERR_SHAPE, "N*K/2=%lld bytes of packed weights exceed 2 GiB - 1", (long long)(N * (K / 2)));
     if (!aligned(q, 16))
         return fail(MXFP4_ERR_ALIGN, "q_packed must be 16-byte aligned");
+    if (!aligned(s, 4))
+        return fail(MXFP4_ERR_ALIGN, "scales_e8m0 must be 4-byte aligned");
     return MXFP4_OK;
 }
 

@@ -12,8 +12,8 @@
 // the 16 bytes of block 4T + g of row i: 32 weights that feed four MFMAs (dword j = the lane's
 // 8 k-slots of MFMA j) after 16 converts; the block's scale goes into the converts.  The
 // activation operand of MFMA j for lane (col = lane % 16, g) is x[col][32 (4T + g) + 8 j .. + 8],
-// one 128-bit LDS read; activations are staged once per workgroup as [chunk][MP] so that the 16
-// columns of a chunk are contiguous.  NW compute waves of a workgroup split K, each accumulates
+// one 128-bit LDS read; activations are staged once per workgroup as [T][j][g][MP] chunks of 8
+// elements, so that one wave read covers one contiguous run.  NW compute waves of a workgroup split K, each accumulates
 // a 16 x 16 FP32 tile over its K slice and leaves it in LDS; one more wave, which never loads
 // weights, sums the partial tiles in a fixed order, rounds and stores (or tracks the argmax), so
 // that the compute waves only ever have loads in flight and their load counter stays exact.
@@ -38,8 +38,8 @@ __device__ __forceinline__ void lds_barrier_mfma()
 }
 
 struct MItem {
-    u32x4_t q[kCh];
-    uint32_t s[kCh];
+    u32x4_t q[kCh];     // 32 nibbles per step
+    u32x4_t s;          // the 16 scale bytes of the row's 16 blocks of this item (4 steps x 4 groups)
 };
 
 struct MPos {
@@ -62,8 +62,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     const int nblk = a.k >> 5;
     const int q_row_bytes = a.k >> 1;
     const int t_total = a.k >> 7;                                 // steps of 4 blocks along K
-    const int steps_w = (t_total + NW - 1) / NW;                  // steps per wave and tile
-    const int items = (steps_w + kCh - 1) / kCh;
+    // steps per wave and tile, in whole items of kCh steps, so that an item's 16 scale bytes per
+    // row are one run that starts at a multiple of 16 blocks
+    const int items = ((t_total + kCh - 1) / kCh + NW - 1) / NW;
+    const int steps_w = items * kCh;
     const int n_tiles = (a.n + 15) >> 4;
     const bool argmax = a.part_val != nullptr;
     const int m_valid = min(MP, a.m - m0);
@@ -73,31 +75,34 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(a.s), 0, a.n * nblk, 0x00020000);
 
-    // Stage the activations: chunk c of row m goes to xs[c * MP + m]; rows past M repeat the last.
-    // Consecutive threads read consecutive chunks of one row (coalesced); eight independent loads
-    // per thread are in flight at a time (one latency per batch, not per load).
-    {
+    // Stage the activations (all waves; the compute waves do it after their first weight loads are
+    // out).  Chunk c = 16 T + 4 g + j of row m goes to xs[(16 T + 4 j + g) * MP + m]: the four lane
+    // groups of one MFMA then read four adjacent segments, 1 KiB contiguous per wave read at
+    // MP = 16, which is free of bank conflicts however the hardware groups the lanes.  Rows past M
+    // repeat the last.  Consecutive threads read consecutive chunks of a row; four independent
+    // loads per thread are in flight at a time.
+    auto stage_x = [&]() {
         const int chunks = a.k >> 3;
-        const int entries = chunks * MP;
-        constexpr int kBatch = 8;
+        constexpr int kBatch = 4;
         constexpr int kThreads = (NW + 1) * 64;
-        for (int e0 = tid; e0 < entries; e0 += kBatch * kThreads) {
-            u32x4_t v[kBatch];
+#pragma unroll 1
+        for (int m = 0; m < MP; ++m) {
+            const int msrc = min(m0 + m, a.m - 1);
+            const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx);
+            for (int c0 = tid; c0 < chunks; c0 += kBatch * kThreads) {
+                u32x4_t v[kBatch];
 #pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                const int e = min(e0 + b * kThreads, entries - 1);
-                const int m = e / chunks, c = e - m * chunks;
-                const int msrc = min(m0 + m, a.m - 1);
-                v[b] = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx)[c];
-            }
+                for (int b = 0; b < kBatch; ++b)
+                    v[b] = xp[min(c0 + b * kThreads, chunks - 1)];
 #pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                const int e = min(e0 + b * kThreads, entries - 1);   // clamped duplicates rewrite the same data
-                const int m = e / chunks, c = e - m * chunks;
-                xs[c * MP + m] = v[b];
+                for (int b = 0; b < kBatch; ++b) {
+                    const int c = min(c0 + b * kThreads, chunks - 1);   // clamped duplicates rewrite the same data
+                    const int slot = (c & ~15) | ((c & 3) << 2) | ((c >> 2) & 3);
+                    xs[slot * MP + m] = v[b];
+                }
             }
         }
-    }
+    };
 
     auto valid = [&](const MPos& p) { return p.tile < n_tiles; };
     auto advance = [&](MPos& p) {
@@ -113,20 +118,24 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         *ok = valid(p) && local < steps_w && t < t_total;
         return t;
     };
-    // Always kCh + kCh loads per item (absent steps read nothing and return zero), so that the
-    // in-order load counter can be waited on exactly.
+    // Always kCh + 1 loads per item (absent steps read nothing and return zero), so that the
+    // in-order load counter can be waited on exactly.  The weight loads carry no streaming hint:
+    // a wave load covers half a cache line per row and the next step wants the other half.  The
+    // scales of an item are one 16-byte load per row (the four lanes of a row load the same bytes):
+    // 16 cache lines touched per item instead of 64 with a byte load per step.
     auto issue = [&](const MPos& p, MItem& it) {
         const int tile = valid(p) ? p.tile : 0;
         const int row = min(tile * 16 + li, a.n - 1);             // ragged N: repeat the last row
         const int vq = row * q_row_bytes + lg * 16;
-        const int vs = row * nblk + lg;
 #pragma unroll
         for (int u = 0; u < kCh; ++u) {
             bool ok;
             const int t = step_of(p, u, &ok);
-            it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? t * 64 : 0, 2);
-            it.s[u] = __builtin_amdgcn_raw_buffer_load_b8(rs, ok ? vs : kSentinel, ok ? t * 4 : 0, 0);   // scale lines are shared by the waves: cached
+            it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? t * 64 : 0, 0);
         }
+        bool ok0;
+        const int t0 = step_of(p, 0, &ok0);
+        it.s = __builtin_amdgcn_raw_buffer_load_b128(rs, ok0 ? row * nblk : kSentinel, ok0 ? t0 * 4 : 0, 0);
     };
 
     const int col = li % MP;
@@ -135,6 +144,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
 
     if (wave == 0) {
         // Epilogue wave: one barrier per tile, like the compute waves; no weight loads of its own.
+        stage_x();
         lds_barrier_mfma();                                       // activations staged
         int tiles_done = 0;
         for (int tile = (int)blockIdx.x; tile < n_tiles; tile += gridDim.x, ++tiles_done) {
@@ -173,9 +183,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
             advance(load);
             __builtin_amdgcn_sched_barrier(0);                    // keep the buffers' loads in issue order
         }
+        stage_x();
         lds_barrier_mfma();                                       // activations staged
 
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: even and odd j
         int tiles_done = 0;
         auto compute = [&](const MPos& p, const MItem& it) {
 #pragma unroll
@@ -183,7 +194,15 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
                 bool ok;
                 const int t = step_of(p, u, &ok);
                 const int tc = ok ? t : 0;                        // absent steps: zero weights, any finite x
-                const float sc = __uint_as_float(it.s[u] << 23);  // the convert reads the exponent field as E8M0
+                u32x4_t xb[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    xb[j] = xs[(16 * tc + 4 * j + lg) * MP + col];
+                // byte lg of dword u is this lane's block scale; the convert reads the exponent field
+                // as E8M0.  A step past the end of K gets scale 2^-127 (its weights are zero, and
+                // bytes read past the row's scales could say NaN).
+                const uint32_t sbyte = ok ? ((it.s[u] >> (8 * lg)) & 0xFFu) : 0u;
+                const float sc = __uint_as_float(sbyte << 23);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t qd = it.q[u][j];
@@ -192,16 +211,20 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
                     w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1));
                     w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2));
                     w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3));
-                    const u32x4_t xb = xs[(16 * tc + 4 * lg + j) * MP + col];
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
-                                                                  __builtin_bit_cast(bf16x8_t, xb), acc, 0, 0, 0);
+                    if (j & 1)
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
+                                                                       __builtin_bit_cast(bf16x8_t, xb[j]), acc1, 0, 0, 0);
+                    else
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
+                                                                       __builtin_bit_cast(bf16x8_t, xb[j]), acc0, 0, 0, 0);
                 }
             }
             if (p.c == items - 1) {
                 // end of the tile: leave the partial tile for the epilogue wave
                 f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
-                slot[kw * 64 + lane] = acc;
-                acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                slot[kw * 64 + lane] = acc0 + acc1;
+                acc0 = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                acc1 = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 lds_barrier_mfma();
                 ++tiles_done;
             }
