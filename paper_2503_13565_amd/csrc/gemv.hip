@@ -121,7 +121,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmArgs a, int m0)
         if constexpr (kScaleDword) {
             const int row = min(g * R + srow, a.n - 1);
             const int voff_s = live ? row * nblk + (lane & 15) * 4 : 0x7FFFFFF0;
-            it.s[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff_s, p.t * 64, 2);
+            it.s[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff_s, p.t * 64, 0);   // a row's scale line serves all its steps: cached
         }
     };
 
@@ -370,44 +370,49 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmArgs a, int m0)
     }
 }
 
-__global__ __launch_bounds__(256) void argmax_finish_kernel(const float* __restrict__ part_val,
-                                                            const int32_t* __restrict__ part_idx,
-                                                            int parts, int parts_used,
-                                                            int32_t* __restrict__ argmax_out,
-                                                            float* __restrict__ max_out)
+// Second stage of the fused argmax: one wave per activation row reduces the partial winners in
+// (value descending, index ascending) order.  No LDS and no barrier: the kernel is all latency.
+__global__ __launch_bounds__(64) void argmax_finish_kernel(const float* __restrict__ part_val,
+                                                           const int32_t* __restrict__ part_idx,
+                                                           int parts, int parts_used,
+                                                           int32_t* __restrict__ argmax_out,
+                                                           float* __restrict__ max_out)
 {
-    __shared__ float sv[256];
-    __shared__ int si[256];
-    const int m = blockIdx.x, tid = threadIdx.x;
+    const int m = blockIdx.x, lane = threadIdx.x;
+    const float* pv = part_val + (int64_t)m * parts;
+    const int32_t* pi = part_idx + (int64_t)m * parts;
     float bv = -INFINITY;
     int bi = 0x7FFFFFFF;
-    for (int p = tid; p < parts_used; p += 256) {
-        const float v = part_val[(int64_t)m * parts + p];
-        const int i = part_idx[(int64_t)m * parts + p];
+    for (int p0 = lane; p0 < parts_used; p0 += 64 * 8) {
+        float v[8];
+        int i[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {                   // eight independent loads in flight
+            const int p = p0 + 64 * u;
+            v[u] = p < parts_used ? pv[p] : -INFINITY;
+            i[u] = p < parts_used ? pi[p] : 0x7FFFFFFF;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (v[u] > bv || (v[u] == bv && i[u] < bi)) {
+                bv = v[u];
+                bi = i[u];
+            }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float v = __shfl_xor(bv, off);
+        const int i = __shfl_xor(bi, off);
         if (v > bv || (v == bv && i < bi)) {
             bv = v;
             bi = i;
         }
     }
-    sv[tid] = bv;
-    si[tid] = bi;
-    __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-        if (tid < off) {
-            const float v = sv[tid + off];
-            const int i = si[tid + off];
-            if (v > sv[tid] || (v == sv[tid] && i < si[tid])) {
-                sv[tid] = v;
-                si[tid] = i;
-            }
-        }
-        __syncthreads();
-    }
-    if (tid == 0) {
+    if (lane == 0) {
         // every accumulator -inf or NaN: report index 0 rather than the sentinel
-        argmax_out[m] = si[0] == 0x7FFFFFFF ? 0 : si[0];
+        argmax_out[m] = bi == 0x7FFFFFFF ? 0 : bi;
         if (max_out)
-            max_out[m] = sv[0];
+            max_out[m] = bv;
     }
 }
 
@@ -554,7 +559,7 @@ hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceI
 hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
                                 int m, int32_t* argmax_out, float* max_out, hipStream_t stream)
 {
-    hipLaunchKernelGGL(argmax_finish_kernel, dim3(m), dim3(256), 0, stream, part_val, part_idx, parts,
+    hipLaunchKernelGGL(argmax_finish_kernel, dim3(m), dim3(64), 0, stream, part_val, part_idx, parts,
                        parts_used, argmax_out, max_out);
     return hipGetLastError();
 }
