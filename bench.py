@@ -159,6 +159,85 @@ def cpu_baseline(m: int):
     }
 
 
+def run_stack(args) -> int:
+    """Optional workloads: the whole linear-only decode step of a model-shaped weight stack that
+    is resident in HBM (the fourth and fifth benchmark configurations).  One step = 4 linears per
+    layer + the LM head with argmax, every layer with its own weights (cold by construction)."""
+    import torch
+    from paper_2503_13565_amd import binding, synth
+    shape = synth.LLAMA_7B if args.workload == "stack7b" else synth.LLAMA_70B
+    layers = args.layers or shape.layers
+    m = args.m
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    binding.load()
+    ops = []
+    cast_ms = cast_bytes = 0.0
+    for layer in range(layers + 1):
+        for li, (name, n, k) in enumerate(shape.linears()):
+            if (layer < layers) == (name == "lm_head"):
+                continue                                 # layers hold 4 linears; the head comes last
+            seed = synth.tensor_seed(0, layer, li)
+            w = synth.weights_student_t(n, k, seed=seed, device=dev)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            q, s = binding.mxfp4_direct_cast(w)
+            e1.record()
+            torch.cuda.synchronize()
+            if layer > 0:
+                cast_ms += e0.elapsed_time(e1)
+                cast_bytes += n * k * 2.53125
+            del w
+            ops.append(dict(name=name, n=n, k=k, q=q, s=s,
+                            x=synth.activations_outlier_channels(m, k, seed=seed + 8, device=dev),
+                            y=torch.empty((m, n), dtype=torch.bfloat16, device=dev)))
+    head = ops[-1]
+    head["idx"] = torch.empty((m,), dtype=torch.int32, device=dev)
+    head["val"] = torch.empty((m,), dtype=torch.float32, device=dev)
+    ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(m, head["n"], head["k"]),),
+                     dtype=torch.uint8, device=dev)
+
+    def step(_lin=None, _ws=None):
+        for t in ops[:-1]:
+            binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+        binding.mxfp4_woq_gemm_argmax(head["x"], head["q"], head["s"], workspace=ws, out=(head["idx"], head["val"]))
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step()
+    torch.cuda.synchronize()
+    graph = None if args.no_graph else capture(step, [None], ws, stream)
+    run = runner(graph, step, [None], ws)
+    steps = max(1, args.steps // 24)
+    timed(run, max(1, args.warmup // 12), stream)
+    ms_per_step = timed(run, steps, stream) / steps
+    plain_ms = timed(runner(None, step, [None], ws), max(1, steps // 2), stream) / max(1, steps // 2)
+    step_bytes = sum(algorithmic_bytes(m, t["n"], t["k"]) for t in ops)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
+        "warmup": max(1, args.warmup // 12), "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d layers x (qkv, o, gate_up, down) + lm_head with argmax, M=%d, "
+                               "%.2f GB of MXFP4 resident, %d launches per step"
+                               % (shape.name, layers, m, sum(t["q"].numel() + t["s"].numel() for t in ops) / 1e9,
+                                  len(ops) + 1),
+                   "M": m, "launch": "hip graph replay" if graph is not None else "stream launches"},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "us_per_step": round(ms_per_step * 1e3, 2), "us_per_step_plain_launches": round(plain_ms * 1e3, 2),
+        "bytes_per_step": step_bytes,
+        "tflops": round(2.0 * m * sum(t["n"] * t["k"] for t in ops) / (ms_per_step * 1e-3) / 1e12, 3),
+        "direct_cast_GBps": round(cast_bytes / (cast_ms * 1e-3) / 1e9, 1) if cast_ms > 0 else None,
+        "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(value / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "whole step (all launches, gaps included)"},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +247,10 @@ def main() -> int:
     ap.add_argument("--m", type=int, default=1, help="activation rows (1 = decode)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of graph replays")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--workload", default="decode7b", choices=["decode7b", "stack7b", "stack70b"],
+                    help="decode7b (default): the five 7B decode linears over rotating weight sets; "
+                         "stack7b / stack70b: the whole linear-only decode step of a resident weight stack")
+    ap.add_argument("--layers", type=int, default=0, help="stack workloads: layers to build (0 = the model's)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: this build has no multi-GPU path (the linears shard by "
@@ -180,6 +263,8 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     binding.load()
+    if args.workload != "decode7b":
+        return run_stack(args)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     m = args.m
