@@ -95,6 +95,21 @@ int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx,
                         void* y_bf16, int64_t ldy, int path, void* stream);
 
 /*
+ * The same product with a caller-provided scratch buffer.  When the activation rows of a pass do
+ * not fit the LDS of a compute unit whole (M * K large), the MFMA path cuts K into phases that
+ * run side by side and adds their FP32 partial products in a fixed order in a second kernel;
+ * the partial products live in `workspace`.  Without it (NULL, or smaller than
+ * mxfp4_woq_gemm_workspace_bytes) the call still works and passes over the weights several
+ * times instead.  workspace: 8-byte aligned, contents unspecified before and after; calls that
+ * overlap in time must not share it.  `path` as in mxfp4_woq_gemm_path.
+ */
+size_t mxfp4_woq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int mxfp4_woq_gemm_ws(const void* x_bf16, int64_t M, int64_t ldx,
+                      const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                      void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                      int path, void* stream);
+
+/*
  * The same product with the greedy pick fused (section 3.1: the target's token at each
  * verified position is compared with the draft's; section 4.1: greedy search): for every
  * activation row m, the index n of the largest FP32 accumulator (before any BF16 rounding),

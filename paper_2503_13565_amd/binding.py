@@ -19,7 +19,7 @@ PATH_AUTO, PATH_VALU_BITS, PATH_VALU_CVT, PATH_VALU_LUT, PATH_MFMA = 0, 1, 2, 3,
 
 EXPORTS = [
     "mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm", "mxfp4_woq_gemm_path",
-    "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
+    "mxfp4_woq_gemm_workspace_bytes", "mxfp4_woq_gemm_ws", "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
 ]
 
@@ -48,6 +48,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_dequant_hwcvt.argtypes = [vp, vp, i64, i64, vp, i64, vp]
     lib.mxfp4_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
     lib.mxfp4_woq_gemm_path.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, i32, vp]
+    lib.mxfp4_woq_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.mxfp4_woq_gemm_workspace_bytes.restype = sz
+    lib.mxfp4_woq_gemm_ws.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp, sz, i32, vp]
+    lib.mxfp4_woq_gemm_ws.restype = i32
     lib.mxfp4_woq_gemm_argmax_workspace_bytes.argtypes = [i64, i64, i64]
     lib.mxfp4_woq_gemm_argmax_workspace_bytes.restype = sz
     lib.mxfp4_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
@@ -128,15 +132,26 @@ def _gemm_shapes(x, q, s):
 
 
 def mxfp4_woq_gemm(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, y: Optional[torch.Tensor] = None,
-                   path: int = PATH_AUTO) -> torch.Tensor:
-    """y ``[M,N]`` BF16 = x ``[M,K]`` BF16 times dequant(q, s)^T."""
+                   path: int = PATH_AUTO, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """y ``[M,N]`` BF16 = x ``[M,K]`` BF16 times dequant(q, s)^T.  With ``workspace`` (uint8, at least
+    ``mxfp4_woq_gemm_workspace_bytes``) the call goes through ``mxfp4_woq_gemm_ws``."""
     m, n, k, ldx = _gemm_shapes(x, q, s)
     if y is None:
         y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
+    ldy = y.stride(0) if m > 1 else n
     with torch.cuda.device(x.device):
-        _check(load().mxfp4_woq_gemm_path(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(y),
-                                         y.stride(0) if m > 1 else n, path, _stream()))
+        if workspace is None:
+            _check(load().mxfp4_woq_gemm_path(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(y), ldy, path,
+                                             _stream()))
+        else:
+            _check(load().mxfp4_woq_gemm_ws(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(y), ldy,
+                                           _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                           path, _stream()))
     return y
+
+
+def mxfp4_woq_gemm_workspace_bytes(m: int, n: int, k: int) -> int:
+    return int(load().mxfp4_woq_gemm_workspace_bytes(m, n, k))
 
 
 def mxfp4_woq_gemm_argmax_workspace_bytes(m: int, n: int, k: int) -> int:

@@ -128,6 +128,14 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
     a.m = (int)M;
     a.n = (int)N;
     a.k = (int)K;
+    // workspace layout: [argmax partial values][argmax partial indices][split-K partial products]
+    const size_t argmax_bytes = argmax ? (size_t)M * gemv_max_parts(dev) * 8 : 0;
+    float* splitk_ws = nullptr;
+    if (workspace && aligned(workspace, 8)) {
+        const size_t sk = mfma_splitk_bytes((int)M, (int)N, (int)K, dev);
+        if (sk > 0 && workspace_bytes >= argmax_bytes + sk)
+            splitk_ws = reinterpret_cast<float*>(static_cast<char*>(workspace) + argmax_bytes);
+    }
     if (argmax) {
         if (!argmax_out)
             return fail(MXFP4_ERR_NULL, "argmax_out is NULL");
@@ -148,7 +156,7 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         a.y = static_cast<uint16_t*>(y);
         a.ldy = ldy;
     }
-    const int chosen = pick_path(path, M, mfma_can_run(a, dev));
+    const int chosen = pick_path(path, M, mfma_can_run(a, dev, splitk_ws != nullptr));
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
     hipError_t e;
@@ -162,10 +170,10 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         e = launch_gemv(a, chosen, argmax, dev, &parts_used, st);
         break;
     case MXFP4_PATH_MFMA:
-        if (!mfma_can_run(a, dev))
-            return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and K <= %d here",
+        if (!mfma_can_run(a, dev, splitk_ws != nullptr))
+            return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and, without a workspace, K <= %d here",
                         (dev.lds_bytes - 16384) / 8);
-        e = launch_mfma(a, dev, &parts_used, st);
+        e = launch_mfma(a, dev, splitk_ws, &parts_used, st);
         break;
     default:
         return fail(MXFP4_ERR_ARG, "unknown or unavailable path %d", chosen);
@@ -292,6 +300,18 @@ int mxfp4_woq_gemm(const void* x_bf16, int64_t M, int64_t ldx, const void* q_pac
                     false, MXFP4_PATH_AUTO, stream);
 }
 
+int mxfp4_woq_gemm_ws(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                      const void* scales_e8m0, int64_t N, int64_t K, void* y_bf16, int64_t ldy,
+                      void* workspace, size_t workspace_bytes, int path, void* stream)
+{
+    if (workspace && !aligned(workspace, 8)) {
+        g_err[0] = 0;
+        return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
+    }
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, workspace,
+                    workspace_bytes, false, path, stream);
+}
+
 int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
                         const void* scales_e8m0, int64_t N, int64_t K, void* y_bf16, int64_t ldy, int path,
                         void* stream)
@@ -300,15 +320,34 @@ int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx, const void* 
                     false, path, stream);
 }
 
+// Device facts for the size queries, which must also answer without a GPU: the target part.
+static DeviceInfo size_query_device()
+{
+    DeviceInfo dev;
+    if (device_info(&dev) != MXFP4_OK) {
+        dev.cus = 256;
+        dev.lds_bytes = 160 * 1024;
+        g_err[0] = 0;
+    }
+    return dev;
+}
+
+size_t mxfp4_woq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M < 1 || N < 1 || K < 32 || K > MXFP4_MAX_K || M > (1 << 20) || N > 0x7FFFFFFF / 8)
+        return 0;
+    return mfma_splitk_bytes((int)M, (int)N, (int)K, size_query_device());
+}
+
 size_t mxfp4_woq_gemm_argmax_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    (void)N;
-    (void)K;
     if (M < 1)
         return 0;
-    // one (value, index) pair per activation row and per workgroup of the product kernel; the
-    // bound on workgroups is taken for the largest device this library targets (256 CUs)
-    return (size_t)M * 256 * 8 * (sizeof(float) + sizeof(int32_t));
+    // one (value, index) pair per activation row and per workgroup of the product kernel (the
+    // bound on workgroups is 8 per compute unit), then the split-K partial products
+    const DeviceInfo dev = size_query_device();
+    return (size_t)M * gemv_max_parts(dev) * (sizeof(float) + sizeof(int32_t)) +
+           mxfp4_woq_gemm_workspace_bytes(M, N, K);
 }
 
 int mxfp4_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,

@@ -22,6 +22,11 @@ struct GemmArgs {
     float* part_val;
     int32_t* part_idx;
     int parts;           // capacity per row of the two arrays above
+    // split-K form of the MFMA path: FP32 partial products [phases, M, N]; the K range is cut
+    // into `phases` runs of `phase_steps` steps of 128 elements, one per workgroup row (grid y)
+    float* splitk_ws;
+    int phases;
+    int phase_steps;
 };
 
 struct DeviceInfo {
@@ -43,8 +48,14 @@ int gemv_max_parts(const DeviceInfo& dev);
 
 // 16-row MFMA tiles (bf16 16x16x32) for verification batches; passes of up to 16 activation rows.
 // mfma_can_run: K % 128 == 0 and the LDS copy of 4 activation rows fits.
-bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev);
-hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev, bool have_splitk_ws);
+// With a workspace of mfma_splitk_bytes() the activations need not fit the LDS whole: K is cut
+// into phases handled by different workgroups and a second kernel adds the partial products in a
+// fixed order.  `splitk_ws` may be NULL: then every pass holds all of K (narrower passes, more of
+// them, when the activations are too large).
+size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev);
+hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
+                       hipStream_t stream);
 
 // Second stage of the fused argmax: reduce `parts_used` partial winners per row.
 hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,

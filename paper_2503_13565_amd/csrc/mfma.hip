@@ -19,6 +19,8 @@
 // that the compute waves only ever have loads in flight and their load counter stays exact.
 // Workgroups are persistent over tiles; loads run one item (4 steps) ahead in a second register
 // buffer.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 #include "../../include/mxfp4.h"
@@ -53,15 +55,18 @@ template <int MP, int NW>
 __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                          // [K/8][MP] chunks of 8 elements
-    f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + (size_t)a.k * 2 * MP);  // [2][NW][64] partial tiles
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                          // [steps][4][4][MP] chunks of 8 elements
+    f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + (size_t)a.phase_steps * 256 * MP);  // [2][NW][64] partial tiles
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kw = wave - 1;                                      // K slice of a compute wave
     const int li = lane & 15, lg = lane >> 4;
     const int nblk = a.k >> 5;
     const int q_row_bytes = a.k >> 1;
-    const int t_total = a.k >> 7;                                 // steps of 4 blocks along K
+    // this workgroup's K range in steps of 4 blocks: all of K, or one phase of the split-K form
+    const int t_begin = (int)blockIdx.y * a.phase_steps;
+    const int t_end = min(a.k >> 7, t_begin + a.phase_steps);
+    const int t_total = t_end - t_begin;
     // steps per wave and tile, in whole items of kCh steps, so that an item's 16 scale bytes per
     // row are one run that starts at a multiple of 16 blocks
     const int items = ((t_total + kCh - 1) / kCh + NW - 1) / NW;
@@ -82,13 +87,13 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     // repeat the last.  Consecutive threads read consecutive chunks of a row; four independent
     // loads per thread are in flight at a time.
     auto stage_x = [&]() {
-        const int chunks = a.k >> 3;
+        const int chunks = t_total * 16;                          // of this K range
         constexpr int kBatch = 4;
         constexpr int kThreads = (NW + 1) * 64;
 #pragma unroll 1
         for (int m = 0; m < MP; ++m) {
             const int msrc = min(m0 + m, a.m - 1);
-            const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx);
+            const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx) + t_begin * 16;
             for (int c0 = tid; c0 < chunks; c0 += kBatch * kThreads) {
                 u32x4_t v[kBatch];
 #pragma unroll
@@ -114,7 +119,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     // Step T of this wave for slot u of item c, and whether it exists (wave-uniform).
     auto step_of = [&](const MPos& p, int u, bool* ok) {
         const int local = p.c * kCh + u;
-        const int t = kw * steps_w + local;
+        const int t = kw * steps_w + local;                       // relative to t_begin
         *ok = valid(p) && local < steps_w && t < t_total;
         return t;
     };
@@ -131,11 +136,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         for (int u = 0; u < kCh; ++u) {
             bool ok;
             const int t = step_of(p, u, &ok);
-            it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? t * 64 : 0, 0);
+            it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? (t_begin + t) * 64 : 0, 0);
         }
         bool ok0;
         const int t0 = step_of(p, 0, &ok0);
-        it.s = __builtin_amdgcn_raw_buffer_load_b128(rs, ok0 ? row * nblk : kSentinel, ok0 ? t0 * 4 : 0, 0);
+        it.s = __builtin_amdgcn_raw_buffer_load_b128(rs, ok0 ? row * nblk : kSentinel, ok0 ? (t_begin + t0) * 4 : 0, 0);
     };
 
     const int col = li % MP;
@@ -160,7 +165,9 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
                 for (int r = 0; r < 4; ++r) {
                     const int row = tile * 16 + 4 * lg + r;
                     if (row < a.n) {
-                        if (argmax) {
+                        if (a.splitk_ws) {
+                            a.splitk_ws[((int64_t)blockIdx.y * a.m + (m0 + li)) * a.n + row] = sum[r];
+                        } else if (argmax) {
                             if (sum[r] > best_val) {              // rows ascend: lowest index wins ties
                                 best_val = sum[r];
                                 best_idx = row;
@@ -246,7 +253,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         }
     }
 
-    if (argmax && wave == 0) {
+    if (argmax && !a.splitk_ws && wave == 0) {
         // combine the four lane groups of each column (value desc, index asc), publish one partial
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
@@ -264,8 +271,62 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     }
 }
 
+// Second kernel of the split-K form: add the phases' partial products in phase order, then round
+// and store, or find each workgroup's (max, index) for the argmax's last stage.
+__global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a)
+{
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int tid = threadIdx.x;
+    const bool argmax = a.part_val != nullptr;
+    for (int m = blockIdx.y; m < a.m; m += gridDim.y) {
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int n = (int)blockIdx.x * 256 + tid; n < a.n; n += gridDim.x * 256) {
+        float sum = 0.f;
+        for (int p = 0; p < a.phases; ++p)
+            sum += a.splitk_ws[((int64_t)p * a.m + m) * a.n + n];
+        if (argmax) {
+            if (sum > bv) {                                       // n ascends per thread
+                bv = sum;
+                bi = n;
+            }
+        } else {
+            a.y[(int64_t)m * a.ldy + n] = f32_to_bf16_rne(sum);
+        }
+    }
+    if (argmax) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float v = __shfl_xor(bv, off);
+            const int i = __shfl_xor(bi, off);
+            if (v > bv || (v == bv && i < bi)) {
+                bv = v;
+                bi = i;
+            }
+        }
+        if ((tid & 63) == 0) {
+            sv[tid >> 6] = bv;
+            si[tid >> 6] = bi;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < 4; ++w)
+                if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) {
+                    bv = sv[w];
+                    bi = si[w];
+                }
+            a.part_val[(int64_t)m * a.parts + blockIdx.x] = bv;
+            a.part_idx[(int64_t)m * a.parts + blockIdx.x] = bi;
+        }
+        __syncthreads();                                          // sv, si are reused by the next row
+    }
+    }
+}
+
 template <int MP, int NW>
-hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
+hipError_t launch_one(const GemmArgs& a, int m0, int blocks, int phases, size_t lds, int max_lds,
+                      hipStream_t stream)
 {
     auto kern = mfma_kernel<MP, NW>;
     static bool attr_set = false;
@@ -276,55 +337,137 @@ hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max
             return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a, m0);
+    hipLaunchKernelGGL(kern, dim3(blocks, phases), dim3((NW + 1) * 64), lds, stream, a, m0);
     return hipGetLastError();
 }
 
-size_t lds_need(int k, int mp, int nw) { return (size_t)k * 2 * mp + (size_t)2 * nw * 64 * 16; }
+constexpr int kNW = 8;
+
+size_t lds_need(int steps, int mp) { return (size_t)steps * 256 * mp + (size_t)2 * kNW * 64 * 16; }
+
+// LDS a workgroup should stay under when K may be split: two workgroups per CU.
+size_t lds_target(const DeviceInfo& dev)
+{
+    static const int env = [] {
+        const char* e = getenv("MXFP4_MFMA_LDS_TARGET");
+        return e ? atoi(e) : 0;
+    }();
+    return env > 0 ? (size_t)env : (size_t)dev.lds_bytes / 2;
+}
+
+// Steps per phase (a multiple of kCh) and number of phases for a pass of `mp` activation rows.
+void plan_phases(int k, int mp, const DeviceInfo& dev, bool may_split, int* phase_steps, int* phases)
+{
+    const int t_total = k / 128;
+    int steps = (t_total + kCh - 1) / kCh * kCh;
+    if (may_split) {
+        // two workgroups per CU if a phase still gives every compute wave an item, else one
+        const size_t red_bytes = (size_t)2 * kNW * 64 * 16;
+        int fit = (int)((lds_target(dev) - red_bytes) / ((size_t)256 * mp)) / kCh * kCh;
+        if (fit < kNW * kCh)
+            fit = (int)(((size_t)dev.lds_bytes - red_bytes) / ((size_t)256 * mp)) / kCh * kCh;
+        if (fit < kCh)
+            fit = kCh;
+        if (fit < steps) {
+            const int p = (t_total + fit - 1) / fit;
+            steps = ((t_total + p - 1) / p + kCh - 1) / kCh * kCh;     // even phases
+        }
+    }
+    *phase_steps = steps;
+    *phases = (t_total + steps - 1) / steps;
+}
+
+int pass_width(int left) { return left > 8 ? 16 : (left > 4 ? 8 : 4); }
 
 }  // namespace
 
-bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev)
+bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev, bool have_splitk_ws)
 {
-    return a.k % 128 == 0 && lds_need(a.k, 4, 8) <= (size_t)dev.lds_bytes;
+    if (a.k % 128 != 0)
+        return false;
+    // with room for split-K partial products any K goes; without, four rows of all of K must fit
+    return have_splitk_ws || lds_need((a.k / 128 + kCh - 1) / kCh * kCh, 4) <= (size_t)dev.lds_bytes;
 }
 
-hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev)
 {
-    if (!mfma_can_run(a, dev))
+    if (k % 128 != 0)
+        return 0;
+    int max_phases = 1;
+    for (int m0 = 0; m0 < m;) {
+        const int mp = pass_width(m - m0);
+        int steps, phases;
+        plan_phases(k, mp, dev, true, &steps, &phases);
+        max_phases = phases > max_phases ? phases : max_phases;
+        m0 += mp;
+    }
+    return max_phases > 1 ? (size_t)max_phases * m * n * sizeof(float) : 0;
+}
+
+hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
+                       hipStream_t stream)
+{
+    if (!mfma_can_run(a_in, dev, splitk_ws != nullptr))
         return hipErrorInvalidValue;
-    constexpr int NW = 8;
+    GemmArgs a = a_in;
     const int n_tiles = (a.n + 15) / 16;
+    // one plan for the whole call: the widest pass decides the phases (narrower passes fit too)
+    bool split = false;
+    int split_steps = 0, split_phases = 1;
+    if (splitk_ws) {
+        plan_phases(a.k, pass_width(a.m), dev, true, &split_steps, &split_phases);
+        split = split_phases > 1;
+    }
     int first_blocks = 0;
+    int max_phases = 1;
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
-        // the widest pass whose activation copy fits the LDS, but no wider than needed
-        int mp = left > 8 ? 16 : (left > 4 ? 8 : 4);
-        while (mp > 4 && lds_need(a.k, mp, NW) > (size_t)dev.lds_bytes)
-            mp >>= 1;
-        const size_t lds = lds_need(a.k, mp, NW);
+        int mp = pass_width(left);
+        int steps = split_steps, phases = split_phases;
+        if (!split) {
+            plan_phases(a.k, mp, dev, false, &steps, &phases);
+            // all of K in one pass: the widest pass whose activation copy fits the LDS
+            while (mp > 4 && lds_need(steps, mp) > (size_t)dev.lds_bytes)
+                mp >>= 1;
+        }
+        const size_t lds = lds_need(steps, mp);
         int per_cu = (int)((size_t)dev.lds_bytes / lds);
-        per_cu = per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu);          // 9 waves each: a third one would not fit the SIMDs evenly
-        int blocks = n_tiles < dev.cus * per_cu ? n_tiles : dev.cus * per_cu;
+        per_cu = per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu);      // 9 waves each: a third would not fit the SIMDs evenly
+        int blocks = dev.cus * per_cu / phases;
+        blocks = blocks < 1 ? 1 : (blocks > n_tiles ? n_tiles : blocks);
         if (blocks > gemv_max_parts(dev))
             blocks = gemv_max_parts(dev);
         if (m0 == 0)
             first_blocks = blocks;
         // the argmax partial arrays are indexed by workgroup: keep the grid the same for all passes
-        if (a.part_val != nullptr)
+        if (a.part_val != nullptr && !split)
             blocks = first_blocks < blocks ? first_blocks : blocks;
+        a.splitk_ws = split ? splitk_ws : nullptr;
+        a.phases = phases;
+        a.phase_steps = steps;
+        max_phases = phases > max_phases ? phases : max_phases;
         hipError_t e;
         if (mp == 16)
-            e = launch_one<16, NW>(a, m0, blocks, lds, dev.lds_bytes, stream);
+            e = launch_one<16, kNW>(a, m0, blocks, phases, lds, dev.lds_bytes, stream);
         else if (mp == 8)
-            e = launch_one<8, NW>(a, m0, blocks, lds, dev.lds_bytes, stream);
+            e = launch_one<8, kNW>(a, m0, blocks, phases, lds, dev.lds_bytes, stream);
         else
-            e = launch_one<4, NW>(a, m0, blocks, lds, dev.lds_bytes, stream);
+            e = launch_one<4, kNW>(a, m0, blocks, phases, lds, dev.lds_bytes, stream);
         if (e != hipSuccess)
             return e;
-        if (a.part_val != nullptr && blocks != first_blocks)
-            return hipErrorInvalidValue;                           // cannot happen: LDS need only shrinks
         m0 += mp;
+    }
+    if (split) {
+        // every pass used the widest pass's plan, so every row has all phases written
+        a.phases = max_phases;
+        int fblocks = (a.n + 255) / 256;
+        if (fblocks > gemv_max_parts(dev))
+            fblocks = gemv_max_parts(dev);
+        hipLaunchKernelGGL(splitk_finish_kernel, dim3(fblocks, a.m < 1024 ? a.m : 1024), dim3(256), 0, stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+        first_blocks = fblocks;
     }
     if (parts_used)
         *parts_used = first_blocks;
