@@ -171,8 +171,8 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         break;
     case MXFP4_PATH_MFMA:
         if (!mfma_can_run(a, dev, splitk_ws != nullptr))
-            return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and, without a workspace, K <= %d here",
-                        (dev.lds_bytes - 16384) / 8);
+            return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and, without a workspace, four rows of "
+                                       "K=%lld elements exceed the LDS", (long long)K);
         e = launch_mfma(a, dev, splitk_ws, &parts_used, st);
         break;
     default:

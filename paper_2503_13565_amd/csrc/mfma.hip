@@ -12,13 +12,14 @@
 // the 16 bytes of block 4T + g of row i: 32 weights that feed four MFMAs (dword j = the lane's
 // 8 k-slots of MFMA j) after 16 converts; the block's scale goes into the converts.  The
 // activation operand of MFMA j for lane (col = lane % 16, g) is x[col][32 (4T + g) + 8 j .. + 8],
-// one 128-bit LDS read; activations are staged once per workgroup as [T][j][g][MP] chunks of 8
-// elements, so that one wave read covers one contiguous run.  NW compute waves of a workgroup split K, each accumulates
-// a 16 x 16 FP32 tile over its K slice and leaves it in LDS; one more wave, which never loads
-// weights, sums the partial tiles in a fixed order, rounds and stores (or tracks the argmax), so
-// that the compute waves only ever have loads in flight and their load counter stays exact.
-// Workgroups are persistent over tiles; loads run one item (4 steps) ahead in a second register
-// buffer.
+// one 128-bit LDS read.  NW compute waves of a workgroup split K; each copies the activations of
+// its own K slice into LDS once, as [T][j][g][MP] chunks of 8 elements so that one wave read
+// covers one contiguous run, accumulates a 16 x 16 FP32 tile over its slice and leaves it in LDS;
+// one more wave, which never loads, sums the partial tiles in a fixed order, rounds and stores
+// (or tracks the argmax), so that the compute waves only ever have loads in flight and their load
+// counter stays exact.  Workgroups are persistent over tiles; loads run one item (4 steps) ahead
+// in a second register buffer.  When M * K outgrows the LDS, K is also cut into phases across
+// workgroups (grid dimension y) whose FP32 partial products meet in a workspace.
 #include <stdlib.h>
 
 #include "common.h"
@@ -30,6 +31,22 @@ namespace mxfp4 {
 namespace {
 
 constexpr int kCh = 4;             // steps (16-byte loads per lane) per pipeline item
+
+// Bytes of the activation copy of a workgroup whose K range is `steps` steps: every one of the NW
+// compute waves owns a slice of whole items.
+template <int NW>
+__host__ __device__ constexpr size_t x_lds_bytes(int steps, int mp)
+{
+    return (size_t)(((steps + kCh - 1) / kCh + NW - 1) / NW) * NW * kCh * 256 * mp;
+}
+
+// Dwords per row of a tile's scale block in LDS: one per step, rounded so that the 16 bytes of an
+// item are aligned and, beyond the last wave's slice, readable; plus a skew against bank conflicts.
+template <int NW>
+__host__ __device__ constexpr int scale_row_dwords_t(int steps)
+{
+    return ((steps + kCh - 1) / kCh + NW - 1) / NW * NW * kCh + 4;
+}
 constexpr int kSentinel = 0x7FFFFFF0;   // lane offset beyond any descriptor: the load returns zero
 
 __device__ __forceinline__ void lds_barrier_mfma()
@@ -41,7 +58,7 @@ __device__ __forceinline__ void lds_barrier_mfma()
 
 struct MItem {
     u32x4_t q[kCh];     // 32 nibbles per step
-    u32x4_t s;          // the 16 scale bytes of the row's 16 blocks of this item (4 steps x 4 groups)
+    uint32_t sp;        // this lane's dword of the scale block of the workgroup's NEXT tile
 };
 
 struct MPos {
@@ -55,8 +72,10 @@ template <int MP, int NW>
 __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                          // [steps][4][4][MP] chunks of 8 elements
-    f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + (size_t)a.phase_steps * 256 * MP);  // [2][NW][64] partial tiles
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                          // [NW][steps_w][4][4][MP] chunks of 8 elements
+    f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + x_lds_bytes<NW>(a.phase_steps, MP));   // [2][NW][64] partial tiles
+    const int scw = scale_row_dwords_t<NW>(a.phase_steps);
+    uint32_t* sc = reinterpret_cast<uint32_t*>(red + 2 * NW * 64);           // [2][16][scw] scale blocks
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kw = wave - 1;                                      // K slice of a compute wave
@@ -80,32 +99,41 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(a.s), 0, a.n * nblk, 0x00020000);
 
-    // Stage the activations (all waves; the compute waves do it after their first weight loads are
-    // out).  Chunk c = 16 T + 4 g + j of row m goes to xs[(16 T + 4 j + g) * MP + m]: the four lane
+    // Activations.  A compute wave only ever multiplies with the K slice it owns, so it copies
+    // just that slice into its own region of the LDS: no wave waits for another's copy and no
+    // barrier is needed.  Per item (64 chunks of 8 elements, one per lane) the MP rows' loads are
+    // all in flight together.  Chunk 4 g + j of step u goes to slot 16 u + 4 j + g: the four lane
     // groups of one MFMA then read four adjacent segments, 1 KiB contiguous per wave read at
-    // MP = 16, which is free of bank conflicts however the hardware groups the lanes.  Rows past M
-    // repeat the last.  Consecutive threads read consecutive chunks of a row; four independent
-    // loads per thread are in flight at a time.
-    auto stage_x = [&]() {
-        const int chunks = t_total * 16;                          // of this K range
-        constexpr int kBatch = 4;
-        constexpr int kThreads = (NW + 1) * 64;
-#pragma unroll 1
-        for (int m = 0; m < MP; ++m) {
-            const int msrc = min(m0 + m, a.m - 1);
-            const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx) + t_begin * 16;
-            for (int c0 = tid; c0 < chunks; c0 += kBatch * kThreads) {
-                u32x4_t v[kBatch];
+    // MP = 16, free of bank conflicts.  Rows past M repeat the last; steps past the end of K copy
+    // the last step (their weights are zero).
+    // The first batch of activation loads goes out before the first weight loads and is written to
+    // LDS behind them: at the start every wave of the grid asks for its first two items at once,
+    // most of a small matrix, and loads queued behind that burst would hold up the first MFMA.
+    u32x4_t* xw = xs + (size_t)max(kw, 0) * steps_w * 16 * MP;
+    constexpr int kXLoads = MP > 8 ? MP : 8;                      // loads in flight per batch (registers:
+    constexpr int kXBatch = kXLoads / MP;                         // two workgroups per CU need <= 96)
+    u32x4_t xv[kXLoads];
+    auto x_load = [&](int c0) {
 #pragma unroll
-                for (int b = 0; b < kBatch; ++b)
-                    v[b] = xp[min(c0 + b * kThreads, chunks - 1)];
+        for (int i = 0; i < kXBatch; ++i) {
+            const int c = min(c0 + i, items - 1);                 // a batch's surplus repeats the last item
+            const int t = min(kw * steps_w + c * kCh + (lane >> 4), t_total - 1);
+            const int chunk = (t_begin + t) * 16 + (lane & 15);
 #pragma unroll
-                for (int b = 0; b < kBatch; ++b) {
-                    const int c = min(c0 + b * kThreads, chunks - 1);   // clamped duplicates rewrite the same data
-                    const int slot = (c & ~15) | ((c & 3) << 2) | ((c >> 2) & 3);
-                    xs[slot * MP + m] = v[b];
-                }
+            for (int m = 0; m < MP; ++m) {
+                const int msrc = min(m0 + m, a.m - 1);
+                xv[i * MP + m] = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx)[chunk];
             }
+        }
+    };
+    auto x_store = [&](int c0) {
+        const int sl = (lane & 48) | ((lane & 3) << 2) | ((lane >> 2) & 3);
+#pragma unroll
+        for (int i = 0; i < kXBatch; ++i) {
+            const int c = min(c0 + i, items - 1);
+#pragma unroll
+            for (int m = 0; m < MP; ++m)
+                xw[(c * 64 + sl) * MP + m] = xv[i * MP + m];
         }
     };
 
@@ -123,11 +151,34 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         *ok = valid(p) && local < steps_w && t < t_total;
         return t;
     };
+    // Scales.  A tile's scale block is 16 rows x t_total dwords (a dword holds the four scales of one
+    // step).  A lane needs 16 bytes of ONE row per item, which as a load touches 16 cache lines per
+    // wave for 256 useful bytes and fills the L1 with lines it uses an eighth of.  Instead the
+    // workgroup's waves fetch the block of the NEXT tile together, one dword per lane and item in
+    // row-major order (256 contiguous bytes per wave load), park it in LDS, and every wave reads the
+    // 16 bytes it needs from there after the barrier that ends the tile.
+    // Dword d = (c * NW + kw) * 64 + lane of the block: its row and step, false past the block.
+    auto sp_place = [&](int c, int* r, int* t) {
+        const uint32_t d = (uint32_t)((c * NW + kw) * 64 + lane);
+        const uint32_t rr = d / (uint32_t)t_total;
+        *r = (int)rr;
+        *t = (int)(d - rr * (uint32_t)t_total);
+        return rr < 16u;
+    };
+    auto sp_load = [&](int tile, int c) {
+        int r, t;
+        const bool ok = sp_place(c, &r, &t) && tile < n_tiles;
+        const int row = min(tile * 16 + r, a.n - 1);
+        return __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? row * nblk + (t_begin + t) * 4 : kSentinel, 0, 0);
+    };
+    auto sp_store = [&](int slot, int c, uint32_t v) {
+        int r, t;
+        if (sp_place(c, &r, &t))
+            sc[(slot * 16 + r) * scw + t] = v;
+    };
     // Always kCh + 1 loads per item (absent steps read nothing and return zero), so that the
     // in-order load counter can be waited on exactly.  The weight loads carry no streaming hint:
-    // a wave load covers half a cache line per row and the next step wants the other half.  The
-    // scales of an item are one 16-byte load per row (the four lanes of a row load the same bytes):
-    // 16 cache lines touched per item instead of 64 with a byte load per step.
+    // a wave load covers half a cache line per row and the next step wants the other half.
     auto issue = [&](const MPos& p, MItem& it) {
         const int tile = valid(p) ? p.tile : 0;
         const int row = min(tile * 16 + li, a.n - 1);             // ragged N: repeat the last row
@@ -138,9 +189,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
             const int t = step_of(p, u, &ok);
             it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? (t_begin + t) * 64 : 0, 0);
         }
-        bool ok0;
-        const int t0 = step_of(p, 0, &ok0);
-        it.s = __builtin_amdgcn_raw_buffer_load_b128(rs, ok0 ? row * nblk : kSentinel, ok0 ? (t_begin + t0) * 4 : 0, 0);
+        it.sp = sp_load(valid(p) ? p.tile + (int)gridDim.x : n_tiles, p.c);
     };
 
     const int col = li % MP;
@@ -148,9 +197,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     int best_idx = 0x7FFFFFFF;
 
     if (wave == 0) {
-        // Epilogue wave: one barrier per tile, like the compute waves; no weight loads of its own.
-        stage_x();
-        lds_barrier_mfma();                                       // activations staged
+        // Epilogue wave: one barrier per tile, like the compute waves; no loads of its own.
+        lds_barrier_mfma();                                       // scales of the first tile are in LDS
         int tiles_done = 0;
         for (int tile = (int)blockIdx.x; tile < n_tiles; tile += gridDim.x, ++tiles_done) {
             const f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
@@ -183,6 +231,13 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         MItem buf[2];
         MPos pos[2];
         MPos load{(int)blockIdx.x, 0};
+        // scale block of the first tile: four items' dwords in flight at a time
+        uint32_t sp0[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            sp0[i] = sp_load(i < items ? (int)blockIdx.x : n_tiles, i);
+        x_load(0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int d = 0; d < 2; ++d) {
             pos[d] = load;
@@ -190,25 +245,47 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
             advance(load);
             __builtin_amdgcn_sched_barrier(0);                    // keep the buffers' loads in issue order
         }
-        stage_x();
-        lds_barrier_mfma();                                       // activations staged
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < items)
+                sp_store(0, i, sp0[i]);
+        x_store(0);
+#pragma unroll 1
+        for (int c0 = kXBatch; c0 < items; c0 += kXBatch) {       // long K slices: the rest, batch by batch
+            x_load(c0);
+            x_store(c0);
+        }
+#pragma unroll 1
+        for (int c0 = 4; c0 < items; c0 += 4) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                sp0[i] = sp_load(c0 + i < items ? (int)blockIdx.x : n_tiles, c0 + i);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (c0 + i < items)
+                    sp_store(0, c0 + i, sp0[i]);
+        }
+        lds_barrier_mfma();                                       // scales of the first tile are in LDS
 
         f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: even and odd j
         int tiles_done = 0;
         auto compute = [&](const MPos& p, const MItem& it) {
+            // the four steps' scale dwords of this lane's row; byte lg of dword u is its block's scale
+            const u32x4_t sv = *reinterpret_cast<const u32x4_t*>(
+                sc + ((tiles_done & 1) * 16 + li) * scw + kw * steps_w + p.c * kCh);
+            sp_store((tiles_done + 1) & 1, p.c, it.sp);
 #pragma unroll
             for (int u = 0; u < kCh; ++u) {
                 bool ok;
-                const int t = step_of(p, u, &ok);
-                const int tc = ok ? t : 0;                        // absent steps: zero weights, any finite x
+                step_of(p, u, &ok);
+                const int local = p.c * kCh + u;                  // absent steps: zero weights, copied x
                 u32x4_t xb[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    xb[j] = xs[(16 * tc + 4 * j + lg) * MP + col];
-                // byte lg of dword u is this lane's block scale; the convert reads the exponent field
-                // as E8M0.  A step past the end of K gets scale 2^-127 (its weights are zero, and
-                // bytes read past the row's scales could say NaN).
-                const uint32_t sbyte = ok ? ((it.s[u] >> (8 * lg)) & 0xFFu) : 0u;
+                    xb[j] = xw[(16 * local + 4 * j + lg) * MP + col];
+                // The convert reads the exponent field as E8M0.  A step past the end of K gets scale
+                // 2^-127 (its weights are zero, and what LDS holds there could say NaN).
+                const uint32_t sbyte = ok ? ((sv[u] >> (8 * lg)) & 0xFFu) : 0u;
                 const float sc = __uint_as_float(sbyte << 23);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -324,26 +401,62 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a)
     }
 }
 
+// Launch one pass.  The grid is what is resident at once (asked of the runtime: the LDS a
+// workgroup may use is less than the nominal size divides into), by default one workgroup per CU
+// (measured: eight compute waves per CU with two items in flight each already saturate the memory
+// system, and a second workgroup only lengthens the start-up burst), split over the phases.
+// *blocks is the cap on workgroups per phase on entry (0 = none) and the count used on return.
 template <int MP, int NW>
-hipError_t launch_one(const GemmArgs& a, int m0, int blocks, int phases, size_t lds, int max_lds,
+hipError_t launch_one(const GemmArgs& a, int m0, int phases, size_t lds, const DeviceInfo& dev, int* blocks,
                       hipStream_t stream)
 {
     auto kern = mfma_kernel<MP, NW>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
         if (e != hipSuccess)
             return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks, phases), dim3((NW + 1) * 64), lds, stream, a, m0);
+    thread_local size_t occ_lds = ~(size_t)0;
+    thread_local int occ = 0;
+    if (occ_lds != lds) {
+        int nb = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void*>(kern),
+                                                                   (NW + 1) * 64, lds);
+        if (e != hipSuccess)
+            return e;
+        occ = nb;
+        occ_lds = lds;
+    }
+    static const int max_per_cu = [] {                             // MXFP4_MFMA_WGS: measurement only
+        const char* e = getenv("MXFP4_MFMA_WGS");
+        const int v = e ? atoi(e) : 0;
+        return v >= 1 && v <= 4 ? v : 1;
+    }();
+    const int per_cu = occ < 1 ? 1 : (occ > max_per_cu ? max_per_cu : occ);
+    const int n_tiles = (a.n + 15) / 16;
+    int nb = dev.cus * per_cu / phases;
+    nb = nb < 1 ? 1 : (nb > n_tiles ? n_tiles : nb);
+    if (nb > gemv_max_parts(dev))
+        nb = gemv_max_parts(dev);
+    if (*blocks > 0 && nb > *blocks)
+        nb = *blocks;
+    *blocks = nb;
+    hipLaunchKernelGGL(kern, dim3(nb, phases), dim3((NW + 1) * 64), lds, stream, a, m0);
     return hipGetLastError();
 }
 
 constexpr int kNW = 8;
 
-size_t lds_need(int steps, int mp) { return (size_t)steps * 256 * mp + (size_t)2 * kNW * 64 * 16; }
+constexpr size_t kRedBytes = (size_t)2 * kNW * 64 * 16;
+constexpr int kGrain = kNW * kCh;      // steps that give every compute wave one item
+
+size_t lds_need(int steps, int mp)
+{
+    return x_lds_bytes<kNW>(steps, mp) + kRedBytes + (size_t)2 * 16 * scale_row_dwords_t<kNW>(steps) * 4;
+}
 
 // LDS a workgroup should stay under when K may be split: two workgroups per CU.
 size_t lds_target(const DeviceInfo& dev)
@@ -362,12 +475,13 @@ void plan_phases(int k, int mp, const DeviceInfo& dev, bool may_split, int* phas
     int steps = (t_total + kCh - 1) / kCh * kCh;
     if (may_split) {
         // two workgroups per CU if a phase still gives every compute wave an item, else one
-        const size_t red_bytes = (size_t)2 * kNW * 64 * 16;
-        int fit = (int)((lds_target(dev) - red_bytes) / ((size_t)256 * mp)) / kCh * kCh;
-        if (fit < kNW * kCh)
-            fit = (int)(((size_t)dev.lds_bytes - red_bytes) / ((size_t)256 * mp)) / kCh * kCh;
-        if (fit < kCh)
-            fit = kCh;
+        // per step: 256 bytes of activations per row and 2 x 16 scale dwords; 512 more for the skew
+        const size_t fixed = kRedBytes + 512, per_step = (size_t)256 * mp + 128;
+        int fit = (int)((lds_target(dev) - fixed) / per_step) / kGrain * kGrain;
+        if (fit < kGrain)
+            fit = (int)(((size_t)dev.lds_bytes - fixed) / per_step) / kGrain * kGrain;
+        if (fit < kGrain)
+            fit = kGrain;                                         // 144 KiB at 16 rows: fits gfx950
         if (fit < steps) {
             const int p = (t_total + fit - 1) / fit;
             steps = ((t_total + p - 1) / p + kCh - 1) / kCh * kCh;     // even phases
@@ -431,30 +545,23 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
                 mp >>= 1;
         }
         const size_t lds = lds_need(steps, mp);
-        int per_cu = (int)((size_t)dev.lds_bytes / lds);
-        per_cu = per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu);      // 9 waves each: a third would not fit the SIMDs evenly
-        int blocks = dev.cus * per_cu / phases;
-        blocks = blocks < 1 ? 1 : (blocks > n_tiles ? n_tiles : blocks);
-        if (blocks > gemv_max_parts(dev))
-            blocks = gemv_max_parts(dev);
-        if (m0 == 0)
-            first_blocks = blocks;
-        // the argmax partial arrays are indexed by workgroup: keep the grid the same for all passes
-        if (a.part_val != nullptr && !split)
-            blocks = first_blocks < blocks ? first_blocks : blocks;
+        // the argmax partial arrays are indexed by workgroup: no pass may use more than the first
+        int blocks = (a.part_val != nullptr && !split) ? first_blocks : 0;
         a.splitk_ws = split ? splitk_ws : nullptr;
         a.phases = phases;
         a.phase_steps = steps;
         max_phases = phases > max_phases ? phases : max_phases;
         hipError_t e;
         if (mp == 16)
-            e = launch_one<16, kNW>(a, m0, blocks, phases, lds, dev.lds_bytes, stream);
+            e = launch_one<16, kNW>(a, m0, phases, lds, dev, &blocks, stream);
         else if (mp == 8)
-            e = launch_one<8, kNW>(a, m0, blocks, phases, lds, dev.lds_bytes, stream);
+            e = launch_one<8, kNW>(a, m0, phases, lds, dev, &blocks, stream);
         else
-            e = launch_one<4, kNW>(a, m0, blocks, phases, lds, dev.lds_bytes, stream);
+            e = launch_one<4, kNW>(a, m0, phases, lds, dev, &blocks, stream);
         if (e != hipSuccess)
             return e;
+        if (m0 == 0)
+            first_blocks = blocks;
         m0 += mp;
     }
     if (split) {

@@ -56,7 +56,7 @@ MFMA = binding.PATH_MFMA
 
 
 @pytest.mark.parametrize("n,k", [(1, 128), (16, 128), (17, 256), (33, 2048), (250, 11008), (1000, 4096),
-                                 (48, 8192), (31, 16384)])
+                                 (48, 8192), (31, 12288)])
 @pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 9, 16, 17, 33])
 def test_mfma_tiles_edge_shapes(n, k, m):
     w = synth.weights_student_t(n, k, seed=3000 + n + k)
