@@ -198,9 +198,13 @@ def run_stack(args) -> int:
     ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(m, head["n"], head["k"]),),
                      dtype=torch.uint8, device=dev)
 
+    # one split-K scratch buffer serves every linear: the calls of a step run one after the other
+    sk_bytes = max(binding.mxfp4_woq_gemm_workspace_bytes(m, t["n"], t["k"]) for t in ops[:-1])
+    sk = torch.empty((sk_bytes,), dtype=torch.uint8, device=dev) if sk_bytes else None
+
     def step(_lin=None, _ws=None):
         for t in ops[:-1]:
-            binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+            binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"], workspace=sk)
         binding.mxfp4_woq_gemm_argmax(head["x"], head["q"], head["s"], workspace=ws, out=(head["idx"], head["val"]))
 
     stream = torch.cuda.Stream()

@@ -68,7 +68,7 @@ struct MPos {
 
 // MP: activation rows held per pass (4, 8 or 16); NW: compute waves per workgroup (they split K);
 // the workgroup has NW + 1 waves, wave 0 is the epilogue wave.
-template <int MP, int NW>
+template <int MP, int NW, int D>
 __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
 {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -106,9 +106,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     // groups of one MFMA then read four adjacent segments, 1 KiB contiguous per wave read at
     // MP = 16, free of bank conflicts.  Rows past M repeat the last; steps past the end of K copy
     // the last step (their weights are zero).
-    // The first batch of activation loads goes out before the first weight loads and is written to
-    // LDS behind them: at the start every wave of the grid asks for its first two items at once,
-    // most of a small matrix, and loads queued behind that burst would hold up the first MFMA.
     u32x4_t* xw = xs + (size_t)max(kw, 0) * steps_w * 16 * MP;
     constexpr int kXLoads = MP > 8 ? MP : 8;                      // loads in flight per batch (registers:
     constexpr int kXBatch = kXLoads / MP;                         // two workgroups per CU need <= 96)
@@ -158,9 +155,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     // row-major order (256 contiguous bytes per wave load), park it in LDS, and every wave reads the
     // 16 bytes it needs from there after the barrier that ends the tile.
     // Dword d = (c * NW + kw) * 64 + lane of the block: its row and step, false past the block.
+    // (d / t_total by multiplication: exact for d < 2^14 and t_total <= 2^9, which K <= 65536 keeps)
+    const uint32_t t_magic = __builtin_amdgcn_readfirstlane((1u << 24) / (uint32_t)t_total + 1u);
     auto sp_place = [&](int c, int* r, int* t) {
         const uint32_t d = (uint32_t)((c * NW + kw) * 64 + lane);
-        const uint32_t rr = d / (uint32_t)t_total;
+        const uint32_t rr = __umulhi(d << 8, t_magic);
         *r = (int)rr;
         *t = (int)(d - rr * (uint32_t)t_total);
         return rr < 16u;
@@ -228,9 +227,19 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
             }
         }
     } else {
-        MItem buf[2];
-        MPos pos[2];
+        MItem buf[D];
+        MPos pos[D];
         MPos load{(int)blockIdx.x, 0};
+        // The weight loads go out first, with as few instructions in front of them as possible:
+        // at three waves per SIMD every hundred instructions of set-up delay them by half a
+        // microsecond, and nothing else can start before they are back anyway.
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            pos[d] = load;
+            issue(load, buf[d]);
+            advance(load);
+            __builtin_amdgcn_sched_barrier(0);                    // keep the buffers' loads in issue order
+        }
         // scale block of the first tile: four items' dwords in flight at a time
         uint32_t sp0[4];
 #pragma unroll
@@ -238,13 +247,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
             sp0[i] = sp_load(i < items ? (int)blockIdx.x : n_tiles, i);
         x_load(0);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int d = 0; d < 2; ++d) {
-            pos[d] = load;
-            issue(load, buf[d]);
-            advance(load);
-            __builtin_amdgcn_sched_barrier(0);                    // keep the buffers' loads in issue order
-        }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             if (i < items)
@@ -315,18 +317,17 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         };
 
         // Positions only grow, so the walk ends when buffer 0 runs dry.  Every trip issues the
-        // same loads whether or not buffer 1 still had work: every path into the loop head then
+        // same loads whether or not the later buffers still had work: every path into the loop head then
         // carries the same queue of outstanding loads and the compiler's counter waits stay exact.
         while (valid(pos[0])) {
-            compute(pos[0], buf[0]);
-            pos[0] = load;
-            issue(load, buf[0]);
-            advance(load);
-            if (valid(pos[1]))
-                compute(pos[1], buf[1]);
-            pos[1] = load;
-            issue(load, buf[1]);
-            advance(load);
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (d == 0 || valid(pos[d]))
+                    compute(pos[d], buf[d]);
+                pos[d] = load;
+                issue(load, buf[d]);
+                advance(load);
+            }
         }
     }
 
@@ -406,11 +407,11 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a)
 // (measured: eight compute waves per CU with two items in flight each already saturate the memory
 // system, and a second workgroup only lengthens the start-up burst), split over the phases.
 // *blocks is the cap on workgroups per phase on entry (0 = none) and the count used on return.
-template <int MP, int NW>
+template <int MP, int NW, int D>
 hipError_t launch_one(const GemmArgs& a, int m0, int phases, size_t lds, const DeviceInfo& dev, int* blocks,
                       hipStream_t stream)
 {
-    auto kern = mfma_kernel<MP, NW>;
+    auto kern = mfma_kernel<MP, NW, D>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -458,14 +459,15 @@ size_t lds_need(int steps, int mp)
     return x_lds_bytes<kNW>(steps, mp) + kRedBytes + (size_t)2 * 16 * scale_row_dwords_t<kNW>(steps) * 4;
 }
 
-// LDS a workgroup should stay under when K may be split: two workgroups per CU.
+// LDS a workgroup should stay under when K may be split: all of it (one workgroup per CU), so K is
+// only cut when the activation rows of a pass cannot be held whole.
 size_t lds_target(const DeviceInfo& dev)
 {
     static const int env = [] {
         const char* e = getenv("MXFP4_MFMA_LDS_TARGET");
         return e ? atoi(e) : 0;
     }();
-    return env > 0 ? (size_t)env : (size_t)dev.lds_bytes / 2;
+    return env > 0 ? (size_t)env : (size_t)dev.lds_bytes;
 }
 
 // Steps per phase (a multiple of kCh) and number of phases for a pass of `mp` activation rows.
@@ -474,7 +476,6 @@ void plan_phases(int k, int mp, const DeviceInfo& dev, bool may_split, int* phas
     const int t_total = k / 128;
     int steps = (t_total + kCh - 1) / kCh * kCh;
     if (may_split) {
-        // two workgroups per CU if a phase still gives every compute wave an item, else one
         // per step: 256 bytes of activations per row and 2 x 16 scale dwords; 512 more for the skew
         const size_t fixed = kRedBytes + 512, per_step = (size_t)256 * mp + 128;
         int fit = (int)((lds_target(dev) - fixed) / per_step) / kGrain * kGrain;
@@ -551,13 +552,23 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
         a.phases = phases;
         a.phase_steps = steps;
         max_phases = phases > max_phases ? phases : max_phases;
+        static const int depth = [] {                             // MXFP4_MFMA_DEPTH: measurement only
+            const char* e = getenv("MXFP4_MFMA_DEPTH");
+            const int v = e ? atoi(e) : 0;
+            return v >= 2 && v <= 4 ? v : 2;
+        }();
         hipError_t e;
+#define MXFP4_MFMA_CASE(MP_)                                                                       \
+    (depth == 4   ? launch_one<MP_, kNW, 4>(a, m0, phases, lds, dev, &blocks, stream)                \
+     : depth == 3 ? launch_one<MP_, kNW, 3>(a, m0, phases, lds, dev, &blocks, stream)                \
+                  : launch_one<MP_, kNW, 2>(a, m0, phases, lds, dev, &blocks, stream))
         if (mp == 16)
-            e = launch_one<16, kNW>(a, m0, phases, lds, dev, &blocks, stream);
+            e = MXFP4_MFMA_CASE(16);
         else if (mp == 8)
-            e = launch_one<8, kNW>(a, m0, phases, lds, dev, &blocks, stream);
+            e = MXFP4_MFMA_CASE(8);
         else
-            e = launch_one<4, kNW>(a, m0, phases, lds, dev, &blocks, stream);
+            e = MXFP4_MFMA_CASE(4);
+#undef MXFP4_MFMA_CASE
         if (e != hipSuccess)
             return e;
         if (m0 == 0)
