@@ -74,13 +74,15 @@ def run_step(lin, ws):
     binding.mxfp4_woq_gemm_argmax(t["x"], t["q"], t["s"], workspace=ws, out=(t["idx"], t["val"]))
 
 
+DOMINANT = ("qkv", "gate_up", "lm_head")
+
+
 def run_dominant(lin, ws):
-    """The two launches of a step that use the dominant kernel instance (4 rows per wave step)."""
+    """The three launches of a step that use the dominant kernel instance (2 rows per wave step)."""
     from paper_2503_13565_amd import binding
-    t = lin["gate_up"]
-    binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
-    t = lin["lm_head"]                                  # same kernel instance as the fused-argmax call
-    binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+    for name in DOMINANT:                               # lm_head: same instance as the fused-argmax call
+        t = lin[name]
+        binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
 
 
 def capture(fn, sets, ws, stream):
@@ -296,16 +298,16 @@ def main() -> int:
     n_plain = max(len(sets), args.steps // 4)
     plain_ms = timed(runner(None, run_step, sets, ws), n_plain, stream) / n_plain
 
-    # dominant kernel: the instance that runs gate+up and the LM head (2 of the 6 launches,
-    # 66 % of the bytes); average launch duration from events around graph replays of these two
+    # dominant kernel: the instance that runs qkv, gate+up and the LM head (3 of the 6 launches,
+    # 81 % of the bytes); average launch duration from events around graph replays of these three
     # launches only, rotating over the weight sets
     dgraph = None if args.no_graph else capture(run_dominant, sets, ws, stream)
     run_dom = runner(dgraph, run_dominant, sets, ws)
     timed(run_dom, len(sets), stream)
     reps = len(sets) * max(2, args.steps // (2 * len(sets)))
     dom_ms = timed(run_dom, reps, stream) / reps
-    dom_launch_us = dom_ms * 1e3 / 2.0
-    dom_bytes = (algorithmic_bytes(m, 22016, 4096) + algorithmic_bytes(m, 32000, 4096)) / 2.0
+    dom_launch_us = dom_ms * 1e3 / len(DOMINANT)
+    dom_bytes = sum(algorithmic_bytes(m, n, k) for name, n, k in shape.linears() if name in DOMINANT) / len(DOMINANT)
     achieved = dom_bytes / (dom_launch_us * 1e-6) / 1e9
 
     # what a plain 128-bit read stream gets on this device, over 4 GiB (context for frac)
@@ -354,7 +356,7 @@ def main() -> int:
         "direct_cast_GBps": None if cast_gbps is None else round(cast_gbps, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": "mxfp4::gemv_kernel<1,4,2,4,2,true> (gate_up and lm_head launches)",
+                     "kernel": "mxfp4::gemv_kernel<1,2,2,4,2,true> (qkv, gate_up and lm_head launches)",
                      "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_launch_us, 3)},
     }
     if not args.no_cpu:
