@@ -52,6 +52,8 @@ def _load():
         lib.oracle_woq_gemm.restype = i32
         lib.oracle_woq_gemm_late_scaled.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp]
         lib.oracle_woq_gemm_late_scaled.restype = i32
+        lib.oracle_bf16_gemm.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, i32]
+        lib.oracle_bf16_gemm.restype = i32
         lib.oracle_argmax.argtypes = [vp, i64, i64, vp, vp]
         lib.oracle_argmax.restype = i32
         lib.oracle_e2m1_magnitude.argtypes = [i32]
@@ -125,6 +127,24 @@ def woq_gemm(x_bits, q, s, threads: int = 0, want_abs: bool = True):
                                  _ptr(a) if want_abs else None, threads)
     if rc:
         raise RuntimeError("oracle_woq_gemm failed: %d" % rc)
+    return (y, a) if want_abs else y
+
+
+def bf16_gemm(x_bits, w_bits, threads: int = 0, want_abs: bool = True):
+    """FP64 product with unquantised BF16 weights: ``y[m,n] = sum_k x[m,k] * w[n,k]`` and the sum of
+    absolute products.  Both inputs are uint16 BF16 bit patterns, ``[M,K]`` and ``[N,K]``."""
+    x = _as(x_bits, np.uint16, 2)
+    w = _as(w_bits, np.uint16, 2)
+    m, k = x.shape
+    n = w.shape[0]
+    if w.shape[1] != k:
+        raise ValueError("shape mismatch: x %r w %r" % (x.shape, w.shape))
+    y = np.empty((m, n), np.float64)
+    a = np.empty((m, n), np.float64) if want_abs else None
+    rc = _load().oracle_bf16_gemm(_ptr(x), m, k, _ptr(w), n, k, k, _ptr(y), _ptr(a) if want_abs else None,
+                                  threads)
+    if rc:
+        raise RuntimeError("oracle_bf16_gemm failed: %d" % rc)
     return (y, a) if want_abs else y
 
 

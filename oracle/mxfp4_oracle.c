@@ -27,7 +27,9 @@
  * floor(log2 amax) - 2, the decision intervals of round-to-nearest-even, an
  * integer closed form over every BF16 magnitude, power-of-two invariance, sign
  * symmetry, idempotence, the error bound, the product against a library FP64
- * matmul on on-grid weights, one-hot activations, and brute-force argmax.
+ * matmul on on-grid weights, one-hot activations, and brute-force argmax; the
+ * BF16-weight product against a library FP64 matmul and against the quantised
+ * product on weights that the cast represents exactly.
  */
 #include <math.h>
 #include <stdint.h>
@@ -270,6 +272,39 @@ int oracle_woq_gemm_late_scaled(const uint16_t *x, int64_t M, int64_t ldx,
             y_ref[m * N + n] = acc;
         }
     }
+    return 0;
+}
+
+/* The unquantised linear layer of the target model (section 3.2: the target
+ * verifies in BF16; section 3.4.3 takes its weight bytes as the 3.76x yardstick):
+ * y_ref[m,n] = sum_k x[m,k] * w[n,k] with W given as BF16 bit patterns [N,K], row
+ * stride ldw, in FP64, k ascending (every product of two BF16 values is exact in a
+ * double); a_ref[m,n] = sum_k |x[m,k] * w[n,k]|, may be NULL. */
+int oracle_bf16_gemm(const uint16_t *x, int64_t M, int64_t ldx,
+                     const uint16_t *w, int64_t N, int64_t K, int64_t ldw,
+                     double *y_ref, double *a_ref, int threads)
+{
+    if (M < 0 || N < 0 || K < 0 || ldx < K || ldw < K)
+        return 2;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t m = 0; m < M; ++m) {
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double p = bf16_to_double(x[m * ldx + k]) * bf16_to_double(w[n * ldw + k]);
+                acc += p;
+                aacc += fabs(p);
+            }
+            y_ref[m * N + n] = acc;
+            if (a_ref)
+                a_ref[m * N + n] = aacc;
+        }
+    }
+    (void)threads;
     return 0;
 }
 
