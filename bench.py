@@ -34,7 +34,7 @@ def algorithmic_bytes(m: int, n: int, k: int) -> float:
     return n * k * 0.53125 + 2.0 * m * k + 2.0 * m * n
 
 
-def build_sets(n_sets: int, m: int, dev):
+def build_sets(n_sets: int, m: int, dev, keep_bf16: int = 0):
     import torch
     from paper_2503_13565_amd import binding, synth
     shape = synth.LLAMA_7B
@@ -56,9 +56,9 @@ def build_sets(n_sets: int, m: int, dev):
             if layer > 0:                              # the first layer's casts pay one-time costs
                 cast_ms += e0.elapsed_time(e1)
                 cast_bytes += n * k * 2.53125
-            del w
-            lin[name] = dict(n=n, k=k, q=q, s=s, x=x,
+            lin[name] = dict(n=n, k=k, q=q, s=s, x=x, w=w if layer < keep_bf16 else None,
                              y=torch.empty((m, n), dtype=torch.bfloat16, device=dev))
+            del w
         lin["lm_head"]["idx"] = torch.empty((m,), dtype=torch.int32, device=dev)
         lin["lm_head"]["val"] = torch.empty((m,), dtype=torch.float32, device=dev)
         sets.append(lin)
@@ -72,6 +72,16 @@ def run_step(lin, ws):
         binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
     t = lin["lm_head"]
     binding.mxfp4_woq_gemm_argmax(t["x"], t["q"], t["s"], workspace=ws, out=(t["idx"], t["val"]))
+
+
+def run_step_bf16(lin, ws):
+    """The same step on the unquantised BF16 weights (what the MXFP4 step is a speed-up over)."""
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up", "down"):
+        t = lin[name]
+        binding.mxfp4_bf16_gemm(t["x"], t["w"], y=t["y"])
+    t = lin["lm_head"]
+    binding.mxfp4_bf16_gemm_argmax(t["x"], t["w"], workspace=ws, out=(t["idx"], t["val"]))
 
 
 DOMINANT = ("qkv", "gate_up", "lm_head")
@@ -253,6 +263,7 @@ def main() -> int:
     ap.add_argument("--m", type=int, default=1, help="activation rows (1 = decode)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of graph replays")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-bf16", action="store_true", help="skip the BF16-weight comparison step")
     ap.add_argument("--workload", default="decode7b", choices=["decode7b", "stack7b", "stack70b"],
                     help="decode7b (default): the five 7B decode linears over rotating weight sets; "
                          "stack7b / stack70b: the whole linear-only decode step of a resident weight stack")
@@ -274,7 +285,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     m = args.m
-    sets, cast_gbps = build_sets(args.sets, m, dev)
+    n_bf16 = 0 if args.no_bf16 else min(args.sets, 4)    # 4 x 0.67 GB of BF16 weights: cold too
+    sets, cast_gbps = build_sets(args.sets, m, dev, keep_bf16=n_bf16)
     ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(m, 32000, 4096),), dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()
     shape = synth.LLAMA_7B
@@ -309,6 +321,23 @@ def main() -> int:
     dom_launch_us = dom_ms * 1e3 / len(DOMINANT)
     dom_bytes = sum(algorithmic_bytes(m, n, k) for name, n, k in shape.linears() if name in DOMINANT) / len(DOMINANT)
     achieved = dom_bytes / (dom_launch_us * 1e-6) / 1e9
+
+    # the unquantised step: same linears, BF16 weights (2 bytes per weight), same launch discipline
+    bf16_us = None
+    if n_bf16:
+        bsets = sets[:n_bf16]
+        with torch.cuda.stream(stream):
+            for lin in bsets:
+                run_step_bf16(lin, ws)
+        torch.cuda.synchronize()
+        bgraph = None if args.no_graph else capture(run_step_bf16, bsets, ws, stream)
+        run_b = runner(bgraph, run_step_bf16, bsets, ws)
+        timed(run_b, n_bf16, stream)
+        nb = n_bf16 * max(2, args.steps // (4 * n_bf16))
+        bf16_us = timed(run_b, nb, stream) / nb * 1e3
+        for lin in bsets:
+            for t in lin.values():
+                t["w"] = None
 
     # what a plain 128-bit read stream gets on this device, over 4 GiB (context for frac)
     buf = torch.empty(4 << 30, dtype=torch.uint8, device=dev)
@@ -352,6 +381,8 @@ def main() -> int:
         "us_per_step_plain_launches": round(plain_ms * 1e3, 2),
         "bytes_per_step": step_bytes,
         "tflops": round(2.0 * m * sum(n * k for _, n, k in shape.linears()) / (ms_per_step * 1e-3) / 1e12, 3),
+        "bf16_weights_us_per_step": None if bf16_us is None else round(bf16_us, 2),
+        "speedup_over_bf16_weights": None if bf16_us is None else round(bf16_us / (ms_per_step * 1e3), 3),
         "stream_read_GBps": round(stream_read_gbps, 1),
         "direct_cast_GBps": None if cast_gbps is None else round(cast_gbps, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

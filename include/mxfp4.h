@@ -131,6 +131,24 @@ int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx,
                                int32_t* argmax_out, float* max_out,
                                void* workspace, size_t workspace_bytes, int path, void* stream);
 
+/*
+ * The unquantised counterpart, y = x * W^T with BF16 weights: the linear layer as the target
+ * model runs it when it verifies draft tokens (section 3.2), and the 2-bytes-per-weight yardstick
+ * of the 3.76x in section 3.4.3.  FP32 accumulation, BF16 RNE output, or the fused greedy pick
+ * with the same rules and workspace contract as mxfp4_woq_gemm_argmax.
+ *   w_bf16 in BF16 [N, K], row stride ldw (ldw >= K, ldw % 8 == 0, base 16-byte aligned);
+ *   K a positive multiple of 8, at most MXFP4_MAX_K; the weights of one call stay below 2 GiB.
+ * Other arguments as for mxfp4_woq_gemm.  Up to 8 activation rows share one pass over the weights.
+ */
+int mxfp4_bf16_gemm(const void* x_bf16, int64_t M, int64_t ldx,
+                    const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                    void* y_bf16, int64_t ldy, void* stream);
+size_t mxfp4_bf16_gemm_argmax_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int mxfp4_bf16_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
+                           const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                           int32_t* argmax_out, float* max_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* The same decode through the gfx950 scaled FP4->BF16 convert instruction (the one the CVT
  * product path uses), so that its semantics can be checked in isolation. */
 int mxfp4_dequant_hwcvt(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,

@@ -20,6 +20,7 @@ PATH_AUTO, PATH_VALU_BITS, PATH_VALU_CVT, PATH_VALU_LUT, PATH_MFMA = 0, 1, 2, 3,
 EXPORTS = [
     "mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm", "mxfp4_woq_gemm_path",
     "mxfp4_woq_gemm_workspace_bytes", "mxfp4_woq_gemm_ws", "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
+    "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
 ]
 
@@ -56,6 +57,12 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_argmax_workspace_bytes.restype = sz
     lib.mxfp4_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     lib.mxfp4_woq_gemm_argmax_path.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, i32, vp]
+    lib.mxfp4_bf16_gemm.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, i64, vp]
+    lib.mxfp4_bf16_gemm.restype = i32
+    lib.mxfp4_bf16_gemm_argmax_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.mxfp4_bf16_gemm_argmax_workspace_bytes.restype = sz
+    lib.mxfp4_bf16_gemm_argmax.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.mxfp4_bf16_gemm_argmax.restype = i32
     lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
     for name in ("mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
@@ -176,6 +183,53 @@ def mxfp4_woq_gemm_argmax(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor,
         _check(load().mxfp4_woq_gemm_argmax_path(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(idx), _ptr(val),
                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                 path, _stream()))
+    return idx, val
+
+
+def _bf16_shapes(x, w):
+    _dev(x)
+    for t, what in ((x, "x"), (w, "w")):
+        if t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("%s must be a 2-D BF16 tensor with a contiguous last dimension" % what)
+    m, k = x.shape
+    n = w.shape[0]
+    if w.shape[1] != k:
+        raise ValueError("shape mismatch: x %r w %r" % (tuple(x.shape), tuple(w.shape)))
+    return m, n, k, (x.stride(0) if m > 1 else k), (w.stride(0) if n > 1 else k)
+
+
+def mxfp4_bf16_gemm(x: torch.Tensor, w: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """y ``[M,N]`` BF16 = x ``[M,K]`` BF16 times w ``[N,K]``^T with unquantised BF16 weights."""
+    m, n, k, ldx, ldw = _bf16_shapes(x, w)
+    if y is None:
+        y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_bf16_gemm(_ptr(x), m, ldx, _ptr(w), n, k, ldw, _ptr(y),
+                                     y.stride(0) if m > 1 else n, _stream()))
+    return y
+
+
+def mxfp4_bf16_gemm_argmax_workspace_bytes(m: int, n: int, k: int) -> int:
+    return int(load().mxfp4_bf16_gemm_argmax_workspace_bytes(m, n, k))
+
+
+def mxfp4_bf16_gemm_argmax(x: torch.Tensor, w: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                           out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
+                           ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Row-wise (argmax int32 ``[M]``, max float32 ``[M]``) of x times w^T."""
+    m, n, k, ldx, ldw = _bf16_shapes(x, w)
+    if workspace is None:
+        workspace = torch.empty((mxfp4_bf16_gemm_argmax_workspace_bytes(m, n, k),), dtype=torch.uint8,
+                                device=x.device)
+    if out is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+        val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    else:
+        idx, val = out
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_bf16_gemm_argmax(_ptr(x), m, ldx, _ptr(w), n, k, ldw, _ptr(idx), _ptr(val),
+                                            _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream()))
     return idx, val
 
 

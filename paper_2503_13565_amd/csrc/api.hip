@@ -188,6 +188,77 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
     return MXFP4_OK;
 }
 
+// ---- BF16-weight product ----------------------------------------------------------------
+
+extern "C" size_t mxfp4_bf16_gemm_argmax_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+static int run_bf16(const void* x, int64_t M, int64_t ldx, const void* w, int64_t N, int64_t K, int64_t ldw,
+                    void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
+                    size_t workspace_bytes, bool argmax, void* stream)
+{
+    g_err[0] = 0;
+    if (!w)
+        return fail(MXFP4_ERR_NULL, "w_bf16 is NULL");
+    if (N < 1 || N > 0x7FFFFFFF / 8)
+        return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
+    if (K < 8 || K % 8 != 0 || K > MXFP4_MAX_K)
+        return fail(MXFP4_ERR_SHAPE, "K=%lld must be a multiple of 8 in [8, %d]", (long long)K, MXFP4_MAX_K);
+    if (ldw < K)
+        return fail(MXFP4_ERR_SHAPE, "ldw=%lld < K=%lld", (long long)ldw, (long long)K);
+    if (((N - 1) * ldw + K) * 2 > 0x7FFFFFFF)
+        return fail(MXFP4_ERR_SHAPE, "%lld bytes of weights exceed 2 GiB - 1", (long long)(((N - 1) * ldw + K) * 2));
+    if (ldw % 8 != 0 || !aligned(w, 16))
+        return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
+    int rc = check_x(x, M, ldx, K);
+    if (rc)
+        return rc;
+    DeviceInfo dev;
+    rc = device_info(&dev);
+    if (rc)
+        return rc;
+    Bf16Args a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.ldx = ldx;
+    a.w = static_cast<const uint16_t*>(w);
+    a.ldw = ldw;
+    a.m = (int)M;
+    a.n = (int)N;
+    a.k = (int)K;
+    if (argmax) {
+        if (!argmax_out)
+            return fail(MXFP4_ERR_NULL, "argmax_out is NULL");
+        const size_t need = mxfp4_bf16_gemm_argmax_workspace_bytes(M, N, K);
+        if (!workspace || workspace_bytes < need)
+            return fail(MXFP4_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                        workspace ? workspace_bytes : (size_t)0);
+        if (!aligned(workspace, 8))
+            return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
+        a.parts = gemv_max_parts(dev);
+        a.part_val = static_cast<float*>(workspace);
+        a.part_idx = reinterpret_cast<int32_t*>(a.part_val + (size_t)M * a.parts);
+    } else {
+        if (!y)
+            return fail(MXFP4_ERR_NULL, "y_bf16 is NULL");
+        if (ldy < N)
+            return fail(MXFP4_ERR_SHAPE, "ldy=%lld < N=%lld", (long long)ldy, (long long)N);
+        a.y = static_cast<uint16_t*>(y);
+        a.ldy = ldy;
+    }
+    if (!bf16_can_run(a, dev))
+        return fail(MXFP4_ERR_SHAPE, "K=%lld does not fit the LDS copy of one activation row", (long long)K);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int parts_used = 0;
+    hipError_t e = launch_bf16_gemv(a, dev, &parts_used, st);
+    if (e != hipSuccess)
+        return hip_fail(e, "BF16 product launch");
+    if (argmax) {
+        e = launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
+        if (e != hipSuccess)
+            return hip_fail(e, "argmax finish launch");
+    }
+    return MXFP4_OK;
+}
+
 // ---- plain streaming kernels ------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ src, size_t n16,
@@ -348,6 +419,29 @@ size_t mxfp4_woq_gemm_argmax_workspace_bytes(int64_t M, int64_t N, int64_t K)
     const DeviceInfo dev = size_query_device();
     return (size_t)M * gemv_max_parts(dev) * (sizeof(float) + sizeof(int32_t)) +
            mxfp4_woq_gemm_workspace_bytes(M, N, K);
+}
+
+int mxfp4_bf16_gemm(const void* x_bf16, int64_t M, int64_t ldx, const void* w_bf16, int64_t N, int64_t K,
+                    int64_t ldw, void* y_bf16, int64_t ldy, void* stream)
+{
+    return run_bf16(x_bf16, M, ldx, w_bf16, N, K, ldw, y_bf16, ldy, nullptr, nullptr, nullptr, 0, false, stream);
+}
+
+size_t mxfp4_bf16_gemm_argmax_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    (void)N;
+    (void)K;
+    if (M < 1)
+        return 0;
+    return (size_t)M * gemv_max_parts(size_query_device()) * (sizeof(float) + sizeof(int32_t));
+}
+
+int mxfp4_bf16_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void* w_bf16, int64_t N,
+                           int64_t K, int64_t ldw, int32_t* argmax_out, float* max_out, void* workspace,
+                           size_t workspace_bytes, void* stream)
+{
+    return run_bf16(x_bf16, M, ldx, w_bf16, N, K, ldw, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, stream);
 }
 
 int mxfp4_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,

@@ -1,0 +1,325 @@
+// The unquantised counterpart: y = x * W^T with BF16 weights, for the few activation rows of a
+// decode or verification step (arXiv 2503.13565, section 3.2: the target model verifies in BF16;
+// section 3.4.3: its 2 bytes per weight are what the 0.53 bytes of MXFP4 are measured against,
+// the 3.76x of the paper).  Same boundary conventions and the same pipeline discipline as the
+// MXFP4 GEMV: a wave walks groups of R weight rows, one 16-byte load per lane and row (8 weights,
+// 1 KiB contiguous per wave instruction), activations staged once per workgroup in LDS,
+// v_dot2_f32_bf16 with FP32 accumulation, DPP reduction at the end of a row group, outputs held
+// one per lane and stored 64 at a time.  At 2 bytes per weight the vector ALUs keep up with the
+// memory system for up to 8 activation rows per pass (4 dot2 per 16 bytes and row), so no matrix
+// core path is needed; more rows take more passes.
+#include "common.h"
+#include "kernels.h"
+#include "../../include/mxfp4.h"
+
+namespace mxfp4 {
+
+namespace {
+
+constexpr int kSentinelB = 0x7FFFFFF0;   // lane offset beyond any descriptor: the load returns zero
+
+struct BPos {
+    int g;      // row group
+    int t;      // step along K (64 chunks of 8 elements per step)
+};
+
+__device__ __forceinline__ void lds_barrier_b()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// MT activation rows per pass, R weight rows per group, NW waves per workgroup; two register
+// buffers of one step each.
+template <int MT, int R, int NW>
+__global__ __launch_bounds__(NW * 64) void bf16_gemv_kernel(Bf16Args a, int m0)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                  // [MT][K / 8] chunks
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int chunks = a.k >> 3;
+    const int steps = (chunks + 63) >> 6;
+    const int tail = chunks - (steps - 1) * 64;                      // chunks in the last step (1..64)
+    const int n_groups = (a.n + R - 1) / R;
+    const int total_waves = gridDim.x * NW;
+    const int first_group = (int)blockIdx.x * NW + wave;
+    const int row_bytes = (int)a.ldw * 2;
+    const bool argmax = a.part_val != nullptr;
+
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(a.w), 0, (int)((a.n - 1) * a.ldw + a.k) * 2, 0x00020000);
+
+    auto valid = [&](const BPos& p) { return p.g < n_groups; };
+    auto advance = [&](BPos& p) {
+        if (++p.t == steps) {
+            p.t = 0;
+            p.g += total_waves;
+        }
+    };
+    // Always R loads per step: past the wave's last position, and for the lanes beyond a ragged
+    // last step, the lane offset is out of the descriptor's range (no memory touched, zero back).
+    auto issue = [&](const BPos& p, u32x4_t (&w)[R]) {
+        const bool live = valid(p) && (p.t < steps - 1 || lane < tail);
+        const int voff = live ? lane * 16 : kSentinelB;
+        const int g = valid(p) ? p.g : 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int row = min(g * R + r, a.n - 1);                  // ragged N: re-read the last row
+            w[r] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, row * row_bytes + p.t * 1024, 2);
+        }
+    };
+
+    // Prologue: activation loads first, weight loads right behind them; only the activations are
+    // waited for before the LDS copy.
+    u32x4_t buf[2][R];
+    BPos pos[2];
+    BPos load{first_group, 0};
+    {
+        constexpr int T = NW * 64;
+        constexpr int kSlots = MT >= 8 ? 1 : 8 / MT;                 // 8 activation loads in flight per batch
+        u32x4_t xr[MT][kSlots];
+        auto x_load = [&](int c0) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const int msrc = min(m0 + m, a.m - 1);               // ragged M: repeat the last row
+                const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx);
+#pragma unroll
+                for (int i = 0; i < kSlots; ++i)
+                    xr[m][i] = xp[min(c0 + i * T, chunks - 1)];
+            }
+        };
+        auto x_store = [&](int c0) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int i = 0; i < kSlots; ++i)
+                    xs[m * chunks + min(c0 + i * T, chunks - 1)] = xr[m][i];   // clamped duplicates rewrite the same data
+        };
+        x_load(tid);
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            pos[d] = load;
+            issue(load, buf[d]);
+            advance(load);
+        }
+        x_store(tid);
+        for (int c0 = tid + kSlots * T; c0 < chunks; c0 += kSlots * T) {   // long rows: the rest, batch by batch
+            x_load(c0);
+            x_store(c0);
+        }
+    }
+    lds_barrier_b();
+
+    float best_val[MT];
+    int best_idx[MT];
+    float res[MT];               // finished outputs, one per lane: slot i = i-th finished row of this wave
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        best_val[m] = -INFINITY;
+        best_idx[m] = 0x7FFFFFFF;
+        res[m] = 0.f;
+    }
+    int slots = 0, flushed_groups = 0;
+    float acc[R][MT];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+            acc[r][m] = 0.f;
+
+    // Stores and loads share one completion counter but complete out of order with respect to
+    // each other, so the counter is drained after the stores; the main loop only sees loads.
+    auto flush = [&]() {
+        if (lane < slots) {
+            const int j = lane / R, r = lane - j * R;
+            const int row = (first_group + (flushed_groups + j) * total_waves) * R + r;
+            if (row < a.n) {
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    if (m0 + m < a.m)
+                        a.y[(int64_t)(m0 + m) * a.ldy + row] = f32_to_bf16_rne(res[m]);
+            }
+        }
+        flushed_groups += slots / R;
+        slots = 0;
+        __builtin_amdgcn_s_waitcnt(0x0F70);                          // vmcnt(0), other counters untouched
+    };
+
+    auto compute = [&](const BPos& p, const u32x4_t (&w)[R]) {
+        const int c = min(p.t * 64 + lane, chunks - 1);               // beyond the tail the weights are zero
+        u32x4_t xv[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+            xv[m] = xs[m * chunks + c];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t wd = w[r][j];                          // (a bit cast needs a plain object,
+#pragma unroll                                                        //  not a vector element)
+                for (int m = 0; m < MT; ++m) {
+                    const uint32_t xd = xv[m][j];
+                    acc[r][m] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, wd),
+                                                                __builtin_bit_cast(bf16x2_t, xd), acc[r][m], false);
+                }
+            }
+        }
+        if (p.t == steps - 1) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int row = p.g * R + r;
+#pragma unroll
+                for (int m = 0; m < MT; ++m) {
+                    const float v = wave_sum(acc[r][m]);
+                    acc[r][m] = 0.f;
+                    if (argmax) {
+                        if (row < a.n && v > best_val[m]) {           // rows ascend: lowest index wins ties
+                            best_val[m] = v;
+                            best_idx[m] = row;
+                        }
+                    } else {
+                        res[m] = (lane == slots + r) ? v : res[m];
+                    }
+                }
+            }
+            if (!argmax) {
+                slots += R;
+                if (slots + R > 64)
+                    flush();
+            }
+        }
+    };
+
+    // Every trip issues the same loads whether or not buffer 1 still had work, so that every path
+    // into the loop head carries the same queue of outstanding loads.
+    while (valid(pos[0])) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            if (d == 0 || valid(pos[d]))
+                compute(pos[d], buf[d]);
+            pos[d] = load;
+            issue(load, buf[d]);
+            advance(load);
+        }
+    }
+    if (!argmax && slots > 0)
+        flush();
+
+    if (argmax) {
+        __syncthreads();
+        float* wv = reinterpret_cast<float*>(smem);
+        int* wi = reinterpret_cast<int*>(smem) + NW * MT;
+        if (lane == 0) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                wv[wave * MT + m] = best_val[m];
+                wi[wave * MT + m] = best_idx[m];
+            }
+        }
+        __syncthreads();
+        if (tid < MT && m0 + tid < a.m) {
+            float bv = wv[tid];
+            int bi = wi[tid];
+            for (int w = 1; w < NW; ++w) {
+                const float v = wv[w * MT + tid];
+                const int i = wi[w * MT + tid];
+                if (v > bv || (v == bv && i < bi)) {
+                    bv = v;
+                    bi = i;
+                }
+            }
+            a.part_val[(int64_t)(m0 + tid) * a.parts + blockIdx.x] = bv;
+            a.part_idx[(int64_t)(m0 + tid) * a.parts + blockIdx.x] = bi;
+        }
+    }
+}
+
+template <int MT, int R, int NW>
+hipError_t launch_b(const Bf16Args& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
+{
+    auto kern = bf16_gemv_kernel<MT, R, NW>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0);
+    return hipGetLastError();
+}
+
+template <int MT>
+hipError_t launch_rows(const Bf16Args& a, int m0, int r, int nw, int blocks, size_t lds, int max_lds,
+                       hipStream_t stream)
+{
+#define MXFP4_BF16_CASE(NW_)                                                              \
+    if (nw == NW_)                                                                        \
+        return r == 2 ? launch_b<MT, 2, NW_>(a, m0, blocks, lds, max_lds, stream)         \
+                      : launch_b<MT, 1, NW_>(a, m0, blocks, lds, max_lds, stream);
+    MXFP4_BF16_CASE(4)
+    MXFP4_BF16_CASE(8)
+    MXFP4_BF16_CASE(16)
+#undef MXFP4_BF16_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// Largest K whose activation copy (one row) fits the LDS.
+bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev) { return (size_t)a.k * 2 <= (size_t)dev.lds_bytes; }
+
+hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+{
+    // two rows per group unless the matrix is so short that SIMDs would idle
+    const int r = (a.n + 1) / 2 >= dev.cus * 16 ? 2 : 1;
+    const int n_groups = (a.n + r - 1) / r;
+    int first_blocks = 0;
+    for (int m0 = 0; m0 < a.m;) {
+        const int left = a.m - m0;
+        int mt = left >= 8 ? 8 : (left >= 4 ? 4 : (left >= 2 ? 2 : 1));
+        while (mt > 1 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes)
+            mt >>= 1;
+        const size_t lds = (size_t)mt * a.k * 2 < 256 ? 256 : (size_t)mt * a.k * 2;   // the argmax combine needs a few bytes
+        int per_cu = (int)((size_t)dev.lds_bytes / lds);
+        per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+        // 16 waves per CU: larger workgroups when the activation copy leaves room for fewer of them
+        const int nw = per_cu >= 3 ? 4 : (per_cu == 2 ? 8 : 16);
+        int blocks = (n_groups + nw - 1) / nw;
+        if (blocks > dev.cus * per_cu)
+            blocks = dev.cus * per_cu;
+        if (blocks > gemv_max_parts(dev))
+            blocks = gemv_max_parts(dev);
+        // the argmax partial arrays are indexed by workgroup: no pass may use more than the first
+        if (m0 == 0)
+            first_blocks = blocks;
+        else if (a.part_val != nullptr && blocks > first_blocks)
+            blocks = first_blocks;
+        hipError_t e;
+        switch (mt) {
+        case 8:
+            e = launch_rows<8>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
+            break;
+        case 4:
+            e = launch_rows<4>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
+            break;
+        case 2:
+            e = launch_rows<2>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
+            break;
+        default:
+            e = launch_rows<1>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
+            break;
+        }
+        if (e != hipSuccess)
+            return e;
+        m0 += mt;
+    }
+    if (parts_used)
+        *parts_used = first_blocks;
+    return hipSuccess;
+}
+
+}  // namespace mxfp4

@@ -57,6 +57,22 @@ size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev);
 hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
                        hipStream_t stream);
 
+// The unquantised product with BF16 weights [N, K] (row stride ldw), same conventions otherwise.
+struct Bf16Args {
+    const uint16_t* x;
+    int64_t ldx;
+    const uint16_t* w;
+    int64_t ldw;
+    int m, n, k;
+    uint16_t* y;
+    int64_t ldy;
+    float* part_val;
+    int32_t* part_idx;
+    int parts;
+};
+bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev);
+hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+
 // Second stage of the fused argmax: reduce `parts_used` partial winners per row.
 hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
                                 int m, int32_t* argmax_out, float* max_out, hipStream_t stream);

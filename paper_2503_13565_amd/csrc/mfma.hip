@@ -525,7 +525,6 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
     if (!mfma_can_run(a_in, dev, splitk_ws != nullptr))
         return hipErrorInvalidValue;
     GemmArgs a = a_in;
-    const int n_tiles = (a.n + 15) / 16;
     // one plan for the whole call: the widest pass decides the phases (narrower passes fit too)
     bool split = false;
     int split_steps = 0, split_phases = 1;
