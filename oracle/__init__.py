@@ -54,6 +54,15 @@ def _load():
         lib.oracle_woq_gemm_late_scaled.restype = i32
         lib.oracle_bf16_gemm.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, i32]
         lib.oracle_bf16_gemm.restype = i32
+        f64 = ctypes.c_double
+        lib.oracle_greedy_accept.argtypes = [vp, vp, i64, vp]
+        lib.oracle_greedy_accept.restype = i32
+        lib.oracle_sd_speedup.argtypes = [f64, f64, f64]
+        lib.oracle_sd_speedup.restype = f64
+        lib.oracle_sd_speedup_alpha.argtypes = [f64, f64, f64]
+        lib.oracle_sd_speedup_alpha.restype = f64
+        lib.oracle_sd_speedup_two_level.argtypes = [f64] * 6
+        lib.oracle_sd_speedup_two_level.restype = f64
         lib.oracle_argmax.argtypes = [vp, i64, i64, vp, vp]
         lib.oracle_argmax.restype = i32
         lib.oracle_e2m1_magnitude.argtypes = [i32]
@@ -172,6 +181,32 @@ def argmax(y):
     if rc:
         raise RuntimeError("oracle_argmax failed: %d" % rc)
     return idx, val
+
+
+def greedy_accept(target_tokens, draft_tokens):
+    """(G, next token): G leading draft tokens equal the target's picks; the round then emits the
+    target's own pick at position G.  ``target_tokens`` has one entry more than ``draft_tokens``."""
+    t = _as(target_tokens, np.int32, 1)
+    d = _as(draft_tokens, np.int32, 1)
+    if t.shape[0] != d.shape[0] + 1:
+        raise ValueError("need N + 1 target picks for N draft tokens")
+    out = np.zeros(2, np.int32)
+    rc = _load().oracle_greedy_accept(_ptr(t), _ptr(d) if d.size else None, d.shape[0], _ptr(out))
+    if rc:
+        raise RuntimeError("oracle_greedy_accept failed: %d" % rc)
+    return int(out[0]), int(out[1])
+
+
+def sd_speedup(g: float, n_draft: float, s: float) -> float:
+    return float(_load().oracle_sd_speedup(g, n_draft, s))
+
+
+def sd_speedup_alpha(alpha: float, n_draft: float, s: float) -> float:
+    return float(_load().oracle_sd_speedup_alpha(alpha, n_draft, s))
+
+
+def sd_speedup_two_level(alpha_mid, n_mid, s_mid, alpha_last, n_last, s_last) -> float:
+    return float(_load().oracle_sd_speedup_two_level(alpha_mid, n_mid, s_mid, alpha_last, n_last, s_last))
 
 
 def bf16_ulp(y) -> np.ndarray:

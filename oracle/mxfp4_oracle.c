@@ -327,6 +327,50 @@ int oracle_argmax(const double *y, int64_t M, int64_t N, int32_t *idx, double *v
     return 0;
 }
 
+/* Verification of a draft (section 3.1): the target's forward pass over the last
+ * accepted token and the N draft tokens gives N + 1 greedy picks; pick m is the
+ * target's token for the position of draft token m.  The draft tokens after the
+ * first mismatch are dropped: G = number of leading draft tokens that equal the
+ * target's picks (0..N), and the round emits those G tokens plus the target's
+ * own pick at position G (the extra token of section 3.2).
+ * target[N + 1], draft[N]; out[0] = G, out[1] = target[G]. */
+int oracle_greedy_accept(const int32_t *target, const int32_t *draft, int64_t n_draft, int32_t out[2])
+{
+    if (n_draft < 0)
+        return 2;
+    int64_t g = 0;
+    while (g < n_draft && draft[g] == target[g])
+        ++g;
+    out[0] = (int32_t)g;
+    out[1] = target[g];
+    return 0;
+}
+
+/* Expected speed-up of one round of speculative decoding over greedy decoding
+ * (Eq. 1, first form): G + 1 tokens for one run of the target and N runs of a
+ * draft that is S times faster. */
+double oracle_sd_speedup(double g, double n_draft, double s)
+{
+    return (g + 1.0) / (1.0 + n_draft / s);
+}
+
+/* The same with the acceptance ratio alpha = G / N (Eq. 1, second form). */
+double oracle_sd_speedup_alpha(double alpha, double n_draft, double s)
+{
+    return (alpha + 1.0 / n_draft) / (1.0 / n_draft + 1.0 / s);
+}
+
+/* Two levels (section 3.3): the intermediate draft, s_mid times faster than the
+ * target, is itself sped up by speculative decoding with a last-level draft that
+ * is s_last times faster than the target (hence s_last / s_mid times faster than
+ * the intermediate model); the target then sees a draft S' = s_mid * that gain. */
+double oracle_sd_speedup_two_level(double alpha_mid, double n_mid, double s_mid,
+                                   double alpha_last, double n_last, double s_last)
+{
+    double s_prime = s_mid * oracle_sd_speedup_alpha(alpha_last, n_last, s_last / s_mid);
+    return oracle_sd_speedup_alpha(alpha_mid, n_mid, s_prime);
+}
+
 /* The E2M1 magnitude of a code, exported so a test can print the grid. */
 double oracle_e2m1_magnitude(int code) { return e2m1_magnitude(code & 7); }
 
