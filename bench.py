@@ -95,6 +95,28 @@ def run_dominant(lin, ws):
         binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
 
 
+def eq1_projection(s_measured: float):
+    """Expected speed-ups of Eq. 1 (arXiv 2503.13565, section 3.2) and of its two-level composition
+    (section 3.3) with the draft speed-up S measured here and the acceptance ratios the paper
+    reports for its models (sections 4.2, 4.3) as inputs.  N = 4 draft tokens as in the text."""
+    def one(alpha, n, s):
+        return (alpha + 1.0 / n) / (1.0 / n + 1.0 / s)
+
+    def two(a_mid, s_mid, a_last, s_last, n=4.0):
+        return one(a_mid, n, s_mid * one(a_last, n, s_last / s_mid))
+    n = 4.0
+    out = {"N": 4, "S_mxfp4_measured": round(s_measured, 3), "S_mxfp4_by_bytes": 3.765}
+    for tag, a_q, a_t, s_t in (("llama2_7b_like", 0.712, 0.417, 100.0), ("qwen2.5_7b_like", 0.91, 0.62, 14.0)):
+        out[tag] = {
+            "alpha_mxfp4_draft": a_q, "alpha_small_draft": a_t, "S_small_draft_assumed": s_t,
+            "one_level_mxfp4_draft": round(one(a_q, n, s_measured), 3),
+            "one_level_mxfp4_draft_at_S_by_bytes": round(one(a_q, n, 3.765), 3),
+            "one_level_small_draft": round(one(a_t, n, s_t), 3),
+            "two_level": round(two(a_q, s_measured, a_t, s_t), 3),
+        }
+    return out
+
+
 def capture(fn, sets, ws, stream):
     """One HIP graph holding one step per weight set, in order; None if capture is unavailable."""
     import torch
@@ -390,6 +412,8 @@ def main() -> int:
                      "kernel": "mxfp4::gemv_kernel<1,2,2,4,2,true> (qkv, gate_up and lm_head launches)",
                      "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_launch_us, 3)},
     }
+    if bf16_us is not None:
+        out["eq1_projection"] = eq1_projection(bf16_us / (ms_per_step * 1e3))
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(m)
         for key in ("value", "seconds_per_step"):

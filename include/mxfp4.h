@@ -149,6 +149,31 @@ int mxfp4_bf16_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
                            int32_t* argmax_out, float* max_out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Verification of a draft in one call (section 3.1): the product with the fused greedy pick, then
+ * the comparison with the draft's tokens fused into the pick's last stage.  Row 0 of x belongs
+ * to the last accepted token, row m >= 1 to draft token m - 1; the pick of row m is the verifier's
+ * token for the position of draft token m.  Draft tokens after the first mismatch are dropped:
+ *   draft_tokens in  int32 [M - 1] (device; may be NULL when M == 1)
+ *   accept_out   out int32 [2] (device): [0] = G, the number of leading draft tokens that equal
+ *                the picks (0 .. M - 1); [1] = the pick at row G, the token the round adds after
+ *                them (sections 3.1 and 3.2: G + 1 tokens per verification pass)
+ *   argmax_out   out int32 [M], required; max_out may be NULL.
+ * M <= 1024.  Workspace as for the matching *_argmax call.  The first form verifies with the
+ * MXFP4 weights (the intermediate model of section 3.3 checking the last-level draft), the second
+ * with BF16 weights (the target checking the MXFP4 model).
+ */
+int mxfp4_woq_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
+                          const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                          const int32_t* draft_tokens, int32_t* accept_out,
+                          int32_t* argmax_out, float* max_out,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
+                           const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                           const int32_t* draft_tokens, int32_t* accept_out,
+                           int32_t* argmax_out, float* max_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
 /* The same decode through the gfx950 scaled FP4->BF16 convert instruction (the one the CVT
  * product path uses), so that its semantics can be checked in isolation. */
 int mxfp4_dequant_hwcvt(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,

@@ -21,6 +21,7 @@ EXPORTS = [
     "mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm", "mxfp4_woq_gemm_path",
     "mxfp4_woq_gemm_workspace_bytes", "mxfp4_woq_gemm_ws", "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
+    "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
 ]
 
@@ -63,6 +64,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_bf16_gemm_argmax_workspace_bytes.restype = sz
     lib.mxfp4_bf16_gemm_argmax.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     lib.mxfp4_bf16_gemm_argmax.restype = i32
+    lib.mxfp4_woq_gemm_verify.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.mxfp4_woq_gemm_verify.restype = i32
+    lib.mxfp4_bf16_gemm_verify.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.mxfp4_bf16_gemm_verify.restype = i32
     lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
     for name in ("mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
@@ -231,6 +236,43 @@ def mxfp4_bf16_gemm_argmax(x: torch.Tensor, w: torch.Tensor, workspace: Optional
                                             _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _stream()))
     return idx, val
+
+
+def _verify_buffers(x, m, draft, need, workspace):
+    if draft is not None and (draft.dtype != torch.int32 or draft.numel() != m - 1 or not draft.is_contiguous()):
+        raise ValueError("draft must hold M - 1 contiguous int32 tokens")
+    if workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    accept = torch.empty((2,), dtype=torch.int32, device=x.device)
+    idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+    val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    return workspace, accept, idx, val
+
+
+def mxfp4_woq_gemm_verify(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, draft: Optional[torch.Tensor],
+                          workspace: Optional[torch.Tensor] = None):
+    """(accept int32 ``[2]`` = (G, next token), argmax int32 ``[M]``, max float32 ``[M]``)."""
+    m, n, k, ldx = _gemm_shapes(x, q, s)
+    workspace, accept, idx, val = _verify_buffers(x, m, draft, mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k),
+                                                  workspace)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_verify(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(draft), _ptr(accept),
+                                           _ptr(idx), _ptr(val), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()))
+    return accept, idx, val
+
+
+def mxfp4_bf16_gemm_verify(x: torch.Tensor, w: torch.Tensor, draft: Optional[torch.Tensor],
+                           workspace: Optional[torch.Tensor] = None):
+    """The same with unquantised BF16 weights."""
+    m, n, k, ldx, ldw = _bf16_shapes(x, w)
+    workspace, accept, idx, val = _verify_buffers(x, m, draft, mxfp4_bf16_gemm_argmax_workspace_bytes(m, n, k),
+                                                  workspace)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_bf16_gemm_verify(_ptr(x), m, ldx, _ptr(w), n, k, ldw, _ptr(draft), _ptr(accept),
+                                            _ptr(idx), _ptr(val), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream()))
+    return accept, idx, val
 
 
 def mxfp4_diag_stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:

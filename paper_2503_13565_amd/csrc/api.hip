@@ -105,12 +105,35 @@ static int pick_path(int path, int64_t M, bool mfma_ok)
     return (M >= 3 && mfma_ok) ? MXFP4_PATH_MFMA : MXFP4_PATH_VALU_CVT;
 }
 
+// Draft verification fused behind the argmax (both product forms): NULL when not asked for.
+struct Verify {
+    const int32_t* draft;
+    int32_t* accept_out;
+};
+
+static int check_verify(const Verify* v, int64_t M)
+{
+    if (!v)
+        return MXFP4_OK;
+    if (!v->accept_out)
+        return fail(MXFP4_ERR_NULL, "accept_out is NULL");
+    if (M > 1 && !v->draft)
+        return fail(MXFP4_ERR_NULL, "draft_tokens is NULL");
+    if (M > kVerifyMaxRows)
+        return fail(MXFP4_ERR_SHAPE, "M=%lld rows exceed the %d a verification pass takes", (long long)M,
+                    kVerifyMaxRows);
+    return MXFP4_OK;
+}
+
 static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const void* s, int64_t N, int64_t K,
                     void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
-                    size_t workspace_bytes, bool argmax, int path, void* stream)
+                    size_t workspace_bytes, bool argmax, int path, void* stream, const Verify* verify = nullptr)
 {
     g_err[0] = 0;
-    int rc = check_weights(q, s, N, K);
+    int rc = check_verify(verify, M);
+    if (rc)
+        return rc;
+    rc = check_weights(q, s, N, K);
     if (rc)
         return rc;
     rc = check_x(x, M, ldx, K);
@@ -181,7 +204,9 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
     if (e != hipSuccess)
         return hip_fail(e, "product launch");
     if (argmax) {
-        e = launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
+        e = verify ? launch_verify_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, verify->draft,
+                                          argmax_out, max_out, verify->accept_out, st)
+                   : launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
         if (e != hipSuccess)
             return hip_fail(e, "argmax finish launch");
     }
@@ -194,9 +219,11 @@ extern "C" size_t mxfp4_bf16_gemm_argmax_workspace_bytes(int64_t M, int64_t N, i
 
 static int run_bf16(const void* x, int64_t M, int64_t ldx, const void* w, int64_t N, int64_t K, int64_t ldw,
                     void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
-                    size_t workspace_bytes, bool argmax, void* stream)
+                    size_t workspace_bytes, bool argmax, void* stream, const Verify* verify = nullptr)
 {
     g_err[0] = 0;
+    if (int vrc = check_verify(verify, M))
+        return vrc;
     if (!w)
         return fail(MXFP4_ERR_NULL, "w_bf16 is NULL");
     if (N < 1 || N > 0x7FFFFFFF / 8)
@@ -252,7 +279,9 @@ static int run_bf16(const void* x, int64_t M, int64_t ldx, const void* w, int64_
     if (e != hipSuccess)
         return hip_fail(e, "BF16 product launch");
     if (argmax) {
-        e = launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
+        e = verify ? launch_verify_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, verify->draft,
+                                          argmax_out, max_out, verify->accept_out, st)
+                   : launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
         if (e != hipSuccess)
             return hip_fail(e, "argmax finish launch");
     }
@@ -459,6 +488,26 @@ int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx, const
 {
     return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, workspace,
                     workspace_bytes, true, path, stream);
+}
+
+int mxfp4_woq_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                          const void* scales_e8m0, int64_t N, int64_t K, const int32_t* draft_tokens,
+                          int32_t* accept_out, int32_t* argmax_out, float* max_out, void* workspace,
+                          size_t workspace_bytes, void* stream)
+{
+    const Verify v{draft_tokens, accept_out};
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, MXFP4_PATH_AUTO, stream, &v);
+}
+
+int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx, const void* w_bf16, int64_t N,
+                           int64_t K, int64_t ldw, const int32_t* draft_tokens, int32_t* accept_out,
+                           int32_t* argmax_out, float* max_out, void* workspace, size_t workspace_bytes,
+                           void* stream)
+{
+    const Verify v{draft_tokens, accept_out};
+    return run_bf16(x_bf16, M, ldx, w_bf16, N, K, ldw, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, stream, &v);
 }
 
 int mxfp4_diag_stream_read(const void* src, size_t bytes, void* sink4, void* stream)

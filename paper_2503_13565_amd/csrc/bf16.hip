@@ -280,7 +280,8 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
     int first_blocks = 0;
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
-        int mt = left >= 8 ? 8 : (left >= 4 ? 4 : (left >= 2 ? 2 : 1));
+        // the narrowest pass that takes all remaining rows (a ragged pass repeats its last row)
+        int mt = left > 4 ? 8 : (left > 2 ? 4 : (left > 1 ? 2 : 1));
         while (mt > 1 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes)
             mt >>= 1;
         const size_t lds = (size_t)mt * a.k * 2 < 256 ? 256 : (size_t)mt * a.k * 2;   // the argmax combine needs a few bytes

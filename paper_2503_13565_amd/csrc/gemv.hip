@@ -416,6 +416,73 @@ __global__ __launch_bounds__(64) void argmax_finish_kernel(const float* __restri
     }
 }
 
+// The argmax's second stage with the draft verification fused behind it (arXiv 2503.13565,
+// section 3.1: the draft tokens after the first mismatch with the target's own picks are
+// dropped).  One workgroup: wave w reduces the partial winners of rows w, w + 16, ...; the picks
+// meet in LDS; then accept[0] = G, the number of leading draft tokens that equal the picks, and
+// accept[1] = the pick at position G (the extra token the verification pass yields).  M - 1
+// draft tokens for M rows; M <= kVerifyMaxRows.
+__global__ __launch_bounds__(1024) void verify_finish_kernel(const float* __restrict__ part_val,
+                                                             const int32_t* __restrict__ part_idx, int parts,
+                                                             int parts_used, int m_rows,
+                                                             const int32_t* __restrict__ draft,
+                                                             int32_t* __restrict__ argmax_out,
+                                                             float* __restrict__ max_out,
+                                                             int32_t* __restrict__ accept)
+{
+    __shared__ int tok[kVerifyMaxRows];
+    __shared__ int first;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0)
+        first = m_rows - 1;
+    for (int m = wave; m < m_rows; m += 16) {
+        const float* pv = part_val + (int64_t)m * parts;
+        const int32_t* pi = part_idx + (int64_t)m * parts;
+        float bv = -INFINITY;
+        int bi = 0x7FFFFFFF;
+        for (int p0 = lane; p0 < parts_used; p0 += 64 * 8) {
+            float v[8];
+            int i[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + 64 * u;
+                v[u] = p < parts_used ? pv[p] : -INFINITY;
+                i[u] = p < parts_used ? pi[p] : 0x7FFFFFFF;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (v[u] > bv || (v[u] == bv && i[u] < bi)) {
+                    bv = v[u];
+                    bi = i[u];
+                }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const float v = __shfl_xor(bv, off);
+            const int i = __shfl_xor(bi, off);
+            if (v > bv || (v == bv && i < bi)) {
+                bv = v;
+                bi = i;
+            }
+        }
+        if (lane == 0) {
+            bi = bi == 0x7FFFFFFF ? 0 : bi;
+            tok[m] = bi;
+            argmax_out[m] = bi;
+            if (max_out)
+                max_out[m] = bv;
+        }
+    }
+    __syncthreads();
+    if (tid < m_rows - 1 && draft[tid] != tok[tid])
+        atomicMin(&first, tid);                         // LDS atomic: the first mismatch
+    __syncthreads();
+    if (tid == 0) {
+        accept[0] = first;
+        accept[1] = tok[first];
+    }
+}
+
 int gemv_max_parts(const DeviceInfo& dev) { return dev.cus * 8; }
 
 namespace {
@@ -562,6 +629,17 @@ hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, 
 {
     hipLaunchKernelGGL(argmax_finish_kernel, dim3(m), dim3(64), 0, stream, part_val, part_idx, parts,
                        parts_used, argmax_out, max_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
+                                int m, const int32_t* draft, int32_t* argmax_out, float* max_out,
+                                int32_t* accept_out, hipStream_t stream)
+{
+    if (m < 1 || m > kVerifyMaxRows)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(verify_finish_kernel, dim3(1), dim3(1024), 0, stream, part_val, part_idx, parts,
+                       parts_used, m, draft, argmax_out, max_out, accept_out);
     return hipGetLastError();
 }
 

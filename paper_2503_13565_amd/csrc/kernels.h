@@ -77,6 +77,14 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
 hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
                                 int m, int32_t* argmax_out, float* max_out, hipStream_t stream);
 
+// The same second stage with the greedy draft verification fused behind it, one workgroup:
+// draft[m - 1] tokens are compared with the picks; accept_out[0] = accepted draft tokens,
+// accept_out[1] = the pick that follows them.  m <= kVerifyMaxRows.
+constexpr int kVerifyMaxRows = 1024;
+hipError_t launch_verify_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
+                                int m, const int32_t* draft, int32_t* argmax_out, float* max_out,
+                                int32_t* accept_out, hipStream_t stream);
+
 // Plain streaming kernels used to measure what the memory system delivers.
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, const DeviceInfo& dev,
                               hipStream_t stream);
