@@ -55,7 +55,8 @@ enum {
  * For every 32-element block along K: scale byte = max(biased_exponent(amax) - 2, 0), i.e.
  * X = 2^(floor(log2 amax) - 2); each element v/X is rounded to the nearest E2M1 value, ties to
  * the even code, saturating at +-6, sign bit preserved (also for zeros).  A block holding NaN
- * or Inf gets scale 0xFF and zero nibbles.  Integer-only on the BF16 bit patterns.
+ * or Inf gets scale 0xFF and zero nibbles.  Maximum and scale are integer arithmetic on the BF16
+ * bit patterns; the elements are rounded by the gfx950 scaled BF16->FP4 convert.
  *   w_bf16      in  BF16 [N, K], row stride ldw elements (ldw >= K, ldw % 8 == 0, 16-byte aligned)
  *   q_packed    out uint8 [N, K/2]   (4-byte aligned)
  *   scales_e8m0 out uint8 [N, K/32]
@@ -63,6 +64,12 @@ enum {
  */
 int mxfp4_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
                       void* q_packed, void* scales_e8m0, void* stream);
+
+/* The same cast with the elements rounded by the integer-only rule on the bit patterns rather
+ * than by the gfx950 scaled BF16->FP4 convert instruction; both give the same bits (kept so that
+ * each can be checked against the other and against the CPU definition). */
+int mxfp4_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                           void* q_packed, void* scales_e8m0, void* stream);
 
 /*
  * Dequantise to BF16 (exact whenever 2^(scale-127) * 6 is a normal BF16 number): the inverse

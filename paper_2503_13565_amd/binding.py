@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmxfp4_hip.so")
 PATH_AUTO, PATH_VALU_BITS, PATH_VALU_CVT, PATH_VALU_LUT, PATH_MFMA = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm", "mxfp4_woq_gemm_path",
+    "mxfp4_direct_cast", "mxfp4_direct_cast_bits", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm", "mxfp4_woq_gemm_path",
     "mxfp4_woq_gemm_workspace_bytes", "mxfp4_woq_gemm_ws", "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
@@ -46,6 +46,8 @@ def load() -> ctypes.CDLL:
     lib = ctypes.CDLL(LIB_PATH)
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
     lib.mxfp4_direct_cast.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    lib.mxfp4_direct_cast_bits.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    lib.mxfp4_direct_cast_bits.restype = i32
     lib.mxfp4_dequant.argtypes = [vp, vp, i64, i64, vp, i64, vp]
     lib.mxfp4_dequant_hwcvt.argtypes = [vp, vp, i64, i64, vp, i64, vp]
     lib.mxfp4_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
@@ -70,7 +72,7 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_bf16_gemm_verify.restype = i32
     lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
-    for name in ("mxfp4_direct_cast", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
+    for name in ("mxfp4_direct_cast", "mxfp4_direct_cast_bits", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
                  "mxfp4_woq_gemm_path", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
                  "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy"):
         getattr(lib, name).restype = i32
@@ -103,8 +105,10 @@ def version() -> str:
 
 
 def mxfp4_direct_cast(w: torch.Tensor, q: Optional[torch.Tensor] = None,
-                      s: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """BF16 ``[N,K]`` (last dim contiguous) -> (q uint8 ``[N,K/2]``, s uint8 ``[N,K/32]``)."""
+                      s: Optional[torch.Tensor] = None, integer_rule: bool = False
+                      ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """BF16 ``[N,K]`` (last dim contiguous) -> (q uint8 ``[N,K/2]``, s uint8 ``[N,K/32]``).
+    ``integer_rule`` calls ``mxfp4_direct_cast_bits``."""
     _dev(w)
     if w.dtype != torch.bfloat16 or w.dim() != 2 or w.stride(1) != 1:
         raise ValueError("w must be a 2-D BF16 tensor with a contiguous last dimension")
@@ -115,7 +119,8 @@ def mxfp4_direct_cast(w: torch.Tensor, q: Optional[torch.Tensor] = None,
         s = torch.empty((n, k // 32), dtype=torch.uint8, device=w.device)
     ldw = w.stride(0) if n > 1 else max(k, 1)
     with torch.cuda.device(w.device):
-        _check(load().mxfp4_direct_cast(_ptr(w), n, k, ldw, _ptr(q), _ptr(s), _stream()))
+        fn = load().mxfp4_direct_cast_bits if integer_rule else load().mxfp4_direct_cast
+        _check(fn(_ptr(w), n, k, ldw, _ptr(q), _ptr(s), _stream()))
     return q, s
 
 

@@ -340,8 +340,8 @@ using namespace mxfp4;
 
 extern "C" {
 
-int mxfp4_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q_packed,
-                      void* scales_e8m0, void* stream)
+static int cast_impl(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q_packed, void* scales_e8m0,
+                     bool integer_rule, void* stream)
 {
     g_err[0] = 0;
     if (N < 0 || N > 0x7FFFFFFF)
@@ -358,8 +358,21 @@ int mxfp4_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, voi
         return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
     if (!aligned(q_packed, 4))
         return fail(MXFP4_ERR_ALIGN, "q_packed must be 4-byte aligned");
-    hipError_t e = launch_direct_cast(w_bf16, N, K, ldw, q_packed, scales_e8m0, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_direct_cast(w_bf16, N, K, ldw, q_packed, scales_e8m0, integer_rule,
+                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MXFP4_OK : hip_fail(e, "direct cast launch");
+}
+
+int mxfp4_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q_packed,
+                      void* scales_e8m0, void* stream)
+{
+    return cast_impl(w_bf16, N, K, ldw, q_packed, scales_e8m0, false, stream);
+}
+
+int mxfp4_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q_packed,
+                           void* scales_e8m0, void* stream)
+{
+    return cast_impl(w_bf16, N, K, ldw, q_packed, scales_e8m0, true, stream);
 }
 
 static int dequant_impl(const void* q, const void* s, int64_t N, int64_t K, void* w, int64_t ldw, bool hw,

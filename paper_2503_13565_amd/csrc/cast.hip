@@ -1,9 +1,11 @@
 // BF16 -> MXFP4 direct cast and its inverse for gfx950 (arXiv 2503.13565, section 3.4.3:
 // the two-step quantisation; E2M1 elements, one E8M0 scale per 32 elements along K).
 //
-// Integer-only on the BF16 bit patterns.  Four lanes share one 32-element block: each lane
-// loads 16 bytes (8 elements), the block maximum is taken across the quad with DPP, and each
-// lane writes one packed dword; a wave therefore reads 1 KiB and writes 256 B, contiguous.
+// Four lanes share one 32-element block: each lane loads 16 bytes (8 elements), the block maximum
+// is taken across the quad with DPP on the integer magnitudes, the scale byte is integer
+// arithmetic on the BF16 exponent, and each lane writes one packed dword; a wave therefore reads
+// 1 KiB and writes 256 B, contiguous.  The elements are rounded by the gfx950 scaled BF16->FP4
+// convert, or by an integer-only rule on the bit patterns that gives the same bits.
 #include "common.h"
 #include "kernels.h"
 
@@ -30,21 +32,14 @@ __device__ __forceinline__ uint32_t quantise_e2m1(uint32_t mag, int scale_byte)
     return code > 7u ? 7u : code;
 }
 
-__global__ __launch_bounds__(256) void direct_cast_kernel(const uint16_t* __restrict__ w,
-                                                          int64_t n_rows, int k, int64_t ldw,
-                                                          uint32_t* __restrict__ q,
-                                                          uint8_t* __restrict__ s)
+// One 8-element group (16 bytes of BF16) of a block per lane; the four lanes of a quad hold one
+// 32-element block.  kHw: elements are rounded by the gfx950 scaled BF16->FP4 convert (one
+// instruction per element pair; checked on the device against the integer rule above for every
+// finite BF16 value and every scale byte); otherwise by the integer rule.
+template <bool kHw>
+__device__ __forceinline__ void cast_group(const u32x4_t v, uint32_t* packed_out, int* scale_out)
 {
-    const int groups_per_row = k >> 3;               // 8-element groups; a multiple of 4
-    const int64_t total = n_rows * groups_per_row;
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (gid >= total)
-        return;                                      // quads are never split: total % 4 == 0
-    const int64_t row = gid / groups_per_row;
-    const int cg = (int)(gid - row * groups_per_row);
-    const uint4 v = *reinterpret_cast<const uint4*>(w + row * ldw + (int64_t)cg * 8);
-    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
-
+    const uint32_t d[4] = {v[0], v[1], v[2], v[3]};
     uint32_t amax = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -62,17 +57,67 @@ __global__ __launch_bounds__(256) void direct_cast_kernel(const uint16_t* __rest
     } else {
         scale_byte = (int)(amax >> 7) - 2;           // biased exponent of amax, minus 2
         scale_byte = scale_byte < 0 ? 0 : scale_byte;
+        if constexpr (kHw) {
+            // the convert divides by 2^(exponent field - 127) of its scale operand (field 0 is 2^-127)
+            const float scale = __uint_as_float((uint32_t)scale_byte << 23);
+            const uint32_t d0 = d[0], d1 = d[1], d2 = d[2], d3 = d[3];
+            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, __builtin_bit_cast(bf16x2_t, d0), scale, 0);
+            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, __builtin_bit_cast(bf16x2_t, d1), scale, 1);
+            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, __builtin_bit_cast(bf16x2_t, d2), scale, 2);
+            packed = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(packed, __builtin_bit_cast(bf16x2_t, d3), scale, 3);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = d[i] & 0xFFFFu, hi = d[i] >> 16;
-            const uint32_t nlo = quantise_e2m1(lo & 0x7FFFu, scale_byte) | ((lo >> 15) << 3);
-            const uint32_t nhi = quantise_e2m1(hi & 0x7FFFu, scale_byte) | ((hi >> 15) << 3);
-            packed |= (nlo | (nhi << 4)) << (8 * i);
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t lo = d[i] & 0xFFFFu, hi = d[i] >> 16;
+                const uint32_t nlo = quantise_e2m1(lo & 0x7FFFu, scale_byte) | ((lo >> 15) << 3);
+                const uint32_t nhi = quantise_e2m1(hi & 0x7FFFu, scale_byte) | ((hi >> 15) << 3);
+                packed |= (nlo | (nhi << 4)) << (8 * i);
+            }
         }
     }
-    q[gid] = packed;
-    if ((cg & 3) == 0)
-        s[gid >> 2] = (uint8_t)scale_byte;
+    *packed_out = packed;
+    *scale_out = scale_byte;
+}
+
+// Persistent grid-stride walk over the groups, kU independent loads in flight per lane.  kFlat:
+// rows are contiguous (ldw == K), so a group's address needs no division.  The grid's stride is a
+// multiple of 4 groups, so quads are never split.
+template <bool kHw, bool kFlat>
+__global__ __launch_bounds__(256) void direct_cast_kernel(const uint16_t* __restrict__ w,
+                                                          int64_t n_rows, int k, int64_t ldw,
+                                                          uint32_t* __restrict__ q,
+                                                          uint8_t* __restrict__ s)
+{
+    constexpr int kU = 4;
+    const int groups_per_row = k >> 3;               // 8-element groups; a multiple of 4
+    const int64_t total = n_rows * groups_per_row;   // a multiple of 4
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < total; g0 += kU * stride) {
+        u32x4_t v[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            int64_t gid = g0 + u * stride;
+            gid = gid < total ? gid : g0;            // surplus slots repeat the first (never stored)
+            int64_t off = gid * 8;
+            if constexpr (!kFlat) {
+                const int64_t row = gid / groups_per_row;
+                off = row * ldw + (gid - row * groups_per_row) * 8;
+            }
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w + off));
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int64_t gid = g0 + u * stride;
+            uint32_t packed;
+            int scale_byte;
+            cast_group<kHw>(v[u], &packed, &scale_byte);   // whole quads take part in the DPP steps
+            if (gid < total) {
+                q[gid] = packed;
+                if ((gid & 3) == 0)
+                    s[gid >> 2] = (uint8_t)scale_byte;
+            }
+        }
+    }
 }
 
 // q, s -> BF16 (scale * magnitude, exact while the product is a normal BF16).  One lane per
@@ -116,14 +161,20 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
 }
 
 hipError_t launch_direct_cast(const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q, void* s,
-                              hipStream_t stream)
+                              bool bits, hipStream_t stream)
 {
     const int64_t total = n_rows * (k / 8);
     if (total == 0)
         return hipSuccess;
-    const int64_t blocks = (total + 255) / 256;
-    hipLaunchKernelGGL(direct_cast_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       (const uint16_t*)w, n_rows, (int)k, ldw, (uint32_t*)q, (uint8_t*)s);
+    int64_t blocks = (total + 255) / 256;
+    const int64_t resident = 256 * 8;                // 8 workgroups of 4 waves per CU on the target part
+    if (blocks > resident)
+        blocks = resident;
+    const bool flat = ldw == k;
+    auto kern = bits ? (flat ? direct_cast_kernel<false, true> : direct_cast_kernel<false, false>)
+                     : (flat ? direct_cast_kernel<true, true> : direct_cast_kernel<true, false>);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint16_t*)w, n_rows, (int)k,
+                       ldw, (uint32_t*)q, (uint8_t*)s);
     return hipGetLastError();
 }
 

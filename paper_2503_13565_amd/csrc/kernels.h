@@ -34,8 +34,9 @@ struct DeviceInfo {
     int lds_bytes;       // LDS per workgroup the device allows
 };
 
+// `integer_rule`: round the elements with the integer-only rule instead of the convert instruction.
 hipError_t launch_direct_cast(const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q, void* s,
-                              hipStream_t stream);
+                              bool integer_rule, hipStream_t stream);
 hipError_t launch_dequant(const void* q, const void* s, int64_t n_rows, int64_t k, void* w, int64_t ldw,
                           bool hw_convert, hipStream_t stream);
 

@@ -22,8 +22,12 @@ def oracle_cast_t(w: torch.Tensor, threads: int = 0):
 
 
 def gpu_cast(w: torch.Tensor):
-    q, s = binding.mxfp4_direct_cast(w.to(DEV))
+    """The cast as the product path runs it; the integer-rule variant must give the same bits."""
+    wg = w.to(DEV)
+    q, s = binding.mxfp4_direct_cast(wg)
+    q2, s2 = binding.mxfp4_direct_cast(wg, integer_rule=True)
     torch.cuda.synchronize()
+    assert torch.equal(q, q2) and torch.equal(s, s2), "convert instruction and integer rule disagree"
     return q, s
 
 
