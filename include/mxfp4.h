@@ -103,12 +103,14 @@ int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx,
 
 /*
  * The same product with a caller-provided scratch buffer.  When the activation rows of a pass do
- * not fit the LDS of a compute unit whole (M * K large), the MFMA path cuts K into phases that
- * run side by side and adds their FP32 partial products in a fixed order in a second kernel;
- * the partial products live in `workspace`.  Without it (NULL, or smaller than
- * mxfp4_woq_gemm_workspace_bytes) the call still works and passes over the weights several
- * times instead.  workspace: 8-byte aligned, contents unspecified before and after; calls that
- * overlap in time must not share it.  `path` as in mxfp4_woq_gemm_path.
+ * not fit the LDS of a compute unit whole (M * K large), the MFMA path cuts K into phases.  With
+ * `workspace` the phases run side by side on different compute units and a second kernel adds
+ * their FP32 partial products, which live in the workspace, in a fixed order: the fast form.
+ * Without it (NULL, or smaller than mxfp4_woq_gemm_workspace_bytes, which is 0 when no split is
+ * needed) the call still works: the phases then run one after the other inside the kernel, or,
+ * for matrices with very many output rows per compute unit, in narrower passes over the weights.
+ * workspace: 8-byte aligned, contents unspecified before and after; calls that overlap in time
+ * must not share it.  `path` as in mxfp4_woq_gemm_path.
  */
 size_t mxfp4_woq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int mxfp4_woq_gemm_ws(const void* x_bf16, int64_t M, int64_t ldx,

@@ -48,12 +48,12 @@ hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceI
 int gemv_max_parts(const DeviceInfo& dev);
 
 // 16-row MFMA tiles (bf16 16x16x32) for verification batches; passes of up to 16 activation rows.
-// mfma_can_run: K % 128 == 0 and the LDS copy of 4 activation rows fits.
+// When the activation rows of a pass do not fit the LDS whole, K is split: in space over
+// workgroups through a workspace of mfma_splitk_bytes() with a second kernel that adds the partial
+// products in a fixed order; without a workspace in time inside the kernel when a workgroup's
+// tiles are few enough to keep their running sums in LDS; else in narrower passes.
+// mfma_can_run: K % 128 == 0 and four activation rows can run in one of these ways.
 bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev, bool have_splitk_ws);
-// With a workspace of mfma_splitk_bytes() the activations need not fit the LDS whole: K is cut
-// into phases handled by different workgroups and a second kernel adds the partial products in a
-// fixed order.  `splitk_ws` may be NULL: then every pass holds all of K (narrower passes, more of
-// them, when the activations are too large).
 size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev);
 hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
                        hipStream_t stream);

@@ -64,10 +64,18 @@ struct MItem {
 struct MPos {
     int tile;
     int c;          // item within the tile
+    int ph;         // phase of the in-time K split this workgroup is in (0 when there is none)
 };
 
 // MP: activation rows held per pass (4, 8 or 16); NW: compute waves per workgroup (they split K);
-// the workgroup has NW + 1 waves, wave 0 is the epilogue wave.
+// the workgroup has NW + 1 waves, wave 0 is the epilogue wave; D: register buffers.
+//
+// K split.  When MP rows of all of K do not fit the LDS, K is cut into a.phases runs of
+// a.phase_steps steps.  In time (a.splitk_ws == NULL): the workgroup walks the phases one after
+// the other over all its tiles; every compute wave re-copies its activation slice when it enters
+// a phase, and the epilogue wave keeps each tile's running FP32 sum in LDS until the last phase.
+// In space (a.splitk_ws != NULL): grid dimension y is the phase and the partial products go to
+// the workspace (for matrices with too many tiles per workgroup to keep their sums in LDS).
 template <int MP, int NW, int D>
 __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
 {
@@ -76,19 +84,23 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + x_lds_bytes<NW>(a.phase_steps, MP));   // [2][NW][64] partial tiles
     const int scw = scale_row_dwords_t<NW>(a.phase_steps);
     uint32_t* sc = reinterpret_cast<uint32_t*>(red + 2 * NW * 64);           // [2][16][scw] scale blocks
+    f32x4_t* accl = reinterpret_cast<f32x4_t*>(sc + 2 * 16 * scw);           // [tiles of this workgroup][64] running sums
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kw = wave - 1;                                      // K slice of a compute wave
     const int li = lane & 15, lg = lane >> 4;
     const int nblk = a.k >> 5;
     const int q_row_bytes = a.k >> 1;
-    // this workgroup's K range in steps of 4 blocks: all of K, or one phase of the split-K form
-    const int t_begin = (int)blockIdx.y * a.phase_steps;
-    const int t_end = min(a.k >> 7, t_begin + a.phase_steps);
-    const int t_total = t_end - t_begin;
-    // steps per wave and tile, in whole items of kCh steps, so that an item's 16 scale bytes per
-    // row are one run that starts at a multiple of 16 blocks
-    const int items = ((t_total + kCh - 1) / kCh + NW - 1) / NW;
+    const int steps_all = a.k >> 7;                               // steps of 4 blocks in all of K
+    const bool in_space = a.splitk_ws != nullptr;
+    const int n_ph = in_space ? 1 : a.phases;                     // phases this workgroup walks
+    __builtin_assume(n_ph >= 1);
+    const int ph0 = in_space ? (int)blockIdx.y : 0;
+    auto t_begin_of = [&](int ph) { return (ph0 + ph) * a.phase_steps; };
+    auto t_total_of = [&](int ph) { return min(steps_all - (ph0 + ph) * a.phase_steps, a.phase_steps); };
+    // steps per wave and tile, in whole items of kCh steps (the same in every phase; a shorter last
+    // phase leaves steps absent)
+    const int items = ((a.phase_steps + kCh - 1) / kCh + NW - 1) / NW;
     const int steps_w = items * kCh;
     const int n_tiles = (a.n + 15) >> 4;
     const bool argmax = a.part_val != nullptr;
@@ -104,18 +116,18 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     // barrier is needed.  Per item (64 chunks of 8 elements, one per lane) the MP rows' loads are
     // all in flight together.  Chunk 4 g + j of step u goes to slot 16 u + 4 j + g: the four lane
     // groups of one MFMA then read four adjacent segments, 1 KiB contiguous per wave read at
-    // MP = 16, free of bank conflicts.  Rows past M repeat the last; steps past the end of K copy
-    // the last step (their weights are zero).
+    // MP = 16, free of bank conflicts.  Rows past M repeat the last; steps past the end of the
+    // phase copy its last step (their weights are zero).
     u32x4_t* xw = xs + (size_t)max(kw, 0) * steps_w * 16 * MP;
-    constexpr int kXLoads = MP > 8 ? MP : 8;                      // loads in flight per batch (registers:
-    constexpr int kXBatch = kXLoads / MP;                         // two workgroups per CU need <= 96)
+    constexpr int kXLoads = MP > 8 ? MP : 8;                      // loads in flight per batch
+    constexpr int kXBatch = kXLoads / MP;
     u32x4_t xv[kXLoads];
-    auto x_load = [&](int c0) {
+    auto x_load = [&](int c0, int ph) {
 #pragma unroll
         for (int i = 0; i < kXBatch; ++i) {
             const int c = min(c0 + i, items - 1);                 // a batch's surplus repeats the last item
-            const int t = min(kw * steps_w + c * kCh + (lane >> 4), t_total - 1);
-            const int chunk = (t_begin + t) * 16 + (lane & 15);
+            const int t = min(kw * steps_w + c * kCh + (lane >> 4), t_total_of(ph) - 1);
+            const int chunk = (t_begin_of(ph) + t) * 16 + (lane & 15);
 #pragma unroll
             for (int m = 0; m < MP; ++m) {
                 const int msrc = min(m0 + m, a.m - 1);
@@ -134,61 +146,87 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         }
     };
 
-    auto valid = [&](const MPos& p) { return p.tile < n_tiles; };
-    auto advance = [&](MPos& p) {
-        if (++p.c == items) {
-            p.c = 0;
-            p.tile += gridDim.x;
-        }
+    // The walk: phase by phase, within a phase this workgroup's tiles in ascending order, within
+    // a tile this wave's items.
+    auto valid = [&](const MPos& p) { return p.ph < n_ph; };
+    // (selects and bitwise conditions rather than branches and short-circuits throughout the walk:
+    // once the compiler turns a condition on the position into control flow around the loads it
+    // can no longer count the loads in flight)
+    auto next_tile = [&](int* tile, int* ph) {
+        const int t = *tile + (int)gridDim.x;
+        const bool wrap = t >= n_tiles;
+        *tile = wrap ? (int)blockIdx.x : t;
+        *ph += wrap ? 1 : 0;
     };
-    // Step T of this wave for slot u of item c, and whether it exists (wave-uniform).
+    auto advance = [&](MPos& p) {
+        const bool last = p.c + 1 == items;
+        int tile = p.tile, ph = p.ph;
+        next_tile(&tile, &ph);
+        p.c = last ? 0 : p.c + 1;
+        p.tile = last ? tile : p.tile;
+        p.ph = last ? ph : p.ph;
+    };
+    // Step T (relative to its phase) of this wave for slot u of item c, and whether it exists.
     auto step_of = [&](const MPos& p, int u, bool* ok) {
-        const int local = p.c * kCh + u;
-        const int t = kw * steps_w + local;                       // relative to t_begin
-        *ok = valid(p) && local < steps_w && t < t_total;
+        const int t = kw * steps_w + p.c * kCh + u;
+        *ok = (int)valid(p) & (int)(t < t_total_of(p.ph));
         return t;
     };
     // Scales.  A tile's scale block is 16 rows x t_total dwords (a dword holds the four scales of one
     // step).  A lane needs 16 bytes of ONE row per item, which as a load touches 16 cache lines per
     // wave for 256 useful bytes and fills the L1 with lines it uses an eighth of.  Instead the
-    // workgroup's waves fetch the block of the NEXT tile together, one dword per lane and item in
-    // row-major order (256 contiguous bytes per wave load), park it in LDS, and every wave reads the
-    // 16 bytes it needs from there after the barrier that ends the tile.
+    // workgroup's waves fetch the block of the NEXT tile of the walk together, one dword per lane
+    // and item in row-major order (256 contiguous bytes per wave load), park it in LDS, and every
+    // wave reads the 16 bytes it needs from there after the barrier that ends the tile.
     // Dword d = (c * NW + kw) * 64 + lane of the block: its row and step, false past the block.
-    // (d / t_total by multiplication: exact for d < 2^14 and t_total <= 2^9, which K <= 65536 keeps)
-    const uint32_t t_magic = __builtin_amdgcn_readfirstlane((1u << 24) / (uint32_t)t_total + 1u);
-    auto sp_place = [&](int c, int* r, int* t) {
+    // (d / t_total by multiplication: exact for d < 2^14 and t_total <= 2^9, which K <= 65536 keeps;
+    // t_total is a.phase_steps except in the last phase of K)
+    const int tt_last = steps_all - (a.phases - 1) * a.phase_steps;
+    const uint32_t magic_full = __builtin_amdgcn_readfirstlane((1u << 24) / (uint32_t)min(a.phase_steps, steps_all) + 1u);
+    const uint32_t magic_last = __builtin_amdgcn_readfirstlane((1u << 24) / (uint32_t)tt_last + 1u);
+    auto sp_place = [&](int c, int ph, int* r, int* t) {
+        const bool last = ph0 + ph == a.phases - 1;
+        const uint32_t tt = (uint32_t)t_total_of(ph);
         const uint32_t d = (uint32_t)((c * NW + kw) * 64 + lane);
-        const uint32_t rr = __umulhi(d << 8, t_magic);
+        const uint32_t rr = __umulhi(d << 8, last ? magic_last : magic_full);
         *r = (int)rr;
-        *t = (int)(d - rr * (uint32_t)t_total);
+        *t = (int)(d - rr * tt);
         return rr < 16u;
     };
-    auto sp_load = [&](int tile, int c) {
+    // the scale block of tile `tile` in phase `ph` (ph == n_ph: there is none, nothing is read)
+    auto sp_load = [&](int tile, int ph, int c) {
+        const int phc = min(ph, n_ph - 1);
         int r, t;
-        const bool ok = sp_place(c, &r, &t) && tile < n_tiles;
+        const bool ok = (int)sp_place(c, phc, &r, &t) & (int)(ph < n_ph);
         const int row = min(tile * 16 + r, a.n - 1);
-        return __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? row * nblk + (t_begin + t) * 4 : kSentinel, 0, 0);
+        return __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? row * nblk + (t_begin_of(phc) + t) * 4 : kSentinel, 0, 0);
     };
-    auto sp_store = [&](int slot, int c, uint32_t v) {
+    auto sp_store = [&](int slot, int ph, int c, uint32_t v) {
         int r, t;
-        if (sp_place(c, &r, &t))
+        if (sp_place(c, min(ph, n_ph - 1), &r, &t))
             sc[(slot * 16 + r) * scw + t] = v;
     };
     // Always kCh + 1 loads per item (absent steps read nothing and return zero), so that the
     // in-order load counter can be waited on exactly.  The weight loads carry no streaming hint:
     // a wave load covers half a cache line per row and the next step wants the other half.
     auto issue = [&](const MPos& p, MItem& it) {
-        const int tile = valid(p) ? p.tile : 0;
+        const bool live = valid(p);
+        const int tile = live ? p.tile : 0;
+        const int ph = live ? p.ph : 0;
         const int row = min(tile * 16 + li, a.n - 1);             // ragged N: repeat the last row
         const int vq = row * q_row_bytes + lg * 16;
 #pragma unroll
         for (int u = 0; u < kCh; ++u) {
             bool ok;
             const int t = step_of(p, u, &ok);
-            it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel, ok ? (t_begin + t) * 64 : 0, 0);
+            // (an absent step's load differs from its neighbours' in the scalar offset, so that the
+            // compiler cannot merge them into one and lose count of the loads in flight)
+            it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, ok ? vq : kSentinel,
+                                                            ok ? (t_begin_of(ph) + t) * 64 : u * 16, 0);
         }
-        it.sp = sp_load(valid(p) ? p.tile + (int)gridDim.x : n_tiles, p.c);
+        int ntile = tile, nph = ph;
+        next_tile(&ntile, &nph);
+        it.sp = sp_load(ntile, live ? nph : n_ph, p.c);
     };
 
     const int col = li % MP;
@@ -196,31 +234,42 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     int best_idx = 0x7FFFFFFF;
 
     if (wave == 0) {
-        // Epilogue wave: one barrier per tile, like the compute waves; no loads of its own.
+        // Epilogue wave: one barrier per tile and phase, like the compute waves; no loads of its own.
         lds_barrier_mfma();                                       // scales of the first tile are in LDS
-        int tiles_done = 0;
-        for (int tile = (int)blockIdx.x; tile < n_tiles; tile += gridDim.x, ++tiles_done) {
-            const f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
-            lds_barrier_mfma();                                   // partial tiles of `tile` are in LDS
-            f32x4_t sum = slot[lane];
+        int tp_done = 0;
+        for (int ph = 0; ph < n_ph; ++ph) {
+            int ti = 0;
+            for (int tile = (int)blockIdx.x; tile < n_tiles; tile += gridDim.x, ++ti, ++tp_done) {
+                const f32x4_t* slot = red + (size_t)(tp_done & 1) * NW * 64;
+                lds_barrier_mfma();                               // partial tiles of (tile, ph) are in LDS
+                f32x4_t sum = slot[lane];
 #pragma unroll
-            for (int w = 1; w < NW; ++w)
-                sum += slot[w * 64 + lane];
-            // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
-            if (li < m_valid) {
+                for (int w = 1; w < NW; ++w)
+                    sum += slot[w * 64 + lane];
+                if (n_ph > 1) {                                   // K split in time: phases add up in order
+                    if (ph > 0)
+                        sum = accl[ti * 64 + lane] + sum;
+                    if (ph < n_ph - 1) {
+                        accl[ti * 64 + lane] = sum;
+                        continue;
+                    }
+                }
+                // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
+                if (li < m_valid) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = tile * 16 + 4 * lg + r;
-                    if (row < a.n) {
-                        if (a.splitk_ws) {
-                            a.splitk_ws[((int64_t)blockIdx.y * a.m + (m0 + li)) * a.n + row] = sum[r];
-                        } else if (argmax) {
-                            if (sum[r] > best_val) {              // rows ascend: lowest index wins ties
-                                best_val = sum[r];
-                                best_idx = row;
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = tile * 16 + 4 * lg + r;
+                        if (row < a.n) {
+                            if (in_space) {
+                                a.splitk_ws[((int64_t)blockIdx.y * a.m + (m0 + li)) * a.n + row] = sum[r];
+                            } else if (argmax) {
+                                if (sum[r] > best_val) {          // rows ascend: lowest index wins ties
+                                    best_val = sum[r];
+                                    best_idx = row;
+                                }
+                            } else {
+                                a.y[(int64_t)(m0 + li) * a.ldy + row] = f32_to_bf16_rne(sum[r]);
                             }
-                        } else {
-                            a.y[(int64_t)(m0 + li) * a.ldy + row] = f32_to_bf16_rne(sum[r]);
                         }
                     }
                 }
@@ -229,7 +278,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
     } else {
         MItem buf[D];
         MPos pos[D];
-        MPos load{(int)blockIdx.x, 0};
+        MPos load{(int)blockIdx.x, 0, 0};
         // The weight loads go out first, with as few instructions in front of them as possible:
         // at three waves per SIMD every hundred instructions of set-up delay them by half a
         // microsecond, and nothing else can start before they are back anyway.
@@ -244,38 +293,52 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         uint32_t sp0[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            sp0[i] = sp_load(i < items ? (int)blockIdx.x : n_tiles, i);
-        x_load(0);
+            sp0[i] = sp_load((int)blockIdx.x, i < items ? 0 : n_ph, i);
+        x_load(0, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             if (i < items)
-                sp_store(0, i, sp0[i]);
+                sp_store(0, 0, i, sp0[i]);
         x_store(0);
 #pragma unroll 1
         for (int c0 = kXBatch; c0 < items; c0 += kXBatch) {       // long K slices: the rest, batch by batch
-            x_load(c0);
+            x_load(c0, 0);
             x_store(c0);
         }
 #pragma unroll 1
         for (int c0 = 4; c0 < items; c0 += 4) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                sp0[i] = sp_load(c0 + i < items ? (int)blockIdx.x : n_tiles, c0 + i);
+                sp0[i] = sp_load((int)blockIdx.x, c0 + i < items ? 0 : n_ph, c0 + i);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 if (c0 + i < items)
-                    sp_store(0, c0 + i, sp0[i]);
+                    sp_store(0, 0, c0 + i, sp0[i]);
         }
         lds_barrier_mfma();                                       // scales of the first tile are in LDS
 
         f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: even and odd j
-        int tiles_done = 0;
+        int tp_done = 0;              // (tile, phase) pairs finished by this workgroup
+        int cur_ph = 0;               // phase whose activations this wave holds in LDS
         auto compute = [&](const MPos& p, const MItem& it) {
+            if (p.ph != cur_ph) {
+                // entering the next phase of an in-time K split: this wave's slice of its activations
+#pragma unroll 1
+                for (int c0 = 0; c0 < items; c0 += kXBatch) {
+                    x_load(c0, p.ph);
+                    x_store(c0);
+                }
+                cur_ph = p.ph;
+            }
             // the four steps' scale dwords of this lane's row; byte lg of dword u is its block's scale
             const u32x4_t sv = *reinterpret_cast<const u32x4_t*>(
-                sc + ((tiles_done & 1) * 16 + li) * scw + kw * steps_w + p.c * kCh);
-            sp_store((tiles_done + 1) & 1, p.c, it.sp);
+                sc + ((tp_done & 1) * 16 + li) * scw + kw * steps_w + p.c * kCh);
+            {
+                int ntile = p.tile, nph = p.ph;
+                next_tile(&ntile, &nph);
+                sp_store((tp_done + 1) & 1, nph, p.c, it.sp);
+            }
 #pragma unroll
             for (int u = 0; u < kCh; ++u) {
                 bool ok;
@@ -288,15 +351,15 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
                 // The convert reads the exponent field as E8M0.  A step past the end of K gets scale
                 // 2^-127 (its weights are zero, and what LDS holds there could say NaN).
                 const uint32_t sbyte = ok ? ((sv[u] >> (8 * lg)) & 0xFFu) : 0u;
-                const float sc = __uint_as_float(sbyte << 23);
+                const float scl = __uint_as_float(sbyte << 23);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t qd = it.q[u][j];
                     u32x4_t w;
-                    w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0));
-                    w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1));
-                    w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2));
-                    w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3));
+                    w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 0));
+                    w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 1));
+                    w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 2));
+                    w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 3));
                     if (j & 1)
                         acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
                                                                        __builtin_bit_cast(bf16x8_t, xb[j]), acc1, 0, 0, 0);
@@ -307,12 +370,12 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
             }
             if (p.c == items - 1) {
                 // end of the tile: leave the partial tile for the epilogue wave
-                f32x4_t* slot = red + (size_t)(tiles_done & 1) * NW * 64;
+                f32x4_t* slot = red + (size_t)(tp_done & 1) * NW * 64;
                 slot[kw * 64 + lane] = acc0 + acc1;
                 acc0 = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 acc1 = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 lds_barrier_mfma();
-                ++tiles_done;
+                ++tp_done;
             }
         };
 
@@ -331,7 +394,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
         }
     }
 
-    if (argmax && !a.splitk_ws && wave == 0) {
+    if (argmax && !in_space && wave == 0) {
         // combine the four lane groups of each column (value desc, index asc), publish one partial
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
@@ -405,10 +468,11 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a)
 // Launch one pass.  The grid is what is resident at once (asked of the runtime: the LDS a
 // workgroup may use is less than the nominal size divides into), by default one workgroup per CU
 // (measured: eight compute waves per CU with two items in flight each already saturate the memory
-// system, and a second workgroup only lengthens the start-up burst), split over the phases.
-// *blocks is the cap on workgroups per phase on entry (0 = none) and the count used on return.
+// system, and a second workgroup only lengthens the start-up burst), split over grid_y phases
+// when K is split in space.  *blocks is the cap on workgroups per phase on entry (0 = none) and
+// the count used on return.
 template <int MP, int NW, int D>
-hipError_t launch_one(const GemmArgs& a, int m0, int phases, size_t lds, const DeviceInfo& dev, int* blocks,
+hipError_t launch_one(const GemmArgs& a, int m0, int grid_y, size_t lds, const DeviceInfo& dev, int* blocks,
                       hipStream_t stream)
 {
     auto kern = mfma_kernel<MP, NW, D>;
@@ -438,14 +502,14 @@ hipError_t launch_one(const GemmArgs& a, int m0, int phases, size_t lds, const D
     }();
     const int per_cu = occ < 1 ? 1 : (occ > max_per_cu ? max_per_cu : occ);
     const int n_tiles = (a.n + 15) / 16;
-    int nb = dev.cus * per_cu / phases;
+    int nb = dev.cus * per_cu / grid_y;
     nb = nb < 1 ? 1 : (nb > n_tiles ? n_tiles : nb);
     if (nb > gemv_max_parts(dev))
         nb = gemv_max_parts(dev);
     if (*blocks > 0 && nb > *blocks)
         nb = *blocks;
     *blocks = nb;
-    hipLaunchKernelGGL(kern, dim3(nb, phases), dim3((NW + 1) * 64), lds, stream, a, m0);
+    hipLaunchKernelGGL(kern, dim3(nb, grid_y), dim3((NW + 1) * 64), lds, stream, a, m0);
     return hipGetLastError();
 }
 
@@ -453,6 +517,7 @@ constexpr int kNW = 8;
 
 constexpr size_t kRedBytes = (size_t)2 * kNW * 64 * 16;
 constexpr int kGrain = kNW * kCh;      // steps that give every compute wave one item
+constexpr size_t kAccCap = 16 * 1024;  // in-time split: running sums of at most 16 tiles per workgroup in LDS
 
 size_t lds_need(int steps, int mp)
 {
@@ -470,19 +535,21 @@ size_t lds_target(const DeviceInfo& dev)
     return env > 0 ? (size_t)env : (size_t)dev.lds_bytes;
 }
 
-// Steps per phase (a multiple of kCh) and number of phases for a pass of `mp` activation rows.
-void plan_phases(int k, int mp, const DeviceInfo& dev, bool may_split, int* phase_steps, int* phases)
+// Steps per phase (a multiple of kCh) and number of phases for a pass of `mp` activation rows,
+// with `reserve` bytes of LDS kept for other use.
+void plan_phases(int k, int mp, const DeviceInfo& dev, bool may_split, size_t reserve, int* phase_steps,
+                 int* phases)
 {
     const int t_total = k / 128;
     int steps = (t_total + kCh - 1) / kCh * kCh;
     if (may_split) {
         // per step: 256 bytes of activations per row and 2 x 16 scale dwords; 512 more for the skew
-        const size_t fixed = kRedBytes + 512, per_step = (size_t)256 * mp + 128;
-        int fit = (int)((lds_target(dev) - fixed) / per_step) / kGrain * kGrain;
-        if (fit < kGrain)
+        const size_t fixed = kRedBytes + 512 + reserve, per_step = (size_t)256 * mp + 128;
+        int fit = lds_target(dev) > fixed ? (int)((lds_target(dev) - fixed) / per_step) / kGrain * kGrain : 0;
+        if (fit < kGrain && (size_t)dev.lds_bytes > fixed)
             fit = (int)(((size_t)dev.lds_bytes - fixed) / per_step) / kGrain * kGrain;
         if (fit < kGrain)
-            fit = kGrain;                                         // 144 KiB at 16 rows: fits gfx950
+            fit = kGrain;                                         // the caller checks that it fits
         if (fit < steps) {
             const int p = (t_total + fit - 1) / fit;
             steps = ((t_total + p - 1) / p + kCh - 1) / kCh * kCh;     // even phases
@@ -494,29 +561,64 @@ void plan_phases(int k, int mp, const DeviceInfo& dev, bool may_split, int* phas
 
 int pass_width(int left) { return left > 8 ? 16 : (left > 4 ? 8 : 4); }
 
+// Workgroups of a pass whose K is split (one per CU: its LDS is more than half full).
+int split_blocks(int n, const DeviceInfo& dev)
+{
+    const int n_tiles = (n + 15) / 16;
+    int nb = dev.cus < n_tiles ? dev.cus : n_tiles;
+    return nb < gemv_max_parts(dev) ? nb : gemv_max_parts(dev);
+}
+
+// How a pass of `mp` rows deals with activations that do not fit the LDS whole.
+enum SplitMode { kNoSplit, kInTime, kInSpace, kNarrow };
+
+// In space when the caller gave a workspace (measured faster: the phases run side by side and
+// every workgroup copies its activations once; in time every phase change exposes the latency of
+// the next copy); else in time when the workgroup's tiles are few enough to keep their running
+// sums in LDS beside one phase of activations; else narrower passes.
+SplitMode split_mode(int mp, int n, int k, const DeviceInfo& dev, bool have_ws, size_t* acc_bytes)
+{
+    const int steps_all = (k / 128 + kCh - 1) / kCh * kCh;
+    *acc_bytes = 0;
+    if (lds_need(steps_all, mp) <= (size_t)dev.lds_bytes)
+        return kNoSplit;
+    if (have_ws)
+        return kInSpace;
+    const int nb = split_blocks(n, dev);
+    const size_t acc = (size_t)(((n + 15) / 16 + nb - 1) / nb) * 1024;
+    if (acc <= kAccCap) {
+        int steps, phases;
+        plan_phases(k, mp, dev, true, acc, &steps, &phases);
+        if (lds_need(steps, mp) + acc <= (size_t)dev.lds_bytes) {
+            *acc_bytes = acc;
+            return kInTime;
+        }
+    }
+    return kNarrow;
+}
+
 }  // namespace
 
 bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev, bool have_splitk_ws)
 {
     if (a.k % 128 != 0)
         return false;
-    // with room for split-K partial products any K goes; without, four rows of all of K must fit
-    return have_splitk_ws || lds_need((a.k / 128 + kCh - 1) / kCh * kCh, 4) <= (size_t)dev.lds_bytes;
+    // four rows must be able to run: whole, split in time, or split in space with a workspace
+    size_t acc;
+    return split_mode(4, a.n, a.k, dev, have_splitk_ws, &acc) != kNarrow;
 }
 
 size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev)
 {
     if (k % 128 != 0)
         return 0;
-    int max_phases = 1;
-    for (int m0 = 0; m0 < m;) {
-        const int mp = pass_width(m - m0);
-        int steps, phases;
-        plan_phases(k, mp, dev, true, &steps, &phases);
-        max_phases = phases > max_phases ? phases : max_phases;
-        m0 += mp;
-    }
-    return max_phases > 1 ? (size_t)max_phases * m * n * sizeof(float) : 0;
+    size_t acc;
+    const int mp = pass_width(m);                                 // the first pass is the widest
+    if (split_mode(mp, n, k, dev, true, &acc) != kInSpace)
+        return 0;
+    int steps, phases;
+    plan_phases(k, mp, dev, true, 0, &steps, &phases);
+    return (size_t)phases * m * n * sizeof(float);
 }
 
 hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
@@ -525,32 +627,51 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
     if (!mfma_can_run(a_in, dev, splitk_ws != nullptr))
         return hipErrorInvalidValue;
     GemmArgs a = a_in;
-    // one plan for the whole call: the widest pass decides the phases (narrower passes fit too)
-    bool split = false;
-    int split_steps = 0, split_phases = 1;
-    if (splitk_ws) {
-        plan_phases(a.k, pass_width(a.m), dev, true, &split_steps, &split_phases);
-        split = split_phases > 1;
-    }
+    // the widest pass decides how the call deals with activations that do not fit the LDS; a split
+    // in space uses one plan for all passes (the finish kernel adds the same phases for every row)
+    size_t acc_bytes = 0;
+    const SplitMode mode = split_mode(pass_width(a.m), a.n, a.k, dev, splitk_ws != nullptr, &acc_bytes);
+    int space_steps = 0, space_phases = 1;
+    if (mode == kInSpace)
+        plan_phases(a.k, pass_width(a.m), dev, true, 0, &space_steps, &space_phases);
     int first_blocks = 0;
-    int max_phases = 1;
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
         int mp = pass_width(left);
-        int steps = split_steps, phases = split_phases;
-        if (!split) {
-            plan_phases(a.k, mp, dev, false, &steps, &phases);
-            // all of K in one pass: the widest pass whose activation copy fits the LDS
-            while (mp > 4 && lds_need(steps, mp) > (size_t)dev.lds_bytes)
+        int steps, phases, grid_y = 1;
+        size_t lds;
+        int blocks = 0;
+        a.splitk_ws = nullptr;
+        if (mode == kInSpace) {
+            steps = space_steps;
+            phases = grid_y = space_phases;
+            lds = lds_need(steps, mp);
+            a.splitk_ws = splitk_ws;
+        } else {
+            // the widest pass that runs whole or with K split in time
+            SplitMode pm = split_mode(mp, a.n, a.k, dev, false, &acc_bytes);
+            while (pm == kNarrow && mp > 4) {
                 mp >>= 1;
+                pm = split_mode(mp, a.n, a.k, dev, false, &acc_bytes);
+            }
+            if (pm == kNarrow)
+                return hipErrorInvalidValue;
+            if (pm == kInTime) {
+                plan_phases(a.k, mp, dev, true, acc_bytes, &steps, &phases);
+                lds = lds_need(steps, mp) + (phases > 1 ? acc_bytes : 0);
+                blocks = split_blocks(a.n, dev);                  // the running sums are sized for this grid
+            } else {
+                plan_phases(a.k, mp, dev, false, 0, &steps, &phases);
+                lds = lds_need(steps, mp);
+            }
         }
-        const size_t lds = lds_need(steps, mp);
+        if (lds > (size_t)dev.lds_bytes)
+            return hipErrorInvalidValue;
         // the argmax partial arrays are indexed by workgroup: no pass may use more than the first
-        int blocks = (a.part_val != nullptr && !split) ? first_blocks : 0;
-        a.splitk_ws = split ? splitk_ws : nullptr;
+        if (a.part_val != nullptr && mode != kInSpace && first_blocks > 0 && (blocks == 0 || blocks > first_blocks))
+            blocks = first_blocks;
         a.phases = phases;
         a.phase_steps = steps;
-        max_phases = phases > max_phases ? phases : max_phases;
         static const int depth = [] {                             // MXFP4_MFMA_DEPTH: measurement only
             const char* e = getenv("MXFP4_MFMA_DEPTH");
             const int v = e ? atoi(e) : 0;
@@ -558,9 +679,9 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
         }();
         hipError_t e;
 #define MXFP4_MFMA_CASE(MP_)                                                                       \
-    (depth == 4   ? launch_one<MP_, kNW, 4>(a, m0, phases, lds, dev, &blocks, stream)                \
-     : depth == 3 ? launch_one<MP_, kNW, 3>(a, m0, phases, lds, dev, &blocks, stream)                \
-                  : launch_one<MP_, kNW, 2>(a, m0, phases, lds, dev, &blocks, stream))
+    (depth == 4   ? launch_one<MP_, kNW, 4>(a, m0, grid_y, lds, dev, &blocks, stream)                \
+     : depth == 3 ? launch_one<MP_, kNW, 3>(a, m0, grid_y, lds, dev, &blocks, stream)                \
+                  : launch_one<MP_, kNW, 2>(a, m0, grid_y, lds, dev, &blocks, stream))
         if (mp == 16)
             e = MXFP4_MFMA_CASE(16);
         else if (mp == 8)
@@ -574,9 +695,10 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
             first_blocks = blocks;
         m0 += mp;
     }
-    if (split) {
+    if (mode == kInSpace) {
         // every pass used the widest pass's plan, so every row has all phases written
-        a.phases = max_phases;
+        a.splitk_ws = splitk_ws;
+        a.phases = space_phases;
         int fblocks = (a.n + 255) / 256;
         if (fblocks > gemv_max_parts(dev))
             fblocks = gemv_max_parts(dev);

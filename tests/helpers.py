@@ -84,7 +84,8 @@ def run_gemm_case(w: torch.Tensor, x: torch.Tensor, paths, what="", argmax=False
         worst[p] = assert_gemm_close(y, y_ref, a_ref, "%s path %d" % (what, p))
         ws_bytes = binding.mxfp4_woq_gemm_workspace_bytes(x.shape[0], w.shape[0], w.shape[1])
         if ws_bytes and p in (binding.PATH_AUTO, binding.PATH_MFMA):
-            # the split-K form of the MFMA path, which needs room for its partial products
+            # with a workspace K is split across workgroups and a second kernel adds the phases; the
+            # call above, without one, split K in time inside the kernel (or ran narrower passes)
             ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=DEV)
             y2 = binding.mxfp4_woq_gemm(xg, q, s, path=p, workspace=ws)
             torch.cuda.synchronize()
