@@ -41,13 +41,17 @@ enum {
     MXFP4_ERR_ARG = 6        /* unknown path / option value */
 };
 
-/* Kernel families the dispatcher can be forced to (tests and measurements); AUTO picks by M. */
+/* Kernel families the dispatcher can be forced to (tests and measurements); AUTO picks by M:
+ * one or two rows take VALU_REG when the shape allows it, else VALU_CVT; three or more take MFMA. */
 enum {
     MXFP4_PATH_AUTO = 0,
     MXFP4_PATH_VALU_BITS = 1, /* wave-per-row GEMV, nibbles decoded with plain integer/FP32 ops  */
     MXFP4_PATH_VALU_CVT = 2,  /* wave-per-row GEMV, gfx950 FP4->BF16 scaled converts + dot2      */
     MXFP4_PATH_VALU_LUT = 3,  /* wave-per-row GEMV, LDS-resident byte -> 2xBF16 lookup table      */
-    MXFP4_PATH_MFMA = 4       /* 16-row MFMA tiles (bf16 16x16x32), for verification batches     */
+    MXFP4_PATH_MFMA = 4,      /* 16-row MFMA tiles (bf16 16x16x32), for verification batches     */
+    MXFP4_PATH_VALU_REG = 5   /* decode-step GEMV: converts + dot2 with the activations in registers,
+                                 one workgroup per compute unit; K % 128 == 0, K <= 12288 (one row)
+                                 or 4096 (two rows at a time), N >= 8 * compute units              */
 };
 
 /*

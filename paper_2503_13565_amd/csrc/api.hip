@@ -88,10 +88,10 @@ static int check_x(const void* x, int64_t M, int64_t ldx, int64_t K)
     return MXFP4_OK;
 }
 
-// AUTO: the vector-ALU GEMV for one or two activation rows, MFMA tiles from three rows on (each
-// extra row costs the GEMV half an instruction per weight; the tiles' cost does not grow up to
-// 16 rows), unless the shape cannot run there.
-static int pick_path(int path, int64_t M, bool mfma_ok)
+// AUTO: the vector-ALU GEMV for one or two activation rows (its register-resident form when the
+// shape allows), MFMA tiles from three rows on (each extra row costs the GEMV half an instruction
+// per weight; the tiles' cost does not grow up to 16 rows), unless the shape cannot run there.
+static int pick_path(int path, int64_t M, bool mfma_ok, bool reg_ok)
 {
     if (path != MXFP4_PATH_AUTO)
         return path;
@@ -102,7 +102,9 @@ static int pick_path(int path, int64_t M, bool mfma_ok)
     }
     if (env_path > 0)
         return env_path;
-    return (M >= 3 && mfma_ok) ? MXFP4_PATH_MFMA : MXFP4_PATH_VALU_CVT;
+    if (M >= 3 && mfma_ok)
+        return MXFP4_PATH_MFMA;
+    return reg_ok ? MXFP4_PATH_VALU_REG : MXFP4_PATH_VALU_CVT;
 }
 
 // Draft verification fused behind the argmax (both product forms): NULL when not asked for.
@@ -179,7 +181,7 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         a.y = static_cast<uint16_t*>(y);
         a.ldy = ldy;
     }
-    const int chosen = pick_path(path, M, mfma_can_run(a, dev, splitk_ws != nullptr));
+    const int chosen = pick_path(path, M, mfma_can_run(a, dev, splitk_ws != nullptr), gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a));
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
     hipError_t e;
@@ -191,6 +193,12 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
             return fail(MXFP4_ERR_SHAPE, "K=%lld does not fit the LDS copy of one activation row",
                         (long long)K);
         e = launch_gemv(a, chosen, argmax, dev, &parts_used, st);
+        break;
+    case MXFP4_PATH_VALU_REG:
+        if (!gemv_reg_can_run(a, dev))
+            return fail(MXFP4_ERR_ARG, "the register-resident GEMV needs K %% 128 == 0, K <= 12288 and N >= %d",
+                        dev.cus * 8);
+        e = launch_gemv_reg(a, dev, &parts_used, st);
         break;
     case MXFP4_PATH_MFMA:
         if (!mfma_can_run(a, dev, splitk_ws != nullptr))

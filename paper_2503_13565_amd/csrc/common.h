@@ -67,4 +67,18 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// Workgroup barrier that waits for LDS traffic only.  __syncthreads() would also drain the
+// vector-memory counter and with it the weight loads that are deliberately in flight.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Wait until every vector-memory operation of this wave has completed (s_waitcnt vmcnt(0),
+// other counters untouched; gfx9 encoding).  A real waitcnt instruction rather than inline
+// assembly, so that the compiler's own wait insertion knows nothing is pending afterwards.
+__device__ __forceinline__ void drain_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 }  // namespace mxfp4

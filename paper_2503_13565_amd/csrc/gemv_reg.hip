@@ -1,0 +1,372 @@
+// The decode-step form of the skinny product y = x * dequant(W)^T (arXiv 2503.13565, section
+// 3.4.3 and Eq. 2; section 4.4: the product with one token must run at memory speed): one or
+// two activation rows, reduction lengths up to 12288, activations held in registers.
+//
+// What differs from the general kernel in gemv.hip:
+//   - A lane always works on the same scale blocks of a row (block t*64 + lane in step t), so
+//     its 32 activations per step never change.  They are staged through LDS once (one global
+//     read per workgroup) and then live in registers: the streaming loop has no LDS reads.
+//   - One workgroup per compute unit, 8 or 16 waves.  The rows of a workgroup are handed to its
+//     waves through an LDS counter, one row at a time: the memory system serves the waves of a
+//     compute unit very unevenly (the first data reaches them 2 to 6 us after the launch), and
+//     with a fixed share per wave the slowest wave set the kernel time.
+//   - One weight row per wave step (1 KiB per load instruction), two steps in flight per wave:
+//     32 KiB in flight per compute unit, which is where a plain read stream peaks here.
+// Decode and multiply-add are as in gemv.hip: the scaled FP4->BF16 convert with the block scale,
+// then v_dot2_f32_bf16 with FP32 accumulation (Eq. 2: scaling a power of two commutes with the
+// sum of the block).
+#include "common.h"
+#include "kernels.h"
+#include "../../include/mxfp4.h"
+
+namespace mxfp4 {
+
+namespace {
+
+// The kernel arguments are 15 dwords of plain scalars so that they can be preloaded into scalar
+// registers when the wave starts (the build passes -amdgpu-kernarg-preload-count=16): every wave
+// needs them before it can send its first load.  Measured per launch: a second 64-byte line of
+// arguments costs 0.4 us, fetching one line instead of having it preloaded 0.15 us.
+struct RegArgs {
+    const uint16_t* x;
+    const uint8_t* q;
+    const uint8_t* s;
+    void* out;           // y (BF16 [M, N]), or in the argmax form the partial winners: float
+                         // [M, parts] followed by int32 [M, parts]
+    int n, k, m, m0;
+    int ldx, ldy;
+    int parts;           // > 0: argmax form
+};
+
+// MT activation rows, STEPS (even) steps of 64 blocks cover K (the last ones may be ragged or
+// empty), D step buffers, NW waves per workgroup.  kRagged: K is not STEPS * 2048.
+// R weight rows per wave step (a group); group i of workgroup b's sequence is i * gridDim.x + b.
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+__global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, const uint8_t* q, const uint8_t* s,
+                                                           void* out, int n, int k, int m, int m0, int ldx,
+                                                           int ldy, int parts)
+{
+    const RegArgs a{x, q, s, out, n, k, m, m0, ldx, ldy, parts};
+    static_assert(STEPS % D == 0, "the buffer of a step must be known at compile time");
+    constexpr int T = NW * 64;
+    constexpr int XPR = (STEPS * 256 + T - 1) / T;          // 16-byte activation chunks per thread and row
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int chunks = a.k >> 3;
+
+    // The activation loads go out before anything else is computed.  Every wave sends its weight
+    // loads right behind its own activation loads, and a compute unit serves its loads in order:
+    // an activation load that leaves late queues behind the weights of the waves that started
+    // earlier and holds the whole workgroup at the barrier below (measured: 50 instructions of
+    // address arithmetic in front of it cost 1 us per launch).
+    u32x4_t xl[MT][XPR];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int msrc = min(m0 + m, a.m - 1);                       // ragged M: repeat the last row
+        const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx);
+#pragma unroll
+        for (int i = 0; i < XPR; ++i)
+            xl[m][i] = xp[min(tid + i * T, chunks - 1)];
+    }
+
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);         // [MT][4][nblk] chunks
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nblk = a.k >> 5;
+    int* ctr = reinterpret_cast<int*>(smem + (size_t)MT * a.k * 2);
+    const int q_row_bytes = a.k >> 1;
+    const bool argmax = a.parts > 0;
+    const int G = gridDim.x, b = blockIdx.x;
+    auto row_of = [&](int i) { return i * G + b; };
+
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(a.q), 0, a.n * q_row_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(a.s), 0, a.n * nblk, 0x00020000);
+
+    if (tid == 0)
+        *ctr = NW;                                                   // indices 0..NW-1 are the waves' first rows
+
+    u32x4_t bq[D][R];
+    uint32_t bs[D];
+    const int n_groups = (a.n + R - 1) / R;
+    const int srow = (lane >> 4) % R;
+    // A step always issues the same loads so that the in-order load counter can be waited on
+    // exactly; past the end (of the groups, or of a ragged K) the lane offset is pushed out of the
+    // descriptor's range: such loads touch no memory and return zero.
+    auto issue = [&](int grp, int t, int d) {
+        const bool live = grp < n_groups;
+        const bool vb = !kRagged || t * 64 + lane < nblk;
+        const int g0 = live ? grp * R : 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int row = min(g0 + r, a.n - 1);                    // odd N: the last row twice
+            bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(rq, (live && vb) ? lane * 16 : 0x7FFFFFF0,
+                                                             row * q_row_bytes + t * 1024, 2);
+        }
+        // scale bytes of the step: 16 dwords per row; lane l loads dword l % 16 of row (l / 16) % R
+        const int row = min(g0 + srow, a.n - 1);
+        bs[d] = __builtin_amdgcn_raw_buffer_load_b32(rs, live ? row * nblk + (lane & 15) * 4 : 0x7FFFFFF0,
+                                                     t * 64, 0);
+    };
+    int grp = row_of(wave);
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        issue(grp, d, d);
+
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int i = 0; i < XPR; ++i) {
+            const int c = min(tid + i * T, chunks - 1);              // clamped duplicates rewrite the same data
+            xs[(m * 4 + (c & 3)) * nblk + (c >> 2)] = xl[m][i];
+        }
+    lds_barrier();
+    u32x4_t xr[MT][STEPS][4];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xr[m][t][j] = (!kRagged || t * 64 + lane < nblk) ? xs[(m * 4 + j) * nblk + t * 64 + lane]
+                                                                 : u32x4_t{0, 0, 0, 0};
+
+    float best_val[MT];
+    int best_idx[MT];
+    float res[MT];                  // finished outputs, one per lane
+    float acc[R][MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        best_val[m] = -INFINITY;
+        best_idx[m] = 0x7FFFFFFF;
+        res[m] = 0.f;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            acc[r][m] = 0.f;
+    }
+    int rowv = 0;                   // the row whose outputs this lane holds
+    int slots = 0;
+
+    // Stores and loads share one completion counter but complete out of order with respect to
+    // each other, so the counter is drained here; the loop only ever sees loads in flight.
+    auto flush = [&]() {
+        if (lane < slots && rowv < a.n) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                if (m0 + m < a.m)
+                    static_cast<uint16_t*>(a.out)[(int64_t)(m0 + m) * a.ldy + rowv] = f32_to_bf16_rne(res[m]);
+        }
+        slots = 0;
+        drain_vmem();
+    };
+    auto fetch = [&]() {
+        int v = 0;
+        if (lane == 0)
+            v = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+
+    const int sh_top = (3 - (lane & 3)) * 8;        // brings this lane's scale byte to bits 31:24
+    int i_next = fetch();
+    while (grp < n_groups) {
+        const int grp_n = row_of(i_next);
+        const int i_next2 = fetch();                // consumed one trip later: its latency is hidden
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            const int d = t % D;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                // the dword with this lane's scale byte of row r sits in lane r * 16 + lane / 4.
+                // The scaled convert reads only the exponent field of its scale operand (as E8M0),
+                // so the byte goes to bits 30:23 and whatever lands below is ignored.
+                const uint32_t dw = (uint32_t)__builtin_amdgcn_ds_bpermute((r * 16 + (lane >> 2)) * 4, (int)bs[d]);
+                float sc = __uint_as_float((dw << sh_top) >> 1);
+                if (kRagged)
+                    sc = (t * 64 + lane < nblk) ? sc : 1.0f;         // no NaN from a neighbour's scale byte
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t qd = bq[d][r][j];
+                    bf16x2_t w[4];
+                    w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0);
+                    w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1);
+                    w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2);
+                    w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        // through scalars: a bit cast applied directly to a vector element reads element 0
+                        const uint32_t x0 = xr[m][t][j][0], x1 = xr[m][t][j][1], x2 = xr[m][t][j][2],
+                                       x3 = xr[m][t][j][3];
+                        float c = acc[r][m];
+                        c = __builtin_amdgcn_fdot2_f32_bf16(w[0], __builtin_bit_cast(bf16x2_t, x0), c, false);
+                        c = __builtin_amdgcn_fdot2_f32_bf16(w[1], __builtin_bit_cast(bf16x2_t, x1), c, false);
+                        c = __builtin_amdgcn_fdot2_f32_bf16(w[2], __builtin_bit_cast(bf16x2_t, x2), c, false);
+                        c = __builtin_amdgcn_fdot2_f32_bf16(w[3], __builtin_bit_cast(bf16x2_t, x3), c, false);
+                        acc[r][m] = c;
+                    }
+                }
+            }
+            const int tn = t + D;
+            if (tn < STEPS)
+                issue(grp, tn, d);
+            else
+                issue(grp_n, tn - STEPS, d);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int row = grp * R + r;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const float v = wave_sum(acc[r][m]);
+                acc[r][m] = 0.f;
+                if (argmax) {
+                    // rows arrive in any order: the lower index wins among equal values
+                    if (row < a.n && (v > best_val[m] || (v == best_val[m] && row < best_idx[m]))) {
+                        best_val[m] = v;
+                        best_idx[m] = row;
+                    }
+                } else {
+                    res[m] = (lane == slots + r) ? v : res[m];
+                }
+            }
+            if (!argmax)
+                rowv = (lane == slots + r) ? row : rowv;
+        }
+        if (!argmax) {
+            slots += R;
+            if (slots + R > 64)
+                flush();
+        }
+        grp = grp_n;
+        i_next = i_next2;
+    }
+    if (!argmax && slots > 0)
+        flush();
+
+    if (argmax) {
+        // combine the waves of the workgroup, then publish one partial winner per activation row
+        __syncthreads();
+        float* wv = reinterpret_cast<float*>(smem);
+        int* wi = reinterpret_cast<int*>(smem) + NW * MT;
+        if (lane == 0) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                wv[wave * MT + m] = best_val[m];
+                wi[wave * MT + m] = best_idx[m];
+            }
+        }
+        __syncthreads();
+        if (tid < MT && m0 + tid < a.m) {
+            float bv = wv[tid];
+            int bi = wi[tid];
+            for (int w = 1; w < NW; ++w) {
+                const float v = wv[w * MT + tid];
+                const int i = wi[w * MT + tid];
+                if (v > bv || (v == bv && i < bi)) {
+                    bv = v;
+                    bi = i;
+                }
+            }
+            float* part_val = static_cast<float*>(a.out);
+            int32_t* part_idx = reinterpret_cast<int32_t*>(part_val + (int64_t)a.m * a.parts);
+            part_val[(int64_t)(m0 + tid) * a.parts + b] = bv;
+            part_idx[(int64_t)(m0 + tid) * a.parts + b] = bi;
+        }
+    }
+}
+
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream)
+{
+    const bool argmax = g.part_val != nullptr;
+    hipLaunchKernelGGL((gemv_reg_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds, stream,
+                       g.x, g.q, g.s, argmax ? static_cast<void*>(g.part_val) : static_cast<void*>(g.y), g.n, g.k,
+                       g.m, m0, (int)g.ldx, (int)g.ldy, argmax ? g.parts : 0);
+    return hipGetLastError();
+}
+
+template <int MT>
+hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int blocks, size_t lds,
+                        hipStream_t stream)
+{
+    // 16 waves hold at most 128 registers each: enough for four steps of one activation row.
+    // Six steps: 8 waves, each with two weight rows and three steps in flight (measured best on
+    // the 7B down projection, 4096 x 11008, where a compute unit has only 16 rows to work on).
+    switch (steps2) {
+    case 2:
+        if constexpr (MT == 1)
+            return ragged ? launch_one<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream)
+                          : launch_one<MT, 1, 2, 2, 16, false>(a, m0, blocks, lds, stream);
+        else                                       // two activation rows need more registers: 8 waves
+            return ragged ? launch_one<MT, 2, 2, 2, 8, true>(a, m0, blocks, lds, stream)
+                          : launch_one<MT, 2, 2, 2, 8, false>(a, m0, blocks, lds, stream);
+    case 4:
+        if constexpr (MT == 1)
+            return ragged ? launch_one<MT, 1, 4, 2, 16, true>(a, m0, blocks, lds, stream)
+                          : launch_one<MT, 1, 4, 2, 16, false>(a, m0, blocks, lds, stream);
+        break;
+    case 6:
+        if constexpr (MT == 1)
+            return ragged ? launch_one<MT, 2, 6, 3, 8, true>(a, m0, blocks, lds, stream)
+                          : launch_one<MT, 2, 6, 3, 8, false>(a, m0, blocks, lds, stream);
+        break;
+    }
+    return hipErrorInvalidValue;
+}
+
+int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
+int waves_for(int steps2, int mt) { return steps2 == 6 || mt == 2 ? 8 : 16; }
+int rows_per_step(int steps2, int mt) { return steps2 == 6 || mt == 2 ? 2 : 1; }
+
+}  // namespace
+
+// K % 128 == 0 (dword scale loads), K <= 12288 (the activations of one row fit the registers of
+// a lane), and enough weight rows to give every compute unit a workgroup's worth.  Activation
+// rows go two per pass up to K = 4096 and one per pass beyond: more rows than that are better
+// served by the general kernel (one pass for two rows at any K) or the MFMA tiles.
+bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev)
+{
+    if (a.k % 128 != 0 || a.m < 1 || even_steps(a.k) > 6)
+        return false;
+    if (a.ldx > 0x7FFFFFFF || a.ldy > 0x7FFFFFFF)           // 32-bit leading dimensions in the kernel
+        return false;
+    if (a.part_val && a.part_idx != reinterpret_cast<int32_t*>(a.part_val + (size_t)a.m * a.parts))
+        return false;                                       // the kernel derives the index array's place
+    if ((size_t)2 * a.k * 2 + 64 > (size_t)dev.lds_bytes)
+        return false;
+    return a.n >= dev.cus * 8;
+}
+
+bool gemv_reg_single_pass(const GemmArgs& a) { return a.m == 1 || (a.m == 2 && even_steps(a.k) <= 2); }
+
+hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+{
+    const int steps2 = even_steps(a.k);
+    const bool ragged = a.k != steps2 * 2048;
+    // one workgroup per compute unit; the argmax form writes one partial winner per workgroup, so
+    // every pass must use the same number of workgroups: the count of the narrowest pass
+    auto blocks_for = [&](int mt) {
+        const int r = rows_per_step(steps2, mt), nw = waves_for(steps2, mt);
+        const int n_groups = (a.n + r - 1) / r;
+        return min(dev.cus, (n_groups + nw - 1) / nw);
+    };
+    const bool pairs = a.m >= 2 && steps2 <= 2;
+    const int blocks = pairs ? min(blocks_for(1), blocks_for(2)) : blocks_for(1);
+    if (parts_used)
+        *parts_used = blocks;
+    for (int m0 = 0; m0 < a.m;) {
+        hipError_t e;
+        if (a.m - m0 >= 2 && steps2 <= 2) {
+            e = launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream);
+            m0 += 2;
+        } else {
+            e = launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream);
+            m0 += 1;
+        }
+        if (e != hipSuccess)
+            return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace mxfp4

@@ -47,6 +47,13 @@ hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceI
                        int* parts_used, hipStream_t stream);
 int gemv_max_parts(const DeviceInfo& dev);
 
+// The decode-step form of the same product (converts + dot2, activations in registers, one
+// workgroup per compute unit, rows dealt to the waves through an LDS counter); see gemv_reg.hip
+// for the shapes it takes.  The argmax form writes one partial winner per workgroup.
+bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev);
+bool gemv_reg_single_pass(const GemmArgs& a);     // all activation rows in one pass over the weights
+hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+
 // 16-row MFMA tiles (bf16 16x16x32) for verification batches; passes of up to 16 activation rows.
 // When the activation rows of a pass do not fit the LDS whole, K is split: in space over
 // workgroups through a workspace of mfma_splitk_bytes() with a second kernel that adds the partial

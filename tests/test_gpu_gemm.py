@@ -52,6 +52,59 @@ def test_edge_shapes(n, k, m):
     run_gemm_case(w, x, paths, "N=%d K=%d M=%d" % (n, k, m), argmax=True)
 
 
+REG = binding.PATH_VALU_REG
+
+
+@pytest.mark.parametrize("n,k", [(2048, 128), (2100, 256), (2049, 2176), (2500, 4096), (2111, 6144),
+                                 (2300, 8192), (2222, 10240), (2100, 11008), (2050, 12288)])
+@pytest.mark.parametrize("m", [1, 2, 3])
+def test_register_gemv_edge_shapes(n, k, m):
+    """The decode-step kernel: full, ragged and padded step counts, rows that do not fill the last
+    round of a workgroup, one and two activation rows per pass, the fused argmax."""
+    w = synth.weights_student_t(n, k, seed=5000 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=6000 + m + k)
+    run_gemm_case(w, x, [REG, binding.PATH_VALU_CVT], "REG N=%d K=%d M=%d" % (n, k, m), argmax=True)
+
+
+def test_register_gemv_refuses_what_it_cannot_run():
+    for n, k in [(100, 4096), (4096, 96), (4096, 16384)]:
+        x = torch.zeros((1, k), dtype=torch.bfloat16, device=DEV)
+        q = torch.zeros((n, k // 2), dtype=torch.uint8, device=DEV)
+        s = torch.zeros((n, k // 32), dtype=torch.uint8, device=DEV)
+        with pytest.raises(binding.Mxfp4Error) as e:
+            binding.mxfp4_woq_gemm(x, q, s, path=REG)
+        assert e.value.code == 6
+        y = binding.mxfp4_woq_gemm(x, q, s)                # AUTO takes the general kernel
+        assert not y.float().abs().sum().item()
+
+
+def test_register_gemv_nan_scale_stays_in_its_row():
+    # ragged K: the lanes past the end of a row see the next row's scale bytes; a NaN block there
+    # (scale 0xFF) must not leak into this row
+    n, k = 2048, 2176
+    w = synth.weights_student_t(n, k, seed=17)
+    w[11, 5] = float("nan")
+    q, s = binding.mxfp4_direct_cast(w.to(DEV))
+    x = synth.activations_gaussian(1, k, seed=18).to(DEV)
+    y = binding.mxfp4_woq_gemm(x, q, s, path=REG).float().cpu()
+    assert torch.isnan(y[0, 11]) and torch.isfinite(y[0, :11]).all() and torch.isfinite(y[0, 12:]).all()
+
+
+def test_register_gemv_exact_ties_pick_lowest_index():
+    w = synth.weights_student_t(2600, 512, seed=21) * 0.1
+    top = synth.weights_student_t(1, 512, seed=22)
+    x = top.clone()
+    for rows in ([5, 300, 2599], [0, 1], [2598, 2599], [255, 256, 257, 1300]):
+        wt = w.clone()
+        wt[rows] = top
+        q, s, q_ref, s_ref = assert_cast_bit_exact(wt)
+        y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref)
+        assert oracle.argmax(y_ref)[0][0] == rows[0]
+        idx, val = binding.mxfp4_woq_gemm_argmax(x.to(DEV), q, s, path=REG)
+        assert int(idx[0]) == rows[0], (rows, int(idx[0]))
+        assert_argmax_ok(idx, val, y_ref, a_ref)
+
+
 MFMA = binding.PATH_MFMA
 
 
