@@ -84,11 +84,12 @@ def run_step_bf16(lin, ws):
     binding.mxfp4_bf16_gemm_argmax(t["x"], t["w"], workspace=ws, out=(t["idx"], t["val"]))
 
 
-DOMINANT = ("qkv", "gate_up", "lm_head")
+DOMINANT = ("qkv", "o", "gate_up", "lm_head")
+DOMINANT_KERNEL = "mxfp4::gemv_reg_kernel<1,1,2,2,16,false>"
 
 
 def run_dominant(lin, ws):
-    """The three launches of a step that use the dominant kernel instance (2 rows per wave step)."""
+    """The four launches of a step that run the dominant kernel instance (every K = 4096 linear)."""
     from paper_2503_13565_amd import binding
     for name in DOMINANT:                               # lm_head: same instance as the fused-argmax call
         t = lin[name]
@@ -332,8 +333,8 @@ def main() -> int:
     n_plain = max(len(sets), args.steps // 4)
     plain_ms = timed(runner(None, run_step, sets, ws), n_plain, stream) / n_plain
 
-    # dominant kernel: the instance that runs qkv, gate+up and the LM head (3 of the 6 launches,
-    # 81 % of the bytes); average launch duration from events around graph replays of these three
+    # dominant kernel: the instance that runs qkv, o, gate+up and the LM head (4 of the 6 launches,
+    # 86 % of the bytes); average launch duration from events around graph replays of these four
     # launches only, rotating over the weight sets
     dgraph = None if args.no_graph else capture(run_dominant, sets, ws, stream)
     run_dom = runner(dgraph, run_dominant, sets, ws)
@@ -409,7 +410,7 @@ def main() -> int:
         "direct_cast_GBps": None if cast_gbps is None else round(cast_gbps, 1),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": "mxfp4::gemv_kernel<1,2,2,4,2,true> (qkv, gate_up and lm_head launches)",
+                     "kernel": DOMINANT_KERNEL + " (qkv, o, gate_up and lm_head launches)",
                      "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_launch_us, 3)},
     }
     if bf16_us is not None:

@@ -15,13 +15,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmxfp4_hip.so")
-SOURCES = ["api.hip", "cast.hip", "gemv.hip", "gemv_reg.hip", "mfma.hip", "bf16.hip"]
+SOURCES = ["api.hip", "cast.hip", "gemv.hip", "gemv_reg.hip", "mfma.hip", "mfma_tile.hip", "bf16.hip"]
 # packed FP32 instructions are disabled on purpose: see the build notes of this project
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # leading scalar kernel arguments arrive in scalar registers when a wave starts (gfx950
-         # supports it; kernels whose first argument is a struct are unaffected)
-         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# per file: the leading scalar kernel arguments arrive in scalar registers when a wave starts
+EXTRA = {"gemv_reg.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"],
+         "mfma_tile.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"]}
 
 
 def _hipcc() -> str:
@@ -33,7 +33,7 @@ def _hipcc() -> str:
 
 def _compile(src: str, verbose: bool) -> str:
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)

@@ -65,6 +65,12 @@ size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev);
 hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
                        hipStream_t stream);
 
+// The same tiles in a leaner kernel for passes whose activation rows fit the LDS whole (no K
+// split); launch_mfma uses it whenever it can run (MXFP4_MFMA_LEGACY=1 keeps the general kernel,
+// for measurements).
+bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev);
+hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+
 // The unquantised product with BF16 weights [N, K] (row stride ldw), same conventions otherwise.
 struct Bf16Args {
     const uint16_t* x;
