@@ -49,6 +49,8 @@ enum {
     MXFP4_PATH_VALU_CVT = 2,  /* wave-per-row GEMV, gfx950 FP4->BF16 scaled converts + dot2      */
     MXFP4_PATH_VALU_LUT = 3,  /* wave-per-row GEMV, LDS-resident byte -> 2xBF16 lookup table      */
     MXFP4_PATH_MFMA = 4,      /* 16-row MFMA tiles (bf16 16x16x32), for verification batches     */
+    MXFP4_PATH_MFMA_GENERAL = 6, /* the general MFMA kernel (K split in time or space) also where the
+                                 leaner tile kernel, which MXFP4_PATH_MFMA prefers, could run      */
     MXFP4_PATH_VALU_REG = 5   /* decode-step GEMV: converts + dot2 with the activations in registers,
                                  one workgroup per compute unit; K % 128 == 0, K <= 12288 (one row)
                                  or 4096 (two rows at a time), N >= 8 * compute units              */

@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmxfp4_hip.so")
 
-PATH_AUTO, PATH_VALU_BITS, PATH_VALU_CVT, PATH_VALU_LUT, PATH_MFMA, PATH_VALU_REG = 0, 1, 2, 3, 4, 5
+PATH_AUTO, PATH_VALU_BITS, PATH_VALU_CVT, PATH_VALU_LUT, PATH_MFMA, PATH_VALU_REG, PATH_MFMA_GENERAL = 0, 1, 2, 3, 4, 5, 6
 
 EXPORTS = [
     "mxfp4_direct_cast", "mxfp4_direct_cast_bits", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm", "mxfp4_woq_gemm_path",

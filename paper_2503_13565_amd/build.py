@@ -20,8 +20,8 @@ SOURCES = ["api.hip", "cast.hip", "gemv.hip", "gemv_reg.hip", "mfma.hip", "mfma_
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # per file: the leading scalar kernel arguments arrive in scalar registers when a wave starts
-EXTRA = {"gemv_reg.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"],
-         "mfma_tile.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"]}
+PRELOAD = ["-mllvm", "-amdgpu-kernarg-preload-count=16"]
+EXTRA = {"gemv_reg.hip": PRELOAD, "mfma_tile.hip": PRELOAD, "gemv.hip": PRELOAD}
 
 
 def _hipcc() -> str:

@@ -201,10 +201,11 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         e = launch_gemv_reg(a, dev, &parts_used, st);
         break;
     case MXFP4_PATH_MFMA:
+    case MXFP4_PATH_MFMA_GENERAL:
         if (!mfma_can_run(a, dev, splitk_ws != nullptr))
             return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and, without a workspace, four rows of "
                                        "K=%lld elements exceed the LDS", (long long)K);
-        e = launch_mfma(a, dev, splitk_ws, &parts_used, st);
+        e = launch_mfma(a, dev, splitk_ws, &parts_used, st, chosen == MXFP4_PATH_MFMA_GENERAL);
         break;
     default:
         return fail(MXFP4_ERR_ARG, "unknown or unavailable path %d", chosen);

@@ -63,11 +63,11 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
 bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev, bool have_splitk_ws);
 size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev);
 hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
-                       hipStream_t stream);
+                       hipStream_t stream, bool general_only = false);
 
 // The same tiles in a leaner kernel for passes whose activation rows fit the LDS whole (no K
-// split); launch_mfma uses it whenever it can run (MXFP4_MFMA_LEGACY=1 keeps the general kernel,
-// for measurements).
+// split); launch_mfma uses it whenever it can run unless told `general_only` (or
+// MXFP4_MFMA_LEGACY=1 in the environment, for measurements).
 bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev);
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
 

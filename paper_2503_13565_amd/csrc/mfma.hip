@@ -622,13 +622,13 @@ size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev)
 }
 
 hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
-                       hipStream_t stream)
+                       hipStream_t stream, bool general_only)
 {
     static const bool legacy = [] {
         const char* e = getenv("MXFP4_MFMA_LEGACY");
         return e && atoi(e) != 0;
     }();
-    if (!legacy && mfma_tile_can_run(a_in, dev))
+    if (!legacy && !general_only && mfma_tile_can_run(a_in, dev))
         return launch_mfma_tile(a_in, dev, parts_used, stream);
     if (!mfma_can_run(a_in, dev, splitk_ws != nullptr))
         return hipErrorInvalidValue;

@@ -9,8 +9,8 @@
 //     the copy's writes and the loop's 128-bit reads are free of bank conflicts;
 //   - a lane loads the 16 scale bytes of its row for an item of four steps directly (the waves of
 //     a workgroup use a row's scale line together, so the lines are fully used);
-//   - NW = 4 compute waves per workgroup split K in items of four steps, two items in flight per
-//     wave; one more wave, which never loads, sums the partial tiles, rounds and stores or tracks
+//   - NW = 4 compute waves per workgroup split K in items of four steps, two or three items in
+//     flight per wave; one more wave, which never loads, sums the partial tiles, rounds and stores or tracks
 //     the argmax; two workgroups per compute unit when the LDS allows.
 //   - all conditions on the position are arithmetic masks: a branch around a load makes the
 //     compiler lose count of the loads in flight and wait for all of them.
@@ -27,7 +27,6 @@ namespace {
 
 constexpr int kOob = 0x7FFFFFF0;        // lane offset beyond any descriptor: the load returns zero
 constexpr int kTileNW = 4;              // compute waves per workgroup
-constexpr int kTileD = 2;               // items in flight per wave
 
 // LDS of a workgroup: activations [items * 4 steps][16 slots][MP] chunks of 16 bytes, then two
 // sets of NW partial tiles.
@@ -259,11 +258,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_kernel(const uint16_t
     }
 }
 
-template <int MP>
+template <int MP, int D>
 hipError_t launch_pass(const GemmArgs& a, int m0, int blocks, size_t lds, const DeviceInfo& dev,
                        hipStream_t stream)
 {
-    auto kern = mfma_tile_kernel<MP, kTileNW, kTileD>;
+    auto kern = mfma_tile_kernel<MP, kTileNW, D>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -299,10 +298,13 @@ bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev)
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
 {
     const int n_tiles = (a.n + 15) / 16;
-    // two workgroups per compute unit when the widest pass leaves room for it (measured best on
-    // the 7B shapes: 8 compute waves per unit in two independent groups)
+    // About 48 to 64 KiB of weights in flight per compute unit is where this kernel peaks
+    // (measured on the 7B and 70B shapes): up to K = 4096-ish two workgroups per unit, when the
+    // widest pass leaves room for them, with two items in flight per wave; from K = 8192 on, where
+    // a wave has four and more items per tile, one workgroup with three.
     const size_t widest = tile_lds_bytes(a.k, tile_pass_width(a.m));
-    const int per_cu = 2 * widest + 2048 <= (size_t)dev.lds_bytes ? 2 : 1;
+    const bool long_k = a.k >= 8192;
+    const int per_cu = !long_k && 2 * widest + 2048 <= (size_t)dev.lds_bytes ? 2 : 1;
     int blocks = dev.cus * per_cu;
     if (blocks > n_tiles)
         blocks = n_tiles;
@@ -313,9 +315,15 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
     for (int m0 = 0; m0 < a.m;) {
         const int mp = tile_pass_width(a.m - m0);
         const size_t lds = tile_lds_bytes(a.k, mp);
-        hipError_t e = mp == 16  ? launch_pass<16>(a, m0, blocks, lds, dev, stream)
-                       : mp == 8 ? launch_pass<8>(a, m0, blocks, lds, dev, stream)
-                                 : launch_pass<4>(a, m0, blocks, lds, dev, stream);
+        hipError_t e;
+        if (long_k)
+            e = mp == 16  ? launch_pass<16, 3>(a, m0, blocks, lds, dev, stream)
+                : mp == 8 ? launch_pass<8, 3>(a, m0, blocks, lds, dev, stream)
+                          : launch_pass<4, 3>(a, m0, blocks, lds, dev, stream);
+        else
+            e = mp == 16  ? launch_pass<16, 2>(a, m0, blocks, lds, dev, stream)
+                : mp == 8 ? launch_pass<8, 2>(a, m0, blocks, lds, dev, stream)
+                          : launch_pass<4, 2>(a, m0, blocks, lds, dev, stream);
         if (e != hipSuccess)
             return e;
         m0 += mp;

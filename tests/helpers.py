@@ -83,7 +83,7 @@ def run_gemm_case(w: torch.Tensor, x: torch.Tensor, paths, what="", argmax=False
         torch.cuda.synchronize()
         worst[p] = assert_gemm_close(y, y_ref, a_ref, "%s path %d" % (what, p))
         ws_bytes = binding.mxfp4_woq_gemm_workspace_bytes(x.shape[0], w.shape[0], w.shape[1])
-        if ws_bytes and p in (binding.PATH_AUTO, binding.PATH_MFMA):
+        if ws_bytes and p in (binding.PATH_AUTO, binding.PATH_MFMA, binding.PATH_MFMA_GENERAL):
             # with a workspace K is split across workgroups and a second kernel adds the phases; the
             # call above, without one, split K in time inside the kernel (or ran narrower passes)
             ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=DEV)

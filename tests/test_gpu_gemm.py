@@ -106,6 +106,7 @@ def test_register_gemv_exact_ties_pick_lowest_index():
 
 
 MFMA = binding.PATH_MFMA
+MFMA_GENERAL = binding.PATH_MFMA_GENERAL
 
 
 @pytest.mark.parametrize("n,k", [(1, 128), (16, 128), (17, 256), (33, 2048), (250, 11008), (1000, 4096),
@@ -114,7 +115,7 @@ MFMA = binding.PATH_MFMA
 def test_mfma_tiles_edge_shapes(n, k, m):
     w = synth.weights_student_t(n, k, seed=3000 + n + k)
     x = synth.activations_outlier_channels(m, k, seed=4000 + m + k)
-    run_gemm_case(w, x, [MFMA], "MFMA N=%d K=%d M=%d" % (n, k, m), argmax=True)
+    run_gemm_case(w, x, [MFMA, MFMA_GENERAL], "MFMA N=%d K=%d M=%d" % (n, k, m), argmax=True)
 
 
 def test_mfma_needs_k_multiple_of_128():
@@ -158,10 +159,10 @@ def test_mfma_large_k_runs_with_and_without_workspace():
 
 def test_mfma_config0_and_llama_shapes():
     data = synth.config0()
-    run_gemm_case(data["w"], data["x"], [MFMA], "config0 MFMA")
+    run_gemm_case(data["w"], data["x"], [MFMA, MFMA_GENERAL], "config0 MFMA")
     for linear in ("down", "o"):
         d = synth.llama_linear(synth.LLAMA_7B, linear, m=8, seed=0)
-        run_gemm_case(d["w"], d["x"], [MFMA], "7B %s M=8 MFMA" % linear)
+        run_gemm_case(d["w"], d["x"], [MFMA, MFMA_GENERAL], "7B %s M=8 MFMA" % linear)
 
 
 @pytest.mark.parametrize("m", [17, 33])
@@ -202,7 +203,7 @@ def test_on_grid_weights_and_one_hot_rows():
     x[3, 65] = 1.0
     xt = torch.from_numpy(x).to(torch.bfloat16)
     qd, sd = torch.from_numpy(q).to(DEV), torch.from_numpy(sb).to(DEV)
-    for p in ALL_VALU + [binding.PATH_MFMA]:
+    for p in ALL_VALU + [binding.PATH_MFMA, binding.PATH_MFMA_GENERAL]:
         y = binding.mxfp4_woq_gemm(xt.to(DEV), qd, sd, path=p).double().cpu().numpy()
         assert np.array_equal(y[0], wh[:, 0]), p
         assert np.array_equal(y[1], -2.0 * wh[:, 33]), p
@@ -221,7 +222,7 @@ def test_argmax_exact_ties_pick_lowest_index():
         q, s, q_ref, s_ref = assert_cast_bit_exact(wt)
         y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref)
         assert oracle.argmax(y_ref)[0][0] == rows[0]
-        for p in ALL_VALU + [binding.PATH_MFMA]:
+        for p in ALL_VALU + [binding.PATH_MFMA, binding.PATH_MFMA_GENERAL]:
             idx, val = binding.mxfp4_woq_gemm_argmax(x.to(DEV), q, s, path=p)
             assert int(idx[0]) == rows[0], (rows, p, int(idx[0]))
             assert_argmax_ok(idx, val, y_ref, a_ref)
@@ -244,7 +245,7 @@ def test_argmax_near_tie_accepts_either_within_tolerance():
     q = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8)
     y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q, sb)
     assert oracle.argmax(y_ref)[0][0] == 10 and y_ref[0, 10] - y_ref[0, 40] < 1e-6 * a_ref[0, 10]
-    for p in ALL_VALU + [binding.PATH_MFMA]:
+    for p in ALL_VALU + [binding.PATH_MFMA, binding.PATH_MFMA_GENERAL]:
         idx, val = binding.mxfp4_woq_gemm_argmax(x.to(DEV), torch.from_numpy(q).to(DEV),
                                                  torch.from_numpy(sb).to(DEV), path=p)
         got = assert_argmax_ok(idx, val, y_ref, a_ref)
