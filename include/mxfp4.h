@@ -189,6 +189,42 @@ int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
                            int32_t* argmax_out, float* max_out,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Tile-major weights for verification passes (an internal layout, made once from the canonical
+ * tensors; bit-exactness is defined on the canonical ones).  The MFMA tile kernel of the
+ * M >= 3 path loads 16 rows x 64 bytes per wave instruction from the row-major tensors; from this
+ * copy the same fragment is 1 KiB contiguous, which is worth 10 to 14 % on such a pass.  A model
+ * that is used for single-row decoding too keeps both copies (the decode kernels want rows
+ * contiguous): +0.53 bytes per weight of the 288 GB.
+ *   q_tiled out uint8, mxfp4_tile_repack_q_bytes(N, K) bytes, 16-byte aligned:
+ *           [tile = ceil(N/16)][step = K/128][lane = i + 16 g][16 bytes] = block 4 step + g of row
+ *           16 tile + i (rows past N are zero)
+ *   s_tiled out uint8, mxfp4_tile_repack_s_bytes(N, K) bytes, 16-byte aligned:
+ *           [tile][item = ceil(K/512)][row i][16 scale bytes of blocks 16 item ..] (bytes past K,
+ *           rows past N: 0x7F)
+ * K % 128 == 0.  The products below take the tile-major pair in place of (q_packed, scales_e8m0)
+ * and are otherwise mxfp4_woq_gemm, mxfp4_woq_gemm_argmax and mxfp4_woq_gemm_verify; they return
+ * MXFP4_ERR_ARG when the activation rows of a pass (min(M, 16) x K BF16) do not fit the LDS of a
+ * compute unit next to 8 KB: such shapes go through the canonical tensors.  Any M >= 1 works
+ * (single rows too, but the decode kernels on the canonical tensors are faster there).
+ */
+size_t mxfp4_tile_repack_q_bytes(int64_t N, int64_t K);
+size_t mxfp4_tile_repack_s_bytes(int64_t N, int64_t K);
+int mxfp4_tile_repack(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                      void* q_tiled, void* s_tiled, void* stream);
+int mxfp4_woq_gemm_tiled(const void* x_bf16, int64_t M, int64_t ldx,
+                         const void* q_tiled, const void* s_tiled, int64_t N, int64_t K,
+                         void* y_bf16, int64_t ldy, void* stream);
+int mxfp4_woq_gemm_tiled_argmax(const void* x_bf16, int64_t M, int64_t ldx,
+                                const void* q_tiled, const void* s_tiled, int64_t N, int64_t K,
+                                int32_t* argmax_out, float* max_out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+int mxfp4_woq_gemm_tiled_verify(const void* x_bf16, int64_t M, int64_t ldx,
+                                const void* q_tiled, const void* s_tiled, int64_t N, int64_t K,
+                                const int32_t* draft_tokens, int32_t* accept_out,
+                                int32_t* argmax_out, float* max_out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* The same decode through the gfx950 scaled FP4->BF16 convert instruction (the one the CVT
  * product path uses), so that its semantics can be checked in isolation. */
 int mxfp4_dequant_hwcvt(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,

@@ -22,6 +22,8 @@ EXPORTS = [
     "mxfp4_woq_gemm_workspace_bytes", "mxfp4_woq_gemm_ws", "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
+    "mxfp4_tile_repack_q_bytes", "mxfp4_tile_repack_s_bytes", "mxfp4_tile_repack", "mxfp4_woq_gemm_tiled",
+    "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
 ]
 
@@ -70,6 +72,18 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_verify.restype = i32
     lib.mxfp4_bf16_gemm_verify.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.mxfp4_bf16_gemm_verify.restype = i32
+    lib.mxfp4_tile_repack_q_bytes.argtypes = [i64, i64]
+    lib.mxfp4_tile_repack_q_bytes.restype = sz
+    lib.mxfp4_tile_repack_s_bytes.argtypes = [i64, i64]
+    lib.mxfp4_tile_repack_s_bytes.restype = sz
+    lib.mxfp4_tile_repack.argtypes = [vp, vp, i64, i64, vp, vp, vp]
+    lib.mxfp4_tile_repack.restype = i32
+    lib.mxfp4_woq_gemm_tiled.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_woq_gemm_tiled.restype = i32
+    lib.mxfp4_woq_gemm_tiled_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.mxfp4_woq_gemm_tiled_argmax.restype = i32
+    lib.mxfp4_woq_gemm_tiled_verify.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.mxfp4_woq_gemm_tiled_verify.restype = i32
     lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
     for name in ("mxfp4_direct_cast", "mxfp4_direct_cast_bits", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
@@ -264,6 +278,74 @@ def mxfp4_woq_gemm_verify(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, dra
         _check(load().mxfp4_woq_gemm_verify(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(draft), _ptr(accept),
                                            _ptr(idx), _ptr(val), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream()))
+    return accept, idx, val
+
+
+class TiledWeights:
+    """The tile-major copy of an MXFP4 weight pair (``mxfp4_tile_repack``) with its logical shape."""
+
+    def __init__(self, q_tiled: torch.Tensor, s_tiled: torch.Tensor, n: int, k: int):
+        self.q, self.s, self.n, self.k = q_tiled, s_tiled, n, k
+
+
+def mxfp4_tile_repack(q: torch.Tensor, s: torch.Tensor) -> TiledWeights:
+    _dev(q)
+    if q.dtype != torch.uint8 or s.dtype != torch.uint8 or not q.is_contiguous() or not s.is_contiguous():
+        raise ValueError("q and s must be contiguous uint8 tensors")
+    n, k = q.shape[0], q.shape[1] * 2
+    qt = torch.empty((int(load().mxfp4_tile_repack_q_bytes(n, k)),), dtype=torch.uint8, device=q.device)
+    st = torch.empty((int(load().mxfp4_tile_repack_s_bytes(n, k)),), dtype=torch.uint8, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(load().mxfp4_tile_repack(_ptr(q), _ptr(s), n, k, _ptr(qt), _ptr(st), _stream()))
+    return TiledWeights(qt, st, n, k)
+
+
+def _tiled_shapes(x: torch.Tensor, w: TiledWeights):
+    _dev(x)
+    if x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1 or x.shape[1] != w.k:
+        raise ValueError("x must be a 2-D BF16 tensor [M, %d] with a contiguous last dimension" % w.k)
+    m = x.shape[0]
+    return m, w.n, w.k, (x.stride(0) if m > 1 else w.k)
+
+
+def mxfp4_woq_gemm_tiled(x: torch.Tensor, w: TiledWeights, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    m, n, k, ldx = _tiled_shapes(x, w)
+    if y is None:
+        y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
+    ldy = y.stride(0) if m > 1 else n
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_tiled(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(y), ldy, _stream()))
+    return y
+
+
+def mxfp4_woq_gemm_tiled_argmax(x: torch.Tensor, w: TiledWeights, workspace: Optional[torch.Tensor] = None,
+                                out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
+                                ) -> Tuple[torch.Tensor, torch.Tensor]:
+    m, n, k, ldx = _tiled_shapes(x, w)
+    if workspace is None:
+        workspace = torch.empty((mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k),), dtype=torch.uint8,
+                                device=x.device)
+    if out is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+        val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    else:
+        idx, val = out
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_tiled_argmax(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(idx),
+                                                 _ptr(val), _ptr(workspace),
+                                                 workspace.numel() * workspace.element_size(), _stream()))
+    return idx, val
+
+
+def mxfp4_woq_gemm_tiled_verify(x: torch.Tensor, w: TiledWeights, draft: Optional[torch.Tensor],
+                                workspace: Optional[torch.Tensor] = None):
+    m, n, k, ldx = _tiled_shapes(x, w)
+    workspace, accept, idx, val = _verify_buffers(x, m, draft, mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k),
+                                                  workspace)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_tiled_verify(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(draft),
+                                                 _ptr(accept), _ptr(idx), _ptr(val), _ptr(workspace),
+                                                 workspace.numel() * workspace.element_size(), _stream()))
     return accept, idx, val
 
 

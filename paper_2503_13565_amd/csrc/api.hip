@@ -129,15 +129,19 @@ static int check_verify(const Verify* v, int64_t M)
 
 static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const void* s, int64_t N, int64_t K,
                     void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
-                    size_t workspace_bytes, bool argmax, int path, void* stream, const Verify* verify = nullptr)
+                    size_t workspace_bytes, bool argmax, int path, void* stream, const Verify* verify = nullptr,
+                    bool tiled = false)
 {
     g_err[0] = 0;
     int rc = check_verify(verify, M);
     if (rc)
         return rc;
-    rc = check_weights(q, s, N, K);
+    rc = check_weights(q, s, tiled ? (N + 15) / 16 * 16 : N, K);      // tile-major tensors hold whole tiles
     if (rc)
         return rc;
+    if (tiled && (K % 128 != 0 || !aligned(s, 16)))
+        return K % 128 != 0 ? fail(MXFP4_ERR_SHAPE, "tile-major weights need K %% 128 == 0, K=%lld", (long long)K)
+                            : fail(MXFP4_ERR_ALIGN, "s_tiled must be 16-byte aligned");
     rc = check_x(x, M, ldx, K);
     if (rc)
         return rc;
@@ -181,11 +185,20 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         a.y = static_cast<uint16_t*>(y);
         a.ldy = ldy;
     }
-    const int chosen = pick_path(path, M, mfma_can_run(a, dev, splitk_ws != nullptr), gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a));
+    const int chosen = tiled ? -1
+                             : pick_path(path, M, mfma_can_run(a, dev, splitk_ws != nullptr),
+                                         gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a));
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
     hipError_t e;
     switch (chosen) {
+    case -1:
+        if (!mfma_tile_can_run(a, dev))
+            return fail(MXFP4_ERR_ARG, "the tile-major product needs a pass's activation rows (%lld x K=%lld) to fit "
+                                       "the LDS; use the canonical tensors for this shape",
+                        (long long)(M > 16 ? 16 : M), (long long)K);
+        e = launch_mfma_tile(a, dev, &parts_used, st, true);
+        break;
     case MXFP4_PATH_VALU_BITS:
     case MXFP4_PATH_VALU_CVT:
     case MXFP4_PATH_VALU_LUT:
@@ -516,6 +529,59 @@ int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx, const
 {
     return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, workspace,
                     workspace_bytes, true, path, stream);
+}
+
+size_t mxfp4_tile_repack_q_bytes(int64_t N, int64_t K)
+{
+    return (N < 1 || K < 128 || K % 128 != 0) ? 0 : tile_repack_q_bytes(N, K);
+}
+
+size_t mxfp4_tile_repack_s_bytes(int64_t N, int64_t K)
+{
+    return (N < 1 || K < 128 || K % 128 != 0) ? 0 : tile_repack_s_bytes(N, K);
+}
+
+int mxfp4_tile_repack(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K, void* q_tiled,
+                      void* s_tiled, void* stream)
+{
+    g_err[0] = 0;
+    int rc = check_weights(q_packed, scales_e8m0, (N + 15) / 16 * 16, K);
+    if (rc)
+        return rc;
+    if (K % 128 != 0)
+        return fail(MXFP4_ERR_SHAPE, "tile-major weights need K %% 128 == 0, K=%lld", (long long)K);
+    if (!q_tiled || !s_tiled)
+        return fail(MXFP4_ERR_NULL, "q_tiled or s_tiled is NULL");
+    if (!aligned(q_tiled, 16) || !aligned(s_tiled, 16))
+        return fail(MXFP4_ERR_ALIGN, "q_tiled and s_tiled must be 16-byte aligned");
+    hipError_t e = launch_tile_repack(q_packed, scales_e8m0, (int)N, (int)K, q_tiled, s_tiled,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "tile repack launch");
+}
+
+int mxfp4_woq_gemm_tiled(const void* x_bf16, int64_t M, int64_t ldx, const void* q_tiled, const void* s_tiled,
+                         int64_t N, int64_t K, void* y_bf16, int64_t ldy, void* stream)
+{
+    return run_gemm(x_bf16, M, ldx, q_tiled, s_tiled, N, K, y_bf16, ldy, nullptr, nullptr, nullptr, 0, false,
+                    MXFP4_PATH_AUTO, stream, nullptr, true);
+}
+
+int mxfp4_woq_gemm_tiled_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void* q_tiled,
+                                const void* s_tiled, int64_t N, int64_t K, int32_t* argmax_out, float* max_out,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_gemm(x_bf16, M, ldx, q_tiled, s_tiled, N, K, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, MXFP4_PATH_AUTO, stream, nullptr, true);
+}
+
+int mxfp4_woq_gemm_tiled_verify(const void* x_bf16, int64_t M, int64_t ldx, const void* q_tiled,
+                                const void* s_tiled, int64_t N, int64_t K, const int32_t* draft_tokens,
+                                int32_t* accept_out, int32_t* argmax_out, float* max_out, void* workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    const Verify v{draft_tokens, accept_out};
+    return run_gemm(x_bf16, M, ldx, q_tiled, s_tiled, N, K, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, MXFP4_PATH_AUTO, stream, &v, true);
 }
 
 int mxfp4_woq_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,

@@ -69,7 +69,14 @@ hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_w
 // split); launch_mfma uses it whenever it can run unless told `general_only` (or
 // MXFP4_MFMA_LEGACY=1 in the environment, for measurements).
 bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev);
-hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
+                            bool tiled = false);
+
+// Tile-major copy of the weights for the tile kernel (`tiled`: a.q / a.s are that copy): what a
+// wave instruction loads is contiguous.  Sizes in bytes; K % 128 == 0.
+size_t tile_repack_q_bytes(int64_t n, int64_t k);
+size_t tile_repack_s_bytes(int64_t n, int64_t k);
+hipError_t launch_tile_repack(const void* q, const void* s, int n, int k, void* qt, void* st, hipStream_t stream);
 
 // The unquantised product with BF16 weights [N, K] (row stride ldw), same conventions otherwise.
 struct Bf16Args {
