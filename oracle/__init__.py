@@ -63,6 +63,8 @@ def _load():
         lib.oracle_sd_speedup_alpha.restype = f64
         lib.oracle_sd_speedup_two_level.argtypes = [f64] * 6
         lib.oracle_sd_speedup_two_level.restype = f64
+        lib.oracle_epilogue.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, vp, vp]
+        lib.oracle_epilogue.restype = i32
         lib.oracle_argmax.argtypes = [vp, i64, i64, vp, vp]
         lib.oracle_argmax.restype = i32
         lib.oracle_e2m1_magnitude.argtypes = [i32]
@@ -169,6 +171,43 @@ def woq_gemm_late_scaled(x_bits, q, s) -> np.ndarray:
     if rc:
         raise RuntimeError("oracle_woq_gemm_late_scaled failed: %d" % rc)
     return y
+
+
+ACT_NONE, ACT_SWIGLU = 0, 1
+
+
+def epilogue(y, a, bias_bits=None, residual_bits=None, act: int = ACT_NONE):
+    """Bias, gated activation and residual add on an exact product ``y`` with its sum of absolute
+    products ``a`` (both ``[M, N]``): returns ``(out, a_out)``, ``[M, N]`` or ``[M, N/2]`` for
+    ``ACT_SWIGLU`` (weight rows interleaved gate, up, gate, up...).  ``bias_bits`` is ``[N]``,
+    ``residual_bits`` ``[M, C]`` (any row stride), both BF16 bit patterns; ``tolerance(out, a_out)``
+    is the parity bar of the fused call."""
+    y = _as(y, np.float64, 2)
+    a = _as(a, np.float64, 2)
+    if y.shape != a.shape:
+        raise ValueError("y %r and a %r differ in shape" % (y.shape, a.shape))
+    m, n = y.shape
+    c = n // 2 if act == ACT_SWIGLU else n
+    b = None if bias_bits is None else _as(bias_bits, np.uint16, 1)
+    if b is not None and b.shape[0] != n:
+        raise ValueError("bias must have N = %d entries" % n)
+    r, ldr = None, 0
+    if residual_bits is not None:
+        r = np.asarray(residual_bits)
+        if r.dtype != np.uint16 or r.ndim != 2 or r.shape != (m, c) or (m > 1 and r.strides[1] != 2):
+            raise ValueError("residual must be uint16 [M, %d]" % c)
+        if m > 1 and r.strides[0] % 2 == 0 and r.strides[0] >= 2 * c and r.strides[1] == 2:
+            ldr = r.strides[0] // 2
+        else:
+            r = np.ascontiguousarray(r)
+            ldr = c
+    out = np.empty((m, c), np.float64)
+    a_out = np.empty((m, c), np.float64)
+    rc = _load().oracle_epilogue(_ptr(y), _ptr(a), m, n, _ptr(b) if b is not None else None,
+                                 _ptr(r) if r is not None else None, ldr, int(act), _ptr(out), _ptr(a_out))
+    if rc:
+        raise RuntimeError("oracle_epilogue failed: %d" % rc)
+    return out, a_out
 
 
 def argmax(y):

@@ -29,7 +29,10 @@
  * symmetry, idempotence, the error bound, the product against a library FP64
  * matmul on on-grid weights, one-hot activations, and brute-force argmax; the
  * BF16-weight product against a library FP64 matmul and against the quantised
- * product on weights that the cast represents exactly.
+ * product on weights that the cast represents exactly; the fused epilogue against
+ * a library FP64 silu, closed-form values, the odd-part identity
+ * silu(v) - silu(-v) = v, additivity of bias and residual with a non-square
+ * padded layout, and the slope constant against a numeric maximum.
  */
 #include <math.h>
 #include <stdint.h>
@@ -305,6 +308,62 @@ int oracle_bf16_gemm(const uint16_t *x, int64_t M, int64_t ldx,
         }
     }
     (void)threads;
+    return 0;
+}
+
+/* What the linear layer's backend fuses around the contraction (section 3.4: bias
+ * and residual add applied to the product's output while it is at hand) and, for
+ * the gated MLP of the Llama and Qwen targets of sections 4.2 and 4.3, the gate:
+ *
+ *   z[m][n] = y[m][n] + bias[n]                                   (bias optional)
+ *   act 0:  t[m][c] = z[m][c],                        c < N
+ *   act 1:  t[m][c] = silu(z[m][2c]) * z[m][2c + 1],  c < N / 2,  silu(v) = v / (1 + exp(-v))
+ *           (weight rows interleaved: row 2c is the gate projection's row c, row
+ *           2c + 1 the up projection's)
+ *   out[m][c] = t[m][c] + residual[m][c]                          (residual optional)
+ *
+ * y and a are the exact product and its sum of absolute products, [M, N]; bias
+ * and residual are BF16 bit patterns ([N]; [M, ldr]); out and a_out are [M, C]
+ * with C = N or N / 2.
+ *
+ * a_out carries the product's error scale through the epilogue, so that the same
+ * rule "error <= 1e-3 * a_out + one BF16 ulp" applies to the fused result: if the
+ * device's z is off by at most e * A (A = a + |bias|), then, L being the largest
+ * slope of silu,
+ *   act 0: |d out| <= e * (A + |residual|)
+ *   act 1: |d out| <= e * (L A_g |z_u| + |silu(z_g)| A_u + e L A_g A_u + |residual|)
+ * with e = 1e-3 in the last product term written out. */
+int oracle_epilogue(const double *y, const double *a, int64_t M, int64_t N,
+                    const uint16_t *bias, const uint16_t *residual, int64_t ldr,
+                    int act, double *out, double *a_out)
+{
+    const double silu_slope = 1.0998393194985438;   /* max of d/dv silu(v), at v = 2.39936... */
+    if (M < 0 || N < 0 || (act != 0 && act != 1) || (act == 1 && N % 2 != 0))
+        return 2;
+    const int64_t C = act == 1 ? N / 2 : N;
+    if (residual && ldr < C)
+        return 2;
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t c = 0; c < C; ++c) {
+            double t, ta;
+            if (act == 0) {
+                double b = bias ? bf16_to_double(bias[c]) : 0.0;
+                t = y[m * N + c] + b;
+                ta = a[m * N + c] + fabs(b);
+            } else {
+                double bg = bias ? bf16_to_double(bias[2 * c]) : 0.0;
+                double bu = bias ? bf16_to_double(bias[2 * c + 1]) : 0.0;
+                double zg = y[m * N + 2 * c] + bg, ag = a[m * N + 2 * c] + fabs(bg);
+                double zu = y[m * N + 2 * c + 1] + bu, au = a[m * N + 2 * c + 1] + fabs(bu);
+                double gate = zg / (1.0 + exp(-zg));
+                t = gate * zu;
+                ta = silu_slope * ag * fabs(zu) + fabs(gate) * au + 1e-3 * silu_slope * ag * au;
+            }
+            double r = residual ? bf16_to_double(residual[m * ldr + c]) : 0.0;
+            out[m * C + c] = t + r;
+            a_out[m * C + c] = ta + fabs(r);
+        }
+    }
     return 0;
 }
 
