@@ -125,6 +125,33 @@ int mxfp4_woq_gemm_ws(const void* x_bf16, int64_t M, int64_t ldx,
                       int path, void* stream);
 
 /*
+ * The same product with the operators that surround a linear layer fused behind it (section
+ * 3.4: the backend applies bias and residual add to the contraction's output while it is at
+ * hand; the gate of the gated MLP of the targets of sections 4.2 and 4.3 is handled the same
+ * way).  All of it in FP32 on the accumulators, one rounding to BF16 at the end:
+ *   z[m][n] = sum_k x[m][k] * w[n][k] + bias[n]
+ *   MXFP4_ACT_NONE:    t[m][c] = z[m][c]                          C = N columns
+ *   MXFP4_ACT_SWIGLU:  t[m][c] = silu(z[m][2c]) * z[m][2c + 1]    C = N / 2 columns, N even;
+ *                      silu(v) = v / (1 + e^-v); the weight rows are interleaved: row 2c is row
+ *                      c of the gate projection, row 2c + 1 row c of the up projection
+ *   y[m][c] = bf16(t[m][c] + residual[m][c])
+ *   bias_bf16      in  BF16 [N], 2-byte aligned, or NULL (no bias)
+ *   residual_bf16  in  BF16 [M, C], row stride ldr >= C, or NULL (none; ldr then ignored).  It
+ *                  may be y itself with ldr == ldy (the residual stream updated in place); any
+ *                  other overlap with y is not allowed
+ *   y_bf16         out BF16 [M, C], row stride ldy >= C
+ * x, q, s, workspace and `path` as in mxfp4_woq_gemm_ws (the workspace is optional in the same
+ * way; mxfp4_woq_gemm_workspace_bytes(M, N, K) gives its size).  MXFP4_ERR_ARG for an unknown
+ * act, MXFP4_ERR_SHAPE for an odd N with the gate.
+ */
+enum { MXFP4_ACT_NONE = 0, MXFP4_ACT_SWIGLU = 1 };
+int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx,
+                         const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                         const void* bias_bf16, int act, const void* residual_bf16, int64_t ldr,
+                         void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                         int path, void* stream);
+
+/*
  * The same product with the greedy pick fused (section 3.1: the target's token at each
  * verified position is compared with the draft's; section 4.1: greedy search): for every
  * activation row m, the index n of the largest FP32 accumulator (before any BF16 rounding),
@@ -224,6 +251,12 @@ int mxfp4_woq_gemm_tiled_verify(const void* x_bf16, int64_t M, int64_t ldx,
                                 const int32_t* draft_tokens, int32_t* accept_out,
                                 int32_t* argmax_out, float* max_out,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* mxfp4_woq_gemm_fused on the tile-major copy (bias, act, residual, y as there). */
+int mxfp4_woq_gemm_tiled_fused(const void* x_bf16, int64_t M, int64_t ldx,
+                               const void* q_tiled, const void* s_tiled, int64_t N, int64_t K,
+                               const void* bias_bf16, int act, const void* residual_bf16, int64_t ldr,
+                               void* y_bf16, int64_t ldy, void* stream);
 
 /* The same decode through the gfx950 scaled FP4->BF16 convert instruction (the one the CVT
  * product path uses), so that its semantics can be checked in isolation. */

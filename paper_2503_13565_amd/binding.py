@@ -22,8 +22,9 @@ EXPORTS = [
     "mxfp4_woq_gemm_workspace_bytes", "mxfp4_woq_gemm_ws", "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
+    "mxfp4_woq_gemm_fused",
     "mxfp4_tile_repack_q_bytes", "mxfp4_tile_repack_s_bytes", "mxfp4_tile_repack", "mxfp4_woq_gemm_tiled",
-    "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify",
+    "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify", "mxfp4_woq_gemm_tiled_fused",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
 ]
 
@@ -72,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_verify.restype = i32
     lib.mxfp4_bf16_gemm_verify.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.mxfp4_bf16_gemm_verify.restype = i32
+    lib.mxfp4_woq_gemm_fused.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i32, vp, i64, vp, i64, vp, sz, i32, vp]
+    lib.mxfp4_woq_gemm_fused.restype = i32
     lib.mxfp4_tile_repack_q_bytes.argtypes = [i64, i64]
     lib.mxfp4_tile_repack_q_bytes.restype = sz
     lib.mxfp4_tile_repack_s_bytes.argtypes = [i64, i64]
@@ -84,6 +87,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_tiled_argmax.restype = i32
     lib.mxfp4_woq_gemm_tiled_verify.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.mxfp4_woq_gemm_tiled_verify.restype = i32
+    lib.mxfp4_woq_gemm_tiled_fused.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i32, vp, i64, vp, i64, vp]
+    lib.mxfp4_woq_gemm_tiled_fused.restype = i32
     lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
     for name in ("mxfp4_direct_cast", "mxfp4_direct_cast_bits", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
@@ -281,6 +286,35 @@ def mxfp4_woq_gemm_verify(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, dra
     return accept, idx, val
 
 
+ACT_NONE, ACT_SWIGLU = 0, 1
+
+
+def mxfp4_woq_gemm_fused(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, bias: Optional[torch.Tensor] = None,
+                         act: int = ACT_NONE, residual: Optional[torch.Tensor] = None,
+                         y: Optional[torch.Tensor] = None, path: int = PATH_AUTO,
+                         workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The product with bias, gate and residual add fused; ``residual`` may be ``y`` itself."""
+    m, n, k, ldx = _gemm_shapes(x, q, s)
+    c = n // 2 if act == ACT_SWIGLU else n
+    if bias is not None and (bias.dtype != torch.bfloat16 or bias.dim() != 1 or bias.shape[0] != n
+                             or not bias.is_contiguous() or bias.device != x.device):
+        raise ValueError("bias must be a contiguous BF16 tensor [N] on the device of x")
+    if residual is not None and (residual.dtype != torch.bfloat16 or residual.dim() != 2
+                                 or residual.shape != (m, c) or residual.stride(1) != 1
+                                 or residual.device != x.device):
+        raise ValueError("residual must be a BF16 tensor [M, %d] with a contiguous last dimension" % c)
+    if y is None:
+        y = torch.empty((m, c), dtype=torch.bfloat16, device=x.device)
+    ldy = y.stride(0) if m > 1 else c
+    ldr = (residual.stride(0) if m > 1 else c) if residual is not None else 0
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_fused(
+            _ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(bias), act, _ptr(residual), ldr, _ptr(y), ldy,
+            _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, path,
+            _stream()))
+    return y
+
+
 class TiledWeights:
     """The tile-major copy of an MXFP4 weight pair (``mxfp4_tile_repack``) with its logical shape."""
 
@@ -315,6 +349,28 @@ def mxfp4_woq_gemm_tiled(x: torch.Tensor, w: TiledWeights, y: Optional[torch.Ten
     ldy = y.stride(0) if m > 1 else n
     with torch.cuda.device(x.device):
         _check(load().mxfp4_woq_gemm_tiled(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(y), ldy, _stream()))
+    return y
+
+
+def mxfp4_woq_gemm_tiled_fused(x: torch.Tensor, w: TiledWeights, bias: Optional[torch.Tensor] = None,
+                               act: int = ACT_NONE, residual: Optional[torch.Tensor] = None,
+                               y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    m, n, k, ldx = _tiled_shapes(x, w)
+    c = n // 2 if act == ACT_SWIGLU else n
+    if bias is not None and (bias.dtype != torch.bfloat16 or bias.dim() != 1 or bias.shape[0] != n
+                             or not bias.is_contiguous() or bias.device != x.device):
+        raise ValueError("bias must be a contiguous BF16 tensor [N] on the device of x")
+    if residual is not None and (residual.dtype != torch.bfloat16 or residual.dim() != 2
+                                 or residual.shape != (m, c) or residual.stride(1) != 1
+                                 or residual.device != x.device):
+        raise ValueError("residual must be a BF16 tensor [M, %d] with a contiguous last dimension" % c)
+    if y is None:
+        y = torch.empty((m, c), dtype=torch.bfloat16, device=x.device)
+    ldy = y.stride(0) if m > 1 else c
+    ldr = (residual.stride(0) if m > 1 else c) if residual is not None else 0
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_tiled_fused(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(bias), act,
+                                                _ptr(residual), ldr, _ptr(y), ldy, _stream()))
     return y
 
 

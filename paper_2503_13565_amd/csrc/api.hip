@@ -91,7 +91,10 @@ static int check_x(const void* x, int64_t M, int64_t ldx, int64_t K)
 // AUTO: the vector-ALU GEMV for one or two activation rows (its register-resident form when the
 // shape allows), MFMA tiles from three rows on (each extra row costs the GEMV half an instruction
 // per weight; the tiles' cost does not grow up to 16 rows), unless the shape cannot run there.
-static int pick_path(int path, int64_t M, bool mfma_ok, bool reg_ok)
+// Two rows with K beyond 8192 also go to the tiles: the register form would take two passes and
+// the general GEMV is slower there (measured: 4096 x 11008 13.3 against 9.5 us, 8192 x 28672 48
+// against 34; at K = 8192 the GEMV still wins by 5 %).
+static int pick_path(int path, int64_t M, int64_t K, bool mfma_ok, bool reg_ok)
 {
     if (path != MXFP4_PATH_AUTO)
         return path;
@@ -104,7 +107,9 @@ static int pick_path(int path, int64_t M, bool mfma_ok, bool reg_ok)
         return env_path;
     if (M >= 3 && mfma_ok)
         return MXFP4_PATH_MFMA;
-    return reg_ok ? MXFP4_PATH_VALU_REG : MXFP4_PATH_VALU_CVT;
+    if (reg_ok)
+        return MXFP4_PATH_VALU_REG;
+    return M == 2 && K > 8192 && mfma_ok ? MXFP4_PATH_MFMA : MXFP4_PATH_VALU_CVT;
 }
 
 // Draft verification fused behind the argmax (both product forms): NULL when not asked for.
@@ -130,12 +135,26 @@ static int check_verify(const Verify* v, int64_t M)
 static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const void* s, int64_t N, int64_t K,
                     void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
                     size_t workspace_bytes, bool argmax, int path, void* stream, const Verify* verify = nullptr,
-                    bool tiled = false)
+                    bool tiled = false, const Epilogue* epi = nullptr)
 {
     g_err[0] = 0;
     int rc = check_verify(verify, M);
     if (rc)
         return rc;
+    int64_t C = N;                                  // columns of y
+    if (epi) {
+        if (epi->act != MXFP4_ACT_NONE && epi->act != MXFP4_ACT_SWIGLU)
+            return fail(MXFP4_ERR_ARG, "unknown act %d", epi->act);
+        if (epi->act == MXFP4_ACT_SWIGLU) {
+            if (N % 2 != 0)
+                return fail(MXFP4_ERR_SHAPE, "the gate pairs rows 2c and 2c + 1: N=%lld must be even", (long long)N);
+            C = N / 2;
+        }
+        if (!aligned(epi->bias, 2) || !aligned(epi->residual, 2))
+            return fail(MXFP4_ERR_ALIGN, "bias_bf16 and residual_bf16 must be 2-byte aligned");
+        if (path == MXFP4_PATH_VALU_BITS || path == MXFP4_PATH_VALU_LUT)
+            return fail(MXFP4_ERR_ARG, "path %d has no fused form", path);
+    }
     rc = check_weights(q, s, tiled ? (N + 15) / 16 * 16 : N, K);      // tile-major tensors hold whole tiles
     if (rc)
         return rc;
@@ -180,13 +199,13 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
     } else {
         if (!y)
             return fail(MXFP4_ERR_NULL, "y_bf16 is NULL");
-        if (ldy < N)
-            return fail(MXFP4_ERR_SHAPE, "ldy=%lld < N=%lld", (long long)ldy, (long long)N);
+        if (ldy < C)
+            return fail(MXFP4_ERR_SHAPE, "ldy=%lld < %lld columns of y", (long long)ldy, (long long)C);
         a.y = static_cast<uint16_t*>(y);
         a.ldy = ldy;
     }
     const int chosen = tiled ? -1
-                             : pick_path(path, M, mfma_can_run(a, dev, splitk_ws != nullptr),
+                             : pick_path(path, M, K, mfma_can_run(a, dev, splitk_ws != nullptr),
                                          gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a));
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
@@ -197,7 +216,7 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
             return fail(MXFP4_ERR_ARG, "the tile-major product needs a pass's activation rows (%lld x K=%lld) to fit "
                                        "the LDS; use the canonical tensors for this shape",
                         (long long)(M > 16 ? 16 : M), (long long)K);
-        e = launch_mfma_tile(a, dev, &parts_used, st, true);
+        e = launch_mfma_tile(a, dev, &parts_used, st, true, epi);
         break;
     case MXFP4_PATH_VALU_BITS:
     case MXFP4_PATH_VALU_CVT:
@@ -205,20 +224,20 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         if ((size_t)K * 2 + (chosen == MXFP4_PATH_VALU_LUT ? 32768u : 0u) > (size_t)dev.lds_bytes)
             return fail(MXFP4_ERR_SHAPE, "K=%lld does not fit the LDS copy of one activation row",
                         (long long)K);
-        e = launch_gemv(a, chosen, argmax, dev, &parts_used, st);
+        e = launch_gemv(a, chosen, argmax, dev, &parts_used, st, epi);
         break;
     case MXFP4_PATH_VALU_REG:
         if (!gemv_reg_can_run(a, dev))
             return fail(MXFP4_ERR_ARG, "the register-resident GEMV needs K %% 128 == 0, K <= 12288 and N >= %d",
                         dev.cus * 8);
-        e = launch_gemv_reg(a, dev, &parts_used, st);
+        e = launch_gemv_reg(a, dev, &parts_used, st, epi);
         break;
     case MXFP4_PATH_MFMA:
     case MXFP4_PATH_MFMA_GENERAL:
         if (!mfma_can_run(a, dev, splitk_ws != nullptr))
             return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and, without a workspace, four rows of "
                                        "K=%lld elements exceed the LDS", (long long)K);
-        e = launch_mfma(a, dev, splitk_ws, &parts_used, st, chosen == MXFP4_PATH_MFMA_GENERAL);
+        e = launch_mfma(a, dev, splitk_ws, &parts_used, st, chosen == MXFP4_PATH_MFMA_GENERAL, epi);
         break;
     default:
         return fail(MXFP4_ERR_ARG, "unknown or unavailable path %d", chosen);
@@ -451,6 +470,41 @@ int mxfp4_woq_gemm_ws(const void* x_bf16, int64_t M, int64_t ldx, const void* q_
     }
     return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, workspace,
                     workspace_bytes, false, path, stream);
+}
+
+int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                         const void* scales_e8m0, int64_t N, int64_t K, const void* bias_bf16, int act,
+                         const void* residual_bf16, int64_t ldr, void* y_bf16, int64_t ldy, void* workspace,
+                         size_t workspace_bytes, int path, void* stream)
+{
+    g_err[0] = 0;
+    if (workspace && !aligned(workspace, 8))
+        return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
+    Epilogue epi{static_cast<const uint16_t*>(bias_bf16), static_cast<const uint16_t*>(residual_bf16), 0, act};
+    if (residual_bf16) {
+        const int64_t C = act == MXFP4_ACT_SWIGLU ? N / 2 : N;
+        if (ldr < C || ldr > 0x7FFFFFFF)
+            return fail(MXFP4_ERR_SHAPE, "ldr=%lld must be in [%lld, 2^31)", (long long)ldr, (long long)C);
+        epi.ldr = (int)ldr;
+    }
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, workspace,
+                    workspace_bytes, false, path, stream, nullptr, false, &epi);
+}
+
+int mxfp4_woq_gemm_tiled_fused(const void* x_bf16, int64_t M, int64_t ldx, const void* q_tiled,
+                               const void* s_tiled, int64_t N, int64_t K, const void* bias_bf16, int act,
+                               const void* residual_bf16, int64_t ldr, void* y_bf16, int64_t ldy, void* stream)
+{
+    g_err[0] = 0;
+    Epilogue epi{static_cast<const uint16_t*>(bias_bf16), static_cast<const uint16_t*>(residual_bf16), 0, act};
+    if (residual_bf16) {
+        const int64_t C = act == MXFP4_ACT_SWIGLU ? N / 2 : N;
+        if (ldr < C || ldr > 0x7FFFFFFF)
+            return fail(MXFP4_ERR_SHAPE, "ldr=%lld must be in [%lld, 2^31)", (long long)ldr, (long long)C);
+        epi.ldr = (int)ldr;
+    }
+    return run_gemm(x_bf16, M, ldx, q_tiled, s_tiled, N, K, y_bf16, ldy, nullptr, nullptr, nullptr, 0, false,
+                    MXFP4_PATH_AUTO, stream, nullptr, true, &epi);
 }
 
 int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,

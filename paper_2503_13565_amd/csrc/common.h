@@ -38,6 +38,10 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
+// The gate of the gated MLP: silu(g) * u with silu(g) = g / (1 + e^-g), in FP32.  The limits
+// come out of the arithmetic: e^-g = inf gives -0 for very negative g, e^-g = 0 gives g.
+__device__ __forceinline__ float silu_gate(float g, float u) { return g / (1.f + __expf(-g)) * u; }
+
 // One E2M1 nibble (sign<<3 | eem) -> FP32, by bit assembly: codes 0 and 1 are 0 and 0.5, a
 // normal code eem is 1.m * 2^(ee-1).
 __device__ __forceinline__ float e2m1_to_f32(uint32_t nib)

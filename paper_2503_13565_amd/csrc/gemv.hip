@@ -48,8 +48,10 @@ constexpr int kXRegChunks = 4;    // activation chunks a thread can hold while t
 
 // MT activation rows per pass, R weight rows per group, D register buffers of one step each
 // (D-1 steps of loads stay in flight while one is computed), NW waves per workgroup.
-template <int MT, int R, int D, int NW, int kDecode, bool kScaleDword>
-__global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmArgs a, int m0)
+// kEpi: the fused form (bias, gate, residual applied at the flush; `epi` is not read otherwise).
+// The gate needs R even: a group then holds whole (gate, up) row pairs in neighbouring lanes.
+template <int MT, int R, int D, int NW, int kDecode, bool kScaleDword, bool kEpi>
+__global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmArgs a, int m0, Epilogue epi)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                  // [MT][4][nblk] chunks
@@ -182,14 +184,37 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(GemmArgs a, int m0)
     // and loads share one completion counter but complete out of order with respect to each
     // other, so the counter is drained here; the main loop then only ever sees loads in flight.
     auto flush = [&]() {
-        if (lane < slots) {
-            const int j = lane / R, r = lane - j * R;
-            const int row = (first_group + (flushed_groups + j) * total_waves) * R + r;
-            if (row < a.n) {
+        const int j = lane / R, r = lane - j * R;
+        const int row = (first_group + (flushed_groups + j) * total_waves) * R + r;
+        if constexpr (!kEpi) {
+            if (lane < slots && row < a.n) {
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
                     if (m0 + m < a.m)
                         a.y[(int64_t)(m0 + m) * a.ldy + row] = f32_to_bf16_rne(res[m]);
+            }
+        } else {
+            const bool gated = epi.act == MXFP4_ACT_SWIGLU;
+            const bool own = lane < slots && row < a.n;
+            const bool writer = own && !(gated && (lane & 1));        // even lanes hold the gate rows
+            const int col = gated ? row >> 1 : row;
+            float bv = 0.f, rv[MT];
+            if (epi.bias && own)
+                bv = bf16_bits_to_f32(epi.bias[row]);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                rv[m] = 0.f;
+                if (epi.residual && writer && m0 + m < a.m)
+                    rv[m] = bf16_bits_to_f32(epi.residual[(int64_t)(m0 + m) * epi.ldr + col]);
+            }
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                float v = res[m] + bv;
+                const float up = __shfl_down(v, 1);
+                if (gated)
+                    v = silu_gate(v, up);
+                if (writer && m0 + m < a.m)
+                    a.y[(int64_t)(m0 + m) * a.ldy + col] = f32_to_bf16_rne(v + rv[m]);
             }
         }
         flushed_groups += slots / R;
@@ -510,10 +535,11 @@ bool env_tune(Tune* out)
     return have;
 }
 
-template <int MT, int R, int D, int NW, int kDecode, bool kScaleDword>
-hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
+template <int MT, int R, int D, int NW, int kDecode, bool kScaleDword, bool kEpi>
+hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream,
+                      const Epilogue& epi)
 {
-    auto kern = gemv_kernel<MT, R, D, NW, kDecode, kScaleDword>;
+    auto kern = gemv_kernel<MT, R, D, NW, kDecode, kScaleDword, kEpi>;
     static bool attr_set = false;                   // per instantiation; racing writers set the same value
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -522,19 +548,31 @@ hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max
             return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0, epi);
     return hipGetLastError();
+}
+
+// The fused form exists for the convert decode only (the one AUTO uses).
+template <int MT, int R, int D, int NW, int kDecode, bool kScaleDword>
+hipError_t launch_either(const GemmArgs& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream,
+                         const Epilogue* epi)
+{
+    if (!epi)
+        return launch_one<MT, R, D, NW, kDecode, kScaleDword, false>(a, m0, blocks, lds, max_lds, stream, Epilogue{});
+    if constexpr (kDecode == kCvt)
+        return launch_one<MT, R, D, NW, kDecode, kScaleDword, true>(a, m0, blocks, lds, max_lds, stream, *epi);
+    return hipErrorInvalidValue;
 }
 
 template <int MT, int kDecode>
 hipError_t launch_shape(const GemmArgs& a, int m0, const Tune& t, int blocks, size_t lds, int max_lds,
-                        hipStream_t stream)
+                        hipStream_t stream, const Epilogue* epi)
 {
     const bool sd = (a.k % 128 == 0) && !t.byte_scales;
-#define MXFP4_CASE(R_, D_, NW_)                                                                      \
-    if (t.r == R_ && t.d == D_ && t.nw == NW_)                                                       \
-        return sd ? launch_one<MT, R_, D_, NW_, kDecode, true>(a, m0, blocks, lds, max_lds, stream)  \
-                  : launch_one<MT, R_, D_, NW_, kDecode, false>(a, m0, blocks, lds, max_lds, stream);
+#define MXFP4_CASE(R_, D_, NW_)                                                                            \
+    if (t.r == R_ && t.d == D_ && t.nw == NW_)                                                             \
+        return sd ? launch_either<MT, R_, D_, NW_, kDecode, true>(a, m0, blocks, lds, max_lds, stream, epi)  \
+                  : launch_either<MT, R_, D_, NW_, kDecode, false>(a, m0, blocks, lds, max_lds, stream, epi);
     MXFP4_CASE(4, 2, 4)
     MXFP4_CASE(2, 2, 4)
     MXFP4_CASE(1, 2, 4)
@@ -554,7 +592,8 @@ hipError_t launch_shape(const GemmArgs& a, int m0, const Tune& t, int blocks, si
 }
 
 template <int kDecode>
-hipError_t launch_decode(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+hipError_t launch_decode(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
+                         const Epilogue* epi)
 {
     Tune t = default_tune(a.n, dev.cus);
     if constexpr (kDecode == kCvt) {
@@ -565,6 +604,8 @@ hipError_t launch_decode(const GemmArgs& a, const DeviceInfo& dev, int* parts_us
             t = e;
         }
     }
+    if (epi && epi->act == MXFP4_ACT_SWIGLU && t.r == 1)
+        t.r = 2;                                    // a group must hold whole (gate, up) pairs
     const size_t extra = kDecode == kLut ? (size_t)kLutBytes : 0;
     // two activation rows per pass when their LDS copy fits, else one
     const bool two_fit = (size_t)2 * a.k * 2 + extra <= (size_t)dev.lds_bytes;
@@ -580,10 +621,10 @@ hipError_t launch_decode(const GemmArgs& a, const DeviceInfo& dev, int* parts_us
         const int left = a.m - m0;
         hipError_t e;
         if (left >= 2 && two_fit) {
-            e = launch_shape<2, kDecode>(a, m0, t, blocks, (size_t)2 * a.k * 2 + extra, dev.lds_bytes, stream);
+            e = launch_shape<2, kDecode>(a, m0, t, blocks, (size_t)2 * a.k * 2 + extra, dev.lds_bytes, stream, epi);
             m0 += 2;
         } else {
-            e = launch_shape<1, kDecode>(a, m0, t, blocks, (size_t)a.k * 2 + extra, dev.lds_bytes, stream);
+            e = launch_shape<1, kDecode>(a, m0, t, blocks, (size_t)a.k * 2 + extra, dev.lds_bytes, stream, epi);
             m0 += 1;
         }
         if (e != hipSuccess)
@@ -595,16 +636,16 @@ hipError_t launch_decode(const GemmArgs& a, const DeviceInfo& dev, int* parts_us
 }  // namespace
 
 hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceInfo& dev, int* parts_used,
-                       hipStream_t stream)
+                       hipStream_t stream, const Epilogue* epi)
 {
     (void)argmax;                                   // the kernels look at a.part_val
     switch (decode) {
     case kBits:
-        return launch_decode<kBits>(a, dev, parts_used, stream);
+        return launch_decode<kBits>(a, dev, parts_used, stream, epi);
     case kCvt:
-        return launch_decode<kCvt>(a, dev, parts_used, stream);
+        return launch_decode<kCvt>(a, dev, parts_used, stream, epi);
     case kLut:
-        return launch_decode<kLut>(a, dev, parts_used, stream);
+        return launch_decode<kLut>(a, dev, parts_used, stream, epi);
     default:
         return hipErrorInvalidValue;
     }

@@ -41,12 +41,14 @@ struct RegArgs {
 // MT activation rows, STEPS (even) steps of 64 blocks cover K (the last ones may be ragged or
 // empty), D step buffers, NW waves per workgroup.  kRagged: K is not STEPS * 2048.
 // R weight rows per wave step (a group); group i of workgroup b's sequence is i * gridDim.x + b.
-template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
-__global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, const uint8_t* q, const uint8_t* s,
-                                                           void* out, int n, int k, int m, int m0, int ldx,
-                                                           int ldy, int parts)
+// Epi: NoEpilogue, or Epilogue for the fused form (bias, gate, residual at the flush).  The gate
+// needs a pair of rows 2c, 2c + 1 in neighbouring lanes of the held outputs: with R = 2 a group is
+// a pair; with R = 1 the counter deals pairs and a wave takes the pair's rows in two trips.
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged, class Epi>
+__device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 {
-    const RegArgs a{x, q, s, out, n, k, m, m0, ldx, ldy, parts};
+    constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
+    const int m0 = a.m0;
     static_assert(STEPS % D == 0, "the buffer of a step must be known at compile time");
     constexpr int T = NW * 64;
     constexpr int XPR = (STEPS * 256 + T - 1) / T;          // 16-byte activation chunks per thread and row
@@ -77,7 +79,12 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, co
     const int q_row_bytes = a.k >> 1;
     const bool argmax = a.parts > 0;
     const int G = gridDim.x, b = blockIdx.x;
-    auto row_of = [&](int i) { return i * G + b; };
+    bool gated = false;
+    if constexpr (kEpi)
+        gated = epi.act == MXFP4_ACT_SWIGLU;
+    const bool pair_trips = kEpi && R == 1 && gated;                 // a dealt index is a pair of rows
+    const int per_index = pair_trips ? 2 : 1;
+    auto row_of = [&](int i) { return (i * G + b) * per_index; };
 
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(a.q), 0, a.n * q_row_bytes, 0x00020000);
@@ -86,6 +93,25 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, co
 
     if (tid == 0)
         *ctr = NW;                                                   // indices 0..NW-1 are the waves' first rows
+
+    // Fused form: a row's bias and residual are fetched when its trip starts (one broadcast load
+    // each, behind descriptors that cover nothing when the operand is absent) and kept with its
+    // slot, so the flush has nothing to wait for.
+    Epilogue ep{nullptr, nullptr, 0, 0};
+    if constexpr (kEpi)
+        ep = epi;
+    float bias_s = 0.f, res_s[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+        res_s[m] = 0.f;
+    const __amdgpu_buffer_rsrc_t rb =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(ep.bias), 0, ep.bias ? a.n * 2 : 0, 0x00020000);
+    auto residual_row = [&](int m) {
+        return __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(ep.residual + (int64_t)min(a.m0 + m, a.m - 1) * ep.ldr), 0,
+            ep.residual ? (gated ? a.n >> 1 : a.n) * 2 : 0, 0x00020000);
+    };
+    const __amdgpu_buffer_rsrc_t rr0 = residual_row(0), rr1 = residual_row(MT - 1);
 
     u32x4_t bq[D][R];
     uint32_t bs[D];
@@ -151,11 +177,27 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, co
     // Stores and loads share one completion counter but complete out of order with respect to
     // each other, so the counter is drained here; the loop only ever sees loads in flight.
     auto flush = [&]() {
-        if (lane < slots && rowv < a.n) {
+        if constexpr (!kEpi) {
+            if (lane < slots && rowv < a.n) {
 #pragma unroll
-            for (int m = 0; m < MT; ++m)
-                if (m0 + m < a.m)
-                    static_cast<uint16_t*>(a.out)[(int64_t)(m0 + m) * a.ldy + rowv] = f32_to_bf16_rne(res[m]);
+                for (int m = 0; m < MT; ++m)
+                    if (m0 + m < a.m)
+                        static_cast<uint16_t*>(a.out)[(int64_t)(m0 + m) * a.ldy + rowv] = f32_to_bf16_rne(res[m]);
+            }
+        } else {
+            // even lanes hold the gate rows, their right neighbours the up rows (slots fill in pairs)
+            const bool own = lane < slots && rowv < a.n;
+            const bool writer = own && !(gated && (lane & 1));
+            const int col = gated ? rowv >> 1 : rowv;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                float v = res[m] + bias_s;
+                const float up = __shfl_down(v, 1);
+                if (gated)
+                    v = silu_gate(v, up);
+                if (writer && m0 + m < a.m)
+                    static_cast<uint16_t*>(a.out)[(int64_t)(m0 + m) * a.ldy + col] = f32_to_bf16_rne(v + res_s[m]);
+            }
         }
         slots = 0;
         drain_vmem();
@@ -169,9 +211,29 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, co
 
     const int sh_top = (3 - (lane & 3)) * 8;        // brings this lane's scale byte to bits 31:24
     int i_next = fetch();
+    bool second = false;                            // pair_trips: this trip takes the pair's second row
     while (grp < n_groups) {
-        const int grp_n = row_of(i_next);
-        const int i_next2 = fetch();                // consumed one trip later: its latency is hidden
+        int grp_n, i_next2;
+        if (pair_trips && !second) {
+            grp_n = grp + 1;
+            i_next2 = i_next;
+        } else {
+            grp_n = row_of(i_next);
+            i_next2 = fetch();                      // consumed one trip later: its latency is hidden
+        }
+        second = !second;
+        uint32_t bias_l[R], res_l[R][MT];
+        if constexpr (kEpi) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int row = grp * R + r;                // past N: outside the descriptors, reads zero
+                bias_l[r] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, row * 2, 0, 0);
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    res_l[r][m] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
+                        m == 0 ? rr0 : rr1, (gated ? row >> 1 : row) * 2, 0, 0);
+            }
+        }
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
             const int d = t % D;
@@ -231,6 +293,12 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, co
             }
             if (!argmax)
                 rowv = (lane == slots + r) ? row : rowv;
+            if constexpr (kEpi) {
+                bias_s = (lane == slots + r) ? bf16_bits_to_f32(bias_l[r]) : bias_s;
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    res_s[m] = (lane == slots + r) ? bf16_bits_to_f32(res_l[r][m]) : res_s[m];
+            }
         }
         if (!argmax) {
             slots += R;
@@ -276,18 +344,45 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, co
 }
 
 template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
-hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream)
+__global__ __launch_bounds__(NW * 64) void gemv_reg_kernel(const uint16_t* x, const uint8_t* q, const uint8_t* s,
+                                                           void* out, int n, int k, int m, int m0, int ldx,
+                                                           int ldy, int parts)
+{
+    gemv_reg_body<MT, R, STEPS, D, NW, kRagged>(RegArgs{x, q, s, out, n, k, m, m0, ldx, ldy, parts}, NoEpilogue{});
+}
+
+// The fused form: `act` decides which rows a wave starts with, so it takes the last preloaded
+// slot; the other epilogue arguments come behind and are first needed when the first trip starts.
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+__global__ __launch_bounds__(NW * 64) void gemv_reg_fused_kernel(const uint16_t* x, const uint8_t* q,
+                                                                 const uint8_t* s, void* out, int n, int k, int m,
+                                                                 int m0, int ldx, int ldy, int parts, int act,
+                                                                 const uint16_t* bias, const uint16_t* residual,
+                                                                 int ldr)
+{
+    gemv_reg_body<MT, R, STEPS, D, NW, kRagged>(RegArgs{x, q, s, out, n, k, m, m0, ldx, ldy, parts},
+                                                Epilogue{bias, residual, ldr, act});
+}
+
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream, const Epilogue* epi)
 {
     const bool argmax = g.part_val != nullptr;
-    hipLaunchKernelGGL((gemv_reg_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds, stream,
-                       g.x, g.q, g.s, argmax ? static_cast<void*>(g.part_val) : static_cast<void*>(g.y), g.n, g.k,
-                       g.m, m0, (int)g.ldx, (int)g.ldy, argmax ? g.parts : 0);
+    if (epi)
+        hipLaunchKernelGGL((gemv_reg_fused_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds,
+                           stream, g.x, g.q, g.s, static_cast<void*>(g.y), g.n, g.k, g.m, m0, (int)g.ldx,
+                           (int)g.ldy, 0, epi->act, epi->bias, epi->residual, epi->ldr);
+    else
+        hipLaunchKernelGGL((gemv_reg_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds,
+                           stream, g.x, g.q, g.s,
+                           argmax ? static_cast<void*>(g.part_val) : static_cast<void*>(g.y), g.n, g.k, g.m, m0,
+                           (int)g.ldx, (int)g.ldy, argmax ? g.parts : 0);
     return hipGetLastError();
 }
 
 template <int MT>
 hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int blocks, size_t lds,
-                        hipStream_t stream)
+                        hipStream_t stream, const Epilogue* epi)
 {
     // 16 waves hold at most 128 registers each: enough for four steps of one activation row.
     // Six steps: 8 waves, each with two weight rows and three steps in flight (measured best on
@@ -295,20 +390,20 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
     switch (steps2) {
     case 2:
         if constexpr (MT == 1)
-            return ragged ? launch_one<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream)
-                          : launch_one<MT, 1, 2, 2, 16, false>(a, m0, blocks, lds, stream);
+            return ragged ? launch_one<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream, epi)
+                          : launch_one<MT, 1, 2, 2, 16, false>(a, m0, blocks, lds, stream, epi);
         else                                       // two activation rows need more registers: 8 waves
-            return ragged ? launch_one<MT, 2, 2, 2, 8, true>(a, m0, blocks, lds, stream)
-                          : launch_one<MT, 2, 2, 2, 8, false>(a, m0, blocks, lds, stream);
+            return ragged ? launch_one<MT, 2, 2, 2, 8, true>(a, m0, blocks, lds, stream, epi)
+                          : launch_one<MT, 2, 2, 2, 8, false>(a, m0, blocks, lds, stream, epi);
     case 4:
         if constexpr (MT == 1)
-            return ragged ? launch_one<MT, 1, 4, 2, 16, true>(a, m0, blocks, lds, stream)
-                          : launch_one<MT, 1, 4, 2, 16, false>(a, m0, blocks, lds, stream);
+            return ragged ? launch_one<MT, 1, 4, 2, 16, true>(a, m0, blocks, lds, stream, epi)
+                          : launch_one<MT, 1, 4, 2, 16, false>(a, m0, blocks, lds, stream, epi);
         break;
     case 6:
         if constexpr (MT == 1)
-            return ragged ? launch_one<MT, 2, 6, 3, 8, true>(a, m0, blocks, lds, stream)
-                          : launch_one<MT, 2, 6, 3, 8, false>(a, m0, blocks, lds, stream);
+            return ragged ? launch_one<MT, 2, 6, 3, 8, true>(a, m0, blocks, lds, stream, epi)
+                          : launch_one<MT, 2, 6, 3, 8, false>(a, m0, blocks, lds, stream, epi);
         break;
     }
     return hipErrorInvalidValue;
@@ -339,7 +434,8 @@ bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev)
 
 bool gemv_reg_single_pass(const GemmArgs& a) { return a.m == 1 || (a.m == 2 && even_steps(a.k) <= 2); }
 
-hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
+                           const Epilogue* epi)
 {
     const int steps2 = even_steps(a.k);
     const bool ragged = a.k != steps2 * 2048;
@@ -357,10 +453,10 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     for (int m0 = 0; m0 < a.m;) {
         hipError_t e;
         if (a.m - m0 >= 2 && steps2 <= 2) {
-            e = launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream);
+            e = launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi);
             m0 += 2;
         } else {
-            e = launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream);
+            e = launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi);
             m0 += 1;
         }
         if (e != hipSuccess)

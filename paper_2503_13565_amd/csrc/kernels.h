@@ -29,6 +29,17 @@ struct GemmArgs {
     int phase_steps;
 };
 
+// What is fused behind the contraction (see mxfp4_woq_gemm_fused in include/mxfp4.h):
+// z = product + bias[n]; gated: t[c] = silu(z[2c]) * z[2c + 1] (C = N / 2 outputs per row),
+// else t = z; y = t + residual[m][c].  y then has C columns.
+struct Epilogue {
+    const uint16_t* bias;       // BF16 [N] or null
+    const uint16_t* residual;   // BF16 [M, C], row stride ldr, or null; may be y itself
+    int ldr;
+    int act;                    // MXFP4_ACT_NONE or MXFP4_ACT_SWIGLU
+};
+struct NoEpilogue {};
+
 struct DeviceInfo {
     int cus;             // compute units
     int lds_bytes;       // LDS per workgroup the device allows
@@ -43,8 +54,9 @@ hipError_t launch_dequant(const void* q, const void* s, int64_t n_rows, int64_t 
 // Wave-per-row-group product on the vector ALUs.  `decode` is one of MXFP4_PATH_VALU_*.
 // Handles any M by passing over the weights once per group of activation rows.
 // `parts_used` receives the number of partial winners written per row (argmax form).
+// `epi`: the fused form (MXFP4_PATH_VALU_CVT only).
 hipError_t launch_gemv(const GemmArgs& a, int decode, bool argmax, const DeviceInfo& dev,
-                       int* parts_used, hipStream_t stream);
+                       int* parts_used, hipStream_t stream, const Epilogue* epi = nullptr);
 int gemv_max_parts(const DeviceInfo& dev);
 
 // The decode-step form of the same product (converts + dot2, activations in registers, one
@@ -52,7 +64,8 @@ int gemv_max_parts(const DeviceInfo& dev);
 // for the shapes it takes.  The argmax form writes one partial winner per workgroup.
 bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev);
 bool gemv_reg_single_pass(const GemmArgs& a);     // all activation rows in one pass over the weights
-hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
+                           const Epilogue* epi = nullptr);
 
 // 16-row MFMA tiles (bf16 16x16x32) for verification batches; passes of up to 16 activation rows.
 // When the activation rows of a pass do not fit the LDS whole, K is split: in space over
@@ -63,14 +76,14 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
 bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev, bool have_splitk_ws);
 size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev);
 hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
-                       hipStream_t stream, bool general_only = false);
+                       hipStream_t stream, bool general_only = false, const Epilogue* epi = nullptr);
 
 // The same tiles in a leaner kernel for passes whose activation rows fit the LDS whole (no K
 // split); launch_mfma uses it whenever it can run unless told `general_only` (or
 // MXFP4_MFMA_LEGACY=1 in the environment, for measurements).
 bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev);
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
-                            bool tiled = false);
+                            bool tiled = false, const Epilogue* epi = nullptr);
 
 // Tile-major copy of the weights for the tile kernel (`tiled`: a.q / a.s are that copy): what a
 // wave instruction loads is contiguous.  Sizes in bytes; K % 128 == 0.

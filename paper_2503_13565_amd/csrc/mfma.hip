@@ -76,8 +76,10 @@ struct MPos {
 // a phase, and the epilogue wave keeps each tile's running FP32 sum in LDS until the last phase.
 // In space (a.splitk_ws != NULL): grid dimension y is the phase and the partial products go to
 // the workspace (for matrices with too many tiles per workgroup to keep their sums in LDS).
-template <int MP, int NW, int D>
-__global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
+// kEpi: the fused form (bias, gate on the row pairs a lane holds, residual; `epi` is not read
+// otherwise).
+template <int MP, int NW, int D, bool kEpi>
+__global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0, Epilogue epi)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                          // [NW][steps_w][4][4][MP] chunks of 8 elements
@@ -255,6 +257,40 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
                     }
                 }
                 // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
+                if constexpr (kEpi) {
+                    // fused form without a split in space (there the finish kernel applies it)
+                    if (!in_space) {
+                        if (li < m_valid) {
+                            const bool gated = epi.act == MXFP4_ACT_SWIGLU;
+                            const int row0 = tile * 16 + 4 * lg;
+                            const int cols = gated ? 2 : 4, col0 = gated ? row0 >> 1 : row0;
+                            const int n_cols = gated ? a.n >> 1 : a.n;
+                            float bias_v[4] = {0.f, 0.f, 0.f, 0.f}, res_v[4] = {0.f, 0.f, 0.f, 0.f};
+                            uint16_t* y = a.y + (int64_t)(m0 + li) * a.ldy;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                if (epi.bias && row0 + r < a.n)
+                                    bias_v[r] = bf16_bits_to_f32(epi.bias[row0 + r]);
+                                if (epi.residual && r < cols && col0 + r < n_cols)
+                                    res_v[r] = bf16_bits_to_f32(epi.residual[(int64_t)(m0 + li) * epi.ldr + col0 + r]);
+                            }
+                            if (gated) {                          // rows (0, 1) and (2, 3) are (gate, up) pairs
+#pragma unroll
+                                for (int c = 0; c < 2; ++c)
+                                    if (col0 + c < n_cols)
+                                        y[col0 + c] = f32_to_bf16_rne(silu_gate(sum[2 * c] + bias_v[2 * c],
+                                                                                sum[2 * c + 1] + bias_v[2 * c + 1]) +
+                                                                      res_v[c]);
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    if (row0 + r < a.n)
+                                        y[row0 + r] = f32_to_bf16_rne(sum[r] + bias_v[r] + res_v[r]);
+                            }
+                        }
+                        continue;
+                    }
+                }
                 if (li < m_valid) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -414,12 +450,41 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_kernel(GemmArgs a, int m0)
 
 // Second kernel of the split-K form: add the phases' partial products in phase order, then round
 // and store, or find each workgroup's (max, index) for the argmax's last stage.
-__global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a)
+// kEpi: the fused form; a thread then takes one output column: one weight row, or with the gate
+// the pair of rows 2c, 2c + 1.
+template <bool kEpi>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a, Epilogue epi)
 {
     __shared__ float sv[4];
     __shared__ int si[4];
     const int tid = threadIdx.x;
     const bool argmax = a.part_val != nullptr;
+    if constexpr (kEpi) {
+        const bool gated = epi.act == MXFP4_ACT_SWIGLU;
+        const int n_cols = gated ? a.n >> 1 : a.n;
+        for (int m = blockIdx.y; m < a.m; m += gridDim.y) {
+            for (int c = (int)blockIdx.x * 256 + tid; c < n_cols; c += gridDim.x * 256) {
+                const int n0 = gated ? 2 * c : c;
+                float z0 = 0.f, z1 = 0.f;
+                for (int p = 0; p < a.phases; ++p) {
+                    const float* w = a.splitk_ws + ((int64_t)p * a.m + m) * a.n + n0;
+                    z0 += w[0];
+                    if (gated)
+                        z1 += w[1];
+                }
+                if (epi.bias) {
+                    z0 += bf16_bits_to_f32(epi.bias[n0]);
+                    if (gated)
+                        z1 += bf16_bits_to_f32(epi.bias[n0 + 1]);
+                }
+                float t = gated ? silu_gate(z0, z1) : z0;
+                if (epi.residual)
+                    t += bf16_bits_to_f32(epi.residual[(int64_t)m * epi.ldr + c]);
+                a.y[(int64_t)m * a.ldy + c] = f32_to_bf16_rne(t);
+            }
+        }
+        return;
+    }
     for (int m = blockIdx.y; m < a.m; m += gridDim.y) {
     float bv = -INFINITY;
     int bi = 0x7FFFFFFF;
@@ -471,11 +536,11 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a)
 // system, and a second workgroup only lengthens the start-up burst), split over grid_y phases
 // when K is split in space.  *blocks is the cap on workgroups per phase on entry (0 = none) and
 // the count used on return.
-template <int MP, int NW, int D>
+template <int MP, int NW, int D, bool kEpi>
 hipError_t launch_one(const GemmArgs& a, int m0, int grid_y, size_t lds, const DeviceInfo& dev, int* blocks,
-                      hipStream_t stream)
+                      hipStream_t stream, const Epilogue& epi)
 {
-    auto kern = mfma_kernel<MP, NW, D>;
+    auto kern = mfma_kernel<MP, NW, D, kEpi>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -509,7 +574,7 @@ hipError_t launch_one(const GemmArgs& a, int m0, int grid_y, size_t lds, const D
     if (*blocks > 0 && nb > *blocks)
         nb = *blocks;
     *blocks = nb;
-    hipLaunchKernelGGL(kern, dim3(nb, grid_y), dim3((NW + 1) * 64), lds, stream, a, m0);
+    hipLaunchKernelGGL(kern, dim3(nb, grid_y), dim3((NW + 1) * 64), lds, stream, a, m0, epi);
     return hipGetLastError();
 }
 
@@ -622,14 +687,14 @@ size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev)
 }
 
 hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
-                       hipStream_t stream, bool general_only)
+                       hipStream_t stream, bool general_only, const Epilogue* epi)
 {
     static const bool legacy = [] {
         const char* e = getenv("MXFP4_MFMA_LEGACY");
         return e && atoi(e) != 0;
     }();
     if (!legacy && !general_only && mfma_tile_can_run(a_in, dev))
-        return launch_mfma_tile(a_in, dev, parts_used, stream);
+        return launch_mfma_tile(a_in, dev, parts_used, stream, false, epi);
     if (!mfma_can_run(a_in, dev, splitk_ws != nullptr))
         return hipErrorInvalidValue;
     GemmArgs a = a_in;
@@ -684,10 +749,12 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
             return v >= 2 && v <= 4 ? v : 2;
         }();
         hipError_t e;
+        // the fused form exists at the default depth only
 #define MXFP4_MFMA_CASE(MP_)                                                                       \
-    (depth == 4   ? launch_one<MP_, kNW, 4>(a, m0, grid_y, lds, dev, &blocks, stream)                \
-     : depth == 3 ? launch_one<MP_, kNW, 3>(a, m0, grid_y, lds, dev, &blocks, stream)                \
-                  : launch_one<MP_, kNW, 2>(a, m0, grid_y, lds, dev, &blocks, stream))
+    (epi          ? launch_one<MP_, kNW, 2, true>(a, m0, grid_y, lds, dev, &blocks, stream, *epi)    \
+     : depth == 4 ? launch_one<MP_, kNW, 4, false>(a, m0, grid_y, lds, dev, &blocks, stream, Epilogue{})  \
+     : depth == 3 ? launch_one<MP_, kNW, 3, false>(a, m0, grid_y, lds, dev, &blocks, stream, Epilogue{})  \
+                  : launch_one<MP_, kNW, 2, false>(a, m0, grid_y, lds, dev, &blocks, stream, Epilogue{}))
         if (mp == 16)
             e = MXFP4_MFMA_CASE(16);
         else if (mp == 8)
@@ -708,7 +775,12 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
         int fblocks = (a.n + 255) / 256;
         if (fblocks > gemv_max_parts(dev))
             fblocks = gemv_max_parts(dev);
-        hipLaunchKernelGGL(splitk_finish_kernel, dim3(fblocks, a.m < 1024 ? a.m : 1024), dim3(256), 0, stream, a);
+        if (epi)
+            hipLaunchKernelGGL(splitk_finish_kernel<true>, dim3(fblocks, a.m < 1024 ? a.m : 1024), dim3(256), 0,
+                               stream, a, *epi);
+        else
+            hipLaunchKernelGGL(splitk_finish_kernel<false>, dim3(fblocks, a.m < 1024 ? a.m : 1024), dim3(256), 0,
+                               stream, a, Epilogue{});
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return e;

@@ -46,12 +46,15 @@ size_t tile_lds_bytes(int k, int mp)
 // MP: activation rows per pass (4, 8 or 16).  Kernel arguments are scalars so that they are
 // preloaded into registers when a wave starts.  `out` is y (BF16 [M, N]) or, in the argmax form
 // (parts > 0), the partial winners: float [M, parts] followed by int32 [M, parts].
-template <int MP, int NW, int D, bool kTiled>
-__global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_kernel(const uint16_t* __restrict__ x,
-                                                                  const uint8_t* __restrict__ q,
-                                                                  const uint8_t* __restrict__ s, void* out, int n,
-                                                                  int k, int m, int m0, int ldx, int ldy, int parts)
+// Epi: NoEpilogue, or Epilogue for the fused form: the epilogue wave adds the bias, applies the
+// gate to the row pairs it holds in one lane and adds the residual; it fetches a tile's bias and
+// residual before it waits for the compute waves, so the loads cost no time.
+template <int MP, int NW, int D, bool kTiled, class Epi>
+__device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, const uint8_t* __restrict__ q,
+                                               const uint8_t* __restrict__ s, void* out, int n, int k, int m,
+                                               int m0, int ldx, int ldy, int parts, const Epi& epi)
 {
+    constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     constexpr int T = (NW + 1) * 64;
     extern __shared__ __align__(16) uint8_t smem[];
     u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);
@@ -174,12 +177,45 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_kernel(const uint16_t
         int done = 0;
         for (int tile = b; tile < n_tiles; tile += G, ++done) {
             const f32x4_t* slot = red + (size_t)(done & 1) * NW * 64;
+            float bias_v[4] = {0.f, 0.f, 0.f, 0.f}, res_v[4] = {0.f, 0.f, 0.f, 0.f};
+            bool gated = false;
+            if constexpr (kEpi) {
+                gated = epi.act == MXFP4_ACT_SWIGLU;
+                const int row0 = tile * 16 + 4 * lg;
+                const int cols = gated ? 2 : 4, col0 = gated ? row0 >> 1 : row0, n_cols = gated ? n >> 1 : n;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (epi.bias && row0 + r < n)
+                        bias_v[r] = bf16_bits_to_f32(epi.bias[row0 + r]);
+                    if (epi.residual && li < m_valid && r < cols && col0 + r < n_cols)
+                        res_v[r] = bf16_bits_to_f32(epi.residual[(int64_t)(m0 + li) * epi.ldr + col0 + r]);
+                }
+            }
             lds_barrier();                                              // partial tiles of `tile` are in LDS
             f32x4_t sum = slot[lane];
 #pragma unroll
             for (int w = 1; w < NW; ++w)
                 sum += slot[w * 64 + lane];
             // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
+            if constexpr (kEpi) {
+                if (li < m_valid) {
+                    uint16_t* y = static_cast<uint16_t*>(out) + (int64_t)(m0 + li) * ldy;
+                    const int row0 = tile * 16 + 4 * lg;
+                    if (gated) {                                        // rows (0, 1) and (2, 3) are (gate, up) pairs
+#pragma unroll
+                        for (int c = 0; c < 2; ++c)
+                            if (row0 + 2 * c < n)
+                                y[(row0 >> 1) + c] = f32_to_bf16_rne(
+                                    silu_gate(sum[2 * c] + bias_v[2 * c], sum[2 * c + 1] + bias_v[2 * c + 1]) + res_v[c]);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (row0 + r < n)
+                                y[row0 + r] = f32_to_bf16_rne(sum[r] + bias_v[r] + res_v[r]);
+                    }
+                }
+                continue;
+            }
             if (li < m_valid) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -279,6 +315,25 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_kernel(const uint16_t
     }
 }
 
+template <int MP, int NW, int D, bool kTiled>
+__global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_kernel(const uint16_t* __restrict__ x,
+                                                                  const uint8_t* __restrict__ q,
+                                                                  const uint8_t* __restrict__ s, void* out, int n,
+                                                                  int k, int m, int m0, int ldx, int ldy, int parts)
+{
+    mfma_tile_body<MP, NW, D, kTiled>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{});
+}
+
+template <int MP, int NW, int D, bool kTiled>
+__global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_fused_kernel(
+    const uint16_t* __restrict__ x, const uint8_t* __restrict__ q, const uint8_t* __restrict__ s, void* out, int n,
+    int k, int m, int m0, int ldx, int ldy, int parts, int act, const uint16_t* bias, const uint16_t* residual,
+    int ldr)
+{
+    mfma_tile_body<MP, NW, D, kTiled>(x, q, s, out, n, k, m, m0, ldx, ldy, parts,
+                                      Epilogue{bias, residual, ldr, act});
+}
+
 // Make the tile-major copy: one thread per 16 bytes of either output.  q_t unit (tile, T, lane =
 // i + 16 g) is block 4T + g of row 16 tile + i; s_t unit (tile, item, i) holds the scale bytes of
 // blocks 16 item .. 16 item + 15 of that row.  Rows past N get zero nibbles, blocks past K and rows
@@ -315,21 +370,30 @@ __global__ __launch_bounds__(256) void tile_repack_kernel(const u32x4_t* __restr
 
 template <int MP, int D, bool kTiled>
 hipError_t launch_pass(const GemmArgs& a, int m0, int blocks, size_t lds, const DeviceInfo& dev,
-                       hipStream_t stream)
+                       hipStream_t stream, const Epilogue* epi)
 {
     auto kern = mfma_tile_kernel<MP, kTileNW, D, kTiled>;
+    auto kern_fused = mfma_tile_fused_kernel<MP, kTileNW, D, kTiled>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_fused),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
         if (e != hipSuccess)
             return e;
         attr_set = true;
     }
     const bool argmax = a.part_val != nullptr;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3((kTileNW + 1) * 64), lds, stream, a.x, a.q, a.s,
-                       argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, a.m, m0,
-                       (int)a.ldx, (int)a.ldy, argmax ? a.parts : 0);
+    if (epi)
+        hipLaunchKernelGGL(kern_fused, dim3(blocks), dim3((kTileNW + 1) * 64), lds, stream, a.x, a.q, a.s,
+                           static_cast<void*>(a.y), a.n, a.k, a.m, m0, (int)a.ldx, (int)a.ldy, 0, epi->act,
+                           epi->bias, epi->residual, epi->ldr);
+    else
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3((kTileNW + 1) * 64), lds, stream, a.x, a.q, a.s,
+                           argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, a.m, m0,
+                           (int)a.ldx, (int)a.ldy, argmax ? a.parts : 0);
     return hipGetLastError();
 }
 
@@ -366,7 +430,7 @@ hipError_t launch_tile_repack(const void* q, const void* s, int n, int k, void* 
 }
 
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
-                            bool tiled)
+                            bool tiled, const Epilogue* epi)
 {
     const int n_tiles = (a.n + 15) / 16;
     // About 48 to 64 KiB of weights in flight per compute unit is where this kernel peaks
@@ -388,9 +452,9 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
         const size_t lds = tile_lds_bytes(a.k, mp);
         hipError_t e;
 #define MXFP4_TILE_CASE(D_, T_)                                                        \
-    (mp == 16  ? launch_pass<16, D_, T_>(a, m0, blocks, lds, dev, stream)              \
-     : mp == 8 ? launch_pass<8, D_, T_>(a, m0, blocks, lds, dev, stream)               \
-               : launch_pass<4, D_, T_>(a, m0, blocks, lds, dev, stream))
+    (mp == 16  ? launch_pass<16, D_, T_>(a, m0, blocks, lds, dev, stream, epi)              \
+     : mp == 8 ? launch_pass<8, D_, T_>(a, m0, blocks, lds, dev, stream, epi)               \
+               : launch_pass<4, D_, T_>(a, m0, blocks, lds, dev, stream, epi))
         if (tiled)
             e = long_k ? MXFP4_TILE_CASE(3, true) : MXFP4_TILE_CASE(2, true);
         else
