@@ -63,6 +63,14 @@ def _load():
         lib.oracle_sd_speedup_alpha.restype = f64
         lib.oracle_sd_speedup_two_level.argtypes = [f64] * 6
         lib.oracle_sd_speedup_two_level.restype = f64
+        lib.oracle_e4m3_direct_cast.argtypes = [vp, i64, i64, i64, vp, vp, i32]
+        lib.oracle_e4m3_direct_cast.restype = i32
+        lib.oracle_e4m3_dequant.argtypes = [vp, vp, i64, i64, vp]
+        lib.oracle_e4m3_dequant.restype = i32
+        lib.oracle_e4m3_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32]
+        lib.oracle_e4m3_woq_gemm.restype = i32
+        lib.oracle_e4m3_magnitude.argtypes = [i32]
+        lib.oracle_e4m3_magnitude.restype = ctypes.c_double
         lib.oracle_epilogue.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, vp, vp]
         lib.oracle_epilogue.restype = i32
         lib.oracle_argmax.argtypes = [vp, i64, i64, vp, vp]
@@ -171,6 +179,55 @@ def woq_gemm_late_scaled(x_bits, q, s) -> np.ndarray:
     if rc:
         raise RuntimeError("oracle_woq_gemm_late_scaled failed: %d" % rc)
     return y
+
+
+def e4m3_magnitude(code: int) -> float:
+    return float(_load().oracle_e4m3_magnitude(int(code)))
+
+
+def e4m3_direct_cast(w_bits, threads: int = 0):
+    """BF16 bit patterns ``[N, K]`` -> (``q8 [N, K]`` E4M3 bytes, ``s [N, K/32]`` E8M0 scale bytes)."""
+    w = _as(w_bits, np.uint16, 2)
+    n, k = w.shape
+    if k % BLOCK:
+        raise ValueError("K must be a multiple of 32")
+    q8 = np.empty((n, k), np.uint8)
+    s = np.empty((n, k // BLOCK), np.uint8)
+    rc = _load().oracle_e4m3_direct_cast(_ptr(w), n, k, k, _ptr(q8), _ptr(s), threads)
+    if rc:
+        raise RuntimeError("oracle_e4m3_direct_cast failed: %d" % rc)
+    return q8, s
+
+
+def e4m3_dequant(q8, s) -> np.ndarray:
+    q8 = _as(q8, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    n, k = q8.shape
+    if s.shape != (n, k // BLOCK):
+        raise ValueError("shape mismatch: q8 %r s %r" % (q8.shape, s.shape))
+    out = np.empty((n, k), np.float64)
+    rc = _load().oracle_e4m3_dequant(_ptr(q8), _ptr(s), n, k, _ptr(out))
+    if rc:
+        raise RuntimeError("oracle_e4m3_dequant failed: %d" % rc)
+    return out
+
+
+def e4m3_woq_gemm(x_bits, q8, s, threads: int = 0, want_abs: bool = True):
+    """FP64 product with 8-bit (E4M3 + E8M0) weights and the sum of absolute products."""
+    x = _as(x_bits, np.uint16, 2)
+    q8 = _as(q8, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    m, k = x.shape
+    n = q8.shape[0]
+    if q8.shape[1] != k or s.shape != (n, k // BLOCK):
+        raise ValueError("shape mismatch: x %r q8 %r s %r" % (x.shape, q8.shape, s.shape))
+    y = np.empty((m, n), np.float64)
+    a = np.empty((m, n), np.float64) if want_abs else None
+    rc = _load().oracle_e4m3_woq_gemm(_ptr(x), m, k, _ptr(q8), _ptr(s), n, k, _ptr(y),
+                                      _ptr(a) if want_abs else None, threads)
+    if rc:
+        raise RuntimeError("oracle_e4m3_woq_gemm failed: %d" % rc)
+    return (y, a) if want_abs else y
 
 
 ACT_NONE, ACT_SWIGLU = 0, 1

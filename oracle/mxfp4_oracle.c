@@ -32,7 +32,10 @@
  * product on weights that the cast represents exactly; the fused epilogue against
  * a library FP64 silu, closed-form values, the odd-part identity
  * silu(v) - silu(-v) = v, additivity of bias and residual with a non-square
- * padded layout, and the slope constant against a numeric maximum.
+ * padded layout, and the slope constant against a numeric maximum; the 8-bit
+ * (E4M3) cast and product against a library float8 conversion and decode, the
+ * decision midpoints in exact rational arithmetic, round trips of every code
+ * point, saturation, and a library FP64 matmul (tests/test_oracle_e4m3.py).
  */
 #include <math.h>
 #include <stdint.h>
@@ -310,6 +313,149 @@ int oracle_bf16_gemm(const uint16_t *x, int64_t M, int64_t ldx,
     (void)threads;
     return 0;
 }
+
+/* ------------------------------------------------------------------------------
+ * An 8-bit draft (sections 1, 3.2 and 5 name 8-bit quantisation as a drop-in for the
+ * 4-bit draft): the same two-step direct cast of section 3.4.3 with the OCP
+ * 8-bit element format E4M3 in place of E2M1: 1 sign, 4 exponent bits (bias 7),
+ * 3 mantissa bits, no infinities, S.1111.111 is NaN, largest magnitude
+ * 1.75 * 2^8 = 448; one E8M0 scale per 32 elements as before.  One byte per
+ * element, q8[N, K]; scales [N, K/32].
+ * Readings: the rule of section 3.4.3 carries over with the largest power of two
+ * of the element format now 2^8 (X = 2^(floor(log2 amax) - 8)); rounding to
+ * nearest, ties to the even code; magnitudes beyond 448 saturate to 448 (never
+ * the NaN code); zero blocks, tiny scales, non-finite inputs and the sign of
+ * zero as in the 4-bit cast. */
+static double e4m3_magnitude(int code)       /* code = eeeemmm, 0..126 */
+{
+    int e = (code >> 3) & 15;
+    int m = code & 7;
+    if (e == 0)
+        return ldexp(m / 8.0, -6);            /* subnormal: 0.mmm * 2^(1-7) */
+    return ldexp(1.0 + m / 8.0, e - 7);       /* normal:    1.mmm * 2^(e-7) */
+}
+
+static int e4m3_round_code(double r)
+{
+    int best = 0;
+    double best_d = fabs(r - e4m3_magnitude(0));
+    for (int c = 1; c < 127; ++c) {           /* 127 is the NaN code: not a target */
+        double d = fabs(r - e4m3_magnitude(c));
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return best;
+}
+
+static uint8_t e4m3_cast_block(const uint16_t *w, uint8_t out[ORACLE_BLOCK])
+{
+    double v[ORACLE_BLOCK];
+    double amax = 0.0;
+    int nonfinite = 0;
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        v[i] = bf16_to_double(w[i]);
+        if (isnan(v[i]) || isinf(v[i]))
+            nonfinite = 1;
+        else if (fabs(v[i]) > amax)
+            amax = fabs(v[i]);
+    }
+    if (nonfinite) {
+        for (int i = 0; i < ORACLE_BLOCK; ++i)
+            out[i] = 0;
+        return 0xFF;
+    }
+    int E;
+    if (amax == 0.0) {
+        E = -127;
+    } else {
+        int ex;
+        (void)frexp(amax, &ex);
+        E = (ex - 1) - 8;                     /* floor(log2 amax) - 8 */
+    }
+    if (E < -127)
+        E = -127;
+    if (E > 127)
+        E = 127;
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        double r = ldexp(fabs(v[i]), -E);
+        int sign = (w[i] >> 15) & 1;
+        out[i] = (uint8_t)((sign << 7) | e4m3_round_code(r));
+    }
+    return (uint8_t)(E + 127);
+}
+
+int oracle_e4m3_direct_cast(const uint16_t *w, int64_t N, int64_t K, int64_t ldw,
+                            uint8_t *q8, uint8_t *s, int threads)
+{
+    if (N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldw < K)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t b = 0; b < nblk; ++b)
+            s[n * nblk + b] = e4m3_cast_block(w + n * ldw + b * ORACLE_BLOCK,
+                                              q8 + n * K + b * ORACLE_BLOCK);
+    (void)threads;
+    return 0;
+}
+
+static double e4m3_dequant_one(uint8_t byte, uint8_t scale_byte)
+{
+    if (scale_byte == 0xFF || (byte & 0x7F) == 0x7F)
+        return NAN;
+    double val = ldexp(e4m3_magnitude(byte & 0x7F), (int)scale_byte - 127);
+    return (byte & 0x80) ? -val : val;
+}
+
+int oracle_e4m3_dequant(const uint8_t *q8, const uint8_t *s, int64_t N, int64_t K, double *w_hat)
+{
+    if (N < 0 || K < 0 || K % ORACLE_BLOCK != 0)
+        return 2;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            w_hat[n * K + k] = e4m3_dequant_one(q8[n * K + k], s[n * (K / ORACLE_BLOCK) + k / ORACLE_BLOCK]);
+    return 0;
+}
+
+/* The product with 8-bit weights: y[m][n] = sum_k x[m][k] * w_hat[n][k], k ascending,
+ * in FP64 (every product of a BF16 value with an E4M3 weight times a power of two
+ * is exact in a double), and the sum of absolute products. */
+int oracle_e4m3_woq_gemm(const uint16_t *x, int64_t M, int64_t ldx,
+                         const uint8_t *q8, const uint8_t *s, int64_t N, int64_t K,
+                         double *y_ref, double *a_ref, int threads)
+{
+    if (M < 0 || N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldx < K)
+        return 2;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t m = 0; m < M; ++m) {
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double p = bf16_to_double(x[m * ldx + k]) *
+                           e4m3_dequant_one(q8[n * K + k], s[n * (K / ORACLE_BLOCK) + k / ORACLE_BLOCK]);
+                acc += p;
+                aacc += fabs(p);
+            }
+            y_ref[m * N + n] = acc;
+            if (a_ref)
+                a_ref[m * N + n] = aacc;
+        }
+    }
+    (void)threads;
+    return 0;
+}
+
+double oracle_e4m3_magnitude(int code) { return e4m3_magnitude(code & 0x7F); }
 
 /* What the linear layer's backend fuses around the contraction (section 3.4: bias
  * and residual add applied to the product's output while it is at hand) and, for
