@@ -78,6 +78,37 @@ int mxfp4_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_t ldw
                            void* q_packed, void* scales_e8m0, void* stream);
 
 /*
+ * An 8-bit draft on the same path (sections 1, 3.2 and 5 name 8-bit quantisation as a drop-in for
+ * the 4-bit draft): the two-step direct cast of section 3.4.3 with the OCP 8-bit element format
+ * E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, largest magnitude 448, no
+ * infinities, S.1111.111 = NaN) in place of E2M1: X = 2^(floor(log2 amax) - 8), elements rounded
+ * to nearest (ties to the even code), magnitudes beyond 448 saturate; zero blocks, tiny scales,
+ * non-finite inputs and the sign of zero as in mxfp4_direct_cast.
+ *   q8           [N, K] one byte per element (sign << 7 | eeeemmm); 8-byte aligned for the cast,
+ *                16-byte aligned for the product and the dequantisation
+ *   scales_e8m0  [N, K/32] as for MXFP4
+ * mxfp4_e4m3_direct_cast_bits rounds with an integer-only rule instead of the convert instruction
+ * (same bits).  mxfp4_e4m3_dequant writes scale * element as BF16 (exact while that is a normal
+ * BF16 number).  mxfp4_e4m3_woq_gemm and mxfp4_e4m3_woq_gemm_argmax are mxfp4_woq_gemm and
+ * mxfp4_woq_gemm_argmax with q8 in place of q_packed (same arguments, same error codes, same
+ * tie rule); N * K stays below 2 GiB; the argmax workspace is M * 8 bytes per workgroup the
+ * device can hold, which mxfp4_woq_gemm_argmax_workspace_bytes(M, N, K) covers.
+ */
+int mxfp4_e4m3_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                           void* q8, void* scales_e8m0, void* stream);
+int mxfp4_e4m3_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                                void* q8, void* scales_e8m0, void* stream);
+int mxfp4_e4m3_dequant(const void* q8, const void* scales_e8m0, int64_t N, int64_t K,
+                       void* w_bf16, int64_t ldw, void* stream);
+int mxfp4_e4m3_woq_gemm(const void* x_bf16, int64_t M, int64_t ldx,
+                        const void* q8, const void* scales_e8m0, int64_t N, int64_t K,
+                        void* y_bf16, int64_t ldy, void* stream);
+int mxfp4_e4m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
+                               const void* q8, const void* scales_e8m0, int64_t N, int64_t K,
+                               int32_t* argmax_out, float* max_out,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Dequantise to BF16 (exact whenever 2^(scale-127) * 6 is a normal BF16 number): the inverse
  * map of the format in section 3.4.3; used to check the weight decode in isolation.
  *   w_bf16 out BF16 [N, K], row stride ldw elements.

@@ -23,6 +23,8 @@ EXPORTS = [
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
     "mxfp4_woq_gemm_fused",
+    "mxfp4_e4m3_direct_cast", "mxfp4_e4m3_direct_cast_bits", "mxfp4_e4m3_dequant", "mxfp4_e4m3_woq_gemm",
+    "mxfp4_e4m3_woq_gemm_argmax",
     "mxfp4_tile_repack_q_bytes", "mxfp4_tile_repack_s_bytes", "mxfp4_tile_repack", "mxfp4_woq_gemm_tiled",
     "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify", "mxfp4_woq_gemm_tiled_fused",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
@@ -73,6 +75,15 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_verify.restype = i32
     lib.mxfp4_bf16_gemm_verify.argtypes = [vp, i64, i64, vp, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.mxfp4_bf16_gemm_verify.restype = i32
+    for name in ("mxfp4_e4m3_direct_cast", "mxfp4_e4m3_direct_cast_bits"):
+        getattr(lib, name).argtypes = [vp, i64, i64, i64, vp, vp, vp]
+        getattr(lib, name).restype = i32
+    lib.mxfp4_e4m3_dequant.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_e4m3_dequant.restype = i32
+    lib.mxfp4_e4m3_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_e4m3_woq_gemm.restype = i32
+    lib.mxfp4_e4m3_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.mxfp4_e4m3_woq_gemm_argmax.restype = i32
     lib.mxfp4_woq_gemm_fused.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i32, vp, i64, vp, i64, vp, sz, i32, vp]
     lib.mxfp4_woq_gemm_fused.restype = i32
     lib.mxfp4_tile_repack_q_bytes.argtypes = [i64, i64]
@@ -284,6 +295,68 @@ def mxfp4_woq_gemm_verify(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, dra
                                            _ptr(idx), _ptr(val), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream()))
     return accept, idx, val
+
+
+def mxfp4_e4m3_direct_cast(w: torch.Tensor, integer_rule: bool = False) -> Tuple[torch.Tensor, torch.Tensor]:
+    """BF16 ``[N, K]`` -> (``q8 [N, K]`` E4M3 bytes, ``s [N, K/32]`` E8M0 scale bytes)."""
+    _dev(w)
+    if w.dtype != torch.bfloat16 or w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be a 2-D BF16 tensor with a contiguous last dimension")
+    n, k = w.shape
+    q8 = torch.empty((n, k), dtype=torch.uint8, device=w.device)
+    s = torch.empty((n, k // 32), dtype=torch.uint8, device=w.device)
+    fn = load().mxfp4_e4m3_direct_cast_bits if integer_rule else load().mxfp4_e4m3_direct_cast
+    with torch.cuda.device(w.device):
+        _check(fn(_ptr(w), n, k, w.stride(0) if n > 1 else k, _ptr(q8), _ptr(s), _stream()))
+    return q8, s
+
+
+def mxfp4_e4m3_dequant(q8: torch.Tensor, s: torch.Tensor) -> torch.Tensor:
+    _dev(q8)
+    n, k = q8.shape
+    w = torch.empty((n, k), dtype=torch.bfloat16, device=q8.device)
+    with torch.cuda.device(q8.device):
+        _check(load().mxfp4_e4m3_dequant(_ptr(q8), _ptr(s), n, k, _ptr(w), k, _stream()))
+    return w
+
+
+def _e4m3_shapes(x, q8, s):
+    _dev(x)
+    if x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D BF16 tensor with a contiguous last dimension")
+    if q8.dtype != torch.uint8 or s.dtype != torch.uint8 or not q8.is_contiguous() or not s.is_contiguous():
+        raise ValueError("q8 and s must be contiguous uint8 tensors")
+    m, k = x.shape
+    n = q8.shape[0]
+    if q8.shape[1] != k or tuple(s.shape) != (n, k // 32):
+        raise ValueError("shape mismatch: x %r q8 %r s %r" % (tuple(x.shape), tuple(q8.shape), tuple(s.shape)))
+    return m, n, k, (x.stride(0) if m > 1 else k)
+
+
+def mxfp4_e4m3_woq_gemm(x: torch.Tensor, q8: torch.Tensor, s: torch.Tensor,
+                        y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    m, n, k, ldx = _e4m3_shapes(x, q8, s)
+    if y is None:
+        y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_e4m3_woq_gemm(_ptr(x), m, ldx, _ptr(q8), _ptr(s), n, k, _ptr(y),
+                                         y.stride(0) if m > 1 else n, _stream()))
+    return y
+
+
+def mxfp4_e4m3_woq_gemm_argmax(x: torch.Tensor, q8: torch.Tensor, s: torch.Tensor,
+                               workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    m, n, k, ldx = _e4m3_shapes(x, q8, s)
+    if workspace is None:
+        workspace = torch.empty((mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k),), dtype=torch.uint8,
+                                device=x.device)
+    idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+    val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_e4m3_woq_gemm_argmax(_ptr(x), m, ldx, _ptr(q8), _ptr(s), n, k, _ptr(idx), _ptr(val),
+                                                _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                _stream()))
+    return idx, val
 
 
 ACT_NONE, ACT_SWIGLU = 0, 1

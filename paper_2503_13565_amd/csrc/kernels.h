@@ -107,6 +107,14 @@ struct Bf16Args {
 bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev);
 hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
 
+// The 8-bit draft format (E4M3 elements, one byte each: a.q is q8 [N, K]; a.s as before); e4m3.hip.
+hipError_t launch_e4m3_cast(const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q8, void* s,
+                            bool integer_rule, hipStream_t stream);
+hipError_t launch_e4m3_dequant(const void* q8, const void* s, int64_t n_rows, int64_t k, void* w, int64_t ldw,
+                               hipStream_t stream);
+bool e4m3_can_run(const GemmArgs& a, const DeviceInfo& dev);
+hipError_t launch_e4m3_gemv(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+
 // Second stage of the fused argmax: reduce `parts_used` partial winners per row.
 hipError_t launch_argmax_finish(const float* part_val, const int32_t* part_idx, int parts, int parts_used,
                                 int m, int32_t* argmax_out, float* max_out, hipStream_t stream);
