@@ -84,6 +84,53 @@ def run_step_bf16(lin, ws):
     binding.mxfp4_bf16_gemm_argmax(t["x"], t["w"], workspace=ws, out=(t["idx"], t["val"]))
 
 
+def run_step_e4m3(lin, ws):
+    """The same step on an 8-bit draft (E4M3 elements with block scales)."""
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up", "down"):
+        t = lin[name]
+        binding.mxfp4_e4m3_woq_gemm(t["x"], t["q8"], t["s8"], y=t["y"])
+    t = lin["lm_head"]
+    binding.mxfp4_e4m3_woq_gemm_argmax(t["x"], t["q8"], t["s8"], workspace=ws, out=(t["idx"], t["val"]))
+
+
+def run_layer_plain(lin, ws):
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up", "down"):
+        t = lin[name]
+        binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+
+
+def run_layer_fused(lin, ws):
+    """The four linears of a decoder layer with what surrounds them fused: the residual add behind
+    the o and the down projection (in place), the gate of the MLP behind gate+up (its weight rows
+    read as interleaved gate/up pairs: same bytes, same time)."""
+    from paper_2503_13565_amd import binding
+    t = lin["qkv"]
+    binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
+    for name in ("o", "down"):
+        t = lin[name]
+        binding.mxfp4_woq_gemm_fused(t["x"], t["q"], t["s"], residual=t["y"], y=t["y"])
+    t = lin["gate_up"]
+    binding.mxfp4_woq_gemm_fused(t["x"], t["q"], t["s"], act=binding.ACT_SWIGLU, y=t["h"])
+
+
+def run_verify8(lin, ws):
+    """A verification pass over eight positions on the canonical tensors."""
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up"):
+        t = lin[name]
+        binding.mxfp4_woq_gemm(t["x8"], t["q"], t["s"], y=t["y8"])
+
+
+def run_verify8_tiled(lin, ws):
+    """The same pass on the tile-major copy of the weights."""
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up"):
+        t = lin[name]
+        binding.mxfp4_woq_gemm_tiled(t["x8"], t["tw"], y=t["y8"])
+
+
 DOMINANT = ("qkv", "o", "gate_up", "lm_head")
 DOMINANT_KERNEL = "mxfp4::gemv_reg_kernel<1,1,2,2,16,false>"
 
@@ -358,9 +405,38 @@ def main() -> int:
         timed(run_b, n_bf16, stream)
         nb = n_bf16 * max(2, args.steps // (4 * n_bf16))
         bf16_us = timed(run_b, nb, stream) / nb * 1e3
+        # further variants on the same four weight sets, each timed like the step above: an 8-bit
+        # draft, the decoder layer with fused epilogues, and an 8-row verification pass on the
+        # canonical and on the tile-major weights
+        def leg(fn):
+            with torch.cuda.stream(stream):
+                for lin in bsets:
+                    fn(lin, ws)
+            torch.cuda.synchronize()
+            g = None if args.no_graph else capture(fn, bsets, ws, stream)
+            r = runner(g, fn, bsets, ws)
+            timed(r, n_bf16, stream)
+            return timed(r, nb, stream) / nb * 1e3
+        for lin in bsets:
+            for name, t in lin.items():
+                t["q8"], t["s8"] = binding.mxfp4_e4m3_direct_cast(t["w"])
+                t["w"] = None
+                if name in ("qkv", "o", "gate_up"):
+                    t["x8"] = synth.activations_outlier_channels(8, t["k"], seed=t["n"], device=dev)
+                    t["y8"] = torch.empty((8, t["n"]), dtype=torch.bfloat16, device=dev)
+                    t["tw"] = binding.mxfp4_tile_repack(t["q"], t["s"])
+            lin["gate_up"]["h"] = torch.empty((m, lin["gate_up"]["n"] // 2), dtype=torch.bfloat16, device=dev)
+        variants = {
+            "e4m3_weights_us_per_step": round(leg(run_step_e4m3), 2),
+            "layer_4_linears_us": round(leg(run_layer_plain), 2),
+            "layer_4_linears_fused_epilogues_us": round(leg(run_layer_fused), 2),
+            "verify_m8_qkv_o_gateup_us": round(leg(run_verify8), 2),
+            "verify_m8_qkv_o_gateup_tile_major_us": round(leg(run_verify8_tiled), 2),
+        }
         for lin in bsets:
             for t in lin.values():
-                t["w"] = None
+                for key in ("q8", "s8", "x8", "y8", "tw", "h"):
+                    t.pop(key, None)
 
     # what a plain 128-bit read stream gets on this device, over 4 GiB (context for frac)
     buf = torch.empty(4 << 30, dtype=torch.uint8, device=dev)
@@ -415,6 +491,7 @@ def main() -> int:
     }
     if bf16_us is not None:
         out["eq1_projection"] = eq1_projection(bf16_us / (ms_per_step * 1e3))
+        out["variants"] = variants
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(m)
         for key in ("value", "seconds_per_step"):

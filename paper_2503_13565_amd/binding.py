@@ -345,13 +345,18 @@ def mxfp4_e4m3_woq_gemm(x: torch.Tensor, q8: torch.Tensor, s: torch.Tensor,
 
 
 def mxfp4_e4m3_woq_gemm_argmax(x: torch.Tensor, q8: torch.Tensor, s: torch.Tensor,
-                               workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+                               workspace: Optional[torch.Tensor] = None,
+                               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
+                               ) -> Tuple[torch.Tensor, torch.Tensor]:
     m, n, k, ldx = _e4m3_shapes(x, q8, s)
     if workspace is None:
         workspace = torch.empty((mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k),), dtype=torch.uint8,
                                 device=x.device)
-    idx = torch.empty((m,), dtype=torch.int32, device=x.device)
-    val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    if out is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+        val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    else:
+        idx, val = out
     with torch.cuda.device(x.device):
         _check(load().mxfp4_e4m3_woq_gemm_argmax(_ptr(x), m, ldx, _ptr(q8), _ptr(s), n, k, _ptr(idx), _ptr(val),
                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
