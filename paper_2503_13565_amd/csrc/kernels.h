@@ -85,6 +85,12 @@ bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev);
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                             bool tiled = false, const Epilogue* epi = nullptr);
 
+// The tile kernel with K split in space for passes whose activation rows do not fit the LDS:
+// FP32 partial products to ws = float [phases][M][N] (mfma.hip's finish kernel adds them).
+bool mfma_tile_split_fits(int phase_steps, int mp, const DeviceInfo& dev);
+hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases, int phase_steps, float* ws,
+                                  const DeviceInfo& dev, hipStream_t stream);
+
 // Tile-major copy of the weights for the tile kernel (`tiled`: a.q / a.s are that copy): what a
 // wave instruction loads is contiguous.  Sizes in bytes; K % 128 == 0.
 size_t tile_repack_q_bytes(int64_t n, int64_t k);

@@ -705,10 +705,20 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
     int space_steps = 0, space_phases = 1;
     if (mode == kInSpace)
         plan_phases(a.k, pass_width(a.m), dev, true, 0, &space_steps, &space_phases);
+    // split in space: the leaner tile kernel takes the passes when a phase's activations fit it
+    const bool tile_split = mode == kInSpace && !legacy && !general_only && a.ldx <= 0x7FFFFFFF &&
+                            mfma_tile_split_fits(space_steps, pass_width(a.m), dev);
     int first_blocks = 0;
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
         int mp = pass_width(left);
+        if (tile_split) {
+            hipError_t e = launch_mfma_tile_split(a, m0, mp, space_phases, space_steps, splitk_ws, dev, stream);
+            if (e != hipSuccess)
+                return e;
+            m0 += mp;
+            continue;
+        }
         int steps, phases, grid_y = 1;
         size_t lds;
         int blocks = 0;

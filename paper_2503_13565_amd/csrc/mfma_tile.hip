@@ -49,17 +49,25 @@ size_t tile_lds_bytes(int k, int mp)
 // Epi: NoEpilogue, or Epilogue for the fused form: the epilogue wave adds the bias, applies the
 // gate to the row pairs it holds in one lane and adds the residual; it fetches a tile's bias and
 // residual before it waits for the compute waves, so the loads cost no time.
+// phase_steps > 0: K split in space.  Grid row y takes the steps [y * phase_steps, (y + 1) *
+// phase_steps) of K (phase_steps a multiple of four), holds only that part of the activation rows
+// in LDS, and writes FP32 partial products to `out` = float [phases][M][N]; a second kernel adds
+// them.  For passes whose activation rows do not fit the LDS whole.
 template <int MP, int NW, int D, bool kTiled, class Epi>
 __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, const uint8_t* __restrict__ q,
                                                const uint8_t* __restrict__ s, void* out, int n, int k, int m,
-                                               int m0, int ldx, int ldy, int parts, const Epi& epi)
+                                               int m0, int ldx, int ldy, int parts, const Epi& epi,
+                                               int phase_steps = 0)
 {
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     constexpr int T = (NW + 1) * 64;
     extern __shared__ __align__(16) uint8_t smem[];
     u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);
     const int tid = threadIdx.x;
-    const int chunks = k >> 3;                                          // 16-byte chunks per activation row
+    const int steps_all = k >> 7;
+    const int t0 = phase_steps > 0 ? (int)blockIdx.y * phase_steps : 0;  // first step of this workgroup
+    const int steps = phase_steps > 0 ? min(phase_steps, steps_all - t0) : steps_all;
+    const int chunks = steps * 16;                                      // 16-byte chunks per activation row
     // ---- activations first: thread -> chunk kc of every row, XB chunk slots per batch
     constexpr int XB = 16 / MP;
     const int xpr = (chunks + T - 1) / T;                               // chunk slots per thread
@@ -71,7 +79,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
 #pragma unroll
             for (int mm = 0; mm < MP; ++mm) {
                 const int msrc = min(m0 + mm, m - 1);                   // ragged M: repeat the last row
-                xl[i][mm] = reinterpret_cast<const u32x4_t*>(x + (int64_t)msrc * ldx)[kc];
+                xl[i][mm] = reinterpret_cast<const u32x4_t*>(x + (int64_t)msrc * ldx)[t0 * 16 + kc];
             }
         }
     };
@@ -82,8 +90,8 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
     const int li = lane & 15, lg = lane >> 4;
     const int nblk = k >> 5;
     const int q_row_bytes = k >> 1;
-    const int steps = k >> 7;
-    const int n_items = (steps + 3) >> 2;                               // items per tile
+    const int n_items = (steps + 3) >> 2;                               // items per tile (of this K range)
+    const int n_items_all = (steps_all + 3) >> 2;
     const int ipw = (n_items + NW - 1) / NW;                            // items per wave and tile
     const int n_tiles = (n + 15) >> 4;
     const int G = gridDim.x, b = blockIdx.x;
@@ -92,7 +100,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(q), 0, kTiled ? n_tiles * 16 * q_row_bytes : n * q_row_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(s), 0, kTiled ? n_tiles * n_items * 256 : n * nblk, 0x00020000);
+        const_cast<uint8_t*>(s), 0, kTiled ? n_tiles * n_items_all * 256 : n * nblk, 0x00020000);
 
     struct Item {
         u32x4_t q[4];       // 32 nibbles per step
@@ -114,22 +122,24 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
             for (int u = 0; u < 4; ++u) {
                 const int mk = -(have & (int)(item * 4 + u < steps));   // all ones when the step exists
                 it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(
-                    rq, (vq & mk) | (kOob & ~mk), (((tile * steps + item * 4 + u) * 1024) & mk) | ((u * 16) & ~mk), 2);
+                    rq, (vq & mk) | (kOob & ~mk),
+                    (((tile * steps_all + t0 + item * 4 + u) * 1024) & mk) | ((u * 16) & ~mk), 2);
             }
             const int mk = -have;
             it.sc = __builtin_amdgcn_raw_buffer_load_b128(rs, ((li * 16) & mk) | (kOob & ~mk),
-                                                          ((tile * n_items + item) * 256) & mk, 0);
+                                                          ((tile * n_items_all + (t0 >> 2) + item) * 256) & mk, 0);
         } else {
             const int row = min(tile * 16 + li, n - 1);                 // ragged N: repeat the last row
             const int vq = row * q_row_bytes + lg * 16;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int mk = -(have & (int)(item * 4 + u < steps));   // all ones when the step exists
-                it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, (vq & mk) | (kOob & ~mk),
-                                                                (((item * 4 + u) * 64) & mk) | ((u * 16) & ~mk), 0);
+                it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 64) & mk) | ((u * 16) & ~mk), 0);
             }
             const int mk = -have;
-            it.sc = __builtin_amdgcn_raw_buffer_load_b128(rs, ((row * nblk) & mk) | (kOob & ~mk), (item * 16) & mk, 0);
+            it.sc = __builtin_amdgcn_raw_buffer_load_b128(rs, ((row * nblk) & mk) | (kOob & ~mk),
+                                                          (t0 * 4 + item * 16) & mk, 0);
         }
         const int wrap = (int)(ld_loc + 1 == ipw);
         ld_loc = (ld_loc + 1) * (1 - wrap);
@@ -221,7 +231,9 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                 for (int r = 0; r < 4; ++r) {
                     const int row = tile * 16 + 4 * lg + r;
                     if (row < n) {
-                        if (argmax) {
+                        if (phase_steps > 0) {
+                            static_cast<float*>(out)[((int64_t)blockIdx.y * m + (m0 + li)) * n + row] = sum[r];
+                        } else if (argmax) {
                             if (sum[r] > best_val) {                    // rows ascend: lowest index wins ties
                                 best_val = sum[r];
                                 best_idx = row;
@@ -233,7 +245,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                 }
             }
         }
-        if (argmax) {
+        if (argmax && phase_steps == 0) {
             // combine the four lane groups of each column (value desc, index asc), publish one partial
 #pragma unroll
             for (int off = 16; off < 64; off <<= 1) {
@@ -334,6 +346,17 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_fused_kernel(
                                       Epilogue{bias, residual, ldr, act});
 }
 
+// K split in space: the last preloaded argument is the number of steps per grid row.
+template <int MP, int NW, int D>
+__global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_split_kernel(const uint16_t* __restrict__ x,
+                                                                        const uint8_t* __restrict__ q,
+                                                                        const uint8_t* __restrict__ s, void* out,
+                                                                        int n, int k, int m, int m0, int ldx,
+                                                                        int ldy, int parts, int phase_steps)
+{
+    mfma_tile_body<MP, NW, D, false>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{}, phase_steps);
+}
+
 // Make the tile-major copy: one thread per 16 bytes of either output.  q_t unit (tile, T, lane =
 // i + 16 g) is block 4T + g of row 16 tile + i; s_t unit (tile, item, i) holds the scale bytes of
 // blocks 16 item .. 16 item + 15 of that row.  Rows past N get zero nibbles, blocks past K and rows
@@ -427,6 +450,46 @@ hipError_t launch_tile_repack(const void* q, const void* s, int n, int k, void* 
     hipLaunchKernelGGL(tile_repack_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const u32x4_t*>(q),
                        static_cast<const uint32_t*>(s), n, k, static_cast<u32x4_t*>(qt), static_cast<u32x4_t*>(st));
     return hipGetLastError();
+}
+
+// One pass of `mp` rows from row m0 with K split over `phases` grid rows of `phase_steps` steps;
+// partial products go to ws = float [phases][M][N].  One workgroup per compute unit and phase
+// (its part of the activation rows fills most of the LDS), three items in flight per wave.
+bool mfma_tile_split_fits(int phase_steps, int mp, const DeviceInfo& dev)
+{
+    return phase_steps % 4 == 0 && tile_lds_bytes(phase_steps * 128, mp) <= (size_t)dev.lds_bytes;
+}
+
+template <int MP>
+hipError_t launch_split_pass(const GemmArgs& a, int m0, int phases, int phase_steps, float* ws, int blocks,
+                             size_t lds, const DeviceInfo& dev, hipStream_t stream)
+{
+    auto kern = mfma_tile_split_kernel<MP, kTileNW, 3>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks, phases), dim3((kTileNW + 1) * 64), lds, stream, a.x, a.q, a.s,
+                       static_cast<void*>(ws), a.n, a.k, a.m, m0, (int)a.ldx, (int)a.ldy, 0, phase_steps);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases, int phase_steps, float* ws,
+                                  const DeviceInfo& dev, hipStream_t stream)
+{
+    if (a.ldx > 0x7FFFFFFF || !mfma_tile_split_fits(phase_steps, mp, dev) || phases < 1)
+        return hipErrorInvalidValue;
+    const int n_tiles = (a.n + 15) / 16;
+    int blocks = dev.cus / phases;
+    blocks = blocks < 1 ? 1 : (blocks > n_tiles ? n_tiles : blocks);
+    const size_t lds = tile_lds_bytes(phase_steps * 128, mp);
+    return mp == 16  ? launch_split_pass<16>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+           : mp == 8 ? launch_split_pass<8>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+                     : launch_split_pass<4>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
 }
 
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
