@@ -502,7 +502,16 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
     // a wave has four and more items per tile, one workgroup with three.
     const size_t widest = tile_lds_bytes(a.k, tile_pass_width(a.m));
     const bool long_k = a.k >= 8192;
-    const int per_cu = !long_k && 2 * widest + 2048 <= (size_t)dev.lds_bytes ? 2 : 1;
+    int per_cu = !long_k && 2 * widest + 2048 <= (size_t)dev.lds_bytes ? 2 : 1;
+    // three items in flight also for 16-row passes over many tiles (7B gate+up and LM head: 5 %)
+    bool deep = long_k || (tile_pass_width(a.m) == 16 && n_tiles >= 4 * dev.cus);
+    // MXFP4_TILE_WGS (1, 2) and MXFP4_TILE_D (2, 3): measurement only
+    static const int env_wgs = [] { const char* e = getenv("MXFP4_TILE_WGS"); return e ? atoi(e) : 0; }();
+    static const int env_d = [] { const char* e = getenv("MXFP4_TILE_D"); return e ? atoi(e) : 0; }();
+    if (env_wgs == 1 || (env_wgs == 2 && 2 * widest + 2048 <= (size_t)dev.lds_bytes))
+        per_cu = env_wgs;
+    if (env_d == 2 || env_d == 3)
+        deep = env_d == 3;
     int blocks = dev.cus * per_cu;
     if (blocks > n_tiles)
         blocks = n_tiles;
@@ -519,9 +528,9 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
      : mp == 8 ? launch_pass<8, D_, T_>(a, m0, blocks, lds, dev, stream, epi)               \
                : launch_pass<4, D_, T_>(a, m0, blocks, lds, dev, stream, epi))
         if (tiled)
-            e = long_k ? MXFP4_TILE_CASE(3, true) : MXFP4_TILE_CASE(2, true);
+            e = deep ? MXFP4_TILE_CASE(3, true) : MXFP4_TILE_CASE(2, true);
         else
-            e = long_k ? MXFP4_TILE_CASE(3, false) : MXFP4_TILE_CASE(2, false);
+            e = deep ? MXFP4_TILE_CASE(3, false) : MXFP4_TILE_CASE(2, false);
 #undef MXFP4_TILE_CASE
         if (e != hipSuccess)
             return e;
