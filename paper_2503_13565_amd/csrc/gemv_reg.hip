@@ -75,7 +75,11 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nblk = a.k >> 5;
-    int* ctr = reinterpret_cast<int*>(smem + (size_t)MT * a.k * 2);
+    // Activations that stay in LDS (see below) use rows of STEPS * 64 chunks, zero beyond K: the
+    // loop then reads them without a check and every address is a constant away from one base.
+    constexpr bool kXLds = MT * STEPS > 6;
+    const int xrow = kXLds ? STEPS * 64 : nblk;              // chunks per (activation row, j)
+    int* ctr = reinterpret_cast<int*>(smem + (size_t)MT * 4 * xrow * 16);
     const int q_row_bytes = a.k >> 1;
     const bool argmax = a.parts > 0;
     const int G = gridDim.x, b = blockIdx.x;
@@ -145,18 +149,32 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 #pragma unroll
         for (int i = 0; i < XPR; ++i) {
             const int c = min(tid + i * T, chunks - 1);              // clamped duplicates rewrite the same data
-            xs[(m * 4 + (c & 3)) * nblk + (c >> 2)] = xl[m][i];
+            xs[(m * 4 + (c & 3)) * xrow + (c >> 2)] = xl[m][i];
         }
+    if constexpr (kXLds) {
+        const int pad = xrow - nblk;
+        for (int e = tid; e < MT * 4 * pad; e += T)
+            xs[(e / pad) * xrow + nblk + e % pad] = u32x4_t{0, 0, 0, 0};
+    }
     lds_barrier();
-    u32x4_t xr[MT][STEPS][4];
+    // Up to 96 registers of activations per lane (six steps of one row, two steps of two rows);
+    // beyond that they stay in the LDS copy and every step reads its 64 bytes per row from there.
+    auto x_of = [&](int m, int t, int j) {
+        if constexpr (kXLds)
+            return xs[((m * 4 + j) * STEPS + t) * 64 + lane];
+        else
+            return (!kRagged || t * 64 + lane < nblk) ? xs[(m * 4 + j) * nblk + t * 64 + lane] : u32x4_t{0, 0, 0, 0};
+    };
+    u32x4_t xr[kXLds ? 1 : MT][kXLds ? 1 : STEPS][4];
+    if constexpr (!kXLds) {
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
+        for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int t = 0; t < STEPS; ++t)
+            for (int t = 0; t < STEPS; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                xr[m][t][j] = (!kRagged || t * 64 + lane < nblk) ? xs[(m * 4 + j) * nblk + t * 64 + lane]
-                                                                 : u32x4_t{0, 0, 0, 0};
+                for (int j = 0; j < 4; ++j)
+                    xr[m][t][j] = x_of(m, t, j);
+    }
 
     float best_val[MT];
     int best_idx[MT];
@@ -237,6 +255,18 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
             const int d = t % D;
+            u32x4_t xq[MT][4];
+            if constexpr (kXLds)
+                __builtin_amdgcn_sched_barrier(0);  // step by step: across steps the scheduler piles up registers
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if constexpr (kXLds)
+                        xq[m][j] = x_of(m, t, j);
+                    else
+                        xq[m][j] = xr[m][t][j];
+                }
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 // the dword with this lane's scale byte of row r sits in lane r * 16 + lane / 4.
@@ -257,8 +287,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 #pragma unroll
                     for (int m = 0; m < MT; ++m) {
                         // through scalars: a bit cast applied directly to a vector element reads element 0
-                        const uint32_t x0 = xr[m][t][j][0], x1 = xr[m][t][j][1], x2 = xr[m][t][j][2],
-                                       x3 = xr[m][t][j][3];
+                        const uint32_t x0 = xq[m][j][0], x1 = xq[m][j][1], x2 = xq[m][j][2], x3 = xq[m][j][3];
                         float c = acc[r][m];
                         c = __builtin_amdgcn_fdot2_f32_bf16(w[0], __builtin_bit_cast(bf16x2_t, x0), c, false);
                         c = __builtin_amdgcn_fdot2_f32_bf16(w[1], __builtin_bit_cast(bf16x2_t, x1), c, false);
@@ -368,6 +397,19 @@ template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
 hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream, const Epilogue* epi)
 {
     const bool argmax = g.part_val != nullptr;
+    if (MT * STEPS > 6)
+        lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
+    static bool attr_set = false;
+    if (!attr_set && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg_fused_kernel<MT, R, STEPS, D, NW, kRagged>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg_kernel<MT, R, STEPS, D, NW, kRagged>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
     if (epi)
         hipLaunchKernelGGL((gemv_reg_fused_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds,
                            stream, g.x, g.q, g.s, static_cast<void*>(g.y), g.n, g.k, g.m, m0, (int)g.ldx,
@@ -387,6 +429,10 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
     // 16 waves hold at most 128 registers each: enough for four steps of one activation row.
     // Six steps: 8 waves, each with two weight rows and three steps in flight (measured best on
     // the 7B down projection, 4096 x 11008, where a compute unit has only 16 rows to work on).
+    // From eight steps on (K > 12288) the activations stay in the LDS copy: registers are free
+    // again, so 16 waves with one weight row per step; the instances cover 8, 12, 14 and 16 steps
+    // and a shorter K leaves the last ones partly or wholly empty.  (Two activation rows from LDS
+    // were tried too: the compiler spills in every such instance.)
     switch (steps2) {
     case 2:
         if constexpr (MT == 1)
@@ -405,23 +451,41 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
             return ragged ? launch_one<MT, 2, 6, 3, 8, true>(a, m0, blocks, lds, stream, epi)
                           : launch_one<MT, 2, 6, 3, 8, false>(a, m0, blocks, lds, stream, epi);
         break;
+    case 8:
+        if constexpr (MT == 1)
+            return launch_one<MT, 1, 8, 2, 16, true>(a, m0, blocks, lds, stream, epi);
+        break;
+    case 10:
+    case 12:
+        if constexpr (MT == 1)
+            return launch_one<MT, 1, 12, 2, 16, true>(a, m0, blocks, lds, stream, epi);
+        break;
+    case 14:
+        if constexpr (MT == 1)
+            return launch_one<MT, 1, 14, 2, 16, true>(a, m0, blocks, lds, stream, epi);
+        break;
+    case 16:
+        if constexpr (MT == 1)
+            return launch_one<MT, 1, 16, 2, 16, true>(a, m0, blocks, lds, stream, epi);
+        break;
     }
     return hipErrorInvalidValue;
 }
 
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
-int waves_for(int steps2, int mt) { return steps2 == 6 || mt == 2 ? 8 : 16; }
-int rows_per_step(int steps2, int mt) { return steps2 == 6 || mt == 2 ? 2 : 1; }
+bool wide_group(int steps2, int mt) { return (mt == 1 && steps2 == 6) || (mt == 2 && steps2 == 2); }
+int waves_for(int steps2, int mt) { return wide_group(steps2, mt) ? 8 : 16; }
+int rows_per_step(int steps2, int mt) { return wide_group(steps2, mt) ? 2 : 1; }
 
 }  // namespace
 
-// K % 128 == 0 (dword scale loads), K <= 12288 (the activations of one row fit the registers of
-// a lane), and enough weight rows to give every compute unit a workgroup's worth.  Activation
-// rows go two per pass up to K = 4096 and one per pass beyond: more rows than that are better
-// served by the general kernel (one pass for two rows at any K) or the MFMA tiles.
+// K % 128 == 0 (dword scale loads), K <= 32768 (16 steps), and enough weight rows to give every
+// compute unit a workgroup's worth.  Activation rows go two per pass up to K = 4096 and one per
+// pass beyond: more rows than that are better served by the general kernel (one pass for two
+// rows at any K) or the MFMA tiles.
 bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev)
 {
-    if (a.k % 128 != 0 || a.m < 1 || even_steps(a.k) > 6)
+    if (a.k % 128 != 0 || a.m < 1 || even_steps(a.k) > 16)
         return false;
     if (a.ldx > 0x7FFFFFFF || a.ldy > 0x7FFFFFFF)           // 32-bit leading dimensions in the kernel
         return false;

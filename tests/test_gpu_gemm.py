@@ -56,7 +56,8 @@ REG = binding.PATH_VALU_REG
 
 
 @pytest.mark.parametrize("n,k", [(2048, 128), (2100, 256), (2049, 2176), (2500, 4096), (2111, 6144),
-                                 (2300, 8192), (2222, 10240), (2100, 11008), (2050, 12288)])
+                                 (2300, 8192), (2222, 10240), (2100, 11008), (2050, 12288), (2049, 14336),
+                                 (2060, 16384), (2111, 20480), (2050, 28672), (2048, 32768)])
 @pytest.mark.parametrize("m", [1, 2, 3])
 def test_register_gemv_edge_shapes(n, k, m):
     """The decode-step kernel: full, ragged and padded step counts, rows that do not fill the last
@@ -67,7 +68,7 @@ def test_register_gemv_edge_shapes(n, k, m):
 
 
 def test_register_gemv_refuses_what_it_cannot_run():
-    for n, k in [(100, 4096), (4096, 96), (4096, 16384)]:
+    for n, k in [(100, 4096), (4096, 96), (4096, 32768 + 128)]:
         x = torch.zeros((1, k), dtype=torch.bfloat16, device=DEV)
         q = torch.zeros((n, k // 2), dtype=torch.uint8, device=DEV)
         s = torch.zeros((n, k // 32), dtype=torch.uint8, device=DEV)
@@ -76,6 +77,20 @@ def test_register_gemv_refuses_what_it_cannot_run():
         assert e.value.code == 6
         y = binding.mxfp4_woq_gemm(x, q, s)                # AUTO takes the general kernel
         assert not y.float().abs().sum().item()
+
+
+def test_register_gemv_long_k_ignores_non_finite_activations_of_other_rows():
+    # from K = 14336 on the activations stay in LDS in padded rows; what pads them is zero, so a
+    # NaN in the next activation row cannot reach this row's outputs
+    n, k = 2048, 20480
+    w = synth.weights_student_t(n, k, seed=31)
+    q, s, q_ref, s_ref = assert_cast_bit_exact(w)
+    x = synth.activations_gaussian(2, k, seed=32)
+    x[1, :64] = float("nan")
+    y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x[:1]), q_ref, s_ref)
+    y = binding.mxfp4_woq_gemm(x.to(DEV), q, s, path=REG)
+    assert_gemm_close(y[:1], y_ref, a_ref, "row 0 beside a NaN row")
+    assert torch.isnan(y[1].float()).all()
 
 
 def test_register_gemv_nan_scale_stays_in_its_row():
