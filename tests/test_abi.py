@@ -84,3 +84,63 @@ def test_argmax_workspace_size_and_checks():
     assert lib.mxfp4_woq_gemm_argmax_workspace_bytes(0, 1, 32) == 0
     # bad K is reported before the workspace is looked at
     assert lib.mxfp4_woq_gemm_argmax(P16, 1, 64, P16, P16, 8, 40, P16, None, None, 0, None) == 2
+
+
+P1 = ctypes.c_void_p(4097)
+
+
+@pytest.mark.parametrize("bias,act,res,ldr,n,code", [
+    (None, 7, None, 0, 8, 6),             # unknown act
+    (None, 1, None, 0, 9, 2),             # the gate needs an even N
+    (None, 0, P16, 4, 8, 2),              # ldr < N
+    (None, 1, P16, 3, 8, 2),              # ldr < N / 2 with the gate
+    (P1, 0, None, 0, 8, 3),               # bias not 2-byte aligned
+    (None, 0, P1, 8, 8, 3),               # residual not 2-byte aligned
+])
+def test_fused_argument_checks(bias, act, res, ldr, n, code):
+    lib = binding.load()
+    rc = lib.mxfp4_woq_gemm_fused(P16, 1, 64, P16, P16, n, 64, bias, act, res, ldr, P16, 8, None, 0, 0, None)
+    assert rc == code and lib.mxfp4_last_error()
+
+
+def test_fused_refuses_paths_without_a_fused_form():
+    lib = binding.load()
+    for path in (binding.PATH_VALU_BITS, binding.PATH_VALU_LUT):
+        assert lib.mxfp4_woq_gemm_fused(P16, 1, 64, P16, P16, 8, 64, None, 0, None, 0, P16, 8, None, 0, path,
+                                        None) == 6
+
+
+def test_tile_repack_sizes_and_checks():
+    lib = binding.load()
+    # whole tiles of 16 rows; whole items of four steps of 128 elements
+    assert lib.mxfp4_tile_repack_q_bytes(17, 256) == 32 * 128
+    assert lib.mxfp4_tile_repack_s_bytes(17, 256) == 2 * 1 * 256
+    assert lib.mxfp4_tile_repack_s_bytes(16, 11008) == 22 * 256
+    assert lib.mxfp4_tile_repack(P16, P16, 16, 96, P16, P16, None) == 2        # K % 128
+    assert lib.mxfp4_tile_repack(None, P16, 16, 128, P16, P16, None) == 1
+    assert lib.mxfp4_tile_repack(P16, P16, 16, 128, None, P16, None) == 1
+    assert lib.mxfp4_tile_repack(P16, P16, 16, 128, P2, P16, None) == 3
+    assert lib.mxfp4_woq_gemm_tiled(P16, 1, 128, P16, P2, 16, 128, P16, 16, None) == 3     # s_tiled alignment
+    assert lib.mxfp4_woq_gemm_tiled(P16, 1, 96, P16, P16, 16, 96, P16, 16, None) == 2      # K % 128
+
+
+@pytest.mark.parametrize("args,code", [
+    ((P16, 4, 48, 48, P16, P16, None), 2),                      # K % 32
+    ((P16, 4, 64, 32, P16, P16, None), 2),                      # ldw < K
+    ((None, 4, 64, 64, P16, P16, None), 1),
+    ((P16, 4, 64, 64, P2, P16, None), 3),                       # q8 not 8-byte aligned
+    ((P16, 0, 64, 64, None, None, None), 0),                    # N == 0 is a no-op
+])
+def test_e4m3_cast_argument_checks(args, code):
+    lib = binding.load()
+    assert lib.mxfp4_e4m3_direct_cast(*args) == code
+    assert lib.mxfp4_e4m3_direct_cast_bits(*args) == code
+
+
+def test_e4m3_product_argument_checks():
+    lib = binding.load()
+    assert lib.mxfp4_e4m3_woq_gemm(None, 1, 64, P16, P16, 8, 64, P16, 8, None) == 1
+    assert lib.mxfp4_e4m3_woq_gemm(P16, 1, 64, P2, P16, 8, 64, P16, 8, None) == 3          # q8 alignment
+    assert lib.mxfp4_e4m3_woq_gemm(P16, 1, 64, P16, P16, 8, 40, P16, 8, None) == 2         # K % 32
+    assert lib.mxfp4_e4m3_woq_gemm(P16, 1, 64, P16, P16, 1 << 20, 4096, P16, 8, None) == 2  # N * K beyond 2 GiB
+    assert lib.mxfp4_e4m3_dequant(P16, P16, 4, 64, None, 64, None) == 1
