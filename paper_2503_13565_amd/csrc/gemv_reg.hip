@@ -15,6 +15,8 @@
 // Decode and multiply-add are as in gemv.hip: the scaled FP4->BF16 convert with the block scale,
 // then v_dot2_f32_bf16 with FP32 accumulation (Eq. 2: scaling a power of two commutes with the
 // sum of the block).
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 #include "../../include/mxfp4.h"
@@ -77,7 +79,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     const int nblk = a.k >> 5;
     // Activations that stay in LDS (see below) use rows of STEPS * 64 chunks, zero beyond K: the
     // loop then reads them without a check and every address is a constant away from one base.
-    constexpr bool kXLds = MT * STEPS > 6;
+    constexpr bool kXLds = MT * STEPS >= 6;
     const int xrow = kXLds ? STEPS * 64 : nblk;              // chunks per (activation row, j)
     int* ctr = reinterpret_cast<int*>(smem + (size_t)MT * 4 * xrow * 16);
     const int q_row_bytes = a.k >> 1;
@@ -157,7 +159,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
             xs[(e / pad) * xrow + nblk + e % pad] = u32x4_t{0, 0, 0, 0};
     }
     lds_barrier();
-    // Up to 96 registers of activations per lane (six steps of one row, two steps of two rows);
+    // Up to 64 registers of activations per lane (four steps of one row, two steps of two rows);
     // beyond that they stay in the LDS copy and every step reads its 64 bytes per row from there.
     auto x_of = [&](int m, int t, int j) {
         if constexpr (kXLds)
@@ -397,7 +399,7 @@ template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
 hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream, const Epilogue* epi)
 {
     const bool argmax = g.part_val != nullptr;
-    if (MT * STEPS > 6)
+    if (MT * STEPS >= 6)
         lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
     static bool attr_set = false;
     if (!attr_set && lds > 64 * 1024) {
@@ -427,12 +429,12 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
                         hipStream_t stream, const Epilogue* epi)
 {
     // 16 waves hold at most 128 registers each: enough for four steps of one activation row.
-    // Six steps: 8 waves, each with two weight rows and three steps in flight (measured best on
-    // the 7B down projection, 4096 x 11008, where a compute unit has only 16 rows to work on).
-    // From eight steps on (K > 12288) the activations stay in the LDS copy: registers are free
-    // again, so 16 waves with one weight row per step; the instances cover 8, 12, 14 and 16 steps
-    // and a shorter K leaves the last ones partly or wholly empty.  (Two activation rows from LDS
-    // were tried too: the compiler spills in every such instance.)
+    // From six steps on (K > 8192) the activations stay in the LDS copy: registers are free
+    // again, so 16 waves with one weight row per step here too; the instances cover 6, 8, 12, 14
+    // and 16 steps and a shorter K leaves the last ones partly or wholly empty.  (Six steps in
+    // registers need 8 waves of two rows, three steps in flight: 7.4 us against 6.6 on the 7B
+    // down projection.  Two activation rows from LDS were tried too: the compiler spills in
+    // every such instance.)
     switch (steps2) {
     case 2:
         if constexpr (MT == 1)
@@ -448,8 +450,7 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
         break;
     case 6:
         if constexpr (MT == 1)
-            return ragged ? launch_one<MT, 2, 6, 3, 8, true>(a, m0, blocks, lds, stream, epi)
-                          : launch_one<MT, 2, 6, 3, 8, false>(a, m0, blocks, lds, stream, epi);
+            return launch_one<MT, 1, 6, 2, 16, true>(a, m0, blocks, lds, stream, epi);
         break;
     case 8:
         if constexpr (MT == 1)
@@ -473,7 +474,7 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
 }
 
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
-bool wide_group(int steps2, int mt) { return (mt == 1 && steps2 == 6) || (mt == 2 && steps2 == 2); }
+bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
 int waves_for(int steps2, int mt) { return wide_group(steps2, mt) ? 8 : 16; }
 int rows_per_step(int steps2, int mt) { return wide_group(steps2, mt) ? 2 : 1; }
 
