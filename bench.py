@@ -134,7 +134,7 @@ def run_verify8_tiled(lin, ws):
 
 
 DOMINANT = ("qkv", "o", "gate_up", "lm_head")
-DOMINANT_KERNEL = "mxfp4::gemv_reg_kernel<1,1,2,2,16,false>"
+DOMINANT_KERNEL = "mxfp4::(anonymous namespace)::gemv_reg_kernel<1, 1, 2, 2, 16, false>"
 
 
 def run_dominant(lin, ws):
