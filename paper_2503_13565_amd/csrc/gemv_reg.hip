@@ -161,9 +161,13 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     lds_barrier();
     // Up to 64 registers of activations per lane (four steps of one row, two steps of two rows);
     // beyond that they stay in the LDS copy and every step reads its 64 bytes per row from there.
+    // (one base per activation row: every read of a row is then within the 64 KB that the LDS
+    // instruction's offset field reaches, and no address has to be kept in a register)
+    const u32x4_t* xrow0 = xs + lane;
+    const u32x4_t* xrow1 = xs + (MT - 1) * 4 * STEPS * 64 + lane;
     auto x_of = [&](int m, int t, int j) {
         if constexpr (kXLds)
-            return xs[((m * 4 + j) * STEPS + t) * 64 + lane];
+            return (m == 0 ? xrow0 : xrow1)[(j * STEPS + t) * 64];
         else
             return (!kRagged || t * 64 + lane < nblk) ? xs[(m * 4 + j) * nblk + t * 64 + lane] : u32x4_t{0, 0, 0, 0};
     };
@@ -261,9 +265,9 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
             if constexpr (kXLds)
                 __builtin_amdgcn_sched_barrier(0);  // step by step: across steps the scheduler piles up registers
 #pragma unroll
-            for (int m = 0; m < MT; ++m)
+            for (int j = 0; j < 4; ++j)             // in the order of use: chunk j of every activation row
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int m = 0; m < MT; ++m) {
                     if constexpr (kXLds)
                         xq[m][j] = x_of(m, t, j);
                     else
