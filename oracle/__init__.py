@@ -71,6 +71,14 @@ def _load():
         lib.oracle_e4m3_woq_gemm.restype = i32
         lib.oracle_e4m3_magnitude.argtypes = [i32]
         lib.oracle_e4m3_magnitude.restype = ctypes.c_double
+        lib.oracle_e2m3_direct_cast.argtypes = [vp, i64, i64, i64, vp, vp, i32]
+        lib.oracle_e2m3_direct_cast.restype = i32
+        lib.oracle_e2m3_dequant.argtypes = [vp, vp, i64, i64, vp]
+        lib.oracle_e2m3_dequant.restype = i32
+        lib.oracle_e2m3_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, i32]
+        lib.oracle_e2m3_woq_gemm.restype = i32
+        lib.oracle_e2m3_magnitude.argtypes = [i32]
+        lib.oracle_e2m3_magnitude.restype = ctypes.c_double
         lib.oracle_epilogue.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, vp, vp]
         lib.oracle_epilogue.restype = i32
         lib.oracle_argmax.argtypes = [vp, i64, i64, vp, vp]
@@ -227,6 +235,55 @@ def e4m3_woq_gemm(x_bits, q8, s, threads: int = 0, want_abs: bool = True):
                                       _ptr(a) if want_abs else None, threads)
     if rc:
         raise RuntimeError("oracle_e4m3_woq_gemm failed: %d" % rc)
+    return (y, a) if want_abs else y
+
+
+def e2m3_magnitude(code: int) -> float:
+    return float(_load().oracle_e2m3_magnitude(int(code)))
+
+
+def e2m3_direct_cast(w_bits, threads: int = 0):
+    """BF16 bit patterns ``[N, K]`` -> (``q6 [N, K/32*24]`` packed 6-bit codes, ``s [N, K/32]`` scale bytes)."""
+    w = _as(w_bits, np.uint16, 2)
+    n, k = w.shape
+    if k % BLOCK:
+        raise ValueError("K must be a multiple of 32")
+    q6 = np.empty((n, k // BLOCK * 24), np.uint8)
+    s = np.empty((n, k // BLOCK), np.uint8)
+    rc = _load().oracle_e2m3_direct_cast(_ptr(w), n, k, k, _ptr(q6), _ptr(s), threads)
+    if rc:
+        raise RuntimeError("oracle_e2m3_direct_cast failed: %d" % rc)
+    return q6, s
+
+
+def e2m3_dequant(q6, s) -> np.ndarray:
+    q6 = _as(q6, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    n, nblk = s.shape
+    if q6.shape != (n, nblk * 24):
+        raise ValueError("shape mismatch: q6 %r s %r" % (q6.shape, s.shape))
+    out = np.empty((n, nblk * BLOCK), np.float64)
+    rc = _load().oracle_e2m3_dequant(_ptr(q6), _ptr(s), n, nblk * BLOCK, _ptr(out))
+    if rc:
+        raise RuntimeError("oracle_e2m3_dequant failed: %d" % rc)
+    return out
+
+
+def e2m3_woq_gemm(x_bits, q6, s, threads: int = 0, want_abs: bool = True):
+    """FP64 product with 6-bit (E2M3 + E8M0) weights and the sum of absolute products."""
+    x = _as(x_bits, np.uint16, 2)
+    q6 = _as(q6, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    m, k = x.shape
+    n = q6.shape[0]
+    if q6.shape[1] != k // BLOCK * 24 or s.shape != (n, k // BLOCK):
+        raise ValueError("shape mismatch: x %r q6 %r s %r" % (x.shape, q6.shape, s.shape))
+    y = np.empty((m, n), np.float64)
+    a = np.empty((m, n), np.float64) if want_abs else None
+    rc = _load().oracle_e2m3_woq_gemm(_ptr(x), m, k, _ptr(q6), _ptr(s), n, k, _ptr(y),
+                                      _ptr(a) if want_abs else None, threads)
+    if rc:
+        raise RuntimeError("oracle_e2m3_woq_gemm failed: %d" % rc)
     return (y, a) if want_abs else y
 
 

@@ -35,7 +35,10 @@
  * padded layout, and the slope constant against a numeric maximum; the 8-bit
  * (E4M3) cast and product against a library float8 conversion and decode, the
  * decision midpoints in exact rational arithmetic, round trips of every code
- * point, saturation, and a library FP64 matmul (tests/test_oracle_e4m3.py).
+ * point, saturation, and a library FP64 matmul (tests/test_oracle_e4m3.py); the
+ * 6-bit (E2M3) cast, packing and product against a grid and a bit string written
+ * out in the test, exact midpoints, round trips, and a library FP64 matmul
+ * (tests/test_oracle_e2m3.py).
  */
 #include <math.h>
 #include <stdint.h>
@@ -456,6 +459,170 @@ int oracle_e4m3_woq_gemm(const uint16_t *x, int64_t M, int64_t ldx,
 }
 
 double oracle_e4m3_magnitude(int code) { return e4m3_magnitude(code & 0x7F); }
+
+/* ------------------------------------------------------------------------------
+ * A 6-bit draft: the same cast with the OCP 6-bit element format E2M3: 1 sign, 2
+ * exponent bits (bias 1), 3 mantissa bits, no infinities and no NaN, magnitudes
+ * m/8 for exponent field 0 and (1 + m/8) * 2^(e-1) above, largest 7.5.  Its largest
+ * power of two is 4 = 2^2 as for E2M1, so X = 2^(floor(log2 amax) - 2); rounding to
+ * nearest, ties to the even code, beyond 7.5 saturates.  Packing: the 32 codes
+ * (sign << 5 | eemmm) of a block are a little-endian bit string of 192 bits, code i
+ * in bits 6i .. 6i+5: 24 bytes per block, q6[N, K/32 * 24]; scales [N, K/32].
+ * Zero blocks, tiny scales, non-finite inputs, the sign of zero: as in the 4-bit
+ * cast. */
+#define E2M3_BLOCK_BYTES 24
+
+static double e2m3_magnitude(int code)       /* code = eemmm, 0..31 */
+{
+    int e = (code >> 3) & 3;
+    int m = code & 7;
+    if (e == 0)
+        return m / 8.0;                       /* subnormal: 0.mmm * 2^(1-1) */
+    return ldexp(1.0 + m / 8.0, e - 1);       /* normal:    1.mmm * 2^(e-1) */
+}
+
+static int e2m3_round_code(double r)
+{
+    int best = 0;
+    double best_d = fabs(r - e2m3_magnitude(0));
+    for (int c = 1; c < 32; ++c) {
+        double d = fabs(r - e2m3_magnitude(c));
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return best;
+}
+
+static void e2m3_put(uint8_t *blk, int i, int code6)
+{
+    for (int b = 0; b < 6; ++b) {
+        int bit = 6 * i + b;
+        if ((code6 >> b) & 1)
+            blk[bit >> 3] |= (uint8_t)(1u << (bit & 7));
+    }
+}
+
+static int e2m3_get(const uint8_t *blk, int i)
+{
+    int code6 = 0;
+    for (int b = 0; b < 6; ++b) {
+        int bit = 6 * i + b;
+        code6 |= ((blk[bit >> 3] >> (bit & 7)) & 1) << b;
+    }
+    return code6;
+}
+
+static uint8_t e2m3_cast_block(const uint16_t *w, uint8_t blk[E2M3_BLOCK_BYTES])
+{
+    double v[ORACLE_BLOCK];
+    double amax = 0.0;
+    int nonfinite = 0;
+    memset(blk, 0, E2M3_BLOCK_BYTES);
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        v[i] = bf16_to_double(w[i]);
+        if (isnan(v[i]) || isinf(v[i]))
+            nonfinite = 1;
+        else if (fabs(v[i]) > amax)
+            amax = fabs(v[i]);
+    }
+    if (nonfinite)
+        return 0xFF;
+    int E;
+    if (amax == 0.0) {
+        E = -127;
+    } else {
+        int ex;
+        (void)frexp(amax, &ex);
+        E = (ex - 1) - 2;                     /* floor(log2 amax) - 2 */
+    }
+    if (E < -127)
+        E = -127;
+    if (E > 127)
+        E = 127;
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        double r = ldexp(fabs(v[i]), -E);
+        int sign = (w[i] >> 15) & 1;
+        e2m3_put(blk, i, (sign << 5) | e2m3_round_code(r));
+    }
+    return (uint8_t)(E + 127);
+}
+
+int oracle_e2m3_direct_cast(const uint16_t *w, int64_t N, int64_t K, int64_t ldw,
+                            uint8_t *q6, uint8_t *s, int threads)
+{
+    if (N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldw < K)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t b = 0; b < nblk; ++b)
+            s[n * nblk + b] = e2m3_cast_block(w + n * ldw + b * ORACLE_BLOCK,
+                                              q6 + (n * nblk + b) * E2M3_BLOCK_BYTES);
+    (void)threads;
+    return 0;
+}
+
+static double e2m3_dequant_one(int code6, uint8_t scale_byte)
+{
+    if (scale_byte == 0xFF)
+        return NAN;
+    double val = ldexp(e2m3_magnitude(code6 & 31), (int)scale_byte - 127);
+    return (code6 & 32) ? -val : val;
+}
+
+int oracle_e2m3_dequant(const uint8_t *q6, const uint8_t *s, int64_t N, int64_t K, double *w_hat)
+{
+    if (N < 0 || K < 0 || K % ORACLE_BLOCK != 0)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t b = k / ORACLE_BLOCK;
+            w_hat[n * K + k] = e2m3_dequant_one(e2m3_get(q6 + (n * nblk + b) * E2M3_BLOCK_BYTES, (int)(k % ORACLE_BLOCK)),
+                                                s[n * nblk + b]);
+        }
+    return 0;
+}
+
+int oracle_e2m3_woq_gemm(const uint16_t *x, int64_t M, int64_t ldx,
+                         const uint8_t *q6, const uint8_t *s, int64_t N, int64_t K,
+                         double *y_ref, double *a_ref, int threads)
+{
+    if (M < 0 || N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldx < K)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t m = 0; m < M; ++m) {
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                int64_t b = k / ORACLE_BLOCK;
+                double wv = e2m3_dequant_one(e2m3_get(q6 + (n * nblk + b) * E2M3_BLOCK_BYTES, (int)(k % ORACLE_BLOCK)),
+                                             s[n * nblk + b]);
+                double p = bf16_to_double(x[m * ldx + k]) * wv;
+                acc += p;
+                aacc += fabs(p);
+            }
+            y_ref[m * N + n] = acc;
+            if (a_ref)
+                a_ref[m * N + n] = aacc;
+        }
+    }
+    (void)threads;
+    return 0;
+}
+
+double oracle_e2m3_magnitude(int code) { return e2m3_magnitude(code & 31); }
 
 /* What the linear layer's backend fuses around the contraction (section 3.4: bias
  * and residual add applied to the product's output while it is at hand) and, for
