@@ -109,6 +109,35 @@ int mxfp4_e4m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * A 6-bit draft on the same path: the same cast with the OCP 6-bit element format E2M3 (1 sign, 2
+ * exponent bits with bias 1, 3 mantissa bits; magnitudes m/8 and (1 + m/8) * 2^(e-1), largest
+ * 7.5; no infinities, no NaN): X = 2^(floor(log2 amax) - 2) as for MXFP4, elements rounded to
+ * nearest (ties to the even code), beyond 7.5 saturates; zero blocks, tiny scales, non-finite
+ * inputs and the sign of zero as in mxfp4_direct_cast.  6.25 bits per weight.
+ *   q6           [N, K/32 * 24] bytes: the 32 codes (sign << 5 | eemmm) of a block are a
+ *                little-endian bit string of 192 bits, code i in bits 6i .. 6i+5; 8-byte aligned
+ *   scales_e8m0  [N, K/32] as for MXFP4 (4-byte aligned for the product)
+ * mxfp4_e2m3_direct_cast_bits rounds and packs with integer arithmetic instead of the convert
+ * instruction (same bits).  mxfp4_e2m3_woq_gemm and mxfp4_e2m3_woq_gemm_argmax are mxfp4_woq_gemm
+ * and mxfp4_woq_gemm_argmax with q6 in place of q_packed, for the shapes the decode GEMV takes:
+ * K % 128 == 0, K <= 32768, N >= 8 x compute units (MXFP4_ERR_SHAPE otherwise); any M, one or two
+ * rows per pass.  Argmax workspace as for mxfp4_e4m3_woq_gemm_argmax.
+ */
+int mxfp4_e2m3_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                           void* q6, void* scales_e8m0, void* stream);
+int mxfp4_e2m3_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                                void* q6, void* scales_e8m0, void* stream);
+int mxfp4_e2m3_dequant(const void* q6, const void* scales_e8m0, int64_t N, int64_t K,
+                       void* w_bf16, int64_t ldw, void* stream);
+int mxfp4_e2m3_woq_gemm(const void* x_bf16, int64_t M, int64_t ldx,
+                        const void* q6, const void* scales_e8m0, int64_t N, int64_t K,
+                        void* y_bf16, int64_t ldy, void* stream);
+int mxfp4_e2m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
+                               const void* q6, const void* scales_e8m0, int64_t N, int64_t K,
+                               int32_t* argmax_out, float* max_out,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Dequantise to BF16 (exact whenever 2^(scale-127) * 6 is a normal BF16 number): the inverse
  * map of the format in section 3.4.3; used to check the weight decode in isolation.
  *   w_bf16 out BF16 [N, K], row stride ldw elements.

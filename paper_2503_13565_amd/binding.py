@@ -25,6 +25,8 @@ EXPORTS = [
     "mxfp4_woq_gemm_fused",
     "mxfp4_e4m3_direct_cast", "mxfp4_e4m3_direct_cast_bits", "mxfp4_e4m3_dequant", "mxfp4_e4m3_woq_gemm",
     "mxfp4_e4m3_woq_gemm_argmax",
+    "mxfp4_e2m3_direct_cast", "mxfp4_e2m3_direct_cast_bits", "mxfp4_e2m3_dequant", "mxfp4_e2m3_woq_gemm",
+    "mxfp4_e2m3_woq_gemm_argmax",
     "mxfp4_tile_repack_q_bytes", "mxfp4_tile_repack_s_bytes", "mxfp4_tile_repack", "mxfp4_woq_gemm_tiled",
     "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify", "mxfp4_woq_gemm_tiled_fused",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
@@ -84,6 +86,15 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_e4m3_woq_gemm.restype = i32
     lib.mxfp4_e4m3_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     lib.mxfp4_e4m3_woq_gemm_argmax.restype = i32
+    for name in ("mxfp4_e2m3_direct_cast", "mxfp4_e2m3_direct_cast_bits"):
+        getattr(lib, name).argtypes = [vp, i64, i64, i64, vp, vp, vp]
+        getattr(lib, name).restype = i32
+    lib.mxfp4_e2m3_dequant.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_e2m3_dequant.restype = i32
+    lib.mxfp4_e2m3_woq_gemm.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_e2m3_woq_gemm.restype = i32
+    lib.mxfp4_e2m3_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.mxfp4_e2m3_woq_gemm_argmax.restype = i32
     lib.mxfp4_woq_gemm_fused.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i32, vp, i64, vp, i64, vp, sz, i32, vp]
     lib.mxfp4_woq_gemm_fused.restype = i32
     lib.mxfp4_tile_repack_q_bytes.argtypes = [i64, i64]
@@ -359,6 +370,73 @@ def mxfp4_e4m3_woq_gemm_argmax(x: torch.Tensor, q8: torch.Tensor, s: torch.Tenso
         idx, val = out
     with torch.cuda.device(x.device):
         _check(load().mxfp4_e4m3_woq_gemm_argmax(_ptr(x), m, ldx, _ptr(q8), _ptr(s), n, k, _ptr(idx), _ptr(val),
+                                                _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                _stream()))
+    return idx, val
+
+
+def mxfp4_e2m3_direct_cast(w: torch.Tensor, integer_rule: bool = False) -> Tuple[torch.Tensor, torch.Tensor]:
+    """BF16 ``[N, K]`` -> (``q6 [N, K/32*24]`` packed E2M3 codes, ``s [N, K/32]`` E8M0 scale bytes)."""
+    _dev(w)
+    if w.dtype != torch.bfloat16 or w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be a 2-D BF16 tensor with a contiguous last dimension")
+    n, k = w.shape
+    q6 = torch.empty((n, k // 32 * 24), dtype=torch.uint8, device=w.device)
+    s = torch.empty((n, k // 32), dtype=torch.uint8, device=w.device)
+    fn = load().mxfp4_e2m3_direct_cast_bits if integer_rule else load().mxfp4_e2m3_direct_cast
+    with torch.cuda.device(w.device):
+        _check(fn(_ptr(w), n, k, w.stride(0) if n > 1 else k, _ptr(q6), _ptr(s), _stream()))
+    return q6, s
+
+
+def mxfp4_e2m3_dequant(q6: torch.Tensor, s: torch.Tensor) -> torch.Tensor:
+    _dev(q6)
+    n, k = s.shape[0], s.shape[1] * 32
+    w = torch.empty((n, k), dtype=torch.bfloat16, device=q6.device)
+    with torch.cuda.device(q6.device):
+        _check(load().mxfp4_e2m3_dequant(_ptr(q6), _ptr(s), n, k, _ptr(w), k, _stream()))
+    return w
+
+
+def _e2m3_shapes(x, q6, s):
+    _dev(x)
+    if x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D BF16 tensor with a contiguous last dimension")
+    if q6.dtype != torch.uint8 or s.dtype != torch.uint8 or not q6.is_contiguous() or not s.is_contiguous():
+        raise ValueError("q6 and s must be contiguous uint8 tensors")
+    m, k = x.shape
+    n = q6.shape[0]
+    if q6.shape[1] != k // 32 * 24 or tuple(s.shape) != (n, k // 32):
+        raise ValueError("shape mismatch: x %r q6 %r s %r" % (tuple(x.shape), tuple(q6.shape), tuple(s.shape)))
+    return m, n, k, (x.stride(0) if m > 1 else k)
+
+
+def mxfp4_e2m3_woq_gemm(x: torch.Tensor, q6: torch.Tensor, s: torch.Tensor,
+                        y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    m, n, k, ldx = _e2m3_shapes(x, q6, s)
+    if y is None:
+        y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_e2m3_woq_gemm(_ptr(x), m, ldx, _ptr(q6), _ptr(s), n, k, _ptr(y),
+                                         y.stride(0) if m > 1 else n, _stream()))
+    return y
+
+
+def mxfp4_e2m3_woq_gemm_argmax(x: torch.Tensor, q6: torch.Tensor, s: torch.Tensor,
+                               workspace: Optional[torch.Tensor] = None,
+                               out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
+                               ) -> Tuple[torch.Tensor, torch.Tensor]:
+    m, n, k, ldx = _e2m3_shapes(x, q6, s)
+    if workspace is None:
+        workspace = torch.empty((mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k),), dtype=torch.uint8,
+                                device=x.device)
+    if out is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+        val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    else:
+        idx, val = out
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_e2m3_woq_gemm_argmax(_ptr(x), m, ldx, _ptr(q6), _ptr(s), n, k, _ptr(idx), _ptr(val),
                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                 _stream()))
     return idx, val

@@ -688,6 +688,151 @@ int mxfp4_e4m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const
                     workspace_bytes, true, stream);
 }
 
+// ---- 6-bit draft format ---------------------------------------------------------------------
+
+static int e2m3_check_weights(const void* q6, const void* s, int64_t N, int64_t K)
+{
+    if (!q6 || !s)
+        return fail(MXFP4_ERR_NULL, "q6 or scales_e8m0 is NULL");
+    if (N < 1 || N > 0x7FFFFFFF / 8)
+        return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
+    if (K < 32 || K % 32 != 0 || K > MXFP4_MAX_K)
+        return fail(MXFP4_ERR_SHAPE, "K=%lld must be a multiple of 32 in [32, %d]", (long long)K, MXFP4_MAX_K);
+    if (N * (K / 32) * 24 > 0x7FFFFFFF)
+        return fail(MXFP4_ERR_SHAPE, "%lld bytes of 6-bit weights exceed 2 GiB - 1", (long long)(N * (K / 32) * 24));
+    if (!aligned(q6, 8))
+        return fail(MXFP4_ERR_ALIGN, "q6 must be 8-byte aligned");
+    return MXFP4_OK;
+}
+
+static int e2m3_cast_impl(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q6, void* scales_e8m0,
+                          bool integer_rule, void* stream)
+{
+    g_err[0] = 0;
+    if (N < 0 || N > 0x7FFFFFFF)
+        return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
+    if (K < 32 || K % 32 != 0 || K > (1 << 24))
+        return fail(MXFP4_ERR_SHAPE, "K=%lld must be a positive multiple of 32", (long long)K);
+    if (ldw < K)
+        return fail(MXFP4_ERR_SHAPE, "ldw=%lld < K=%lld", (long long)ldw, (long long)K);
+    if (N == 0)
+        return MXFP4_OK;
+    if (!w_bf16 || !q6 || !scales_e8m0)
+        return fail(MXFP4_ERR_NULL, "w_bf16, q6 or scales_e8m0 is NULL");
+    if (ldw % 8 != 0 || !aligned(w_bf16, 16))
+        return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
+    if (!aligned(q6, 8))
+        return fail(MXFP4_ERR_ALIGN, "q6 must be 8-byte aligned");
+    hipError_t e = launch_e2m3_cast(w_bf16, N, K, ldw, q6, scales_e8m0, integer_rule,
+                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "6-bit cast launch");
+}
+
+int mxfp4_e2m3_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q6, void* scales_e8m0,
+                           void* stream)
+{
+    return e2m3_cast_impl(w_bf16, N, K, ldw, q6, scales_e8m0, false, stream);
+}
+
+int mxfp4_e2m3_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q6,
+                                void* scales_e8m0, void* stream)
+{
+    return e2m3_cast_impl(w_bf16, N, K, ldw, q6, scales_e8m0, true, stream);
+}
+
+int mxfp4_e2m3_dequant(const void* q6, const void* scales_e8m0, int64_t N, int64_t K, void* w_bf16, int64_t ldw,
+                       void* stream)
+{
+    g_err[0] = 0;
+    if (N == 0)
+        return MXFP4_OK;
+    int rc = e2m3_check_weights(q6, scales_e8m0, N, K);
+    if (rc)
+        return rc;
+    if (!w_bf16)
+        return fail(MXFP4_ERR_NULL, "w_bf16 is NULL");
+    if (ldw < K)
+        return fail(MXFP4_ERR_SHAPE, "ldw=%lld < K=%lld", (long long)ldw, (long long)K);
+    if (ldw % 8 != 0 || !aligned(w_bf16, 16))
+        return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
+    hipError_t e = launch_e2m3_dequant(q6, scales_e8m0, N, K, w_bf16, ldw, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "6-bit dequant launch");
+}
+
+static int run_e2m3(const void* x, int64_t M, int64_t ldx, const void* q6, const void* s, int64_t N, int64_t K,
+                    void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
+                    size_t workspace_bytes, bool argmax, void* stream)
+{
+    g_err[0] = 0;
+    int rc = e2m3_check_weights(q6, s, N, K);
+    if (rc)
+        return rc;
+    if (!aligned(s, 4))
+        return fail(MXFP4_ERR_ALIGN, "scales_e8m0 must be 4-byte aligned");
+    rc = check_x(x, M, ldx, K);
+    if (rc)
+        return rc;
+    DeviceInfo dev;
+    rc = device_info(&dev);
+    if (rc)
+        return rc;
+    GemmArgs a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.ldx = ldx;
+    a.q = static_cast<const uint8_t*>(q6);
+    a.s = static_cast<const uint8_t*>(s);
+    a.m = (int)M;
+    a.n = (int)N;
+    a.k = (int)K;
+    if (argmax) {
+        if (!argmax_out)
+            return fail(MXFP4_ERR_NULL, "argmax_out is NULL");
+        const size_t need = (size_t)M * gemv_max_parts(dev) * 8;
+        if (!workspace || workspace_bytes < need)
+            return fail(MXFP4_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                        workspace ? workspace_bytes : (size_t)0);
+        if (!aligned(workspace, 8))
+            return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
+        a.parts = gemv_max_parts(dev);
+        a.part_val = static_cast<float*>(workspace);
+        a.part_idx = reinterpret_cast<int32_t*>(a.part_val + (size_t)M * a.parts);
+    } else {
+        if (!y)
+            return fail(MXFP4_ERR_NULL, "y_bf16 is NULL");
+        if (ldy < N)
+            return fail(MXFP4_ERR_SHAPE, "ldy=%lld < N=%lld", (long long)ldy, (long long)N);
+        a.y = static_cast<uint16_t*>(y);
+        a.ldy = ldy;
+    }
+    if (!gemv_reg_can_run(a, dev))
+        return fail(MXFP4_ERR_SHAPE, "the 6-bit product needs K %% 128 == 0, K <= 32768 and N >= %d", dev.cus * 8);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int parts_used = 0;
+    hipError_t e = launch_gemv_reg(a, dev, &parts_used, st, nullptr, 6);
+    if (e != hipSuccess)
+        return hip_fail(e, "6-bit product launch");
+    if (argmax) {
+        e = launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
+        if (e != hipSuccess)
+            return hip_fail(e, "argmax finish launch");
+    }
+    return MXFP4_OK;
+}
+
+int mxfp4_e2m3_woq_gemm(const void* x_bf16, int64_t M, int64_t ldx, const void* q6, const void* scales_e8m0,
+                        int64_t N, int64_t K, void* y_bf16, int64_t ldy, void* stream)
+{
+    return run_e2m3(x_bf16, M, ldx, q6, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, nullptr, 0, false, stream);
+}
+
+int mxfp4_e2m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void* q6,
+                               const void* scales_e8m0, int64_t N, int64_t K, int32_t* argmax_out, float* max_out,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_e2m3(x_bf16, M, ldx, q6, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, workspace,
+                    workspace_bytes, true, stream);
+}
+
 int mxfp4_bf16_gemm(const void* x_bf16, int64_t M, int64_t ldx, const void* w_bf16, int64_t N, int64_t K,
                     int64_t ldw, void* y_bf16, int64_t ldy, void* stream)
 {

@@ -46,9 +46,18 @@ struct RegArgs {
 // Epi: NoEpilogue, or Epilogue for the fused form (bias, gate, residual at the flush).  The gate
 // needs a pair of rows 2c, 2c + 1 in neighbouring lanes of the held outputs: with R = 2 a group is
 // a pair; with R = 1 the counter deals pairs and a wave takes the pair's rows in two trips.
-template <int MT, int R, int STEPS, int D, int NW, bool kRagged, class Epi>
+// kBits: 4 (E2M1 nibbles, 16 bytes per block) or 6 (E2M3 codes, 24 bytes per block: the lane loads
+// 16 + 8 bytes and one v_cvt_scalef32_pk32_bf16_fp6 decodes the whole block).
+typedef __attribute__((ext_vector_type(32))) __bf16 bf16x32_t;
+typedef __attribute__((ext_vector_type(6))) unsigned int u32x6_t;
+typedef __attribute__((ext_vector_type(16))) unsigned int u32x16_t;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged, class Epi, int kBits = 4>
 __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 {
+    static_assert(kBits == 4 || kBits == 6, "element width");
+    constexpr int kBlkBytes = kBits == 6 ? 24 : 16;
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     const int m0 = a.m0;
     static_assert(STEPS % D == 0, "the buffer of a step must be known at compile time");
@@ -82,7 +91,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     constexpr bool kXLds = MT * STEPS >= 6;
     const int xrow = kXLds ? STEPS * 64 : nblk;              // chunks per (activation row, j)
     int* ctr = reinterpret_cast<int*>(smem + (size_t)MT * 4 * xrow * 16);
-    const int q_row_bytes = a.k >> 1;
+    const int q_row_bytes = (a.k >> 5) * kBlkBytes;
     const bool argmax = a.parts > 0;
     const int G = gridDim.x, b = blockIdx.x;
     bool gated = false;
@@ -120,6 +129,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     const __amdgpu_buffer_rsrc_t rr0 = residual_row(0), rr1 = residual_row(MT - 1);
 
     u32x4_t bq[D][R];
+    u32x2_t bq2[D][kBits == 6 ? R : 1];             // bytes 16..23 of a 6-bit block
     uint32_t bs[D];
     const int n_groups = (a.n + R - 1) / R;
     const int srow = (lane >> 4) % R;
@@ -133,8 +143,11 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int row = min(g0 + r, a.n - 1);                    // odd N: the last row twice
-            bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(rq, (live && vb) ? lane * 16 : 0x7FFFFFF0,
-                                                             row * q_row_bytes + t * 1024, 2);
+            bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(rq, (live && vb) ? lane * kBlkBytes : 0x7FFFFFF0,
+                                                             row * q_row_bytes + t * (64 * kBlkBytes), 2);
+            if constexpr (kBits == 6)
+                bq2[d][r] = __builtin_amdgcn_raw_buffer_load_b64(rq, (live && vb) ? lane * 24 + 16 : 0x7FFFFFF0,
+                                                                row * q_row_bytes + t * 1536, 2);
         }
         // scale bytes of the step: 16 dwords per row; lane l loads dword l % 16 of row (l / 16) % R
         const int row = min(g0 + srow, a.n - 1);
@@ -282,14 +295,29 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                 float sc = __uint_as_float((dw << sh_top) >> 1);
                 if (kRagged)
                     sc = (t * 64 + lane < nblk) ? sc : 1.0f;         // no NaN from a neighbour's scale byte
+                u32x16_t w6 = {};
+                if constexpr (kBits == 6) {
+                    const u32x4_t lo = bq[d][r];
+                    const u32x2_t hi = bq2[d][r];
+                    const u32x6_t packed = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1]};
+                    w6 = __builtin_bit_cast(u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(packed, sc));
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t qd = bq[d][r][j];
                     bf16x2_t w[4];
-                    w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0);
-                    w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1);
-                    w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2);
-                    w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3);
+                    if constexpr (kBits == 6) {
+                        const uint32_t w0 = w6[4 * j], w1 = w6[4 * j + 1], w2 = w6[4 * j + 2], w3 = w6[4 * j + 3];
+                        w[0] = __builtin_bit_cast(bf16x2_t, w0);
+                        w[1] = __builtin_bit_cast(bf16x2_t, w1);
+                        w[2] = __builtin_bit_cast(bf16x2_t, w2);
+                        w[3] = __builtin_bit_cast(bf16x2_t, w3);
+                    } else {
+                        const uint32_t qd = bq[d][r][j];
+                        w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0);
+                        w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1);
+                        w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2);
+                        w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3);
+                    }
 #pragma unroll
                     for (int m = 0; m < MT; ++m) {
                         // through scalars: a bit cast applied directly to a vector element reads element 0
@@ -399,6 +427,36 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_fused_kernel(const uint16_t*
                                                 Epilogue{bias, residual, ldr, act});
 }
 
+// The 6-bit format (q = q6, 24 bytes per block).
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+__global__ __launch_bounds__(NW * 64) void gemv_reg6_kernel(const uint16_t* x, const uint8_t* q, const uint8_t* s,
+                                                            void* out, int n, int k, int m, int m0, int ldx,
+                                                            int ldy, int parts)
+{
+    gemv_reg_body<MT, R, STEPS, D, NW, kRagged, NoEpilogue, 6>(RegArgs{x, q, s, out, n, k, m, m0, ldx, ldy, parts},
+                                                               NoEpilogue{});
+}
+
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+hipError_t launch_one6(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream)
+{
+    const bool argmax = g.part_val != nullptr;
+    if (MT * STEPS >= 6)
+        lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
+    static bool attr_set = false;
+    if (!attr_set && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds, stream,
+                       g.x, g.q, g.s, argmax ? static_cast<void*>(g.part_val) : static_cast<void*>(g.y), g.n, g.k,
+                       g.m, m0, (int)g.ldx, (int)g.ldy, argmax ? g.parts : 0);
+    return hipGetLastError();
+}
+
 template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
 hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream, const Epilogue* epi)
 {
@@ -477,6 +535,45 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
     return hipErrorInvalidValue;
 }
 
+// The 6-bit format: the same instances (all of them ready for a ragged K), no fused form.
+template <int MT>
+hipError_t launch_steps6(const GemmArgs& a, int m0, int steps2, int blocks, size_t lds, hipStream_t stream)
+{
+    switch (steps2) {
+    case 2:
+        if constexpr (MT == 1)
+            return launch_one6<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream);
+        else
+            return launch_one6<MT, 2, 2, 2, 8, true>(a, m0, blocks, lds, stream);
+    case 4:
+        if constexpr (MT == 1)
+            return launch_one6<MT, 1, 4, 2, 16, true>(a, m0, blocks, lds, stream);
+        break;
+    case 6:
+        if constexpr (MT == 1)
+            return launch_one6<MT, 1, 6, 2, 16, true>(a, m0, blocks, lds, stream);
+        break;
+    case 8:
+        if constexpr (MT == 1)
+            return launch_one6<MT, 1, 8, 2, 16, true>(a, m0, blocks, lds, stream);
+        break;
+    case 10:
+    case 12:
+        if constexpr (MT == 1)
+            return launch_one6<MT, 1, 12, 2, 16, true>(a, m0, blocks, lds, stream);
+        break;
+    case 14:
+        if constexpr (MT == 1)
+            return launch_one6<MT, 1, 14, 2, 16, true>(a, m0, blocks, lds, stream);
+        break;
+    case 16:
+        if constexpr (MT == 1)
+            return launch_one6<MT, 1, 16, 2, 16, true>(a, m0, blocks, lds, stream);
+        break;
+    }
+    return hipErrorInvalidValue;
+}
+
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
 bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
 int waves_for(int steps2, int mt) { return wide_group(steps2, mt) ? 8 : 16; }
@@ -504,8 +601,10 @@ bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev)
 bool gemv_reg_single_pass(const GemmArgs& a) { return a.m == 1 || (a.m == 2 && even_steps(a.k) <= 2); }
 
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
-                           const Epilogue* epi)
+                           const Epilogue* epi, int bits)
 {
+    if (bits != 4 && (bits != 6 || epi))
+        return hipErrorInvalidValue;
     const int steps2 = even_steps(a.k);
     const bool ragged = a.k != steps2 * 2048;
     // one workgroup per compute unit; the argmax form writes one partial winner per workgroup, so
@@ -522,10 +621,12 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     for (int m0 = 0; m0 < a.m;) {
         hipError_t e;
         if (a.m - m0 >= 2 && steps2 <= 2) {
-            e = launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi);
+            e = bits == 6 ? launch_steps6<2>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+                          : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi);
             m0 += 2;
         } else {
-            e = launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi);
+            e = bits == 6 ? launch_steps6<1>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+                          : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi);
             m0 += 1;
         }
         if (e != hipSuccess)

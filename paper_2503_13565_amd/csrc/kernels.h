@@ -64,8 +64,15 @@ int gemv_max_parts(const DeviceInfo& dev);
 // for the shapes it takes.  The argmax form writes one partial winner per workgroup.
 bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev);
 bool gemv_reg_single_pass(const GemmArgs& a);     // all activation rows in one pass over the weights
+// `bits`: 4 (a.q = packed nibbles) or 6 (a.q = q6, 24 bytes per block; no fused form).
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
-                           const Epilogue* epi = nullptr);
+                           const Epilogue* epi = nullptr, int bits = 4);
+
+// The 6-bit draft format (E2M3 codes as a 192-bit string per block: a.q is q6 [N, K/32 * 24]); e2m3.hip.
+hipError_t launch_e2m3_cast(const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q6, void* s,
+                            bool integer_rule, hipStream_t stream);
+hipError_t launch_e2m3_dequant(const void* q6, const void* s, int64_t n_rows, int64_t k, void* w, int64_t ldw,
+                               hipStream_t stream);
 
 // 16-row MFMA tiles (bf16 16x16x32) for verification batches; passes of up to 16 activation rows.
 // When the activation rows of a pass do not fit the LDS whole, K is split: in space over
