@@ -144,3 +144,25 @@ def test_e4m3_product_argument_checks():
     assert lib.mxfp4_e4m3_woq_gemm(P16, 1, 64, P16, P16, 8, 40, P16, 8, None) == 2         # K % 32
     assert lib.mxfp4_e4m3_woq_gemm(P16, 1, 64, P16, P16, 1 << 20, 4096, P16, 8, None) == 2  # N * K beyond 2 GiB
     assert lib.mxfp4_e4m3_dequant(P16, P16, 4, 64, None, 64, None) == 1
+
+
+@pytest.mark.parametrize("args,code", [
+    ((P16, 4, 48, 48, P16, P16, None), 2),                      # K % 32
+    ((P16, 4, 64, 32, P16, P16, None), 2),                      # ldw < K
+    ((None, 4, 64, 64, P16, P16, None), 1),
+    ((P16, 4, 64, 64, P2, P16, None), 3),                       # q6 not 8-byte aligned
+    ((P16, 0, 64, 64, None, None, None), 0),                    # N == 0 is a no-op
+])
+def test_e2m3_cast_argument_checks(args, code):
+    lib = binding.load()
+    assert lib.mxfp4_e2m3_direct_cast(*args) == code
+    assert lib.mxfp4_e2m3_direct_cast_bits(*args) == code
+
+
+def test_e2m3_product_argument_checks():
+    lib = binding.load()
+    assert lib.mxfp4_e2m3_woq_gemm(None, 1, 128, P16, P16, 8, 128, P16, 8, None) == 1
+    assert lib.mxfp4_e2m3_woq_gemm(P16, 1, 128, P2, P16, 8, 128, P16, 8, None) == 3          # q6 alignment
+    assert lib.mxfp4_e2m3_woq_gemm(P16, 1, 64, P16, P16, 8, 40, P16, 8, None) == 2           # K % 32
+    assert lib.mxfp4_e2m3_woq_gemm(P16, 1, 4096, P16, P16, 1 << 20, 4096, P16, 8, None) == 2  # beyond 2 GiB
+    assert lib.mxfp4_e2m3_dequant(P16, P16, 4, 64, None, 64, None) == 1
