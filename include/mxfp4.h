@@ -212,6 +212,44 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx,
                          int path, void* stream);
 
 /*
+ * A sequence of products in one call: the linear layers of a decode or verification step run
+ * back to back (sections 3.1 and 3.4: one forward pass is a fixed chain of contractions), and a
+ * host that issues them one call at a time spends longer per call than most of these kernels
+ * run.  Equivalent to calling, for i = 0 .. count - 1 in this order on `stream`,
+ * mxfp4_woq_gemm_ws (descriptor without bias, residual and act) or mxfp4_woq_gemm_fused
+ * (otherwise) with path MXFP4_PATH_AUTO and the one workspace: same kernels, same bits.  A
+ * descriptor may read what an earlier one wrote (the stream orders them).
+ *   descs      HOST array of `count` descriptors, read during the call only; the fields have
+ *              the meaning, layout and alignment rules of the arguments of the same name of
+ *              mxfp4_woq_gemm_fused; `reserved` must be 0
+ *   workspace  device scratch shared by all products, optional as in mxfp4_woq_gemm_ws;
+ *              mxfp4_woq_gemm_grouped_workspace_bytes gives the size that serves every
+ *              descriptor (the largest single need; 0 for a NULL or invalid array)
+ * Every descriptor is checked before anything is launched: on an argument error nothing has
+ * run, the code is that of the single call and mxfp4_last_error() names the descriptor's
+ * index.  count == 0 is a no-op.
+ */
+typedef struct mxfp4_gemm_desc {
+    const void* x_bf16;
+    int64_t M;
+    int64_t ldx;
+    const void* q_packed;
+    const void* scales_e8m0;
+    int64_t N;
+    int64_t K;
+    const void* bias_bf16;
+    const void* residual_bf16;
+    int64_t ldr;
+    void* y_bf16;
+    int64_t ldy;
+    int32_t act;
+    int32_t reserved;
+} mxfp4_gemm_desc;
+size_t mxfp4_woq_gemm_grouped_workspace_bytes(const mxfp4_gemm_desc* descs, int64_t count);
+int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The same product with the greedy pick fused (section 3.1: the target's token at each
  * verified position is compared with the draft's; section 4.1: greedy search): for every
  * activation row m, the index n of the largest FP32 accumulator (before any BF16 rounding),

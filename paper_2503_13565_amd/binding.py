@@ -22,7 +22,7 @@ EXPORTS = [
     "mxfp4_woq_gemm_workspace_bytes", "mxfp4_woq_gemm_ws", "mxfp4_woq_gemm_argmax_workspace_bytes", "mxfp4_woq_gemm_argmax", "mxfp4_woq_gemm_argmax_path",
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
-    "mxfp4_woq_gemm_fused",
+    "mxfp4_woq_gemm_fused", "mxfp4_woq_gemm_grouped_workspace_bytes", "mxfp4_woq_gemm_grouped",
     "mxfp4_e4m3_direct_cast", "mxfp4_e4m3_direct_cast_bits", "mxfp4_e4m3_dequant", "mxfp4_e4m3_woq_gemm",
     "mxfp4_e4m3_woq_gemm_argmax",
     "mxfp4_e2m3_direct_cast", "mxfp4_e2m3_direct_cast_bits", "mxfp4_e2m3_dequant", "mxfp4_e2m3_woq_gemm",
@@ -33,6 +33,15 @@ EXPORTS = [
 ]
 
 _lib = None
+
+
+class GemmDesc(ctypes.Structure):
+    """``mxfp4_gemm_desc`` of the header, field for field."""
+    _fields_ = [("x_bf16", ctypes.c_void_p), ("M", ctypes.c_int64), ("ldx", ctypes.c_int64),
+                ("q_packed", ctypes.c_void_p), ("scales_e8m0", ctypes.c_void_p), ("N", ctypes.c_int64),
+                ("K", ctypes.c_int64), ("bias_bf16", ctypes.c_void_p), ("residual_bf16", ctypes.c_void_p),
+                ("ldr", ctypes.c_int64), ("y_bf16", ctypes.c_void_p), ("ldy", ctypes.c_int64),
+                ("act", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class Mxfp4Error(RuntimeError):
@@ -111,6 +120,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_tiled_verify.restype = i32
     lib.mxfp4_woq_gemm_tiled_fused.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i32, vp, i64, vp, i64, vp]
     lib.mxfp4_woq_gemm_tiled_fused.restype = i32
+    lib.mxfp4_woq_gemm_grouped_workspace_bytes.argtypes = [ctypes.POINTER(GemmDesc), i64]
+    lib.mxfp4_woq_gemm_grouped_workspace_bytes.restype = sz
+    lib.mxfp4_woq_gemm_grouped.argtypes = [ctypes.POINTER(GemmDesc), i64, vp, sz, vp]
+    lib.mxfp4_woq_gemm_grouped.restype = i32
     lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
     for name in ("mxfp4_direct_cast", "mxfp4_direct_cast_bits", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
@@ -469,6 +482,53 @@ def mxfp4_woq_gemm_fused(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, bias
             _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, path,
             _stream()))
     return y
+
+
+class GemmGroup:
+    """A fixed sequence of products (``mxfp4_woq_gemm_grouped``): the descriptor array is built once,
+    ``run()`` is one library call.  ``items``: dicts with ``x``, ``q``, ``s`` and optionally ``bias``,
+    ``act``, ``residual``, ``y`` (allocated when missing), as for ``mxfp4_woq_gemm_fused``.  The
+    tensors are kept alive by the group; ``ys`` lists the outputs in order."""
+
+    def __init__(self, items):
+        self._keep, self.ys = [], []
+        self._descs = (GemmDesc * max(1, len(items)))()
+        self.count = len(items)
+        for d, it in zip(self._descs, items):
+            x, q, s = it["x"], it["q"], it["s"]
+            bias, residual, act = it.get("bias"), it.get("residual"), int(it.get("act", ACT_NONE))
+            m, n, k, ldx = _gemm_shapes(x, q, s)
+            c = n // 2 if act == ACT_SWIGLU else n
+            y = it.get("y")
+            if y is None:
+                y = torch.empty((m, c), dtype=torch.bfloat16, device=x.device)
+            if y.dtype != torch.bfloat16 or y.dim() != 2 or y.shape != (m, c) or y.stride(1) != 1:
+                raise ValueError("y must be a BF16 tensor [M, %d] with a contiguous last dimension" % c)
+            if bias is not None and (bias.dtype != torch.bfloat16 or bias.shape != (n,) or not bias.is_contiguous()):
+                raise ValueError("bias must be a contiguous BF16 tensor [N]")
+            if residual is not None and (residual.dtype != torch.bfloat16 or residual.shape != (m, c)
+                                         or residual.stride(1) != 1):
+                raise ValueError("residual must be a BF16 tensor [M, %d] with a contiguous last dimension" % c)
+            d.x_bf16, d.M, d.ldx = x.data_ptr(), m, ldx
+            d.q_packed, d.scales_e8m0, d.N, d.K = q.data_ptr(), s.data_ptr(), n, k
+            d.bias_bf16 = bias.data_ptr() if bias is not None else None
+            d.residual_bf16 = residual.data_ptr() if residual is not None else None
+            d.ldr = (residual.stride(0) if m > 1 else c) if residual is not None else 0
+            d.y_bf16, d.ldy = y.data_ptr(), (y.stride(0) if m > 1 else c)
+            d.act, d.reserved = act, 0
+            self._keep.append((x, q, s, bias, residual, y))
+            self.ys.append(y)
+        self.device = items[0]["x"].device if items else None
+        need = int(load().mxfp4_woq_gemm_grouped_workspace_bytes(self._descs, self.count))
+        self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.device) if need else None
+
+    def run(self) -> None:
+        if self.count == 0:
+            return
+        with torch.cuda.device(self.device):
+            _check(load().mxfp4_woq_gemm_grouped(
+                self._descs, self.count, _ptr(self.workspace),
+                self.workspace.numel() if self.workspace is not None else 0, _stream()))
 
 
 class TiledWeights:

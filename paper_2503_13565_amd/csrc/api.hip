@@ -14,6 +14,8 @@
 namespace mxfp4 {
 
 static thread_local char g_err[512] = "";
+// Set while a grouped call checks its descriptors: run_gemm then does everything but launch.
+static thread_local bool g_check_only = false;
 
 static int fail(int code, const char* fmt, ...)
 {
@@ -209,14 +211,16 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
                                          gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a));
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
-    hipError_t e;
+    hipError_t e = hipSuccess;
+    const bool go = !g_check_only;
     switch (chosen) {
     case -1:
         if (!mfma_tile_can_run(a, dev))
             return fail(MXFP4_ERR_ARG, "the tile-major product needs a pass's activation rows (%lld x K=%lld) to fit "
                                        "the LDS; use the canonical tensors for this shape",
                         (long long)(M > 16 ? 16 : M), (long long)K);
-        e = launch_mfma_tile(a, dev, &parts_used, st, true, epi);
+        if (go)
+            e = launch_mfma_tile(a, dev, &parts_used, st, true, epi);
         break;
     case MXFP4_PATH_VALU_BITS:
     case MXFP4_PATH_VALU_CVT:
@@ -224,27 +228,30 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         if ((size_t)K * 2 + (chosen == MXFP4_PATH_VALU_LUT ? 32768u : 0u) > (size_t)dev.lds_bytes)
             return fail(MXFP4_ERR_SHAPE, "K=%lld does not fit the LDS copy of one activation row",
                         (long long)K);
-        e = launch_gemv(a, chosen, argmax, dev, &parts_used, st, epi);
+        if (go)
+            e = launch_gemv(a, chosen, argmax, dev, &parts_used, st, epi);
         break;
     case MXFP4_PATH_VALU_REG:
         if (!gemv_reg_can_run(a, dev))
             return fail(MXFP4_ERR_ARG, "the register-resident GEMV needs K %% 128 == 0, K <= 12288 and N >= %d",
                         dev.cus * 8);
-        e = launch_gemv_reg(a, dev, &parts_used, st, epi);
+        if (go)
+            e = launch_gemv_reg(a, dev, &parts_used, st, epi);
         break;
     case MXFP4_PATH_MFMA:
     case MXFP4_PATH_MFMA_GENERAL:
         if (!mfma_can_run(a, dev, splitk_ws != nullptr))
             return fail(MXFP4_ERR_ARG, "the MFMA path needs K %% 128 == 0 and, without a workspace, four rows of "
                                        "K=%lld elements exceed the LDS", (long long)K);
-        e = launch_mfma(a, dev, splitk_ws, &parts_used, st, chosen == MXFP4_PATH_MFMA_GENERAL, epi);
+        if (go)
+            e = launch_mfma(a, dev, splitk_ws, &parts_used, st, chosen == MXFP4_PATH_MFMA_GENERAL, epi);
         break;
     default:
         return fail(MXFP4_ERR_ARG, "unknown or unavailable path %d", chosen);
     }
     if (e != hipSuccess)
         return hip_fail(e, "product launch");
-    if (argmax) {
+    if (argmax && go) {
         e = verify ? launch_verify_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, verify->draft,
                                           argmax_out, max_out, verify->accept_out, st)
                    : launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
@@ -489,6 +496,60 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx, const void*
     }
     return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, workspace,
                     workspace_bytes, false, path, stream, nullptr, false, &epi);
+}
+
+// ---- a sequence of products in one call -----------------------------------------------------
+
+static int grouped_one(const mxfp4_gemm_desc& d, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (d.reserved != 0) {
+        g_err[0] = 0;
+        return fail(MXFP4_ERR_ARG, "reserved must be 0");
+    }
+    if (d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE)
+        return mxfp4_woq_gemm_fused(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.bias_bf16, d.act,
+                                    d.residual_bf16, d.ldr, d.y_bf16, d.ldy, workspace, workspace_bytes,
+                                    MXFP4_PATH_AUTO, stream);
+    return mxfp4_woq_gemm_ws(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.y_bf16, d.ldy, workspace,
+                             workspace_bytes, MXFP4_PATH_AUTO, stream);
+}
+
+size_t mxfp4_woq_gemm_grouped_workspace_bytes(const mxfp4_gemm_desc* descs, int64_t count)
+{
+    size_t need = 0;
+    if (!descs || count < 1 || count > (1 << 20))
+        return 0;
+    for (int64_t i = 0; i < count; ++i) {
+        const size_t b = mxfp4_woq_gemm_workspace_bytes(descs[i].M, descs[i].N, descs[i].K);
+        need = b > need ? b : need;
+    }
+    return need;
+}
+
+int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count, void* workspace, size_t workspace_bytes,
+                           void* stream)
+{
+    g_err[0] = 0;
+    if (count < 0 || count > (1 << 20))
+        return fail(MXFP4_ERR_SHAPE, "count=%lld out of range", (long long)count);
+    if (count == 0)
+        return MXFP4_OK;
+    if (!descs)
+        return fail(MXFP4_ERR_NULL, "descs is NULL");
+    // first pass: every check of the single calls and nothing launched; second pass: the launches
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int64_t i = 0; i < count; ++i) {
+            g_check_only = pass == 0;
+            const int rc = grouped_one(descs[i], workspace, workspace_bytes, stream);
+            g_check_only = false;
+            if (rc != MXFP4_OK) {
+                char text[sizeof g_err];
+                snprintf(text, sizeof text, "%s", g_err);
+                return fail(rc, "descriptor %lld: %s", (long long)i, text);
+            }
+        }
+    }
+    return MXFP4_OK;
 }
 
 int mxfp4_woq_gemm_tiled_fused(const void* x_bf16, int64_t M, int64_t ldx, const void* q_tiled,

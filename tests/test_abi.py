@@ -166,3 +166,48 @@ def test_e2m3_product_argument_checks():
     assert lib.mxfp4_e2m3_woq_gemm(P16, 1, 64, P16, P16, 8, 40, P16, 8, None) == 2           # K % 32
     assert lib.mxfp4_e2m3_woq_gemm(P16, 1, 4096, P16, P16, 1 << 20, 4096, P16, 8, None) == 2  # beyond 2 GiB
     assert lib.mxfp4_e2m3_dequant(P16, P16, 4, 64, None, 64, None) == 1
+
+
+def _desc(**kw):
+    d = binding.GemmDesc()
+    base = dict(x_bf16=P16.value, M=1, ldx=64, q_packed=P16.value, scales_e8m0=P16.value, N=8, K=64,
+                bias_bf16=None, residual_bf16=None, ldr=0, y_bf16=P16.value, ldy=8, act=0, reserved=0)
+    base.update(kw)
+    for name, v in base.items():
+        setattr(d, name, v)
+    return d
+
+
+def test_grouped_descriptor_matches_the_header():
+    # 12 eight-byte fields and two 32-bit ones, no padding
+    assert ctypes.sizeof(binding.GemmDesc) == 12 * 8 + 8
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    body = re.search(r"typedef struct mxfp4_gemm_desc \{(.*?)\} mxfp4_gemm_desc;", text, flags=re.S).group(1)
+    fields = re.findall(r"(\w+);", body)
+    assert fields == [name for name, _ in binding.GemmDesc._fields_]
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(K=40), 2),                          # K % 32
+    (dict(x_bf16=None), 1),
+    (dict(reserved=7), 6),
+    (dict(act=9), 6),
+    (dict(act=1, N=7, ldy=4), 2),             # the gate needs an even N
+    (dict(residual_bf16=P16.value, ldr=4), 2),
+])
+def test_grouped_argument_checks_name_the_descriptor(kw, code):
+    # (without a GPU a valid descriptor ends at the device query, so the bad one stands first)
+    lib = binding.load()
+    descs = (binding.GemmDesc * 2)(_desc(**kw), _desc())
+    assert lib.mxfp4_woq_gemm_grouped(descs, 2, None, 0, None) == code
+    assert lib.mxfp4_last_error().decode().startswith("descriptor 0: ")
+
+
+def test_grouped_trivial_cases():
+    lib = binding.load()
+    assert lib.mxfp4_woq_gemm_grouped(None, 0, None, 0, None) == 0
+    assert lib.mxfp4_woq_gemm_grouped(None, 2, None, 0, None) == 1
+    assert lib.mxfp4_woq_gemm_grouped(None, -1, None, 0, None) == 2
+    assert lib.mxfp4_woq_gemm_grouped_workspace_bytes(None, 3) == 0
+    descs = (binding.GemmDesc * 2)(_desc(M=16, N=4096, K=28672), _desc(M=1, N=4096, K=4096))
+    assert lib.mxfp4_woq_gemm_grouped_workspace_bytes(descs, 2) == lib.mxfp4_woq_gemm_workspace_bytes(16, 4096, 28672) > 0

@@ -1,0 +1,114 @@
+"""GPU checks of mxfp4_woq_gemm_grouped: a sequence of products in one call gives the bits of the
+single calls (and with them the oracle's product), in order on the stream, and launches nothing
+when a descriptor is invalid (arXiv 2503.13565, sections 3.1 and 3.4: a step is a fixed chain of
+contractions with fused operators around them)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_13565_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+from helpers import DEV, assert_cast_bit_exact, assert_gemm_close  # noqa: E402
+
+NONE, SWIGLU = binding.ACT_NONE, binding.ACT_SWIGLU
+
+
+def make_linear(n, k, seed):
+    w = synth.weights_student_t(n, k, seed=seed)
+    q, s, q_ref, s_ref = assert_cast_bit_exact(w)
+    return q, s, q_ref, s_ref
+
+
+def bf16_randn(shape, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(shape, generator=g) * scale).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("m", [1, 2, 4, 8, 16])
+def test_grouped_equals_single_calls_and_oracle(m):
+    # a small layer: qkv-like, o-like with residual, gate+up with the gate, down with bias and residual
+    h, f = 2048, 2816
+    shapes = [(3 * h, h), (h, h), (2 * f, h), (h, f)]
+    lins = [make_linear(n, k, 11000 + i) for i, (n, k) in enumerate(shapes)]
+    xs = [synth.activations_outlier_channels(m, k, seed=11100 + i + m) for i, (_, k) in enumerate(shapes)]
+    res = bf16_randn((m, h), 5, 0.5)
+    bias = bf16_randn((h,), 6, 0.5)
+    xg = [x.to(DEV) for x in xs]
+    items = [
+        dict(x=xg[0], q=lins[0][0], s=lins[0][1]),
+        dict(x=xg[1], q=lins[1][0], s=lins[1][1], residual=res.to(DEV)),
+        dict(x=xg[2], q=lins[2][0], s=lins[2][1], act=SWIGLU),
+        dict(x=xg[3], q=lins[3][0], s=lins[3][1], bias=bias.to(DEV), residual=res.to(DEV)),
+    ]
+    group = binding.GemmGroup(items)
+    group.run()
+    torch.cuda.synchronize()
+    ws = group.workspace
+    for i, it in enumerate(items):
+        if len(it) == 3:
+            single = binding.mxfp4_woq_gemm(it["x"], it["q"], it["s"], workspace=ws)
+        else:
+            single = binding.mxfp4_woq_gemm_fused(it["x"], it["q"], it["s"], bias=it.get("bias"),
+                                                  act=it.get("act", NONE), residual=it.get("residual"), workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(group.ys[i].view(torch.int16), single.view(torch.int16)), "descriptor %d M=%d" % (i, m)
+        y_ref, a_ref = oracle.woq_gemm(synth.to_bits(xs[i]), lins[i][2], lins[i][3])
+        out_ref, a_out = oracle.epilogue(
+            y_ref, a_ref, synth.to_bits(bias) if "bias" in it else None,
+            synth.to_bits(res) if "residual" in it else None, it.get("act", NONE))
+        assert_gemm_close(group.ys[i], out_ref, a_out, "grouped descriptor %d M=%d" % (i, m))
+
+
+def test_grouped_chain_reads_what_an_earlier_descriptor_wrote():
+    # y0 = x W0^T, y1 = y0 W1^T in one call; the second product's input is the first one's output
+    m, h = 4, 2048
+    l0, l1 = make_linear(h, h, 11200), make_linear(h, h, 11201)
+    x = synth.activations_outlier_channels(m, h, seed=11210)
+    y0 = torch.zeros((m, h), dtype=torch.bfloat16, device=DEV)
+    group = binding.GemmGroup([dict(x=x.to(DEV), q=l0[0], s=l0[1], y=y0), dict(x=y0, q=l1[0], s=l1[1])])
+    group.run()
+    group.run()                                       # a second run gives the same bits
+    torch.cuda.synchronize()
+    y0_ref, a0 = oracle.woq_gemm(synth.to_bits(x), l0[2], l0[3])
+    assert_gemm_close(group.ys[0], y0_ref, a0, "chain first")
+    y1_ref, a1 = oracle.woq_gemm(synth.to_bits(group.ys[0].cpu()), l1[2], l1[3])
+    assert_gemm_close(group.ys[1], y1_ref, a1, "chain second")
+
+
+def test_grouped_launches_nothing_when_a_descriptor_is_invalid():
+    m, h = 1, 2048
+    l0 = make_linear(h, h, 11300)
+    x = synth.activations_outlier_channels(m, h, seed=11310).to(DEV)
+    y = torch.full((m, h), 7.0, dtype=torch.bfloat16, device=DEV)
+    group = binding.GemmGroup([dict(x=x, q=l0[0], s=l0[1], y=y), dict(x=x, q=l0[0], s=l0[1])])
+    group._descs[1].K = 40                             # not a multiple of 32
+    with pytest.raises(binding.Mxfp4Error) as err:
+        group.run()
+    torch.cuda.synchronize()
+    assert err.value.code == 2 and "descriptor 1: " in str(err.value)
+    assert bool((y == 7.0).all())                      # the valid first product did not run either
+
+
+def test_grouped_in_a_graph_replays_identically():
+    m, h = 1, 4096
+    l0, l1 = make_linear(h, h, 11400), make_linear(h, h, 11401)
+    x = synth.activations_outlier_channels(m, h, seed=11410).to(DEV)
+    group = binding.GemmGroup([dict(x=x, q=l0[0], s=l0[1]), dict(x=x, q=l1[0], s=l1[1])])
+    group.run()
+    torch.cuda.synchronize()
+    eager = [y.clone() for y in group.ys]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            group.run()
+        for _ in range(3):
+            for y in group.ys:
+                y.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            for y, e in zip(group.ys, eager):
+                assert torch.equal(y.view(torch.int16), e.view(torch.int16))
