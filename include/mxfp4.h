@@ -216,13 +216,16 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx,
  * back to back (sections 3.1 and 3.4: one forward pass is a fixed chain of contractions), and a
  * host that issues them one call at a time spends longer per call than most of these kernels
  * run.  Equivalent to calling, for i = 0 .. count - 1 in this order on `stream`,
- * mxfp4_woq_gemm_ws (descriptor without bias, residual and act) or mxfp4_woq_gemm_fused
- * (otherwise) with path MXFP4_PATH_AUTO and the one workspace: same kernels, same bits.  A
- * descriptor may read what an earlier one wrote (the stream orders them).
+ * mxfp4_woq_gemm_ws (descriptor without bias, residual, act and argmax_out),
+ * mxfp4_woq_gemm_argmax (argmax_out given: the LM head at the end of the step; y, bias, residual
+ * must then be NULL and act MXFP4_ACT_NONE) or mxfp4_woq_gemm_fused (otherwise) with path
+ * MXFP4_PATH_AUTO and the one workspace: same kernels, same bits.  A descriptor may read what an
+ * earlier one wrote (the stream orders them).
  *   descs      HOST array of `count` descriptors, read during the call only; the fields have
  *              the meaning, layout and alignment rules of the arguments of the same name of
- *              mxfp4_woq_gemm_fused; `reserved` must be 0
- *   workspace  device scratch shared by all products, optional as in mxfp4_woq_gemm_ws;
+ *              mxfp4_woq_gemm_fused and mxfp4_woq_gemm_argmax; `reserved` must be 0
+ *   workspace  device scratch shared by all products: optional as in mxfp4_woq_gemm_ws when no
+ *              descriptor asks for the argmax, required as in mxfp4_woq_gemm_argmax otherwise;
  *              mxfp4_woq_gemm_grouped_workspace_bytes gives the size that serves every
  *              descriptor (the largest single need; 0 for a NULL or invalid array)
  * Every descriptor is checked before anything is launched: on an argument error nothing has
@@ -242,6 +245,8 @@ typedef struct mxfp4_gemm_desc {
     int64_t ldr;
     void* y_bf16;
     int64_t ldy;
+    int32_t* argmax_out;
+    float* max_out;
     int32_t act;
     int32_t reserved;
 } mxfp4_gemm_desc;

@@ -41,6 +41,7 @@ class GemmDesc(ctypes.Structure):
                 ("q_packed", ctypes.c_void_p), ("scales_e8m0", ctypes.c_void_p), ("N", ctypes.c_int64),
                 ("K", ctypes.c_int64), ("bias_bf16", ctypes.c_void_p), ("residual_bf16", ctypes.c_void_p),
                 ("ldr", ctypes.c_int64), ("y_bf16", ctypes.c_void_p), ("ldy", ctypes.c_int64),
+                ("argmax_out", ctypes.c_void_p), ("max_out", ctypes.c_void_p),
                 ("act", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
@@ -487,8 +488,10 @@ def mxfp4_woq_gemm_fused(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, bias
 class GemmGroup:
     """A fixed sequence of products (``mxfp4_woq_gemm_grouped``): the descriptor array is built once,
     ``run()`` is one library call.  ``items``: dicts with ``x``, ``q``, ``s`` and optionally ``bias``,
-    ``act``, ``residual``, ``y`` (allocated when missing), as for ``mxfp4_woq_gemm_fused``.  The
-    tensors are kept alive by the group; ``ys`` lists the outputs in order."""
+    ``act``, ``residual``, ``y`` (allocated when missing), as for ``mxfp4_woq_gemm_fused``; or with
+    ``argmax=True`` (optionally ``out=(idx int32 [M], val float32 [M])``) for the fused pick, whose
+    entry in ``ys`` is the ``(idx, val)`` pair.  The tensors are kept alive by the group; ``ys`` lists
+    the outputs in order."""
 
     def __init__(self, items):
         self._keep, self.ys = [], []
@@ -498,6 +501,19 @@ class GemmGroup:
             x, q, s = it["x"], it["q"], it["s"]
             bias, residual, act = it.get("bias"), it.get("residual"), int(it.get("act", ACT_NONE))
             m, n, k, ldx = _gemm_shapes(x, q, s)
+            d.x_bf16, d.M, d.ldx = x.data_ptr(), m, ldx
+            d.q_packed, d.scales_e8m0, d.N, d.K = q.data_ptr(), s.data_ptr(), n, k
+            d.act, d.reserved = act, 0
+            if it.get("argmax"):
+                idx, val = it.get("out") or (torch.empty((m,), dtype=torch.int32, device=x.device),
+                                             torch.empty((m,), dtype=torch.float32, device=x.device))
+                if (idx.dtype != torch.int32 or val.dtype != torch.float32 or idx.shape != (m,) or val.shape != (m,)
+                        or not idx.is_contiguous() or not val.is_contiguous()):
+                    raise ValueError("out must be (int32 [M], float32 [M]), contiguous")
+                d.argmax_out, d.max_out = idx.data_ptr(), val.data_ptr()
+                self._keep.append((x, q, s, idx, val))
+                self.ys.append((idx, val))
+                continue
             c = n // 2 if act == ACT_SWIGLU else n
             y = it.get("y")
             if y is None:
@@ -509,13 +525,10 @@ class GemmGroup:
             if residual is not None and (residual.dtype != torch.bfloat16 or residual.shape != (m, c)
                                          or residual.stride(1) != 1):
                 raise ValueError("residual must be a BF16 tensor [M, %d] with a contiguous last dimension" % c)
-            d.x_bf16, d.M, d.ldx = x.data_ptr(), m, ldx
-            d.q_packed, d.scales_e8m0, d.N, d.K = q.data_ptr(), s.data_ptr(), n, k
             d.bias_bf16 = bias.data_ptr() if bias is not None else None
             d.residual_bf16 = residual.data_ptr() if residual is not None else None
             d.ldr = (residual.stride(0) if m > 1 else c) if residual is not None else 0
             d.y_bf16, d.ldy = y.data_ptr(), (y.stride(0) if m > 1 else c)
-            d.act, d.reserved = act, 0
             self._keep.append((x, q, s, bias, residual, y))
             self.ys.append(y)
         self.device = items[0]["x"].device if items else None

@@ -506,6 +506,14 @@ static int grouped_one(const mxfp4_gemm_desc& d, void* workspace, size_t workspa
         g_err[0] = 0;
         return fail(MXFP4_ERR_ARG, "reserved must be 0");
     }
+    if (d.argmax_out) {
+        if (d.y_bf16 || d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE) {
+            g_err[0] = 0;
+            return fail(MXFP4_ERR_ARG, "a descriptor with argmax_out takes no y, bias, residual or act");
+        }
+        return mxfp4_woq_gemm_argmax(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.argmax_out,
+                                     d.max_out, workspace, workspace_bytes, stream);
+    }
     if (d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE)
         return mxfp4_woq_gemm_fused(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.bias_bf16, d.act,
                                     d.residual_bf16, d.ldr, d.y_bf16, d.ldy, workspace, workspace_bytes,
@@ -520,7 +528,9 @@ size_t mxfp4_woq_gemm_grouped_workspace_bytes(const mxfp4_gemm_desc* descs, int6
     if (!descs || count < 1 || count > (1 << 20))
         return 0;
     for (int64_t i = 0; i < count; ++i) {
-        const size_t b = mxfp4_woq_gemm_workspace_bytes(descs[i].M, descs[i].N, descs[i].K);
+        const size_t b = descs[i].argmax_out
+                             ? mxfp4_woq_gemm_argmax_workspace_bytes(descs[i].M, descs[i].N, descs[i].K)
+                             : mxfp4_woq_gemm_workspace_bytes(descs[i].M, descs[i].N, descs[i].K);
         need = b > need ? b : need;
     }
     return need;

@@ -171,7 +171,8 @@ def test_e2m3_product_argument_checks():
 def _desc(**kw):
     d = binding.GemmDesc()
     base = dict(x_bf16=P16.value, M=1, ldx=64, q_packed=P16.value, scales_e8m0=P16.value, N=8, K=64,
-                bias_bf16=None, residual_bf16=None, ldr=0, y_bf16=P16.value, ldy=8, act=0, reserved=0)
+                bias_bf16=None, residual_bf16=None, ldr=0, y_bf16=P16.value, ldy=8, argmax_out=None, max_out=None,
+                act=0, reserved=0)
     base.update(kw)
     for name, v in base.items():
         setattr(d, name, v)
@@ -179,8 +180,8 @@ def _desc(**kw):
 
 
 def test_grouped_descriptor_matches_the_header():
-    # 12 eight-byte fields and two 32-bit ones, no padding
-    assert ctypes.sizeof(binding.GemmDesc) == 12 * 8 + 8
+    # 14 eight-byte fields and two 32-bit ones, no padding
+    assert ctypes.sizeof(binding.GemmDesc) == 14 * 8 + 8
     text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
     body = re.search(r"typedef struct mxfp4_gemm_desc \{(.*?)\} mxfp4_gemm_desc;", text, flags=re.S).group(1)
     fields = re.findall(r"(\w+);", body)
@@ -194,6 +195,9 @@ def test_grouped_descriptor_matches_the_header():
     (dict(act=9), 6),
     (dict(act=1, N=7, ldy=4), 2),             # the gate needs an even N
     (dict(residual_bf16=P16.value, ldr=4), 2),
+    (dict(argmax_out=P16.value), 6),          # the pick takes no y
+    (dict(argmax_out=P16.value, y_bf16=None, act=1), 6),
+    (dict(argmax_out=P16.value, y_bf16=None, K=40), 2),
 ])
 def test_grouped_argument_checks_name_the_descriptor(kw, code):
     # (without a GPU a valid descriptor ends at the device query, so the bad one stands first)

@@ -11,7 +11,7 @@ from paper_2503_13565_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
 
-from helpers import DEV, assert_cast_bit_exact, assert_gemm_close  # noqa: E402
+from helpers import DEV, assert_argmax_ok, assert_cast_bit_exact, assert_gemm_close  # noqa: E402
 
 NONE, SWIGLU = binding.ACT_NONE, binding.ACT_SWIGLU
 
@@ -60,6 +60,28 @@ def test_grouped_equals_single_calls_and_oracle(m):
             y_ref, a_ref, synth.to_bits(bias) if "bias" in it else None,
             synth.to_bits(res) if "residual" in it else None, it.get("act", NONE))
         assert_gemm_close(group.ys[i], out_ref, a_out, "grouped descriptor %d M=%d" % (i, m))
+
+
+@pytest.mark.parametrize("m", [1, 2, 5, 16])
+def test_grouped_step_ends_with_the_fused_pick(m):
+    # two products and the LM-head pick in one call, one workspace for all three
+    h, vocab = 2048, 8192
+    l0, head = make_linear(h, h, 11500), make_linear(vocab, h, 11501)
+    x = synth.activations_outlier_channels(m, h, seed=11510 + m)
+    xg = x.to(DEV)
+    group = binding.GemmGroup([dict(x=xg, q=l0[0], s=l0[1]), dict(x=xg, q=head[0], s=head[1], argmax=True),
+                               dict(x=xg, q=l0[0], s=l0[1], act=SWIGLU)])
+    group.run()
+    torch.cuda.synchronize()
+    idx, val = group.ys[1]
+    ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(m, vocab, h),), dtype=torch.uint8, device=DEV)
+    idx1, val1 = binding.mxfp4_woq_gemm_argmax(xg, head[0], head[1], workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx1) and torch.equal(val.view(torch.int32), val1.view(torch.int32))
+    y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), head[2], head[3])
+    assert_argmax_ok(idx, val, y_ref, a_ref, "grouped pick M=%d" % m)
+    single = binding.mxfp4_woq_gemm(xg, l0[0], l0[1])
+    assert torch.equal(group.ys[0].view(torch.int16), single.view(torch.int16))
 
 
 def test_grouped_chain_reads_what_an_earlier_descriptor_wrote():
