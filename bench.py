@@ -278,20 +278,46 @@ def run_stack(args) -> int:
             ops.append(dict(name=name, n=n, k=k, q=q, s=s,
                             x=synth.activations_outlier_channels(m, k, seed=seed + 8, device=dev),
                             y=torch.empty((m, n), dtype=torch.bfloat16, device=dev)))
+    # one split-K scratch buffer serves every linear: the calls of a step run one after the other
+    sk_bytes = max(binding.mxfp4_woq_gemm_workspace_bytes(m, t["n"], t["k"]) for t in ops[:-1])
+    sk = torch.empty((sk_bytes,), dtype=torch.uint8, device=dev) if sk_bytes else None
+    n_tiled = 0
+    if args.tiled:
+        # a pure verifier keeps only the tile-major copy of a linear
+        for t in ops[:-1]:
+            tw = binding.mxfp4_tile_repack(t["q"], t["s"])
+            try:
+                binding.mxfp4_woq_gemm_tiled(t["x"], tw, y=t["y"], workspace=sk)
+            except binding.Mxfp4Error:
+                continue
+            t["tw"], t["q"], t["s"] = tw, None, None
+            n_tiled += 1
+        torch.cuda.synchronize()
     head = ops[-1]
     head["idx"] = torch.empty((m,), dtype=torch.int32, device=dev)
     head["val"] = torch.empty((m,), dtype=torch.float32, device=dev)
     ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(m, head["n"], head["k"]),),
                      dtype=torch.uint8, device=dev)
-
-    # one split-K scratch buffer serves every linear: the calls of a step run one after the other
-    sk_bytes = max(binding.mxfp4_woq_gemm_workspace_bytes(m, t["n"], t["k"]) for t in ops[:-1])
-    sk = torch.empty((sk_bytes,), dtype=torch.uint8, device=dev) if sk_bytes else None
+    if args.tiled:
+        tw = binding.mxfp4_tile_repack(head["q"], head["s"])
+        try:
+            binding.mxfp4_woq_gemm_tiled_argmax(head["x"], tw, workspace=ws, out=(head["idx"], head["val"]))
+            head["tw"], head["q"], head["s"] = tw, None, None
+            n_tiled += 1
+        except binding.Mxfp4Error:
+            pass
+        torch.cuda.synchronize()
 
     def step(_lin=None, _ws=None):
         for t in ops[:-1]:
-            binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"], workspace=sk)
-        binding.mxfp4_woq_gemm_argmax(head["x"], head["q"], head["s"], workspace=ws, out=(head["idx"], head["val"]))
+            if "tw" in t:
+                binding.mxfp4_woq_gemm_tiled(t["x"], t["tw"], y=t["y"], workspace=sk)
+            else:
+                binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"], workspace=sk)
+        if "tw" in head:
+            binding.mxfp4_woq_gemm_tiled_argmax(head["x"], head["tw"], workspace=ws, out=(head["idx"], head["val"]))
+        else:
+            binding.mxfp4_woq_gemm_argmax(head["x"], head["q"], head["s"], workspace=ws, out=(head["idx"], head["val"]))
 
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
@@ -304,20 +330,24 @@ def run_stack(args) -> int:
     graph_ms_per_step = timed(run, steps, stream) / steps
     plain_ms = timed(runner(None, step, [None], ws), max(1, steps // 2), stream) / max(1, steps // 2)
     # the same launches issued by one library call per step (the host loop is the library's)
-    group = binding.GemmGroup([dict(x=t["x"], q=t["q"], s=t["s"], y=t["y"]) for t in ops[:-1]] +
-                              [dict(x=head["x"], q=head["q"], s=head["s"], argmax=True, out=(head["idx"], head["val"]))])
+    grouped_ms = float("inf")
+    if not n_tiled:                                      # the grouped call takes the canonical tensors
+        group = binding.GemmGroup([dict(x=t["x"], q=t["q"], s=t["s"], y=t["y"]) for t in ops[:-1]] +
+                                  [dict(x=head["x"], q=head["q"], s=head["s"], argmax=True,
+                                        out=(head["idx"], head["val"]))])
 
-    def step_grouped(_lin=None, _ws=None):
-        group.run()
+        def step_grouped(_lin=None, _ws=None):
+            group.run()
 
-    timed(runner(None, step_grouped, [None], ws), 1, stream)
-    grouped_ms = timed(runner(None, step_grouped, [None], ws), steps, stream) / steps
+        timed(runner(None, step_grouped, [None], ws), 1, stream)
+        grouped_ms = timed(runner(None, step_grouped, [None], ws), steps, stream) / steps
     # the headline is the faster of the two ways to issue the same kernels, named in config.launch
     launch = "hip graph replay" if graph is not None else "stream launches"
     ms_per_step = graph_ms_per_step
     if grouped_ms < graph_ms_per_step:
         launch, ms_per_step = "stream launches from one grouped library call per step", grouped_ms
     step_bytes = sum(algorithmic_bytes(m, t["n"], t["k"]) for t in ops)
+    step_weight_bytes = sum(t["n"] * t["k"] * 0.53125 for t in ops)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps,
@@ -325,13 +355,12 @@ def run_stack(args) -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d layers x (qkv, o, gate_up, down) + lm_head with argmax, M=%d, "
                                "%.2f GB of MXFP4 resident, %d launches per step"
-                               % (shape.name, layers, m, sum(t["q"].numel() + t["s"].numel() for t in ops) / 1e9,
-                                  len(ops) + 1),
-                   "M": m, "launch": launch},
+                               % (shape.name, layers, m, step_weight_bytes / 1e9, len(ops) + 1),
+                   "M": m, "launch": launch, "linears_on_tile_major_weights": n_tiled},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "us_per_step": round(ms_per_step * 1e3, 2), "us_per_step_graph_replay": round(graph_ms_per_step * 1e3, 2),
         "us_per_step_plain_launches": round(plain_ms * 1e3, 2),
-        "us_per_step_grouped_call": round(grouped_ms * 1e3, 2),
+        "us_per_step_grouped_call": round(grouped_ms * 1e3, 2) if n_tiled == 0 else None,
         "bytes_per_step": step_bytes,
         "tflops": round(2.0 * m * sum(t["n"] * t["k"] for t in ops) / (ms_per_step * 1e-3) / 1e12, 3),
         "direct_cast_GBps": round(cast_bytes / (cast_ms * 1e-3) / 1e9, 1) if cast_ms > 0 else None,
@@ -358,6 +387,8 @@ def main() -> int:
                     help="decode7b (default): the five 7B decode linears over rotating weight sets; "
                          "stack7b / stack70b: the whole linear-only decode step of a resident weight stack")
     ap.add_argument("--layers", type=int, default=0, help="stack workloads: layers to build (0 = the model's)")
+    ap.add_argument("--tiled", action="store_true",
+                    help="stack workloads: verification passes on the tile-major copy of the weights where it can run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: this build has no multi-GPU path (the linears shard by "

@@ -333,10 +333,14 @@ int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
  *           [tile][item = ceil(K/512)][row i][16 scale bytes of blocks 16 item ..] (bytes past K,
  *           rows past N: 0x7F)
  * K % 128 == 0.  The products below take the tile-major pair in place of (q_packed, scales_e8m0)
- * and are otherwise mxfp4_woq_gemm, mxfp4_woq_gemm_argmax and mxfp4_woq_gemm_verify; they return
- * MXFP4_ERR_ARG when the activation rows of a pass (min(M, 16) x K BF16) do not fit the LDS of a
- * compute unit next to 8 KB: such shapes go through the canonical tensors.  Any M >= 1 works
- * (single rows too, but the decode kernels on the canonical tensors are faster there).
+ * and are otherwise mxfp4_woq_gemm, mxfp4_woq_gemm_ws, mxfp4_woq_gemm_argmax and
+ * mxfp4_woq_gemm_verify.  When the activation rows of a pass (min(M, 16) x K BF16) do not fit the
+ * LDS of a compute unit next to 8 KB, K is split through the workspace as in mxfp4_woq_gemm_ws
+ * (mxfp4_woq_gemm_workspace_bytes(M, N, K) bytes for mxfp4_woq_gemm_tiled_ws; the argmax and
+ * verify workspaces of mxfp4_woq_gemm_argmax_workspace_bytes include them); a call without one
+ * (mxfp4_woq_gemm_tiled, a NULL or short workspace) returns MXFP4_ERR_ARG for such a shape, which
+ * then goes through the canonical tensors.  Any M >= 1 works (single rows too, but the decode
+ * kernels on the canonical tensors are faster there).
  */
 size_t mxfp4_tile_repack_q_bytes(int64_t N, int64_t K);
 size_t mxfp4_tile_repack_s_bytes(int64_t N, int64_t K);
@@ -345,6 +349,10 @@ int mxfp4_tile_repack(const void* q_packed, const void* scales_e8m0, int64_t N, 
 int mxfp4_woq_gemm_tiled(const void* x_bf16, int64_t M, int64_t ldx,
                          const void* q_tiled, const void* s_tiled, int64_t N, int64_t K,
                          void* y_bf16, int64_t ldy, void* stream);
+int mxfp4_woq_gemm_tiled_ws(const void* x_bf16, int64_t M, int64_t ldx,
+                            const void* q_tiled, const void* s_tiled, int64_t N, int64_t K,
+                            void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                            void* stream);
 int mxfp4_woq_gemm_tiled_argmax(const void* x_bf16, int64_t M, int64_t ldx,
                                 const void* q_tiled, const void* s_tiled, int64_t N, int64_t K,
                                 int32_t* argmax_out, float* max_out,

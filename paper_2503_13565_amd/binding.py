@@ -28,6 +28,7 @@ EXPORTS = [
     "mxfp4_e2m3_direct_cast", "mxfp4_e2m3_direct_cast_bits", "mxfp4_e2m3_dequant", "mxfp4_e2m3_woq_gemm",
     "mxfp4_e2m3_woq_gemm_argmax",
     "mxfp4_tile_repack_q_bytes", "mxfp4_tile_repack_s_bytes", "mxfp4_tile_repack", "mxfp4_woq_gemm_tiled",
+    "mxfp4_woq_gemm_tiled_ws",
     "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify", "mxfp4_woq_gemm_tiled_fused",
     "mxfp4_diag_stream_read", "mxfp4_diag_stream_copy", "mxfp4_last_error", "mxfp4_version",
 ]
@@ -115,6 +116,8 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_tile_repack.restype = i32
     lib.mxfp4_woq_gemm_tiled.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
     lib.mxfp4_woq_gemm_tiled.restype = i32
+    lib.mxfp4_woq_gemm_tiled_ws.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.mxfp4_woq_gemm_tiled_ws.restype = i32
     lib.mxfp4_woq_gemm_tiled_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     lib.mxfp4_woq_gemm_tiled_argmax.restype = i32
     lib.mxfp4_woq_gemm_tiled_verify.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, sz, vp]
@@ -571,13 +574,21 @@ def _tiled_shapes(x: torch.Tensor, w: TiledWeights):
     return m, w.n, w.k, (x.stride(0) if m > 1 else w.k)
 
 
-def mxfp4_woq_gemm_tiled(x: torch.Tensor, w: TiledWeights, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+def mxfp4_woq_gemm_tiled(x: torch.Tensor, w: TiledWeights, y: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The product on the tile-major copy; with ``workspace`` (uint8, ``mxfp4_woq_gemm_workspace_bytes``)
+    through ``mxfp4_woq_gemm_tiled_ws``, which also takes the shapes that need K split."""
     m, n, k, ldx = _tiled_shapes(x, w)
     if y is None:
         y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
     ldy = y.stride(0) if m > 1 else n
     with torch.cuda.device(x.device):
-        _check(load().mxfp4_woq_gemm_tiled(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(y), ldy, _stream()))
+        if workspace is None:
+            _check(load().mxfp4_woq_gemm_tiled(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(y), ldy, _stream()))
+        else:
+            _check(load().mxfp4_woq_gemm_tiled_ws(_ptr(x), m, ldx, _ptr(w.q), _ptr(w.s), n, k, _ptr(y), ldy,
+                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                 _stream()))
     return y
 
 

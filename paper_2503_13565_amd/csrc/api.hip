@@ -215,12 +215,18 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
     const bool go = !g_check_only;
     switch (chosen) {
     case -1:
-        if (!mfma_tile_can_run(a, dev))
+        if (mfma_tile_can_run(a, dev)) {
+            if (go)
+                e = launch_mfma_tile(a, dev, &parts_used, st, true, epi);
+        } else if (splitk_ws && mfma_tiled_split_can_run(a, dev)) {
+            if (go)
+                e = launch_mfma(a, dev, splitk_ws, &parts_used, st, false, epi, true);
+        } else {
             return fail(MXFP4_ERR_ARG, "the tile-major product needs a pass's activation rows (%lld x K=%lld) to fit "
-                                       "the LDS; use the canonical tensors for this shape",
+                                       "the LDS, or a workspace of mxfp4_woq_gemm_workspace_bytes to split K; "
+                                       "else use the canonical tensors for this shape",
                         (long long)(M > 16 ? 16 : M), (long long)K);
-        if (go)
-            e = launch_mfma_tile(a, dev, &parts_used, st, true, epi);
+        }
         break;
     case MXFP4_PATH_VALU_BITS:
     case MXFP4_PATH_VALU_CVT:
@@ -977,6 +983,18 @@ int mxfp4_woq_gemm_tiled(const void* x_bf16, int64_t M, int64_t ldx, const void*
 {
     return run_gemm(x_bf16, M, ldx, q_tiled, s_tiled, N, K, y_bf16, ldy, nullptr, nullptr, nullptr, 0, false,
                     MXFP4_PATH_AUTO, stream, nullptr, true);
+}
+
+int mxfp4_woq_gemm_tiled_ws(const void* x_bf16, int64_t M, int64_t ldx, const void* q_tiled, const void* s_tiled,
+                            int64_t N, int64_t K, void* y_bf16, int64_t ldy, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if (workspace && !aligned(workspace, 8)) {
+        g_err[0] = 0;
+        return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
+    }
+    return run_gemm(x_bf16, M, ldx, q_tiled, s_tiled, N, K, y_bf16, ldy, nullptr, nullptr, workspace,
+                    workspace_bytes, false, MXFP4_PATH_AUTO, stream, nullptr, true);
 }
 
 int mxfp4_woq_gemm_tiled_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void* q_tiled,

@@ -82,8 +82,13 @@ hipError_t launch_e2m3_dequant(const void* q6, const void* s, int64_t n_rows, in
 // mfma_can_run: K % 128 == 0 and four activation rows can run in one of these ways.
 bool mfma_can_run(const GemmArgs& a, const DeviceInfo& dev, bool have_splitk_ws);
 size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev);
+// `tiled`: a.q / a.s are the tile-major copy and the call is one that mfma_tiled_split_can_run
+// accepts (K split in space through the workspace; the whole-K tile-major passes go to
+// launch_mfma_tile directly).
 hipError_t launch_mfma(const GemmArgs& a, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
-                       hipStream_t stream, bool general_only = false, const Epilogue* epi = nullptr);
+                       hipStream_t stream, bool general_only = false, const Epilogue* epi = nullptr,
+                       bool tiled = false);
+bool mfma_tiled_split_can_run(const GemmArgs& a, const DeviceInfo& dev);
 
 // The same tiles in a leaner kernel for passes whose activation rows fit the LDS whole (no K
 // split); launch_mfma uses it whenever it can run unless told `general_only` (or
@@ -96,7 +101,7 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
 // FP32 partial products to ws = float [phases][M][N] (mfma.hip's finish kernel adds them).
 bool mfma_tile_split_fits(int phase_steps, int mp, const DeviceInfo& dev);
 hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases, int phase_steps, float* ws,
-                                  const DeviceInfo& dev, hipStream_t stream);
+                                  const DeviceInfo& dev, hipStream_t stream, bool tiled = false);
 
 // Tile-major copy of the weights for the tile kernel (`tiled`: a.q / a.s are that copy): what a
 // wave instruction loads is contiguous.  Sizes in bytes; K % 128 == 0.

@@ -686,14 +686,30 @@ size_t mfma_splitk_bytes(int m, int n, int k, const DeviceInfo& dev)
     return (size_t)phases * m * n * sizeof(float);
 }
 
-hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
-                       hipStream_t stream, bool general_only, const Epilogue* epi)
+// The tile-major copy with K split in space: the call has a workspace and a phase of the widest
+// pass fits the tile kernel.
+bool mfma_tiled_split_can_run(const GemmArgs& a, const DeviceInfo& dev)
 {
+    if (a.k % 128 != 0 || a.m < 1 || a.ldx > 0x7FFFFFFF)
+        return false;
+    size_t acc_bytes = 0;
+    if (split_mode(pass_width(a.m), a.n, a.k, dev, true, &acc_bytes) != kInSpace)
+        return false;
+    int steps = 0, phases = 1;
+    plan_phases(a.k, pass_width(a.m), dev, true, 0, &steps, &phases);
+    return mfma_tile_split_fits(steps, pass_width(a.m), dev);
+}
+
+hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* splitk_ws, int* parts_used,
+                       hipStream_t stream, bool general_only, const Epilogue* epi, bool tiled)
+{
+    if (tiled && (!splitk_ws || !mfma_tiled_split_can_run(a_in, dev)))
+        return hipErrorInvalidValue;
     static const bool legacy = [] {
         const char* e = getenv("MXFP4_MFMA_LEGACY");
         return e && atoi(e) != 0;
     }();
-    if (!legacy && !general_only && mfma_tile_can_run(a_in, dev))
+    if (!tiled && !legacy && !general_only && mfma_tile_can_run(a_in, dev))
         return launch_mfma_tile(a_in, dev, parts_used, stream, false, epi);
     if (!mfma_can_run(a_in, dev, splitk_ws != nullptr))
         return hipErrorInvalidValue;
@@ -706,14 +722,14 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
     if (mode == kInSpace)
         plan_phases(a.k, pass_width(a.m), dev, true, 0, &space_steps, &space_phases);
     // split in space: the leaner tile kernel takes the passes when a phase's activations fit it
-    const bool tile_split = mode == kInSpace && !legacy && !general_only && a.ldx <= 0x7FFFFFFF &&
-                            mfma_tile_split_fits(space_steps, pass_width(a.m), dev);
+    const bool tile_split = tiled || (mode == kInSpace && !legacy && !general_only && a.ldx <= 0x7FFFFFFF &&
+                                      mfma_tile_split_fits(space_steps, pass_width(a.m), dev));
     int first_blocks = 0;
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
         int mp = pass_width(left);
         if (tile_split) {
-            hipError_t e = launch_mfma_tile_split(a, m0, mp, space_phases, space_steps, splitk_ws, dev, stream);
+            hipError_t e = launch_mfma_tile_split(a, m0, mp, space_phases, space_steps, splitk_ws, dev, stream, tiled);
             if (e != hipSuccess)
                 return e;
             m0 += mp;

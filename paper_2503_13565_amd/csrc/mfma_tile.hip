@@ -11,7 +11,8 @@
 //     a workgroup use a row's scale line together, so the lines are fully used);
 //   - NW = 4 compute waves per workgroup split K in items of four steps, two or three items in
 //     flight per wave; one more wave, which never loads, sums the partial tiles, rounds and stores or tracks
-//     the argmax; two workgroups per compute unit when the LDS allows.
+//     the argmax; two workgroups per compute unit when the LDS allows, else (on the tile-major
+//     copy) one workgroup of NW = 8.
 //   - all conditions on the position are arithmetic masks: a branch around a load makes the
 //     compiler lose count of the loads in flight and wait for all of them.
 // Measured against mfma.hip on the 7B linears: 10 to 15 % faster at 4 rows, 15 to 30 % at 16.
@@ -33,14 +34,14 @@ namespace mxfp4 {
 namespace {
 
 constexpr int kOob = 0x7FFFFFF0;        // lane offset beyond any descriptor: the load returns zero
-constexpr int kTileNW = 4;              // compute waves per workgroup
+constexpr int kTileNW = 4;              // compute waves per workgroup (8 in the wide form)
 
 // LDS of a workgroup: activations [items * 4 steps][16 slots][MP] chunks of 16 bytes, then two
 // sets of NW partial tiles.
-size_t tile_lds_bytes(int k, int mp)
+size_t tile_lds_bytes(int k, int mp, int nw = kTileNW)
 {
     const int items = (k / 128 + 3) / 4;
-    return (size_t)items * 4 * 256 * mp + (size_t)2 * kTileNW * 1024;
+    return (size_t)items * 4 * 256 * mp + (size_t)2 * nw * 1024;
 }
 
 // MP: activation rows per pass (4, 8 or 16).  Kernel arguments are scalars so that they are
@@ -347,14 +348,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_fused_kernel(
 }
 
 // K split in space: the last preloaded argument is the number of steps per grid row.
-template <int MP, int NW, int D>
+template <int MP, int NW, int D, bool kTiled>
 __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_split_kernel(const uint16_t* __restrict__ x,
                                                                         const uint8_t* __restrict__ q,
                                                                         const uint8_t* __restrict__ s, void* out,
                                                                         int n, int k, int m, int m0, int ldx,
                                                                         int ldy, int parts, int phase_steps)
 {
-    mfma_tile_body<MP, NW, D, false>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{}, phase_steps);
+    mfma_tile_body<MP, NW, D, kTiled>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{}, phase_steps);
 }
 
 // Make the tile-major copy: one thread per 16 bytes of either output.  q_t unit (tile, T, lane =
@@ -391,12 +392,12 @@ __global__ __launch_bounds__(256) void tile_repack_kernel(const u32x4_t* __restr
     }
 }
 
-template <int MP, int D, bool kTiled>
+template <int MP, int D, bool kTiled, int NW = kTileNW>
 hipError_t launch_pass(const GemmArgs& a, int m0, int blocks, size_t lds, const DeviceInfo& dev,
                        hipStream_t stream, const Epilogue* epi)
 {
-    auto kern = mfma_tile_kernel<MP, kTileNW, D, kTiled>;
-    auto kern_fused = mfma_tile_fused_kernel<MP, kTileNW, D, kTiled>;
+    auto kern = mfma_tile_kernel<MP, NW, D, kTiled>;
+    auto kern_fused = mfma_tile_fused_kernel<MP, NW, D, kTiled>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -410,11 +411,11 @@ hipError_t launch_pass(const GemmArgs& a, int m0, int blocks, size_t lds, const 
     }
     const bool argmax = a.part_val != nullptr;
     if (epi)
-        hipLaunchKernelGGL(kern_fused, dim3(blocks), dim3((kTileNW + 1) * 64), lds, stream, a.x, a.q, a.s,
+        hipLaunchKernelGGL(kern_fused, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
                            static_cast<void*>(a.y), a.n, a.k, a.m, m0, (int)a.ldx, (int)a.ldy, 0, epi->act,
                            epi->bias, epi->residual, epi->ldr);
     else
-        hipLaunchKernelGGL(kern, dim3(blocks), dim3((kTileNW + 1) * 64), lds, stream, a.x, a.q, a.s,
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
                            argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, a.m, m0,
                            (int)a.ldx, (int)a.ldy, argmax ? a.parts : 0);
     return hipGetLastError();
@@ -454,17 +455,18 @@ hipError_t launch_tile_repack(const void* q, const void* s, int n, int k, void* 
 
 // One pass of `mp` rows from row m0 with K split over `phases` grid rows of `phase_steps` steps;
 // partial products go to ws = float [phases][M][N].  One workgroup per compute unit and phase
-// (its part of the activation rows fills most of the LDS), three items in flight per wave.
+// (its part of the activation rows fills most of the LDS): four compute waves with three items
+// in flight each from the row-major tensors, eight with two from the tile-major copy.
 bool mfma_tile_split_fits(int phase_steps, int mp, const DeviceInfo& dev)
 {
     return phase_steps % 4 == 0 && tile_lds_bytes(phase_steps * 128, mp) <= (size_t)dev.lds_bytes;
 }
 
-template <int MP>
+template <int MP, int NW, int D, bool kTiled>
 hipError_t launch_split_pass(const GemmArgs& a, int m0, int phases, int phase_steps, float* ws, int blocks,
                              size_t lds, const DeviceInfo& dev, hipStream_t stream)
 {
-    auto kern = mfma_tile_split_kernel<MP, kTileNW, 3>;
+    auto kern = mfma_tile_split_kernel<MP, NW, D, kTiled>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -473,23 +475,33 @@ hipError_t launch_split_pass(const GemmArgs& a, int m0, int phases, int phase_st
             return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks, phases), dim3((kTileNW + 1) * 64), lds, stream, a.x, a.q, a.s,
+    hipLaunchKernelGGL(kern, dim3(blocks, phases), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
                        static_cast<void*>(ws), a.n, a.k, a.m, m0, (int)a.ldx, (int)a.ldy, 0, phase_steps);
     return hipGetLastError();
 }
 
 hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases, int phase_steps, float* ws,
-                                  const DeviceInfo& dev, hipStream_t stream)
+                                  const DeviceInfo& dev, hipStream_t stream, bool tiled)
 {
     if (a.ldx > 0x7FFFFFFF || !mfma_tile_split_fits(phase_steps, mp, dev) || phases < 1)
         return hipErrorInvalidValue;
     const int n_tiles = (a.n + 15) / 16;
     int blocks = dev.cus / phases;
     blocks = blocks < 1 ? 1 : (blocks > n_tiles ? n_tiles : blocks);
+    if (tiled && tile_lds_bytes(phase_steps * 128, mp, 8) <= (size_t)dev.lds_bytes) {
+        const size_t lds = tile_lds_bytes(phase_steps * 128, mp, 8);
+        return mp == 16  ? launch_split_pass<16, 8, 2, true>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+               : mp == 8 ? launch_split_pass<8, 8, 2, true>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+                         : launch_split_pass<4, 8, 2, true>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
+    }
     const size_t lds = tile_lds_bytes(phase_steps * 128, mp);
-    return mp == 16  ? launch_split_pass<16>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
-           : mp == 8 ? launch_split_pass<8>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
-                     : launch_split_pass<4>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
+    if (tiled)
+        return mp == 16  ? launch_split_pass<16, kTileNW, 3, true>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+               : mp == 8 ? launch_split_pass<8, kTileNW, 3, true>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+                         : launch_split_pass<4, kTileNW, 3, true>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
+    return mp == 16  ? launch_split_pass<16, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+           : mp == 8 ? launch_split_pass<8, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
+                     : launch_split_pass<4, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
 }
 
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
@@ -505,13 +517,14 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
     int per_cu = !long_k && 2 * widest + 2048 <= (size_t)dev.lds_bytes ? 2 : 1;
     // three items in flight also for 16-row passes over many tiles (7B gate+up and LM head: 5 %)
     bool deep = long_k || (tile_pass_width(a.m) == 16 && n_tiles >= 4 * dev.cus);
-    // MXFP4_TILE_WGS (1, 2) and MXFP4_TILE_D (2, 3): measurement only
+    // MXFP4_TILE_WGS (1, 2), MXFP4_TILE_D (2, 3) and MXFP4_TILE_NW (4, 8): measurement only
     static const int env_wgs = [] { const char* e = getenv("MXFP4_TILE_WGS"); return e ? atoi(e) : 0; }();
     static const int env_d = [] { const char* e = getenv("MXFP4_TILE_D"); return e ? atoi(e) : 0; }();
     if (env_wgs == 1 || (env_wgs == 2 && 2 * widest + 2048 <= (size_t)dev.lds_bytes))
         per_cu = env_wgs;
     if (env_d == 2 || env_d == 3)
         deep = env_d == 3;
+    static const int env_nw = [] { const char* e = getenv("MXFP4_TILE_NW"); return e ? atoi(e) : 0; }();
     int blocks = dev.cus * per_cu;
     if (blocks > n_tiles)
         blocks = n_tiles;
@@ -521,16 +534,32 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
         *parts_used = blocks;                   // every pass uses the same grid: the partials line up
     for (int m0 = 0; m0 < a.m;) {
         const int mp = tile_pass_width(a.m - m0);
-        const size_t lds = tile_lds_bytes(a.k, mp);
+        // Wide form, eight compute waves with two items in flight each: with one workgroup per
+        // compute unit four waves sit alone on their SIMDs and nothing hides a wave's LDS and
+        // matrix-instruction latencies.  On the tile-major copy that is worth 3 to 18 % (7B at 16
+        // rows, 7B down projection at 4, the 70B shapes at 4 and 8); from the row-major tensors the
+        // half-line loads set the pace and it gains nothing.
+        bool wide = per_cu == 1 && tiled;
+        if (env_nw == 4 || env_nw == 8)
+            wide = env_nw == 8 && per_cu == 1;
+        wide = wide && tile_lds_bytes(a.k, mp, 8) <= (size_t)dev.lds_bytes;
+        const size_t lds = tile_lds_bytes(a.k, mp, wide ? 8 : kTileNW);
+        const bool deep_pass = env_d == 2 || env_d == 3 ? deep : deep && !wide;
         hipError_t e;
-#define MXFP4_TILE_CASE(D_, T_)                                                        \
-    (mp == 16  ? launch_pass<16, D_, T_>(a, m0, blocks, lds, dev, stream, epi)              \
-     : mp == 8 ? launch_pass<8, D_, T_>(a, m0, blocks, lds, dev, stream, epi)               \
-               : launch_pass<4, D_, T_>(a, m0, blocks, lds, dev, stream, epi))
-        if (tiled)
-            e = deep ? MXFP4_TILE_CASE(3, true) : MXFP4_TILE_CASE(2, true);
-        else
-            e = deep ? MXFP4_TILE_CASE(3, false) : MXFP4_TILE_CASE(2, false);
+#define MXFP4_TILE_CASE(D_, T_, NW_)                                                        \
+    (mp == 16  ? launch_pass<16, D_, T_, NW_>(a, m0, blocks, lds, dev, stream, epi)              \
+     : mp == 8 ? launch_pass<8, D_, T_, NW_>(a, m0, blocks, lds, dev, stream, epi)               \
+               : launch_pass<4, D_, T_, NW_>(a, m0, blocks, lds, dev, stream, epi))
+        if (wide) {
+            if (tiled)
+                e = deep_pass ? MXFP4_TILE_CASE(3, true, 8) : MXFP4_TILE_CASE(2, true, 8);
+            else
+                e = deep_pass ? MXFP4_TILE_CASE(3, false, 8) : MXFP4_TILE_CASE(2, false, 8);
+        } else if (tiled) {
+            e = deep_pass ? MXFP4_TILE_CASE(3, true, kTileNW) : MXFP4_TILE_CASE(2, true, kTileNW);
+        } else {
+            e = deep_pass ? MXFP4_TILE_CASE(3, false, kTileNW) : MXFP4_TILE_CASE(2, false, kTileNW);
+        }
 #undef MXFP4_TILE_CASE
         if (e != hipSuccess)
             return e;

@@ -134,3 +134,31 @@ def test_grouped_in_a_graph_replays_identically():
             torch.cuda.synchronize()
             for y, e in zip(group.ys, eager):
                 assert torch.equal(y.view(torch.int16), e.view(torch.int16))
+
+
+def test_grouped_decode_step_at_full_7b_sizes_equals_single_calls():
+    # the launch configuration the benchmark times: the five 7B linears at one row, the pick on the
+    # LM head, one call; the single calls are checked against the oracle at these sizes elsewhere
+    shape = synth.LLAMA_7B
+    g = torch.Generator(device=DEV).manual_seed(11600)
+    items, singles = [], []
+    for name, n, k in shape.linears():
+        q = torch.randint(0, 256, (n, k // 2), dtype=torch.uint8, device=DEV, generator=g)
+        s = torch.randint(112, 130, (n, k // 32), dtype=torch.uint8, device=DEV, generator=g)
+        x = synth.activations_outlier_channels(1, k, seed=11610 + n, device=DEV)
+        if name == "lm_head":
+            items.append(dict(x=x, q=q, s=s, argmax=True))
+            ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(1, n, k),), dtype=torch.uint8, device=DEV)
+            singles.append(binding.mxfp4_woq_gemm_argmax(x, q, s, workspace=ws))
+        else:
+            items.append(dict(x=x, q=q, s=s))
+            singles.append(binding.mxfp4_woq_gemm(x, q, s))
+    group = binding.GemmGroup(items)
+    for _ in range(2):
+        group.run()
+    torch.cuda.synchronize()
+    for y, ref in zip(group.ys, singles):
+        if isinstance(y, tuple):
+            assert torch.equal(y[0], ref[0]) and torch.equal(y[1].view(torch.int32), ref[1].view(torch.int32))
+        else:
+            assert torch.equal(y.view(torch.int16), ref.view(torch.int16))

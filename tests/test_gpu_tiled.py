@@ -45,7 +45,7 @@ def test_tile_repack_is_the_stated_permutation(n, k):
 
 
 @pytest.mark.parametrize("n,k", [(16, 128), (17, 256), (250, 11008), (1000, 4096), (48, 8192), (2050, 2048),
-                                 (31, 12288)])
+                                 (31, 12288), (4100, 11008), (530, 28672)])
 @pytest.mark.parametrize("m", [1, 3, 4, 5, 8, 16, 17, 33])
 def test_tiled_product_edge_shapes(n, k, m):
     w = synth.weights_student_t(n, k, seed=7000 + n + k)
@@ -55,13 +55,21 @@ def test_tiled_product_edge_shapes(n, k, m):
     xg = x.to(DEV)
     # the widest pass (4, 8 or 16 rows) keeps its rows, padded to whole items of 512 columns, in the LDS
     width = 16 if m > 8 else (8 if m > 4 else 4)
+    y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref)
+    ws_bytes = binding.mxfp4_woq_gemm_workspace_bytes(m, n, k)
     if (k + 511) // 512 * 1024 * width + 8192 > 160 * 1024:
+        # no workspace: refused; with one, K is split over grid rows
         with pytest.raises(binding.Mxfp4Error) as e:
             binding.mxfp4_woq_gemm_tiled(xg, tw)
         assert e.value.code == 6
-        return
-    y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref)
-    y = binding.mxfp4_woq_gemm_tiled(xg, tw)
+        assert ws_bytes > 0
+        ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=DEV)
+        y = binding.mxfp4_woq_gemm_tiled(xg, tw, workspace=ws)
+    else:
+        y = binding.mxfp4_woq_gemm_tiled(xg, tw)
+        if ws_bytes == 0:                               # a workspace changes nothing when K is not split
+            y2 = binding.mxfp4_woq_gemm_tiled(xg, tw, workspace=torch.empty((64,), dtype=torch.uint8, device=DEV))
+            assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
     torch.cuda.synchronize()
     assert_gemm_close(y, y_ref, a_ref, "tiled N=%d K=%d M=%d" % (n, k, m))
     idx, val = binding.mxfp4_woq_gemm_tiled_argmax(xg, tw)
