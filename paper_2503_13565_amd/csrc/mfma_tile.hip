@@ -517,10 +517,10 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
     int per_cu = !long_k && 2 * widest + 2048 <= (size_t)dev.lds_bytes ? 2 : 1;
     // three items in flight also for 16-row passes over many tiles (7B gate+up and LM head: 5 %)
     bool deep = long_k || (tile_pass_width(a.m) == 16 && n_tiles >= 4 * dev.cus);
-    // MXFP4_TILE_WGS (1, 2), MXFP4_TILE_D (2, 3) and MXFP4_TILE_NW (4, 8): measurement only
+    // MXFP4_TILE_WGS (1 to 4), MXFP4_TILE_D (2, 3) and MXFP4_TILE_NW (4, 8): measurement only
     static const int env_wgs = [] { const char* e = getenv("MXFP4_TILE_WGS"); return e ? atoi(e) : 0; }();
     static const int env_d = [] { const char* e = getenv("MXFP4_TILE_D"); return e ? atoi(e) : 0; }();
-    if (env_wgs == 1 || (env_wgs == 2 && 2 * widest + 2048 <= (size_t)dev.lds_bytes))
+    if (env_wgs >= 1 && env_wgs <= 4 && env_wgs * widest + 2048 <= (size_t)dev.lds_bytes)
         per_cu = env_wgs;
     if (env_d == 2 || env_d == 3)
         deep = env_d == 3;
