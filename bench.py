@@ -330,17 +330,17 @@ def run_stack(args) -> int:
     graph_ms_per_step = timed(run, steps, stream) / steps
     plain_ms = timed(runner(None, step, [None], ws), max(1, steps // 2), stream) / max(1, steps // 2)
     # the same launches issued by one library call per step (the host loop is the library's)
-    grouped_ms = float("inf")
-    if not n_tiled:                                      # the grouped call takes the canonical tensors
-        group = binding.GemmGroup([dict(x=t["x"], q=t["q"], s=t["s"], y=t["y"]) for t in ops[:-1]] +
-                                  [dict(x=head["x"], q=head["q"], s=head["s"], argmax=True,
-                                        out=(head["idx"], head["val"]))])
+    def weights_of(t):
+        return dict(w=t["tw"]) if "tw" in t else dict(q=t["q"], s=t["s"])
 
-        def step_grouped(_lin=None, _ws=None):
-            group.run()
+    group = binding.GemmGroup([dict(x=t["x"], y=t["y"], **weights_of(t)) for t in ops[:-1]] +
+                              [dict(x=head["x"], argmax=True, out=(head["idx"], head["val"]), **weights_of(head))])
 
-        timed(runner(None, step_grouped, [None], ws), 1, stream)
-        grouped_ms = timed(runner(None, step_grouped, [None], ws), steps, stream) / steps
+    def step_grouped(_lin=None, _ws=None):
+        group.run()
+
+    timed(runner(None, step_grouped, [None], ws), 1, stream)
+    grouped_ms = timed(runner(None, step_grouped, [None], ws), steps, stream) / steps
     # the headline is the faster of the two ways to issue the same kernels, named in config.launch
     launch = "hip graph replay" if graph is not None else "stream launches"
     ms_per_step = graph_ms_per_step
@@ -360,7 +360,7 @@ def run_stack(args) -> int:
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "us_per_step": round(ms_per_step * 1e3, 2), "us_per_step_graph_replay": round(graph_ms_per_step * 1e3, 2),
         "us_per_step_plain_launches": round(plain_ms * 1e3, 2),
-        "us_per_step_grouped_call": round(grouped_ms * 1e3, 2) if n_tiled == 0 else None,
+        "us_per_step_grouped_call": round(grouped_ms * 1e3, 2),
         "bytes_per_step": step_bytes,
         "tflops": round(2.0 * m * sum(t["n"] * t["k"] for t in ops) / (ms_per_step * 1e-3) / 1e12, 3),
         "direct_cast_GBps": round(cast_bytes / (cast_ms * 1e-3) / 1e9, 1) if cast_ms > 0 else None,

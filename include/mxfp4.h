@@ -223,7 +223,9 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx,
  * earlier one wrote (the stream orders them).
  *   descs      HOST array of `count` descriptors, read during the call only; the fields have
  *              the meaning, layout and alignment rules of the arguments of the same name of
- *              mxfp4_woq_gemm_fused and mxfp4_woq_gemm_argmax; `reserved` must be 0
+ *              mxfp4_woq_gemm_fused and mxfp4_woq_gemm_argmax; `flags` is 0 or MXFP4_DESC_TILED:
+ *              q_packed and scales_e8m0 are then the tile-major pair of mxfp4_tile_repack and the
+ *              product is the mxfp4_woq_gemm_tiled_* call of the same kind (other bits: error)
  *   workspace  device scratch shared by all products: optional as in mxfp4_woq_gemm_ws when no
  *              descriptor asks for the argmax, required as in mxfp4_woq_gemm_argmax otherwise;
  *              mxfp4_woq_gemm_grouped_workspace_bytes gives the size that serves every
@@ -248,8 +250,9 @@ typedef struct mxfp4_gemm_desc {
     int32_t* argmax_out;
     float* max_out;
     int32_t act;
-    int32_t reserved;
+    int32_t flags;
 } mxfp4_gemm_desc;
+enum { MXFP4_DESC_TILED = 1 };
 size_t mxfp4_woq_gemm_grouped_workspace_bytes(const mxfp4_gemm_desc* descs, int64_t count);
 int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count,
                            void* workspace, size_t workspace_bytes, void* stream);

@@ -43,7 +43,7 @@ class GemmDesc(ctypes.Structure):
                 ("K", ctypes.c_int64), ("bias_bf16", ctypes.c_void_p), ("residual_bf16", ctypes.c_void_p),
                 ("ldr", ctypes.c_int64), ("y_bf16", ctypes.c_void_p), ("ldy", ctypes.c_int64),
                 ("argmax_out", ctypes.c_void_p), ("max_out", ctypes.c_void_p),
-                ("act", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("act", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class Mxfp4Error(RuntimeError):
@@ -488,25 +488,36 @@ def mxfp4_woq_gemm_fused(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, bias
     return y
 
 
+DESC_TILED = 1
+
+
 class GemmGroup:
     """A fixed sequence of products (``mxfp4_woq_gemm_grouped``): the descriptor array is built once,
     ``run()`` is one library call.  ``items``: dicts with ``x``, ``q``, ``s`` and optionally ``bias``,
     ``act``, ``residual``, ``y`` (allocated when missing), as for ``mxfp4_woq_gemm_fused``; or with
     ``argmax=True`` (optionally ``out=(idx int32 [M], val float32 [M])``) for the fused pick, whose
     entry in ``ys`` is the ``(idx, val)`` pair.  The tensors are kept alive by the group; ``ys`` lists
-    the outputs in order."""
+    the outputs in order.  An item with ``w`` (a ``TiledWeights``) in place of ``q`` and ``s`` runs on
+    the tile-major copy."""
 
     def __init__(self, items):
         self._keep, self.ys = [], []
         self._descs = (GemmDesc * max(1, len(items)))()
         self.count = len(items)
         for d, it in zip(self._descs, items):
-            x, q, s = it["x"], it["q"], it["s"]
+            x = it["x"]
             bias, residual, act = it.get("bias"), it.get("residual"), int(it.get("act", ACT_NONE))
-            m, n, k, ldx = _gemm_shapes(x, q, s)
+            if "w" in it:                                  # TiledWeights in place of (q, s)
+                q, s = it["w"].q, it["w"].s
+                m, n, k, ldx = _tiled_shapes(x, it["w"])
+                d.flags = DESC_TILED
+            else:
+                q, s = it["q"], it["s"]
+                m, n, k, ldx = _gemm_shapes(x, q, s)
+                d.flags = 0
             d.x_bf16, d.M, d.ldx = x.data_ptr(), m, ldx
             d.q_packed, d.scales_e8m0, d.N, d.K = q.data_ptr(), s.data_ptr(), n, k
-            d.act, d.reserved = act, 0
+            d.act = act
             if it.get("argmax"):
                 idx, val = it.get("out") or (torch.empty((m,), dtype=torch.int32, device=x.device),
                                              torch.empty((m,), dtype=torch.float32, device=x.device))

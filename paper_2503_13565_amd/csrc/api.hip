@@ -508,17 +508,28 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx, const void*
 
 static int grouped_one(const mxfp4_gemm_desc& d, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (d.reserved != 0) {
+    if ((d.flags & ~MXFP4_DESC_TILED) != 0) {
         g_err[0] = 0;
-        return fail(MXFP4_ERR_ARG, "reserved must be 0");
+        return fail(MXFP4_ERR_ARG, "unknown flags %#x", (unsigned)d.flags);
     }
+    const bool tiled = (d.flags & MXFP4_DESC_TILED) != 0;
     if (d.argmax_out) {
         if (d.y_bf16 || d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE) {
             g_err[0] = 0;
             return fail(MXFP4_ERR_ARG, "a descriptor with argmax_out takes no y, bias, residual or act");
         }
+        if (tiled)
+            return mxfp4_woq_gemm_tiled_argmax(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K,
+                                               d.argmax_out, d.max_out, workspace, workspace_bytes, stream);
         return mxfp4_woq_gemm_argmax(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.argmax_out,
                                      d.max_out, workspace, workspace_bytes, stream);
+    }
+    if (tiled) {
+        if (d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE)
+            return mxfp4_woq_gemm_tiled_fused(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.bias_bf16,
+                                              d.act, d.residual_bf16, d.ldr, d.y_bf16, d.ldy, stream);
+        return mxfp4_woq_gemm_tiled_ws(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.y_bf16, d.ldy,
+                                       workspace, workspace_bytes, stream);
     }
     if (d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE)
         return mxfp4_woq_gemm_fused(d.x_bf16, d.M, d.ldx, d.q_packed, d.scales_e8m0, d.N, d.K, d.bias_bf16, d.act,

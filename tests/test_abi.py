@@ -172,7 +172,7 @@ def _desc(**kw):
     d = binding.GemmDesc()
     base = dict(x_bf16=P16.value, M=1, ldx=64, q_packed=P16.value, scales_e8m0=P16.value, N=8, K=64,
                 bias_bf16=None, residual_bf16=None, ldr=0, y_bf16=P16.value, ldy=8, argmax_out=None, max_out=None,
-                act=0, reserved=0)
+                act=0, flags=0)
     base.update(kw)
     for name, v in base.items():
         setattr(d, name, v)
@@ -191,7 +191,7 @@ def test_grouped_descriptor_matches_the_header():
 @pytest.mark.parametrize("kw,code", [
     (dict(K=40), 2),                          # K % 32
     (dict(x_bf16=None), 1),
-    (dict(reserved=7), 6),
+    (dict(flags=6), 6),
     (dict(act=9), 6),
     (dict(act=1, N=7, ldy=4), 2),             # the gate needs an even N
     (dict(residual_bf16=P16.value, ldr=4), 2),

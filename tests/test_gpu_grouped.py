@@ -162,3 +162,32 @@ def test_grouped_decode_step_at_full_7b_sizes_equals_single_calls():
             assert torch.equal(y[0], ref[0]) and torch.equal(y[1].view(torch.int32), ref[1].view(torch.int32))
         else:
             assert torch.equal(y.view(torch.int16), ref.view(torch.int16))
+
+
+@pytest.mark.parametrize("m", [3, 8, 16])
+def test_grouped_on_tile_major_weights(m):
+    # plain (whole K and K split through the workspace), fused and the pick, all on the tile-major copy
+    h, f, vocab = 2048, 11008, 4096
+    shapes = [(2 * h, h), (h, f), (2 * h, h), (vocab, h)]
+    lins = [make_linear(n, k, 11700 + i) for i, (n, k) in enumerate(shapes)]
+    tws = [binding.mxfp4_tile_repack(l[0], l[1]) for l in lins]
+    xs = [synth.activations_outlier_channels(m, k, seed=11710 + i + m) for i, (_, k) in enumerate(shapes)]
+    xg = [x.to(DEV) for x in xs]
+    res = bf16_randn((m, h), 7, 0.5)
+    group = binding.GemmGroup([
+        dict(x=xg[0], w=tws[0]),
+        dict(x=xg[1], w=tws[1]),
+        dict(x=xg[2], w=tws[2], act=SWIGLU, residual=res.to(DEV)),
+        dict(x=xg[3], w=tws[3], argmax=True),
+    ])
+    group.run()
+    torch.cuda.synchronize()
+    refs = [oracle.woq_gemm(synth.to_bits(xs[i]), lins[i][2], lins[i][3]) for i in range(4)]
+    assert_gemm_close(group.ys[0], refs[0][0], refs[0][1], "tiled grouped plain M=%d" % m)
+    assert_gemm_close(group.ys[1], refs[1][0], refs[1][1], "tiled grouped long K M=%d" % m)
+    out_ref, a_out = oracle.epilogue(refs[2][0], refs[2][1], None, synth.to_bits(res), SWIGLU)
+    assert_gemm_close(group.ys[2], out_ref, a_out, "tiled grouped fused M=%d" % m)
+    assert_argmax_ok(group.ys[3][0], group.ys[3][1], refs[3][0], refs[3][1], "tiled grouped pick M=%d" % m)
+    single = binding.mxfp4_woq_gemm_tiled(xg[1], tws[1], workspace=group.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(group.ys[1].view(torch.int16), single.view(torch.int16))
