@@ -46,8 +46,12 @@ struct RegArgs {
 // Epi: NoEpilogue, or Epilogue for the fused form (bias, gate, residual at the flush).  The gate
 // needs a pair of rows 2c, 2c + 1 in neighbouring lanes of the held outputs: with R = 2 a group is
 // a pair; with R = 1 the counter deals pairs and a wave takes the pair's rows in two trips.
-// kBits: 4 (E2M1 nibbles, 16 bytes per block) or 6 (E2M3 codes, 24 bytes per block: the lane loads
-// 16 + 8 bytes and one v_cvt_scalef32_pk32_bf16_fp6 decodes the whole block).
+// kBits: 4 (E2M1 nibbles, 16 bytes per block) or 6 (E2M3 codes, 24 bytes per block; one
+// v_cvt_scalef32_pk32_bf16_fp6 decodes the whole block).  A wave step of the 6-bit form is 1536
+// bytes of a row.  Loading a lane's own 24 bytes directly (16 + 8 at a stride of 24) leaves every
+// wave instruction with misaligned, gapped accesses and costs 16 to 21 % of the kernel's time;
+// instead the wave loads the 1536 bytes lane-contiguous (16 bytes per lane, then 8), passes them
+// through 1536 bytes of LDS of its own and reads back bytes [24 lane, 24 lane + 24).
 typedef __attribute__((ext_vector_type(32))) __bf16 bf16x32_t;
 typedef __attribute__((ext_vector_type(6))) unsigned int u32x6_t;
 typedef __attribute__((ext_vector_type(16))) unsigned int u32x16_t;
@@ -91,6 +95,8 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     constexpr bool kXLds = MT * STEPS >= 6;
     const int xrow = kXLds ? STEPS * 64 : nblk;              // chunks per (activation row, j)
     int* ctr = reinterpret_cast<int*>(smem + (size_t)MT * 4 * xrow * 16);
+    // 6-bit form: R * 1536 bytes per wave behind the counter's 64
+    uint8_t* stage = smem + (size_t)MT * 4 * xrow * 16 + 64 + (size_t)wave * (R * 1536);
     const int q_row_bytes = (a.k >> 5) * kBlkBytes;
     const bool argmax = a.parts > 0;
     const int G = gridDim.x, b = blockIdx.x;
@@ -136,18 +142,28 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     // A step always issues the same loads so that the in-order load counter can be waited on
     // exactly; past the end (of the groups, or of a ragged K) the lane offset is pushed out of the
     // descriptor's range: such loads touch no memory and return zero.
-    auto issue = [&](int grp, int t, int d) {
+    // (nb: the blocks per row again, for the 6-bit form, which hands in a copy the compiler cannot
+    // see through once per trip: two lane masks per step kept in registers across the whole row
+    // loop made every long-K instance spill)
+    auto issue = [&](int grp, int t, int d, int nb) {
         const bool live = grp < n_groups;
         const bool vb = !kRagged || t * 64 + lane < nblk;
         const int g0 = live ? grp * R : 0;
+        // 6-bit form: the step's valid bytes are 24 per block left in the row (a multiple of 96)
+        const int valid6 = kRagged ? 24 * max(0, min(64, nb - t * 64)) : 1536;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int row = min(g0 + r, a.n - 1);                    // odd N: the last row twice
-            bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(rq, (live && vb) ? lane * kBlkBytes : 0x7FFFFFF0,
-                                                             row * q_row_bytes + t * (64 * kBlkBytes), 2);
-            if constexpr (kBits == 6)
-                bq2[d][r] = __builtin_amdgcn_raw_buffer_load_b64(rq, (live && vb) ? lane * 24 + 16 : 0x7FFFFFF0,
-                                                                row * q_row_bytes + t * 1536, 2);
+            if constexpr (kBits == 6) {
+                bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rq, (live && lane * 16 < valid6) ? lane * 16 : 0x7FFFFFF0, row * q_row_bytes + t * 1536, 2);
+                bq2[d][r] = __builtin_amdgcn_raw_buffer_load_b64(
+                    rq, (live && 1024 + lane * 8 < valid6) ? 1024 + lane * 8 : 0x7FFFFFF0,
+                    row * q_row_bytes + t * 1536, 2);
+            } else {
+                bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(rq, (live && vb) ? lane * kBlkBytes : 0x7FFFFFF0,
+                                                                 row * q_row_bytes + t * (64 * kBlkBytes), 2);
+            }
         }
         // scale bytes of the step: 16 dwords per row; lane l loads dword l % 16 of row (l / 16) % R
         const int row = min(g0 + srow, a.n - 1);
@@ -157,7 +173,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     int grp = row_of(wave);
 #pragma unroll
     for (int d = 0; d < D; ++d)
-        issue(grp, d, d);
+        issue(grp, d, d, nblk);
 
 #pragma unroll
     for (int m = 0; m < MT; ++m)
@@ -259,6 +275,9 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
             i_next2 = fetch();                      // consumed one trip later: its latency is hidden
         }
         second = !second;
+        int nb = nblk;
+        if constexpr (kBits == 6)
+            asm volatile("" : "+s"(nb));
         uint32_t bias_l[R], res_l[R][MT];
         if constexpr (kEpi) {
 #pragma unroll
@@ -297,9 +316,20 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                     sc = (t * 64 + lane < nblk) ? sc : 1.0f;         // no NaN from a neighbour's scale byte
                 u32x16_t w6 = {};
                 if constexpr (kBits == 6) {
-                    const u32x4_t lo = bq[d][r];
-                    const u32x2_t hi = bq2[d][r];
-                    const u32x6_t packed = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1]};
+                    // lane-contiguous bytes -> the lane's own block.  The buffer is the wave's alone
+                    // and a wave's LDS instructions execute in order: no barrier, only the compiler
+                    // must keep the order.
+                    uint8_t* st = stage + r * 1536;
+                    reinterpret_cast<u32x4_t*>(st)[lane] = bq[d][r];
+                    reinterpret_cast<u32x2_t*>(st + 1024)[lane] = bq2[d][r];
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    const u32x2_t* rd = reinterpret_cast<const u32x2_t*>(st + lane * 24);
+                    const u32x2_t p0 = rd[0], p1 = rd[1], p2 = rd[2];
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    const u32x6_t packed = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1]};
                     w6 = __builtin_bit_cast(u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(packed, sc));
                 }
 #pragma unroll
@@ -333,9 +363,9 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
             }
             const int tn = t + D;
             if (tn < STEPS)
-                issue(grp, tn, d);
+                issue(grp, tn, d, nb);
             else
-                issue(grp_n, tn - STEPS, d);
+                issue(grp_n, tn - STEPS, d, nb);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -443,6 +473,7 @@ hipError_t launch_one6(const GemmArgs& g, int m0, int blocks, size_t lds, hipStr
     const bool argmax = g.part_val != nullptr;
     if (MT * STEPS >= 6)
         lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
+    lds += (size_t)NW * R * 1536;                   // the waves' buffers for the lane exchange
     static bool attr_set = false;
     if (!attr_set && lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged>),
