@@ -751,7 +751,13 @@ static int run_e4m3(const void* x, int64_t M, int64_t ldx, const void* q8, const
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
-    hipError_t e = launch_e4m3_gemv(a, dev, &parts_used, st);
+    // one or two rows in one pass over the weights: the decode-step frame; else the general kernel
+    static const bool general_only = [] {
+        const char* e = getenv("MXFP4_E4M3_GENERAL");              // measurement only
+        return e && atoi(e) != 0;
+    }();
+    const bool reg = !general_only && aligned(s, 4) && gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a);
+    hipError_t e = reg ? launch_gemv_reg(a, dev, &parts_used, st, nullptr, 8) : launch_e4m3_gemv(a, dev, &parts_used, st);
     if (e != hipSuccess)
         return hip_fail(e, "8-bit product launch");
     if (argmax) {

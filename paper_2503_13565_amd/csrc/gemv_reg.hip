@@ -52,6 +52,11 @@ struct RegArgs {
 // wave instruction with misaligned, gapped accesses and costs 16 to 21 % of the kernel's time;
 // instead the wave loads the 1536 bytes lane-contiguous (16 bytes per lane, then 8), passes them
 // through 1536 bytes of LDS of its own and reads back bytes [24 lane, 24 lane + 24).
+// kBits 8 (E4M3 bytes, 32 bytes per block, 2048 bytes per wave step): loaded lane-contiguous too
+// (16 bytes per lane, twice), and no exchange is needed: a lane keeps what it loaded, two half
+// blocks -- elements [16 lane, 16 lane + 16) of the step, block lane / 2, and the same 1024
+// elements further, block 32 + lane / 2 -- each with its own scale, and holds the activations of
+// exactly those elements (four 16-byte chunks per step, as in the other forms).
 typedef __attribute__((ext_vector_type(32))) __bf16 bf16x32_t;
 typedef __attribute__((ext_vector_type(6))) unsigned int u32x6_t;
 typedef __attribute__((ext_vector_type(16))) unsigned int u32x16_t;
@@ -60,8 +65,8 @@ typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
 template <int MT, int R, int STEPS, int D, int NW, bool kRagged, class Epi, int kBits = 4>
 __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 {
-    static_assert(kBits == 4 || kBits == 6, "element width");
-    constexpr int kBlkBytes = kBits == 6 ? 24 : 16;
+    static_assert(kBits == 4 || kBits == 6 || kBits == 8, "element width");
+    constexpr int kBlkBytes = kBits == 8 ? 32 : (kBits == 6 ? 24 : 16);
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     const int m0 = a.m0;
     static_assert(STEPS % D == 0, "the buffer of a step must be known at compile time");
@@ -136,6 +141,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 
     u32x4_t bq[D][R];
     u32x2_t bq2[D][kBits == 6 ? R : 1];             // bytes 16..23 of a 6-bit block
+    u32x4_t bqb[D][kBits == 8 ? R : 1];             // 8-bit form: the lane's second 16 bytes
     uint32_t bs[D];
     const int n_groups = (a.n + R - 1) / R;
     const int srow = (lane >> 4) % R;
@@ -151,6 +157,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
         const int g0 = live ? grp * R : 0;
         // 6-bit form: the step's valid bytes are 24 per block left in the row (a multiple of 96)
         const int valid6 = kRagged ? 24 * max(0, min(64, nb - t * 64)) : 1536;
+        const int valid8 = kRagged ? 32 * max(0, min(64, nb - t * 64)) : 2048;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int row = min(g0 + r, a.n - 1);                    // odd N: the last row twice
@@ -160,6 +167,12 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                 bq2[d][r] = __builtin_amdgcn_raw_buffer_load_b64(
                     rq, (live && 1024 + lane * 8 < valid6) ? 1024 + lane * 8 : 0x7FFFFFF0,
                     row * q_row_bytes + t * 1536, 2);
+            } else if constexpr (kBits == 8) {
+                bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rq, (live && lane * 16 < valid8) ? lane * 16 : 0x7FFFFFF0, row * q_row_bytes + t * 2048, 2);
+                bqb[d][r] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rq, (live && 1024 + lane * 16 < valid8) ? 1024 + lane * 16 : 0x7FFFFFF0,
+                    row * q_row_bytes + t * 2048, 2);
             } else {
                 bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(rq, (live && vb) ? lane * kBlkBytes : 0x7FFFFFF0,
                                                                  row * q_row_bytes + t * (64 * kBlkBytes), 2);
@@ -192,13 +205,23 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     // beyond that they stay in the LDS copy and every step reads its 64 bytes per row from there.
     // (one base per activation row: every read of a row is then within the 64 KB that the LDS
     // instruction's offset field reaches, and no address has to be kept in a register)
-    const u32x4_t* xrow0 = xs + lane;
-    const u32x4_t* xrow1 = xs + (MT - 1) * 4 * STEPS * 64 + lane;
+    // 8-bit form: chunk j of the lane is chunk 2 (lane % 2) + j % 2 of block lane / 2 + 32 (j / 2)
+    const u32x4_t* xrow0 = kBits == 8 ? xs + 2 * (lane & 1) * xrow + (lane >> 1) : xs + lane;
+    const u32x4_t* xrow1 = xrow0 + (MT - 1) * 4 * STEPS * 64;
     auto x_of = [&](int m, int t, int j) {
-        if constexpr (kXLds)
+        if constexpr (kBits == 8) {
+            if constexpr (kXLds) {
+                return (m == 0 ? xrow0 : xrow1)[((j & 1) * STEPS + t) * 64 + 32 * (j >> 1)];
+            } else {
+                const int blk = t * 64 + (lane >> 1) + 32 * (j >> 1);
+                return (!kRagged || blk < nblk) ? xs[(m * 4 + 2 * (lane & 1) + (j & 1)) * nblk + blk]
+                                                : u32x4_t{0, 0, 0, 0};
+            }
+        } else if constexpr (kXLds) {
             return (m == 0 ? xrow0 : xrow1)[(j * STEPS + t) * 64];
-        else
+        } else {
             return (!kRagged || t * 64 + lane < nblk) ? xs[(m * 4 + j) * nblk + t * 64 + lane] : u32x4_t{0, 0, 0, 0};
+        }
     };
     u32x4_t xr[kXLds ? 1 : MT][kXLds ? 1 : STEPS][4];
     if constexpr (!kXLds) {
@@ -276,7 +299,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
         }
         second = !second;
         int nb = nblk;
-        if constexpr (kBits == 6)
+        if constexpr (kBits != 4)
             asm volatile("" : "+s"(nb));
         uint32_t bias_l[R], res_l[R][MT];
         if constexpr (kEpi) {
@@ -307,6 +330,45 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                 }
 #pragma unroll
             for (int r = 0; r < R; ++r) {
+                if constexpr (kBits == 8) {
+                    // scale bytes of blocks lane / 2 and 32 + lane / 2: dwords lane / 8 and 8 + lane / 8
+                    // of the row's 16, byte (lane / 2) % 4 of either
+                    const int src = (r * 16 + (lane >> 3)) * 4;
+                    const int sh8 = (3 - ((lane >> 1) & 3)) * 8;
+                    const uint32_t dwa = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)bs[d]);
+                    const uint32_t dwb = (uint32_t)__builtin_amdgcn_ds_bpermute(src + 32, (int)bs[d]);
+                    float sc2[2] = {__uint_as_float((dwa << sh8) >> 1), __uint_as_float((dwb << sh8) >> 1)};
+                    if (kRagged) {
+                        const int blk = t * 64 + (lane >> 1);
+                        sc2[0] = blk < nblk ? sc2[0] : 1.0f;
+                        sc2[1] = blk + 32 < nblk ? sc2[1] : 1.0f;
+                    }
+#pragma unroll
+                    for (int p = 0; p < 2; ++p) {
+                        const u32x4_t piece = p ? bqb[d][r] : bq[d][r];
+#pragma unroll
+                        for (int jj = 0; jj < 2; ++jj) {
+                            const uint32_t qd0 = piece[2 * jj], qd1 = piece[2 * jj + 1];
+                            bf16x2_t w[4];
+                            w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd0, sc2[p], false);
+                            w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd0, sc2[p], true);
+                            w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd1, sc2[p], false);
+                            w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd1, sc2[p], true);
+#pragma unroll
+                            for (int m = 0; m < MT; ++m) {
+                                const u32x4_t xv = xq[m][2 * p + jj];
+                                const uint32_t x0 = xv[0], x1 = xv[1], x2 = xv[2], x3 = xv[3];
+                                float c = acc[r][m];
+                                c = __builtin_amdgcn_fdot2_f32_bf16(w[0], __builtin_bit_cast(bf16x2_t, x0), c, false);
+                                c = __builtin_amdgcn_fdot2_f32_bf16(w[1], __builtin_bit_cast(bf16x2_t, x1), c, false);
+                                c = __builtin_amdgcn_fdot2_f32_bf16(w[2], __builtin_bit_cast(bf16x2_t, x2), c, false);
+                                c = __builtin_amdgcn_fdot2_f32_bf16(w[3], __builtin_bit_cast(bf16x2_t, x3), c, false);
+                                acc[r][m] = c;
+                            }
+                        }
+                    }
+                    continue;
+                }
                 // the dword with this lane's scale byte of row r sits in lane r * 16 + lane / 4.
                 // The scaled convert reads only the exponent field of its scale operand (as E8M0),
                 // so the byte goes to bits 30:23 and whatever lands below is ignored.
@@ -457,32 +519,33 @@ __global__ __launch_bounds__(NW * 64) void gemv_reg_fused_kernel(const uint16_t*
                                                 Epilogue{bias, residual, ldr, act});
 }
 
-// The 6-bit format (q = q6, 24 bytes per block).
-template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+// The 6-bit format (q = q6, 24 bytes per block) and the 8-bit format (q = q8, 32 bytes per block).
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged, int kBits>
 __global__ __launch_bounds__(NW * 64) void gemv_reg6_kernel(const uint16_t* x, const uint8_t* q, const uint8_t* s,
                                                             void* out, int n, int k, int m, int m0, int ldx,
                                                             int ldy, int parts)
 {
-    gemv_reg_body<MT, R, STEPS, D, NW, kRagged, NoEpilogue, 6>(RegArgs{x, q, s, out, n, k, m, m0, ldx, ldy, parts},
-                                                               NoEpilogue{});
+    gemv_reg_body<MT, R, STEPS, D, NW, kRagged, NoEpilogue, kBits>(
+        RegArgs{x, q, s, out, n, k, m, m0, ldx, ldy, parts}, NoEpilogue{});
 }
 
-template <int MT, int R, int STEPS, int D, int NW, bool kRagged>
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged, int kBits>
 hipError_t launch_one6(const GemmArgs& g, int m0, int blocks, size_t lds, hipStream_t stream)
 {
     const bool argmax = g.part_val != nullptr;
     if (MT * STEPS >= 6)
         lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
-    lds += (size_t)NW * R * 1536;                   // the waves' buffers for the lane exchange
+    if (kBits == 6)
+        lds += (size_t)NW * R * 1536;               // the waves' buffers for the lane exchange
     static bool attr_set = false;
     if (!attr_set && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged, kBits>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess)
             return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds, stream,
+    hipLaunchKernelGGL((gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged, kBits>), dim3(blocks), dim3(NW * 64), lds, stream,
                        g.x, g.q, g.s, argmax ? static_cast<void*>(g.part_val) : static_cast<void*>(g.y), g.n, g.k,
                        g.m, m0, (int)g.ldx, (int)g.ldy, argmax ? g.parts : 0);
     return hipGetLastError();
@@ -566,40 +629,40 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
     return hipErrorInvalidValue;
 }
 
-// The 6-bit format: the same instances (all of them ready for a ragged K), no fused form.
-template <int MT>
+// The 6-bit and 8-bit formats: the same instances (all of them ready for a ragged K), no fused form.
+template <int MT, int kBits>
 hipError_t launch_steps6(const GemmArgs& a, int m0, int steps2, int blocks, size_t lds, hipStream_t stream)
 {
     switch (steps2) {
     case 2:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 2, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
         else
-            return launch_one6<MT, 2, 2, 2, 8, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 2, 2, 2, 8, true, kBits>(a, m0, blocks, lds, stream);
     case 4:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 4, 2, 16, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 4, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
         break;
     case 6:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 6, 2, 16, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 6, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
         break;
     case 8:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 8, 2, 16, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 8, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
         break;
     case 10:
     case 12:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 12, 2, 16, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 12, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
         break;
     case 14:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 14, 2, 16, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 14, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
         break;
     case 16:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 16, 2, 16, true>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 16, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
         break;
     }
     return hipErrorInvalidValue;
@@ -634,7 +697,7 @@ bool gemv_reg_single_pass(const GemmArgs& a) { return a.m == 1 || (a.m == 2 && e
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                            const Epilogue* epi, int bits)
 {
-    if (bits != 4 && (bits != 6 || epi))
+    if (bits != 4 && ((bits != 6 && bits != 8) || epi))
         return hipErrorInvalidValue;
     const int steps2 = even_steps(a.k);
     const bool ragged = a.k != steps2 * 2048;
@@ -652,12 +715,14 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     for (int m0 = 0; m0 < a.m;) {
         hipError_t e;
         if (a.m - m0 >= 2 && steps2 <= 2) {
-            e = bits == 6 ? launch_steps6<2>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
-                          : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi);
+            e = bits == 6   ? launch_steps6<2, 6>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+                : bits == 8 ? launch_steps6<2, 8>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+                            : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi);
             m0 += 2;
         } else {
-            e = bits == 6 ? launch_steps6<1>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
-                          : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi);
+            e = bits == 6   ? launch_steps6<1, 6>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+                : bits == 8 ? launch_steps6<1, 8>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+                            : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi);
             m0 += 1;
         }
         if (e != hipSuccess)

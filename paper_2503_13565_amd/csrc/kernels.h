@@ -64,7 +64,8 @@ int gemv_max_parts(const DeviceInfo& dev);
 // for the shapes it takes.  The argmax form writes one partial winner per workgroup.
 bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev);
 bool gemv_reg_single_pass(const GemmArgs& a);     // all activation rows in one pass over the weights
-// `bits`: 4 (a.q = packed nibbles) or 6 (a.q = q6, 24 bytes per block; no fused form).
+// `bits`: 4 (a.q = packed nibbles), 6 (a.q = q6, 24 bytes per block) or 8 (a.q = q8, 32 bytes per
+// block); the fused form exists for 4 only.
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                            const Epilogue* epi = nullptr, int bits = 4);
 

@@ -89,6 +89,49 @@ def test_product_edge_shapes(n, k, m):
     assert_argmax_ok(idx, val, y_ref, a_ref, "e4m3 argmax N=%d K=%d M=%d" % (n, k, m))
 
 
+@pytest.mark.parametrize("n,k", [(2048, 128), (2100, 256), (2049, 2176), (2500, 4096), (2300, 8192),
+                                 (2100, 11008), (2049, 14336), (2050, 28672), (2051, 32768)])
+@pytest.mark.parametrize("m", [1, 2])
+def test_product_decode_frame_shapes(n, k, m):
+    # enough rows, K % 128 == 0, one or two activation rows: the decode-step kernel (two half blocks
+    # per lane); every step count, ragged and whole K, odd N
+    w = synth.weights_student_t(n, k, seed=300 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=400 + m + k)
+    q, s, q_ref, s_ref = cast_both_ways(w)
+    y_ref, a_ref = oracle.e4m3_woq_gemm(synth.to_bits(x), q_ref, s_ref)
+    xg = x.to(DEV)
+    y = binding.mxfp4_e4m3_woq_gemm(xg, q, s)
+    torch.cuda.synchronize()
+    assert_gemm_close(y, y_ref, a_ref, "e4m3 decode frame N=%d K=%d M=%d" % (n, k, m))
+    idx, val = binding.mxfp4_e4m3_woq_gemm_argmax(xg, q, s)
+    torch.cuda.synchronize()
+    assert_argmax_ok(idx, val, y_ref, a_ref, "e4m3 decode frame argmax N=%d K=%d M=%d" % (n, k, m))
+
+
+def test_decode_frame_ties_nan_scale_and_non_finite_rows():
+    n, k = 2100, 6144                                    # three steps: ragged, activations in registers
+    w = synth.weights_student_t(n, k, seed=21) * 0.1
+    top = synth.weights_student_t(1, k, seed=22)
+    x = top.clone()
+    for rows in ([5, 300, 2099], [0, 1], [2098, 2099]):
+        wt = w.clone()
+        wt[rows] = top
+        q, s, q_ref, s_ref = cast_both_ways(wt)
+        y_ref, a_ref = oracle.e4m3_woq_gemm(synth.to_bits(x), q_ref, s_ref)
+        idx, val = binding.mxfp4_e4m3_woq_gemm_argmax(x.to(DEV), q, s)
+        assert idx.cpu().numpy().tolist() == [rows[0]], (rows, idx)
+        assert_argmax_ok(idx, val, y_ref, a_ref)
+    q, s, q_ref, s_ref = cast_both_ways(w)
+    s2 = s.clone()
+    s2[17, 3] = 0xFF                                     # one NaN block in row 17 ...
+    s2[18, k // 32 - 1] = 0xFF                           # ... and one at the very end of row 18
+    y = binding.mxfp4_e4m3_woq_gemm(x.to(DEV), q, s2).float().cpu().numpy()
+    y0 = binding.mxfp4_e4m3_woq_gemm(x.to(DEV), q, s).float().cpu().numpy()
+    assert np.all(np.isnan(y[:, [17, 18]]))
+    keep = ~np.isin(np.arange(n), [17, 18])
+    assert np.array_equal(y[:, keep], y0[:, keep])
+
+
 def test_product_llama_shapes_and_padded_strides():
     sh = synth.LLAMA_7B
     for name, m in (("o", 1), ("down", 5)):
