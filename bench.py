@@ -96,6 +96,16 @@ def run_step_e4m3(lin, ws):
     binding.mxfp4_e4m3_woq_gemm_argmax(t["x"], t["q8"], t["s8"], workspace=ws, out=(t["idx"], t["val"]))
 
 
+def run_step_e2m3(lin, ws):
+    """The same step on a 6-bit draft (E2M3 elements with block scales)."""
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up", "down"):
+        t = lin[name]
+        binding.mxfp4_e2m3_woq_gemm(t["x"], t["q6"], t["s6"], y=t["y"])
+    t = lin["lm_head"]
+    binding.mxfp4_e2m3_woq_gemm_argmax(t["x"], t["q6"], t["s6"], workspace=ws, out=(t["idx"], t["val"]))
+
+
 def run_layer_plain(lin, ws):
     from paper_2503_13565_amd import binding
     for name in ("qkv", "o", "gate_up", "down"):
@@ -500,6 +510,7 @@ def main() -> int:
         for lin in bsets:
             for name, t in lin.items():
                 t["q8"], t["s8"] = binding.mxfp4_e4m3_direct_cast(t["w"])
+                t["q6"], t["s6"] = binding.mxfp4_e2m3_direct_cast(t["w"])
                 t["w"] = None
                 if name in ("qkv", "o", "gate_up"):
                     t["x8"] = synth.activations_outlier_channels(8, t["k"], seed=t["n"], device=dev)
@@ -508,6 +519,7 @@ def main() -> int:
             lin["gate_up"]["h"] = torch.empty((m, lin["gate_up"]["n"] // 2), dtype=torch.bfloat16, device=dev)
         variants = {
             "e4m3_weights_us_per_step": round(leg(run_step_e4m3), 2),
+            "e2m3_weights_us_per_step": round(leg(run_step_e2m3), 2),
             "layer_4_linears_us": round(leg(run_layer_plain), 2),
             "layer_4_linears_fused_epilogues_us": round(leg(run_layer_fused), 2),
             "verify_m8_qkv_o_gateup_us": round(leg(run_verify8), 2),
@@ -515,7 +527,7 @@ def main() -> int:
         }
         for lin in bsets:
             for t in lin.values():
-                for key in ("q8", "s8", "x8", "y8", "tw", "h"):
+                for key in ("q8", "s8", "q6", "s6", "x8", "y8", "tw", "h"):
                     t.pop(key, None)
 
     # what a plain 128-bit read stream gets on this device, over 4 GiB (context for frac)
