@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # per file: the leading scalar kernel arguments arrive in scalar registers when a wave starts
 PRELOAD = ["-mllvm", "-amdgpu-kernarg-preload-count=16"]
-EXTRA = {"gemv_reg.hip": PRELOAD, "mfma_tile.hip": PRELOAD, "gemv.hip": PRELOAD}
+EXTRA = {"gemv_reg.hip": PRELOAD, "mfma_tile.hip": PRELOAD, "gemv.hip": PRELOAD, "bf16.hip": PRELOAD}
 
 
 def _hipcc() -> str:

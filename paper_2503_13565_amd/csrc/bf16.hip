@@ -8,6 +8,8 @@
 // one per lane and stored 64 at a time.  At 2 bytes per weight the vector ALUs keep up with the
 // memory system for up to 8 activation rows per pass (4 dot2 per 16 bytes and row), so no matrix
 // core path is needed; more rows take more passes.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 #include "../../include/mxfp4.h"
@@ -236,6 +238,185 @@ __global__ __launch_bounds__(NW * 64) void bf16_gemv_kernel(Bf16Args a, int m0)
     }
 }
 
+// The decode step (one activation row) in the frame of the MXFP4 register GEMV: one workgroup of
+// 16 waves per compute unit; the activation row staged once through LDS and then held in
+// registers (a lane owns elements [8 lane, 8 lane + 8) of every 512-element step); weight rows
+// dealt to the waves through an LDS counter, fetched one row ahead; D steps of 1 KiB per wave in
+// flight; every step issues the same loads (a lane past a ragged K, or a wave out of rows, reads
+// through an offset outside the descriptor: no memory touched, zero back), so the in-order load
+// counter is waited on exactly; scalar, preloaded kernel arguments.
+// NS: steps per row the instance is unrolled for (K <= 512 NS), a multiple of D.
+template <int NS, int D, int NW>
+__global__ __launch_bounds__(NW * 64) void bf16_reg_kernel(const uint16_t* __restrict__ x,
+                                                           const uint16_t* __restrict__ w, void* out, int n, int k,
+                                                           int ldw, int m0, int ldy, int parts)
+{
+    static_assert(NS % D == 0, "the buffer of a step must be known at compile time");
+    constexpr int T = NW * 64;
+    constexpr int XPR = (NS * 64 + T - 1) / T;                       // activation chunks per thread
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int chunks = k >> 3;
+    // activation loads first: nothing may sit in front of them in the compute unit's load queue
+    u32x4_t xl[XPR];
+#pragma unroll
+    for (int i = 0; i < XPR; ++i)
+        xl[i] = reinterpret_cast<const u32x4_t*>(x)[min(tid + i * T, chunks - 1)];
+
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                  // [NS * 64] chunks, zero past K
+    int* ctr = reinterpret_cast<int*>(smem + (size_t)NS * 1024);
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool argmax = parts > 0;
+    const int G = gridDim.x, b = blockIdx.x;
+    const int row_bytes = ldw * 2;
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(w), 0, ((n - 1) * ldw + k) * 2, 0x00020000);
+    if (tid == 0)
+        *ctr = NW;                                                   // indices 0 .. NW-1 are the waves' first rows
+    auto row_of = [&](int i) { return i * G + b; };
+
+    u32x4_t buf[D];
+    auto issue = [&](int row, int t, int d) {
+        const bool live = row < n && (t * 64 + lane) < chunks;
+        buf[d] = __builtin_amdgcn_raw_buffer_load_b128(rw, live ? lane * 16 : kSentinelB,
+                                                       (row < n ? row : 0) * row_bytes + t * 1024, 2);
+    };
+    int row = row_of(wave);
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        issue(row, d, d);
+
+#pragma unroll
+    for (int i = 0; i < XPR; ++i) {
+        const int c = tid + i * T;
+        if (c < NS * 64)
+            xs[c] = c < chunks ? xl[i] : u32x4_t{0, 0, 0, 0};
+    }
+    lds_barrier_b();
+    u32x4_t xr[NS];
+#pragma unroll
+    for (int t = 0; t < NS; ++t)
+        xr[t] = xs[t * 64 + lane];
+
+    float best_val = -INFINITY;
+    int best_idx = 0x7FFFFFFF;
+    float res = 0.f;                    // finished outputs, one per lane
+    int rowv = 0, slots = 0;
+    auto flush = [&]() {
+        if (lane < slots && rowv < n)
+            static_cast<uint16_t*>(out)[(int64_t)m0 * ldy + rowv] = f32_to_bf16_rne(res);
+        slots = 0;
+        drain_vmem();                   // stores and loads share the counter: the loop only ever sees loads
+    };
+    auto fetch = [&]() {
+        int v = 0;
+        if (lane == 0)
+            v = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+    int i_next = fetch();
+    float acc = 0.f;
+    while (row < n) {
+        const int row_n = row_of(i_next);
+        i_next = fetch();               // consumed one trip later: its latency is hidden
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            const int d = t % D;
+            const u32x4_t wv = buf[d];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t wd = wv[j], xd = xr[t][j];            // (a bit cast needs a plain object)
+                acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, wd),
+                                                      __builtin_bit_cast(bf16x2_t, xd), acc, false);
+            }
+            const int tn = t + D;
+            if (tn < NS)
+                issue(row, tn, d);
+            else
+                issue(row_n, tn - NS, d);
+        }
+        const float v = wave_sum(acc);
+        acc = 0.f;
+        if (argmax) {
+            // rows arrive in any order: the lower index wins among equal values
+            if (v > best_val || (v == best_val && row < best_idx)) {
+                best_val = v;
+                best_idx = row;
+            }
+        } else {
+            res = (lane == slots) ? v : res;
+            rowv = (lane == slots) ? row : rowv;
+            if (++slots == 64)
+                flush();
+        }
+        row = row_n;
+    }
+    if (!argmax && slots > 0)
+        flush();
+    if (argmax) {
+        __syncthreads();
+        float* wvals = reinterpret_cast<float*>(smem);
+        int* widx = reinterpret_cast<int*>(smem) + NW;
+        if (lane == 0) {
+            wvals[wave] = best_val;
+            widx[wave] = best_idx;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            float bv = wvals[0];
+            int bi = widx[0];
+            for (int i = 1; i < NW; ++i) {
+                if (wvals[i] > bv || (wvals[i] == bv && widx[i] < bi)) {
+                    bv = wvals[i];
+                    bi = widx[i];
+                }
+            }
+            float* part_val = static_cast<float*>(out);
+            int32_t* part_idx = reinterpret_cast<int32_t*>(part_val + parts);     // one activation row
+            part_val[b] = bv;
+            part_idx[b] = bi;
+        }
+    }
+}
+
+template <int NS, int D>
+hipError_t launch_reg_b(const Bf16Args& a, int blocks, hipStream_t stream)
+{
+    constexpr int NW = 16;
+    const bool argmax = a.part_val != nullptr;
+    const size_t lds = (size_t)NS * 1024 + 64;
+    hipLaunchKernelGGL((bf16_reg_kernel<NS, D, NW>), dim3(blocks), dim3(NW * 64), lds, stream, a.x, a.w,
+                       argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, (int)a.ldw, 0,
+                       (int)a.ldy, argmax ? a.parts : 0);
+    return hipGetLastError();
+}
+
+// One activation row, K a multiple of 8 up to 8192 (16 steps of activations in registers; with 22
+// steps, the 7B down projection, it is 12 % slower than the general kernel), rows
+// 16-byte aligned, enough rows to give every compute unit a workgroup's worth; in the argmax form
+// the index array directly behind the one row of values.
+bool bf16_reg_can_run(const Bf16Args& a, const DeviceInfo& dev)
+{
+    if (a.m != 1 || a.k % 8 != 0 || a.k > 8192 || a.n < dev.cus * 8)
+        return false;
+    if (a.ldw > 0x3FFFFFFF || a.ldy > 0x7FFFFFFF)
+        return false;
+    if (a.part_val && a.part_idx != reinterpret_cast<int32_t*>(a.part_val + a.parts))
+        return false;
+    return true;
+}
+
+hipError_t launch_bf16_reg(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+{
+    const int blocks = dev.cus < (a.n + 15) / 16 ? dev.cus : (a.n + 15) / 16;
+    if (parts_used)
+        *parts_used = blocks;
+    const int steps = (a.k + 511) / 512;
+    // (four steps in flight: 2 % faster on the largest matrices, 5 % slower on the smallest; one: 7 to 20 % slower)
+    return steps <= 8 ? launch_reg_b<8, 2>(a, blocks, stream) : launch_reg_b<16, 2>(a, blocks, stream);
+}
+
 template <int MT, int R, int NW>
 hipError_t launch_b(const Bf16Args& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
@@ -274,6 +455,12 @@ bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev) { return (size_t)a.k
 
 hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
 {
+    static const bool general_only = [] {
+        const char* e = getenv("MXFP4_BF16_GENERAL");                // measurement only
+        return e && atoi(e) != 0;
+    }();
+    if (!general_only && bf16_reg_can_run(a, dev))
+        return launch_bf16_reg(a, dev, parts_used, stream);
     // two rows per group unless the matrix is so short that SIMDs would idle
     const int r = (a.n + 1) / 2 >= dev.cus * 16 ? 2 : 1;
     const int n_groups = (a.n + r - 1) / r;
