@@ -417,6 +417,264 @@ hipError_t launch_bf16_reg(const Bf16Args& a, const DeviceInfo& dev, int* parts_
     return steps <= 8 ? launch_reg_b<8, 2>(a, blocks, stream) : launch_reg_b<16, 2>(a, blocks, stream);
 }
 
+// Verification passes (three and more activation rows) on the matrix cores: the frame of the
+// MXFP4 tile kernel without the decode.  A tile is 16 weight rows; in step T (128 elements of K)
+// lane (i = lane % 16, g = lane / 16) loads, for each of the four v_mfma_f32_16x16x32_bf16 of the
+// step, the 8 weights [128 T + 32 j + 8 g, + 8) of row i straight into the instruction's operand
+// (64 bytes of a row per wave load); the MP activation rows of the pass sit in LDS as 16-byte
+// chunks [chunk][row ^ (chunk % MP)] (the copy's writes and the loop's 128-bit reads are then
+// free of bank conflicts); NW compute waves split the steps of a tile, keep D steps in flight
+// each, leave their partial tiles in LDS; one more wave, which never loads, adds them in a fixed
+// order and stores or tracks the argmax; one barrier per tile.  Every position-dependent condition
+// is an arithmetic mask on the offsets, so every trip issues the same loads.
+typedef __attribute__((ext_vector_type(4))) float bf_f32x4_t;
+
+template <int MP, int NW, int D>
+__global__ __launch_bounds__((NW + 1) * 64) void bf16_mfma_kernel(const uint16_t* __restrict__ x,
+                                                                  const uint16_t* __restrict__ w, void* out, int n,
+                                                                  int k, int ldw, int m, int m0, int ldx, int ldy,
+                                                                  int parts)
+{
+    constexpr int T = (NW + 1) * 64;
+    extern __shared__ __align__(16) uint8_t smem[];
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);
+    const int tid = threadIdx.x;
+    const int steps = k >> 7;
+    const int chunks = steps * 16;                                      // 16-byte chunks per activation row
+    constexpr int XB = 16 / MP;
+    const int xpr = (chunks + T - 1) / T;
+    u32x4_t xl[XB][MP];
+    auto x_load = [&](int i0) {
+#pragma unroll
+        for (int i = 0; i < XB; ++i) {
+            const int kc = min(tid + (i0 + i) * T, chunks - 1);
+#pragma unroll
+            for (int mm = 0; mm < MP; ++mm) {
+                const int msrc = min(m0 + mm, m - 1);                   // ragged M: repeat the last row
+                xl[i][mm] = reinterpret_cast<const u32x4_t*>(x + (int64_t)msrc * ldx)[kc];
+            }
+        }
+    };
+    x_load(0);
+
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int row_bytes = ldw * 2;
+    const int spw = (steps + NW - 1) / NW;                              // steps per wave and tile
+    const int n_tiles = (n + 15) >> 4;
+    const int G = gridDim.x, b = blockIdx.x;
+    bf_f32x4_t* red = reinterpret_cast<bf_f32x4_t*>(smem + (size_t)chunks * 16 * MP);   // [2][NW][64]
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(w), 0, ((n - 1) * ldw + k) * 2, 0x00020000);
+
+    struct Item {
+        u32x4_t w[4];
+    };
+    Item buf[D];
+    int ld_tile = b, ld_loc = 0;
+    auto issue = [&](Item& it) {
+        const int live = (int)(ld_tile < n_tiles);
+        const int step = wave + NW * ld_loc;
+        const int mk = -(live & (int)(step < steps) & (int)(wave < NW));   // all ones when the step exists
+        const int row = min(ld_tile * live * 16 + li, n - 1);             // ragged N: repeat the last row
+        const int vq = row * row_bytes + lg * 16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            it.w[j] = __builtin_amdgcn_raw_buffer_load_b128(rw, (vq & mk) | (kSentinelB & ~mk),
+                                                            ((step * 256 + j * 64) & mk) | ((j * 16) & ~mk), 0);
+        const int wrap = (int)(ld_loc + 1 == spw);
+        ld_loc = (ld_loc + 1) * (1 - wrap);
+        ld_tile += G * wrap;
+    };
+    if (wave < NW) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            issue(buf[d]);
+            __builtin_amdgcn_sched_barrier(0);                          // keep the buffers' loads in issue order
+        }
+    }
+    auto x_store = [&](int i0) {
+#pragma unroll
+        for (int i = 0; i < XB; ++i) {
+            const int kc = tid + (i0 + i) * T;
+            if (kc < chunks) {
+#pragma unroll
+                for (int mm = 0; mm < MP; ++mm)
+                    xs[kc * MP + (mm ^ (kc & (MP - 1)))] = xl[i][mm];
+            }
+        }
+    };
+    x_store(0);
+#pragma unroll 1
+    for (int i0 = XB; i0 < xpr; i0 += XB) {
+        x_load(i0);
+        x_store(i0);
+    }
+    lds_barrier_b();
+
+    const bool argmax = parts > 0;
+    if (wave == NW) {
+        // Epilogue wave: one barrier per tile, like the compute waves; no loads of its own.
+        const int m_valid = min(MP, m - m0);
+        float best_val = -INFINITY;
+        int best_idx = 0x7FFFFFFF;
+        int done = 0;
+        for (int tile = b; tile < n_tiles; tile += G, ++done) {
+            const bf_f32x4_t* slot = red + (size_t)(done & 1) * NW * 64;
+            lds_barrier_b();                                            // partial tiles of `tile` are in LDS
+            bf_f32x4_t sum = slot[lane];
+#pragma unroll
+            for (int v = 1; v < NW; ++v)
+                sum += slot[v * 64 + lane];
+            // lane (li, lg) holds weight rows 4 lg + r of the tile for activation row li
+            if (li < m_valid) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = tile * 16 + 4 * lg + r;
+                    if (row < n) {
+                        if (argmax) {
+                            if (sum[r] > best_val) {                    // rows ascend: lowest index wins ties
+                                best_val = sum[r];
+                                best_idx = row;
+                            }
+                        } else {
+                            static_cast<uint16_t*>(out)[(int64_t)(m0 + li) * ldy + row] = f32_to_bf16_rne(sum[r]);
+                        }
+                    }
+                }
+            }
+        }
+        if (argmax) {
+#pragma unroll
+            for (int off = 16; off < 64; off <<= 1) {
+                const float v = __shfl_xor(best_val, off);
+                const int i = __shfl_xor(best_idx, off);
+                if (v > best_val || (v == best_val && i < best_idx)) {
+                    best_val = v;
+                    best_idx = i;
+                }
+            }
+            if (lane < m_valid) {
+                float* part_val = static_cast<float*>(out);
+                int32_t* part_idx = reinterpret_cast<int32_t*>(part_val + (int64_t)m * parts);
+                part_val[(int64_t)(m0 + lane) * parts + b] = best_val;
+                part_idx[(int64_t)(m0 + lane) * parts + b] = best_idx;
+            }
+        }
+        return;
+    }
+
+    bf_f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: even and odd j
+    const int col = li & (MP - 1);
+    int c_tile = b, c_loc = 0, done = 0;
+    // Positions only grow, so the walk ends when buffer 0 runs dry; every trip issues the same loads.
+    while (c_tile < n_tiles) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (d == 0 || c_tile < n_tiles) {
+                const Item& it = buf[d];
+                const int step = wave + NW * c_loc;
+                const int Tq = step < steps ? step : 0;                 // a step that does not exist has zero weights
+                u32x4_t xb[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    xb[j] = xs[(Tq * 16 + 4 * j + lg) * MP + (col ^ ((4 * j + lg) & (MP - 1)))];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const u32x4_t wv = it.w[j];
+                    if (j & 1)
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv),
+                                                                       __builtin_bit_cast(bf16x8_t, xb[j]), acc1, 0, 0, 0);
+                    else
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv),
+                                                                       __builtin_bit_cast(bf16x8_t, xb[j]), acc0, 0, 0, 0);
+                }
+                if (c_loc == spw - 1) {
+                    bf_f32x4_t* slot = red + (size_t)(done & 1) * NW * 64;
+                    slot[wave * 64 + lane] = acc0 + acc1;
+                    acc0 = bf_f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    acc1 = bf_f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    lds_barrier_b();
+                    ++done;
+                }
+                if (++c_loc == spw) {
+                    c_loc = 0;
+                    c_tile += G;
+                }
+            }
+            issue(buf[d]);
+        }
+    }
+}
+
+size_t bf16_mfma_lds(int k, int mp, int nw) { return (size_t)k * 2 * mp + (size_t)2 * nw * 1024; }
+int bf16_pass_width(int left) { return left > 8 ? 16 : (left > 4 ? 8 : 4); }
+
+template <int MP, int NW>
+hipError_t launch_mfma_b(const Bf16Args& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
+{
+    auto kern = bf16_mfma_kernel<MP, NW, 2>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    const bool argmax = a.part_val != nullptr;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.w,
+                       argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, (int)a.ldw, a.m,
+                       m0, (int)a.ldx, (int)a.ldy, argmax ? a.parts : 0);
+    return hipGetLastError();
+}
+
+// Three and more rows, K % 128 == 0, the widest pass's activation rows fit the LDS beside the
+// partial tiles; 32-bit leading dimensions; the argmax index array directly behind the values.
+bool bf16_mfma_can_run(const Bf16Args& a, const DeviceInfo& dev)
+{
+    if (a.m < 3 || a.k % 128 != 0 || a.n < 16)
+        return false;
+    if (a.ldx > 0x7FFFFFFF || a.ldy > 0x7FFFFFFF || a.ldw > 0x3FFFFFFF)
+        return false;
+    if (a.part_val && a.part_idx != reinterpret_cast<int32_t*>(a.part_val + (size_t)a.m * a.parts))
+        return false;
+    return bf16_mfma_lds(a.k, bf16_pass_width(a.m), 4) <= (size_t)dev.lds_bytes;
+}
+
+hipError_t launch_bf16_mfma(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+{
+    const int n_tiles = (a.n + 15) / 16;
+    // two workgroups of four compute waves per compute unit when two copies of the widest pass's
+    // activations fit, else one of eight (what the MXFP4 tile kernel settled on)
+    const int widest = bf16_pass_width(a.m);
+    const bool two = 2 * bf16_mfma_lds(a.k, widest, 4) + 2048 <= (size_t)dev.lds_bytes;
+    const bool wide = !two && bf16_mfma_lds(a.k, widest, 8) <= (size_t)dev.lds_bytes;
+    int blocks = dev.cus * (two ? 2 : 1);
+    blocks = blocks > n_tiles ? n_tiles : blocks;
+    blocks = blocks > gemv_max_parts(dev) ? gemv_max_parts(dev) : blocks;
+    if (parts_used)
+        *parts_used = blocks;                       // every pass uses the same grid: the partials line up
+    for (int m0 = 0; m0 < a.m;) {
+        const int mp = bf16_pass_width(a.m - m0);
+        const size_t lds = bf16_mfma_lds(a.k, mp, wide ? 8 : 4);
+        hipError_t e;
+        if (wide)
+            e = mp == 16  ? launch_mfma_b<16, 8>(a, m0, blocks, lds, dev.lds_bytes, stream)
+                : mp == 8 ? launch_mfma_b<8, 8>(a, m0, blocks, lds, dev.lds_bytes, stream)
+                          : launch_mfma_b<4, 8>(a, m0, blocks, lds, dev.lds_bytes, stream);
+        else
+            e = mp == 16  ? launch_mfma_b<16, 4>(a, m0, blocks, lds, dev.lds_bytes, stream)
+                : mp == 8 ? launch_mfma_b<8, 4>(a, m0, blocks, lds, dev.lds_bytes, stream)
+                          : launch_mfma_b<4, 4>(a, m0, blocks, lds, dev.lds_bytes, stream);
+        if (e != hipSuccess)
+            return e;
+        m0 += mp;
+    }
+    return hipSuccess;
+}
+
 template <int MT, int R, int NW>
 hipError_t launch_b(const Bf16Args& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
@@ -461,6 +719,11 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
     }();
     if (!general_only && bf16_reg_can_run(a, dev))
         return launch_bf16_reg(a, dev, parts_used, stream);
+    // Up to eight rows the vector-ALU kernel below is as fast or faster in one pass (7B shapes, µs:
+    // 20.1 / 33.0 / 46.3 against 21.2 / 36.8 / 48.6 at four rows, equal at eight); from nine rows on
+    // it needs two passes and the matrix cores one.
+    if (!general_only && a.m > 8 && bf16_mfma_can_run(a, dev))
+        return launch_bf16_mfma(a, dev, parts_used, stream);
     // two rows per group unless the matrix is so short that SIMDs would idle
     const int r = (a.n + 1) / 2 >= dev.cus * 16 ? 2 : 1;
     const int n_groups = (a.n + r - 1) / r;
@@ -469,8 +732,10 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
         const int left = a.m - m0;
         // the narrowest pass that takes all remaining rows (a ragged pass repeats its last row)
         int mt = left > 4 ? 8 : (left > 2 ? 4 : (left > 1 ? 2 : 1));
+        if (mt == 8 && (size_t)8 * a.k * 2 > (size_t)dev.lds_bytes && left <= 6)
+            mt = 6;                                                 // five or six rows of a long K in one pass
         while (mt > 1 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes)
-            mt >>= 1;
+            mt = mt == 6 ? 4 : mt >> 1;
         const size_t lds = (size_t)mt * a.k * 2 < 256 ? 256 : (size_t)mt * a.k * 2;   // the argmax combine needs a few bytes
         int per_cu = (int)((size_t)dev.lds_bytes / lds);
         per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
@@ -490,6 +755,9 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
         switch (mt) {
         case 8:
             e = launch_rows<8>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
+            break;
+        case 6:
+            e = launch_rows<6>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
             break;
         case 4:
             e = launch_rows<4>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);

@@ -38,6 +38,59 @@ def test_edge_shapes(n, k, m):
     run_case(w, x, "BF16 N=%d K=%d M=%d" % (n, k, m))
 
 
+@pytest.mark.parametrize("n,k", [(2048, 8), (2049, 520), (2100, 4096), (2060, 2056), (2050, 5000), (2500, 8192),
+                                 (2051, 8200)])
+def test_decode_frame_shapes(n, k):
+    # one activation row and enough weight rows: the decode-step kernel (K up to 8192, ragged and
+    # whole steps of 512, odd N), and just beyond its range the general one
+    w = synth.weights_student_t(n, k, seed=900 + n + k)
+    x = synth.activations_outlier_channels(1, k, seed=950 + k)
+    run_case(w, x, "BF16 decode frame N=%d K=%d" % (n, k))
+
+
+def test_decode_frame_strided_weights_and_ties():
+    n, k = 2100, 1024
+    wbig = synth.weights_student_t(n, k + 64, seed=41)
+    x = synth.activations_gaussian(1, k, seed=42)
+    w = wbig[:, :k].contiguous()
+    y_ref, a_ref = oracle.bf16_gemm(synth.to_bits(x), synth.to_bits(w))
+    best = int(np.argmax(y_ref[0]))
+    for rows in ([7, 2099], [0, 1]):
+        wt = wbig.clone()
+        for r in rows:
+            wt[r] = wbig[best]
+        lo = min(rows + [best])
+        wg = wt.to(DEV)[:, :k]                              # row stride k + 64
+        idx, _ = binding.mxfp4_bf16_gemm_argmax(x.to(DEV), wg)
+        y = binding.mxfp4_bf16_gemm(x.to(DEV), wg)
+        torch.cuda.synchronize()
+        assert int(idx[0]) == lo, (rows, best, int(idx[0]))
+        y_t, a_t = oracle.bf16_gemm(synth.to_bits(x), synth.to_bits(wt[:, :k].contiguous()))
+        assert_gemm_close(y, y_t, a_t, "BF16 decode frame strided")
+
+
+@pytest.mark.parametrize("m", [3, 4, 5, 8, 9, 16, 17, 33])
+@pytest.mark.parametrize("n,k", [(16, 128), (2050, 4096), (4100, 1024), (300, 8192), (530, 11008)])
+def test_matrix_core_passes(n, k, m):
+    # three and more rows with K % 128 == 0: the matrix-core kernel where a pass's rows fit the LDS
+    w = synth.weights_student_t(n, k, seed=1000 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=1050 + m + k)
+    run_case(w, x, "BF16 matrix cores N=%d K=%d M=%d" % (n, k, m))
+
+
+def test_matrix_core_exact_ties_pick_lowest_index():
+    n, k, m = 600, 512, 4
+    w = synth.weights_student_t(n, k, seed=51) * 0.1
+    top = synth.weights_student_t(1, k, seed=52)
+    x = top.clone().repeat(m, 1)
+    for rows in ([5, 300, 599], [0, 1], [598, 599], [15, 16, 17]):
+        wt = w.clone()
+        wt[rows] = top
+        idx, val = binding.mxfp4_bf16_gemm_argmax(x.to(DEV), wt.to(DEV))
+        torch.cuda.synchronize()
+        assert idx.cpu().numpy().tolist() == [rows[0]] * m, (rows, idx)
+
+
 @pytest.mark.parametrize("m", [1, 8])
 def test_config0_shape(m):
     w = synth.weights_gaussian_outliers(4096, 4096, seed=0)
