@@ -675,6 +675,194 @@ hipError_t launch_bf16_mfma(const Bf16Args& a, const DeviceInfo& dev, int* parts
     return hipSuccess;
 }
 
+// The same product when the MT activation rows of a pass do not fit the LDS whole: K is cut into
+// phases of `phase_steps` steps.  For every phase the workgroup stages that part of the activation
+// rows, every wave walks all of its row groups over the phase's K range and adds the partial sums
+// to the outputs it holds, one row per lane (at most 64 rows per wave: the host checks), and only
+// after the last phase rounds and stores them.  The weights are still read once; the cost is one
+// pipeline start per phase.  Fixed order of additions: deterministic.
+template <int MT, int R, int NW>
+__global__ __launch_bounds__(NW * 64) void bf16_phased_kernel(Bf16Args a, int m0, int phase_steps)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                  // [MT][phase_steps * 64] chunks
+    constexpr int T = NW * 64;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int chunks = a.k >> 3;
+    const int steps = (chunks + 63) >> 6;
+    const int pc = phase_steps * 64;                                 // chunks per row and phase
+    const int n_groups = (a.n + R - 1) / R;
+    const int total_waves = gridDim.x * NW;
+    const int first_group = (int)blockIdx.x * NW + wave;
+    const int row_bytes = (int)a.ldw * 2;
+    const bool argmax = a.part_val != nullptr;
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(a.w), 0, (int)((a.n - 1) * a.ldw + a.k) * 2, 0x00020000);
+
+    float res[MT];               // lane s holds the running output of the wave's s-th row
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+        res[m] = 0.f;
+    float acc[R][MT];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+            acc[r][m] = 0.f;
+
+    for (int t_lo = 0; t_lo < steps; t_lo += phase_steps) {
+        const int t_hi = min(steps, t_lo + phase_steps);
+        __syncthreads();                                             // everyone is done with the previous phase's rows
+        for (int c = tid; c < pc; c += T) {
+            const int cg = t_lo * 64 + c;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const int msrc = min(m0 + m, a.m - 1);               // ragged M: repeat the last row
+                const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.x + (int64_t)msrc * a.ldx);
+                xs[m * pc + c] = cg < chunks ? xp[cg] : u32x4_t{0, 0, 0, 0};
+            }
+        }
+        __syncthreads();
+
+        auto valid = [&](const BPos& p) { return p.g < n_groups; };
+        auto advance = [&](BPos& p) {
+            if (++p.t == t_hi) {
+                p.t = t_lo;
+                p.g += total_waves;
+            }
+        };
+        auto issue = [&](const BPos& p, u32x4_t (&w)[R]) {
+            const bool live = valid(p) && p.t * 64 + lane < chunks;
+            const int voff = live ? lane * 16 : kSentinelB;
+            const int g = valid(p) ? p.g : 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int row = min(g * R + r, a.n - 1);              // ragged N: re-read the last row
+                w[r] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, row * row_bytes + p.t * 1024, 2);
+            }
+        };
+        u32x4_t buf[2][R];
+        BPos pos[2];
+        BPos load{first_group, t_lo};
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            pos[d] = load;
+            issue(load, buf[d]);
+            advance(load);
+        }
+        int slot = 0;                                                // first row slot of the group being summed
+        auto compute = [&](const BPos& p, const u32x4_t (&w)[R]) {
+            u32x4_t xv[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                xv[m] = xs[m * pc + (p.t - t_lo) * 64 + lane];        // zero past K, as are the weights
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t wd = w[r][j];
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        const uint32_t xd = xv[m][j];
+                        acc[r][m] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, wd),
+                                                                    __builtin_bit_cast(bf16x2_t, xd), acc[r][m], false);
+                    }
+                }
+            }
+            if (p.t == t_hi - 1) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        const float v = wave_sum(acc[r][m]);
+                        acc[r][m] = 0.f;
+                        res[m] += (lane == slot + r) ? v : 0.f;
+                    }
+                slot += R;
+            }
+        };
+        while (valid(pos[0])) {
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+                if (d == 0 || valid(pos[d]))
+                    compute(pos[d], buf[d]);
+                pos[d] = load;
+                issue(load, buf[d]);
+                advance(load);
+            }
+        }
+    }
+
+    // lane s holds row (first_group + (s / R) * total_waves) * R + s % R
+    const int j = lane / R, r = lane - j * R;
+    const int grp = first_group + j * total_waves;
+    const int row = grp * R + r;
+    const bool own = grp < n_groups && row < a.n;
+    if (!argmax) {
+        if (own) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                if (m0 + m < a.m)
+                    a.y[(int64_t)(m0 + m) * a.ldy + row] = f32_to_bf16_rne(res[m]);
+        }
+        return;
+    }
+    __syncthreads();
+    float* wv = reinterpret_cast<float*>(smem);
+    int* wi = reinterpret_cast<int*>(smem) + NW * MT;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        float bv = own ? res[m] : -INFINITY;
+        int bi = own ? row : 0x7FFFFFFF;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float v = __shfl_xor(bv, off);
+            const int i = __shfl_xor(bi, off);
+            if (v > bv || (v == bv && i < bi)) {
+                bv = v;
+                bi = i;
+            }
+        }
+        if (lane == 0) {
+            wv[wave * MT + m] = bv;
+            wi[wave * MT + m] = bi;
+        }
+    }
+    __syncthreads();
+    if (tid < MT && m0 + tid < a.m) {
+        float bv = wv[tid];
+        int bi = wi[tid];
+        for (int w = 1; w < NW; ++w) {
+            const float v = wv[w * MT + tid];
+            const int i = wi[w * MT + tid];
+            if (v > bv || (v == bv && i < bi)) {
+                bv = v;
+                bi = i;
+            }
+        }
+        a.part_val[(int64_t)(m0 + tid) * a.parts + blockIdx.x] = bv;
+        a.part_idx[(int64_t)(m0 + tid) * a.parts + blockIdx.x] = bi;
+    }
+}
+
+template <int MT, int R>
+hipError_t launch_phased(const Bf16Args& a, int m0, int blocks, int phase_steps, int max_lds, hipStream_t stream)
+{
+    auto kern = bf16_phased_kernel<MT, R, 16>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    const size_t lds = (size_t)MT * phase_steps * 1024;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(16 * 64), lds, stream, a, m0, phase_steps);
+    return hipGetLastError();
+}
+
 template <int MT, int R, int NW>
 hipError_t launch_b(const Bf16Args& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
@@ -722,7 +910,11 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
     // Up to eight rows the vector-ALU kernel below is as fast or faster in one pass (7B shapes, µs:
     // 20.1 / 33.0 / 46.3 against 21.2 / 36.8 / 48.6 at four rows, equal at eight); from nine rows on
     // it needs two passes and the matrix cores one.
-    if (!general_only && a.m > 8 && bf16_mfma_can_run(a, dev))
+    static const int mfma_from = [] {
+        const char* e = getenv("MXFP4_BF16_MFMA_FROM");             // measurement only
+        return e ? atoi(e) : 9;
+    }();
+    if (!general_only && a.m >= mfma_from && bf16_mfma_can_run(a, dev))
         return launch_bf16_mfma(a, dev, parts_used, stream);
     // two rows per group unless the matrix is so short that SIMDs would idle
     const int r = (a.n + 1) / 2 >= dev.cus * 16 ? 2 : 1;
@@ -732,6 +924,35 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
         const int left = a.m - m0;
         // the narrowest pass that takes all remaining rows (a ragged pass repeats its last row)
         int mt = left > 4 ? 8 : (left > 2 ? 4 : (left > 1 ? 2 : 1));
+        // The rows of the pass do not fit the LDS whole: K in phases, still one pass over the weights,
+        // when a wave's rows fit its 64 lanes (one workgroup of 16 waves per compute unit).
+        if (mt >= 2 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes && !general_only) {
+            const int pblocks = dev.cus < (n_groups + 15) / 16 ? dev.cus : (n_groups + 15) / 16;
+            const int groups_per_wave = (n_groups + pblocks * 16 - 1) / (pblocks * 16);
+            const int fit_steps = (int)(((size_t)dev.lds_bytes - 16 * 1024) / ((size_t)mt * 1024));
+            const int k_steps = (a.k / 8 + 63) / 64;
+            const int n_phases = fit_steps > 0 ? (k_steps + fit_steps - 1) / fit_steps : 0;
+            const int phase_steps = n_phases > 0 ? (k_steps + n_phases - 1) / n_phases : 0;   // even phases
+            const bool parts_ok = a.part_val == nullptr || first_blocks == 0 || pblocks <= first_blocks;
+            if (groups_per_wave * r <= 64 && phase_steps >= 4 && pblocks <= gemv_max_parts(dev) && parts_ok &&
+                (m0 == 0 || a.part_val == nullptr || pblocks == first_blocks)) {
+                hipError_t e;
+                if (r == 2)
+                    e = mt == 8   ? launch_phased<8, 2>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
+                        : mt == 4 ? launch_phased<4, 2>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
+                                  : launch_phased<2, 2>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream);
+                else
+                    e = mt == 8   ? launch_phased<8, 1>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
+                        : mt == 4 ? launch_phased<4, 1>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
+                                  : launch_phased<2, 1>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream);
+                if (e != hipSuccess)
+                    return e;
+                if (m0 == 0)
+                    first_blocks = pblocks;
+                m0 += mt;
+                continue;
+            }
+        }
         if (mt == 8 && (size_t)8 * a.k * 2 > (size_t)dev.lds_bytes && left <= 6)
             mt = 6;                                                 // five or six rows of a long K in one pass
         while (mt > 1 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes)

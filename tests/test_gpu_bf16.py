@@ -78,6 +78,15 @@ def test_matrix_core_passes(n, k, m):
     run_case(w, x, "BF16 matrix cores N=%d K=%d M=%d" % (n, k, m))
 
 
+@pytest.mark.parametrize("n,k,m", [(2100, 28672, 8), (300, 11008, 8), (4100, 11008, 7), (70, 28672, 3),
+                                   (2050, 20480, 16)])
+def test_long_k_passes_in_phases(n, k, m):
+    # the rows of a pass do not fit the LDS whole: K in phases, one pass over the weights
+    w = synth.weights_student_t(n, k, seed=1100 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=1150 + m + k)
+    run_case(w, x, "BF16 phased N=%d K=%d M=%d" % (n, k, m))
+
+
 def test_matrix_core_exact_ties_pick_lowest_index():
     n, k, m = 600, 512, 4
     w = synth.weights_student_t(n, k, seed=51) * 0.1
