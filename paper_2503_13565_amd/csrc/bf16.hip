@@ -924,6 +924,9 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
         const int left = a.m - m0;
         // the narrowest pass that takes all remaining rows (a ragged pass repeats its last row)
         int mt = left > 4 ? 8 : (left > 2 ? 4 : (left > 1 ? 2 : 1));
+        if (mt == 8 && left <= 6 && (size_t)8 * a.k * 2 > (size_t)dev.lds_bytes &&
+            (size_t)6 * a.k * 2 <= (size_t)dev.lds_bytes)
+            mt = 6;                                                 // five or six rows that fit where eight do not
         // The rows of the pass do not fit the LDS whole: K in phases, still one pass over the weights,
         // when a wave's rows fit its 64 lanes (one workgroup of 16 waves per compute unit).
         if (mt >= 2 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes && !general_only) {
@@ -938,11 +941,11 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
                 (m0 == 0 || a.part_val == nullptr || pblocks == first_blocks)) {
                 hipError_t e;
                 if (r == 2)
-                    e = mt == 8   ? launch_phased<8, 2>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
+                    e = mt >= 6   ? launch_phased<8, 2>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
                         : mt == 4 ? launch_phased<4, 2>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
                                   : launch_phased<2, 2>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream);
                 else
-                    e = mt == 8   ? launch_phased<8, 1>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
+                    e = mt >= 6   ? launch_phased<8, 1>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
                         : mt == 4 ? launch_phased<4, 1>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream)
                                   : launch_phased<2, 1>(a, m0, pblocks, phase_steps, dev.lds_bytes, stream);
                 if (e != hipSuccess)
@@ -953,8 +956,6 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
                 continue;
             }
         }
-        if (mt == 8 && (size_t)8 * a.k * 2 > (size_t)dev.lds_bytes && left <= 6)
-            mt = 6;                                                 // five or six rows of a long K in one pass
         while (mt > 1 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes)
             mt = mt == 6 ? 4 : mt >> 1;
         const size_t lds = (size_t)mt * a.k * 2 < 256 ? 256 : (size_t)mt * a.k * 2;   // the argmax combine needs a few bytes
