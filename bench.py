@@ -86,6 +86,16 @@ def run_step_bf16(lin, ws):
     binding.mxfp4_bf16_gemm_argmax(t["x"], t["w"], workspace=ws, out=(t["idx"], t["val"]))
 
 
+def run_verify5_bf16(lin, ws):
+    """The target's verification pass over N + 1 = 5 rows on the unquantised weights (section 3.1)."""
+    from paper_2503_13565_amd import binding
+    for name in ("qkv", "o", "gate_up", "down"):
+        t = lin[name]
+        binding.mxfp4_bf16_gemm(t["x5"], t["w"], y=t["y5"])
+    t = lin["lm_head"]
+    binding.mxfp4_bf16_gemm_argmax(t["x5"], t["w"], workspace=ws, out=(t["idx5"], t["val5"]))
+
+
 def run_step_e4m3(lin, ws):
     """The same step on an 8-bit draft (E4M3 elements with block scales)."""
     from paper_2503_13565_amd import binding
@@ -155,17 +165,21 @@ def run_dominant(lin, ws):
         binding.mxfp4_woq_gemm(t["x"], t["q"], t["s"], y=t["y"])
 
 
-def eq1_projection(s_measured: float):
+def eq1_projection(s_measured: float, verify_cost: float = 1.0):
     """Expected speed-ups of Eq. 1 (arXiv 2503.13565, section 3.2) and of its two-level composition
     (section 3.3) with the draft speed-up S measured here and the acceptance ratios the paper
-    reports for its models (sections 4.2, 4.3) as inputs.  N = 4 draft tokens as in the text."""
+    reports for its models (sections 4.2, 4.3) as inputs.  N = 4 draft tokens as in the text.
+    Eq. 1 prices the verification pass at one target step; `verify_cost` is what it costs here (the
+    target's pass over N + 1 rows over its single-row step), and the last figure of each entry uses
+    it: (alpha N + 1) / (verify_cost + N / S)."""
     def one(alpha, n, s):
         return (alpha + 1.0 / n) / (1.0 / n + 1.0 / s)
 
     def two(a_mid, s_mid, a_last, s_last, n=4.0):
         return one(a_mid, n, s_mid * one(a_last, n, s_last / s_mid))
     n = 4.0
-    out = {"N": 4, "S_mxfp4_measured": round(s_measured, 3), "S_mxfp4_by_bytes": 3.765}
+    out = {"N": 4, "S_mxfp4_measured": round(s_measured, 3), "S_mxfp4_by_bytes": 3.765,
+           "verify_cost_5_rows_over_1": round(verify_cost, 3)}
     for tag, a_q, a_t, s_t in (("llama2_7b_like", 0.712, 0.417, 100.0), ("qwen2.5_7b_like", 0.91, 0.62, 14.0)):
         out[tag] = {
             "alpha_mxfp4_draft": a_q, "alpha_small_draft": a_t, "S_small_draft_assumed": s_t,
@@ -173,6 +187,8 @@ def eq1_projection(s_measured: float):
             "one_level_mxfp4_draft_at_S_by_bytes": round(one(a_q, n, 3.765), 3),
             "one_level_small_draft": round(one(a_t, n, s_t), 3),
             "two_level": round(two(a_q, s_measured, a_t, s_t), 3),
+            "one_level_mxfp4_draft_with_measured_verify_cost":
+                round((a_q * n + 1.0) / (verify_cost + n / s_measured), 3),
         }
     return out
 
@@ -258,6 +274,62 @@ def cpu_baseline(m: int):
                   "(not in value)" % (m, reps, t_gemm, t_cast),
         "seconds_per_step": per_step,
     }
+
+
+def run_stack_bf16(args) -> int:
+    """The same stack with unquantised BF16 weights (the target model's step and verification pass;
+    arXiv 2503.13565, section 3.2): what the MXFP4 stack's times are compared with."""
+    import torch
+    from paper_2503_13565_amd import binding, synth
+    shape = synth.LLAMA_7B if args.workload == "stack7b" else synth.LLAMA_70B
+    layers = args.layers or shape.layers
+    m = args.m
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    binding.load()
+    ops = []
+    for layer in range(layers + 1):
+        for li, (name, n, k) in enumerate(shape.linears()):
+            if (layer < layers) == (name == "lm_head"):
+                continue
+            seed = synth.tensor_seed(0, layer, li)
+            ops.append(dict(name=name, n=n, k=k, w=synth.weights_student_t(n, k, seed=seed, device=dev),
+                            x=synth.activations_outlier_channels(m, k, seed=seed + 8, device=dev),
+                            y=torch.empty((m, n), dtype=torch.bfloat16, device=dev)))
+    head = ops[-1]
+    head["idx"] = torch.empty((m,), dtype=torch.int32, device=dev)
+    head["val"] = torch.empty((m,), dtype=torch.float32, device=dev)
+    ws = torch.empty((binding.mxfp4_bf16_gemm_argmax_workspace_bytes(m, head["n"], head["k"]),),
+                     dtype=torch.uint8, device=dev)
+
+    def step(_lin=None, _ws=None):
+        for t in ops[:-1]:
+            binding.mxfp4_bf16_gemm(t["x"], t["w"], y=t["y"])
+        binding.mxfp4_bf16_gemm_argmax(head["x"], head["w"], workspace=ws, out=(head["idx"], head["val"]))
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step()
+    torch.cuda.synchronize()
+    graph = None if args.no_graph else capture(step, [None], ws, stream)
+    run = runner(graph, step, [None], ws)
+    steps = max(1, args.steps // 24)
+    timed(run, max(1, args.warmup // 12), stream)
+    ms_per_step = timed(run, steps, stream) / steps
+    step_bytes = sum(2.0 * t["n"] * t["k"] + 2.0 * m * t["k"] + 2.0 * m * t["n"] for t in ops)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "BF16-weight linear stack, effective HBM GB/s (the unquantised reference of the MXFP4 stack)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": max(1, args.warmup // 12),
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s with BF16 weights: %d layers x (qkv, o, gate_up, down) + lm_head with argmax, "
+                               "M=%d, %.2f GB resident" % (shape.name, layers, m,
+                                                           sum(2.0 * t["n"] * t["k"] for t in ops) / 1e9),
+                   "M": m, "launch": "hip graph replay" if graph is not None else "stream launches"},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2), "us_per_step": round(ms_per_step * 1e3, 2),
+        "bytes_per_step": step_bytes, "roofline": None, "cpu_baseline": None}))
+    return 0
 
 
 def run_stack(args) -> int:
@@ -404,6 +476,8 @@ def main() -> int:
                     help="decode7b (default): the five 7B decode linears over rotating weight sets; "
                          "stack7b / stack70b: the whole linear-only decode step of a resident weight stack")
     ap.add_argument("--layers", type=int, default=0, help="stack workloads: layers to build (0 = the model's)")
+    ap.add_argument("--weights", default="mxfp4", choices=["mxfp4", "bf16"],
+                    help="stack workloads: bf16 runs the unquantised reference stack")
     ap.add_argument("--tiled", action="store_true",
                     help="stack workloads: verification passes on the tile-major copy of the weights where it can run")
     args = ap.parse_args()
@@ -419,7 +493,7 @@ def main() -> int:
         return 2
     binding.load()
     if args.workload != "decode7b":
-        return run_stack(args)
+        return run_stack_bf16(args) if args.weights == "bf16" else run_stack(args)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     m = args.m
@@ -515,6 +589,23 @@ def main() -> int:
         timed(run_b, n_bf16, stream)
         nb = n_bf16 * max(2, args.steps // (4 * n_bf16))
         bf16_us = timed(run_b, nb, stream) / nb * 1e3
+        # the target's verification pass over N + 1 = 5 rows on the same BF16 weights
+        for lin in bsets:
+            for t in lin.values():
+                t["x5"] = synth.activations_outlier_channels(5, t["k"], seed=t["n"] + 5, device=dev)
+                t["y5"] = torch.empty((5, t["n"]), dtype=torch.bfloat16, device=dev)
+            lin["lm_head"]["idx5"] = torch.empty((5,), dtype=torch.int32, device=dev)
+            lin["lm_head"]["val5"] = torch.empty((5,), dtype=torch.float32, device=dev)
+        ws5 = torch.empty((binding.mxfp4_bf16_gemm_argmax_workspace_bytes(5, 32000, 4096),), dtype=torch.uint8,
+                          device=dev)
+        with torch.cuda.stream(stream):
+            for lin in bsets:
+                run_verify5_bf16(lin, ws5)
+        torch.cuda.synchronize()
+        vgraph = None if args.no_graph else capture(run_verify5_bf16, bsets, ws5, stream)
+        run_v = runner(vgraph, run_verify5_bf16, bsets, ws5)
+        timed(run_v, n_bf16, stream)
+        bf16_verify5_us = timed(run_v, nb, stream) / nb * 1e3
         # further variants on the same four weight sets, each timed like the step above: an 8-bit
         # draft, the decoder layer with fused epilogues, and an 8-row verification pass on the
         # canonical and on the tile-major weights
@@ -547,7 +638,7 @@ def main() -> int:
         }
         for lin in bsets:
             for t in lin.values():
-                for key in ("q8", "s8", "q6", "s6", "x8", "y8", "tw", "h"):
+                for key in ("q8", "s8", "q6", "s6", "x8", "y8", "x5", "y5", "tw", "h"):
                     t.pop(key, None)
 
     # what a plain 128-bit read stream gets on this device, over 4 GiB (context for frac)
@@ -606,7 +697,8 @@ def main() -> int:
                      "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_launch_us, 3)},
     }
     if bf16_us is not None:
-        out["eq1_projection"] = eq1_projection(bf16_us / (graph_ms_per_step * 1e3))
+        out["eq1_projection"] = eq1_projection(bf16_us / (graph_ms_per_step * 1e3), bf16_verify5_us / bf16_us)
+        out["bf16_weights_verify_5_rows_us"] = round(bf16_verify5_us, 2)
         out["variants"] = variants
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(m)
