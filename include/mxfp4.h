@@ -286,7 +286,9 @@ int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx,
  * with the same rules and workspace contract as mxfp4_woq_gemm_argmax.
  *   w_bf16 in BF16 [N, K], row stride ldw (ldw >= K, ldw % 8 == 0, base 16-byte aligned);
  *   K a positive multiple of 8, at most MXFP4_MAX_K; the weights of one call stay below 2 GiB.
- * Other arguments as for mxfp4_woq_gemm.  Up to 8 activation rows share one pass over the weights.
+ * Other arguments as for mxfp4_woq_gemm.  Up to 8 activation rows share one pass over the weights
+ * on the vector ALUs (K in phases inside the kernel when the rows do not fit the LDS whole), up
+ * to 16 on the matrix cores (M > 8, K % 128 == 0, rows that fit the LDS); more rows take passes.
  */
 int mxfp4_bf16_gemm(const void* x_bf16, int64_t M, int64_t ldx,
                     const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
