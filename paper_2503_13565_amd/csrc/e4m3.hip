@@ -14,6 +14,8 @@
 // (two weights each) and v_dot2_f32_bf16 with FP32 accumulation.  At one byte per weight the
 // vector ALUs keep up with memory for up to four activation rows per pass (8 converts + 8 dot2 per
 // row and 16 bytes); more rows take more passes.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 #include "../../include/mxfp4.h"
@@ -451,7 +453,11 @@ hipError_t launch_e4m3_gemv(const GemmArgs& a, const DeviceInfo& dev, int* parts
     int first_blocks = 0;
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
-        int mt = left > 2 ? 4 : (left > 1 ? 2 : 1);
+        static const int max_mt = [] {
+            const char* e = getenv("MXFP4_E4M3_MAX_ROWS");           // measurement only
+            return e ? atoi(e) : 8;
+        }();
+        int mt = left > 4 && max_mt >= 8 ? 8 : (left > 2 ? 4 : (left > 1 ? 2 : 1));
         while (mt > 1 && (size_t)mt * a.k * 2 > (size_t)dev.lds_bytes)
             mt >>= 1;
         const size_t lds = (size_t)mt * a.k * 2 < 256 ? 256 : (size_t)mt * a.k * 2;   // the argmax combine needs a few bytes
@@ -470,6 +476,9 @@ hipError_t launch_e4m3_gemv(const GemmArgs& a, const DeviceInfo& dev, int* parts
             blocks = first_blocks;
         hipError_t e;
         switch (mt) {
+        case 8:
+            e = launch_rows<8>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
+            break;
         case 4:
             e = launch_rows<4>(a, m0, r, nw, blocks, lds, dev.lds_bytes, stream);
             break;
