@@ -757,7 +757,12 @@ static int run_e4m3(const void* x, int64_t M, int64_t ldx, const void* q8, const
         return e && atoi(e) != 0;
     }();
     const bool reg = !general_only && aligned(s, 4) && gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a);
-    hipError_t e = reg ? launch_gemv_reg(a, dev, &parts_used, st, nullptr, 8) : launch_e4m3_gemv(a, dev, &parts_used, st);
+    // five and more rows: the matrix-core tiles when a pass's activation rows fit the LDS (up to
+    // four rows the vector-ALU kernel is faster: 13.5 against 16.8 us on the 7B qkv shape)
+    const bool tiles = !general_only && !reg && a.m >= 5 && aligned(s, 4) && aligned(q8, 16) && mfma_tile_can_run(a, dev);
+    hipError_t e = reg     ? launch_gemv_reg(a, dev, &parts_used, st, nullptr, 8)
+                   : tiles ? launch_mfma_tile8(a, dev, &parts_used, st)
+                           : launch_e4m3_gemv(a, dev, &parts_used, st);
     if (e != hipSuccess)
         return hip_fail(e, "8-bit product launch");
     if (argmax) {

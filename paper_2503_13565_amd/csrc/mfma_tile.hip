@@ -54,12 +54,16 @@ size_t tile_lds_bytes(int k, int mp, int nw = kTileNW)
 // phase_steps) of K (phase_steps a multiple of four), holds only that part of the activation rows
 // in LDS, and writes FP32 partial products to `out` = float [phases][M][N]; a second kernel adds
 // them.  For passes whose activation rows do not fit the LDS whole.
-template <int MP, int NW, int D, bool kTiled, class Epi>
+// kBits: 4, or 8 for the 8-bit draft format (q = q8 [N, K], one E4M3 byte per element, row-major only):
+// a lane's block is then 32 bytes, two loads per step, and MFMA j takes bytes 8 j .. 8 j + 7 of it
+// through four v_cvt_scalef32_pk_bf16_fp8; everything else is shared.
+template <int MP, int NW, int D, bool kTiled, class Epi, int kBits = 4>
 __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, const uint8_t* __restrict__ q,
                                                const uint8_t* __restrict__ s, void* out, int n, int k, int m,
                                                int m0, int ldx, int ldy, int parts, const Epi& epi,
                                                int phase_steps = 0)
 {
+    static_assert(kBits == 4 || (kBits == 8 && !kTiled), "element width");
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     constexpr int T = (NW + 1) * 64;
     extern __shared__ __align__(16) uint8_t smem[];
@@ -90,7 +94,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
     const int nblk = k >> 5;
-    const int q_row_bytes = k >> 1;
+    const int q_row_bytes = kBits == 8 ? k : k >> 1;
     const int n_items = (steps + 3) >> 2;                               // items per tile (of this K range)
     const int n_items_all = (steps_all + 3) >> 2;
     const int ipw = (n_items + NW - 1) / NW;                            // items per wave and tile
@@ -104,7 +108,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
         const_cast<uint8_t*>(s), 0, kTiled ? n_tiles * n_items_all * 256 : n * nblk, 0x00020000);
 
     struct Item {
-        u32x4_t q[4];       // 32 nibbles per step
+        u32x4_t q[kBits == 8 ? 8 : 4];      // 32 elements per step (8-bit: two loads of 16)
         u32x4_t sc;         // the row's 16 scale bytes of the item: dword u = step u, byte g = block 4u + g
     };
     Item buf[D];
@@ -131,12 +135,19 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                                                           ((tile * n_items_all + (t0 >> 2) + item) * 256) & mk, 0);
         } else {
             const int row = min(tile * 16 + li, n - 1);                 // ragged N: repeat the last row
-            const int vq = row * q_row_bytes + lg * 16;
+            const int vq = row * q_row_bytes + lg * (kBits == 8 ? 32 : 16);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int mk = -(have & (int)(item * 4 + u < steps));   // all ones when the step exists
-                it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(
-                    rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 64) & mk) | ((u * 16) & ~mk), 0);
+                if constexpr (kBits == 8) {
+                    it.q[2 * u] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 128) & mk) | ((u * 32) & ~mk), 0);
+                    it.q[2 * u + 1] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 128 + 16) & mk) | ((u * 32 + 16) & ~mk), 0);
+                } else {
+                    it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 64) & mk) | ((u * 16) & ~mk), 0);
+                }
             }
             const int mk = -have;
             it.sc = __builtin_amdgcn_raw_buffer_load_b128(rs, ((row * nblk) & mk) | (kOob & ~mk),
@@ -295,12 +306,21 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                         xb[j] = xs[(Tq * 16 + 4 * j + lg) * MP + (col ^ ((4 * lg + j) & (MP - 1)))];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const uint32_t qd = it.q[u][j];
                         u32x4_t w;
-                        w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 0));
-                        w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 1));
-                        w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 2));
-                        w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 3));
+                        if constexpr (kBits == 8) {
+                            const uint32_t q0 = it.q[2 * u + (j >> 1)][2 * (j & 1)];
+                            const uint32_t q1 = it.q[2 * u + (j >> 1)][2 * (j & 1) + 1];
+                            w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q0, scl, false));
+                            w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q0, scl, true));
+                            w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q1, scl, false));
+                            w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q1, scl, true));
+                        } else {
+                            const uint32_t qd = it.q[u][j];
+                            w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 0));
+                            w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 1));
+                            w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 2));
+                            w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 3));
+                        }
                         if (j & 1)
                             acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
                                                                            __builtin_bit_cast(bf16x8_t, xb[j]), acc1, 0, 0, 0);
@@ -345,6 +365,16 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_fused_kernel(
 {
     mfma_tile_body<MP, NW, D, kTiled>(x, q, s, out, n, k, m, m0, ldx, ldy, parts,
                                       Epilogue{bias, residual, ldr, act});
+}
+
+// The 8-bit draft format (row-major q8), plain and argmax forms.
+template <int MP, int NW, int D>
+__global__ __launch_bounds__((NW + 1) * 64) void mfma_tile8_kernel(const uint16_t* __restrict__ x,
+                                                                   const uint8_t* __restrict__ q,
+                                                                   const uint8_t* __restrict__ s, void* out, int n,
+                                                                   int k, int m, int m0, int ldx, int ldy, int parts)
+{
+    mfma_tile_body<MP, NW, D, false, NoEpilogue, 8>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{});
 }
 
 // K split in space: the last preloaded argument is the number of steps per grid row.
@@ -418,6 +448,25 @@ hipError_t launch_pass(const GemmArgs& a, int m0, int blocks, size_t lds, const 
         hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
                            argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, a.m, m0,
                            (int)a.ldx, (int)a.ldy, argmax ? a.parts : 0);
+    return hipGetLastError();
+}
+
+template <int MP, int NW>
+hipError_t launch_pass8(const GemmArgs& a, int m0, int blocks, size_t lds, const DeviceInfo& dev, hipStream_t stream)
+{
+    auto kern = mfma_tile8_kernel<MP, NW, 2>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    const bool argmax = a.part_val != nullptr;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
+                       argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, a.m, m0,
+                       (int)a.ldx, (int)a.ldy, argmax ? a.parts : 0);
     return hipGetLastError();
 }
 
@@ -502,6 +551,38 @@ hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases,
     return mp == 16  ? launch_split_pass<16, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
            : mp == 8 ? launch_split_pass<8, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
                      : launch_split_pass<4, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
+}
+
+// The 8-bit draft format on the tile kernel: a.q = q8 [N, K]; shapes as mfma_tile_can_run; two
+// workgroups of four compute waves per compute unit when the LDS allows, else one of eight.
+hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+{
+    const int n_tiles = (a.n + 15) / 16;
+    const size_t widest = tile_lds_bytes(a.k, tile_pass_width(a.m));
+    const bool two = 2 * widest + 2048 <= (size_t)dev.lds_bytes;
+    int blocks = dev.cus * (two ? 2 : 1);
+    blocks = blocks > n_tiles ? n_tiles : blocks;
+    blocks = blocks > gemv_max_parts(dev) ? gemv_max_parts(dev) : blocks;
+    if (parts_used)
+        *parts_used = blocks;
+    for (int m0 = 0; m0 < a.m;) {
+        const int mp = tile_pass_width(a.m - m0);
+        const bool wide = !two && tile_lds_bytes(a.k, mp, 8) <= (size_t)dev.lds_bytes;
+        const size_t lds = tile_lds_bytes(a.k, mp, wide ? 8 : kTileNW);
+        hipError_t e;
+        if (wide)
+            e = mp == 16  ? launch_pass8<16, 8>(a, m0, blocks, lds, dev, stream)
+                : mp == 8 ? launch_pass8<8, 8>(a, m0, blocks, lds, dev, stream)
+                          : launch_pass8<4, 8>(a, m0, blocks, lds, dev, stream);
+        else
+            e = mp == 16  ? launch_pass8<16, kTileNW>(a, m0, blocks, lds, dev, stream)
+                : mp == 8 ? launch_pass8<8, kTileNW>(a, m0, blocks, lds, dev, stream)
+                          : launch_pass8<4, kTileNW>(a, m0, blocks, lds, dev, stream);
+        if (e != hipSuccess)
+            return e;
+        m0 += mp;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
