@@ -907,7 +907,11 @@ static int run_e2m3(const void* x, int64_t M, int64_t ldx, const void* q6, const
         return fail(MXFP4_ERR_SHAPE, "the 6-bit product needs K %% 128 == 0, K <= 32768 and N >= %d", dev.cus * 8);
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
-    hipError_t e = launch_gemv_reg(a, dev, &parts_used, st, nullptr, 6);
+    // three and more rows: the matrix-core tiles when a pass's activation rows fit the LDS, else
+    // passes of the decode kernel over the weights
+    const bool tiles = a.m >= 3 && mfma_tile_can_run(a, dev);
+    hipError_t e = tiles ? launch_mfma_tile8(a, dev, &parts_used, st, 6)
+                         : launch_gemv_reg(a, dev, &parts_used, st, nullptr, 6);
     if (e != hipSuccess)
         return hip_fail(e, "6-bit product launch");
     if (argmax) {

@@ -98,8 +98,10 @@ bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev);
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                             bool tiled = false, const Epilogue* epi = nullptr);
 
-// The 8-bit draft format (a.q = q8 [N, K]) on the same tiles; shapes as mfma_tile_can_run.
-hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+// The 8-bit (a.q = q8 [N, K]) and 6-bit (a.q = q6) draft formats on the same tiles; shapes as
+// mfma_tile_can_run; `bits` 8 or 6.
+hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
+                             int bits = 8);
 
 // The tile kernel with K split in space for passes whose activation rows do not fit the LDS:
 // FP32 partial products to ws = float [phases][M][N] (mfma.hip's finish kernel adds them).

@@ -56,14 +56,21 @@ size_t tile_lds_bytes(int k, int mp, int nw = kTileNW)
 // them.  For passes whose activation rows do not fit the LDS whole.
 // kBits: 4, or 8 for the 8-bit draft format (q = q8 [N, K], one E4M3 byte per element, row-major only):
 // a lane's block is then 32 bytes, two loads per step, and MFMA j takes bytes 8 j .. 8 j + 7 of it
-// through four v_cvt_scalef32_pk_bf16_fp8; everything else is shared.
+// through four v_cvt_scalef32_pk_bf16_fp8; or 6 for the 6-bit draft format (q = q6, 24 bytes per
+// block as a bit string, row-major only): 16 + 8 bytes per step and one
+// v_cvt_scalef32_pk32_bf16_fp6 for the whole block, whose 16 result registers are the operands of
+// the step's four matrix instructions.  Everything else is shared.
+typedef __attribute__((ext_vector_type(2))) unsigned int t_u32x2_t;
+typedef __attribute__((ext_vector_type(6))) unsigned int t_u32x6_t;
+typedef __attribute__((ext_vector_type(16))) unsigned int t_u32x16_t;
+
 template <int MP, int NW, int D, bool kTiled, class Epi, int kBits = 4>
 __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, const uint8_t* __restrict__ q,
                                                const uint8_t* __restrict__ s, void* out, int n, int k, int m,
                                                int m0, int ldx, int ldy, int parts, const Epi& epi,
                                                int phase_steps = 0)
 {
-    static_assert(kBits == 4 || (kBits == 8 && !kTiled), "element width");
+    static_assert(kBits == 4 || ((kBits == 8 || kBits == 6) && !kTiled), "element width");
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     constexpr int T = (NW + 1) * 64;
     extern __shared__ __align__(16) uint8_t smem[];
@@ -94,7 +101,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
     const int nblk = k >> 5;
-    const int q_row_bytes = kBits == 8 ? k : k >> 1;
+    const int q_row_bytes = kBits == 8 ? k : (kBits == 6 ? (k >> 5) * 24 : k >> 1);
     const int n_items = (steps + 3) >> 2;                               // items per tile (of this K range)
     const int n_items_all = (steps_all + 3) >> 2;
     const int ipw = (n_items + NW - 1) / NW;                            // items per wave and tile
@@ -109,6 +116,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
 
     struct Item {
         u32x4_t q[kBits == 8 ? 8 : 4];      // 32 elements per step (8-bit: two loads of 16)
+        t_u32x2_t qh[kBits == 6 ? 4 : 1];   // 6-bit: bytes 16 .. 23 of the block
         u32x4_t sc;         // the row's 16 scale bytes of the item: dword u = step u, byte g = block 4u + g
     };
     Item buf[D];
@@ -135,7 +143,7 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                                                           ((tile * n_items_all + (t0 >> 2) + item) * 256) & mk, 0);
         } else {
             const int row = min(tile * 16 + li, n - 1);                 // ragged N: repeat the last row
-            const int vq = row * q_row_bytes + lg * (kBits == 8 ? 32 : 16);
+            const int vq = row * q_row_bytes + lg * (kBits == 8 ? 32 : (kBits == 6 ? 24 : 16));
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int mk = -(have & (int)(item * 4 + u < steps));   // all ones when the step exists
@@ -144,6 +152,11 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                         rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 128) & mk) | ((u * 32) & ~mk), 0);
                     it.q[2 * u + 1] = __builtin_amdgcn_raw_buffer_load_b128(
                         rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 128 + 16) & mk) | ((u * 32 + 16) & ~mk), 0);
+                } else if constexpr (kBits == 6) {
+                    it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 96) & mk) | ((u * 32) & ~mk), 0);
+                    it.qh[u] = __builtin_amdgcn_raw_buffer_load_b64(
+                        rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 96 + 16) & mk) | ((u * 32 + 16) & ~mk), 0);
                 } else {
                     it.q[u] = __builtin_amdgcn_raw_buffer_load_b128(
                         rq, (vq & mk) | (kOob & ~mk), (((t0 + item * 4 + u) * 64) & mk) | ((u * 16) & ~mk), 0);
@@ -304,10 +317,20 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         xb[j] = xs[(Tq * 16 + 4 * j + lg) * MP + (col ^ ((4 * lg + j) & (MP - 1)))];
+                    t_u32x16_t w6 = {};
+                    if constexpr (kBits == 6) {
+                        const u32x4_t lo = it.q[u];
+                        const t_u32x2_t hi = it.qh[u];
+                        const t_u32x6_t packed = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1]};
+                        w6 = __builtin_bit_cast(t_u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(packed, scl));
+                    }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         u32x4_t w;
-                        if constexpr (kBits == 8) {
+                        if constexpr (kBits == 6) {
+                            const uint32_t w0 = w6[4 * j], w1 = w6[4 * j + 1], w2 = w6[4 * j + 2], w3 = w6[4 * j + 3];
+                            w = u32x4_t{w0, w1, w2, w3};
+                        } else if constexpr (kBits == 8) {
                             const uint32_t q0 = it.q[2 * u + (j >> 1)][2 * (j & 1)];
                             const uint32_t q1 = it.q[2 * u + (j >> 1)][2 * (j & 1) + 1];
                             w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q0, scl, false));
@@ -367,14 +390,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_fused_kernel(
                                       Epilogue{bias, residual, ldr, act});
 }
 
-// The 8-bit draft format (row-major q8), plain and argmax forms.
-template <int MP, int NW, int D>
+// The 8-bit and 6-bit draft formats (row-major q8 / q6), plain and argmax forms.
+template <int MP, int NW, int D, int kBits>
 __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile8_kernel(const uint16_t* __restrict__ x,
                                                                    const uint8_t* __restrict__ q,
                                                                    const uint8_t* __restrict__ s, void* out, int n,
                                                                    int k, int m, int m0, int ldx, int ldy, int parts)
 {
-    mfma_tile_body<MP, NW, D, false, NoEpilogue, 8>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{});
+    mfma_tile_body<MP, NW, D, false, NoEpilogue, kBits>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{});
 }
 
 // K split in space: the last preloaded argument is the number of steps per grid row.
@@ -451,10 +474,10 @@ hipError_t launch_pass(const GemmArgs& a, int m0, int blocks, size_t lds, const 
     return hipGetLastError();
 }
 
-template <int MP, int NW>
+template <int MP, int NW, int kBits>
 hipError_t launch_pass8(const GemmArgs& a, int m0, int blocks, size_t lds, const DeviceInfo& dev, hipStream_t stream)
 {
-    auto kern = mfma_tile8_kernel<MP, NW, 2>;
+    auto kern = mfma_tile8_kernel<MP, NW, 2, kBits>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -553,13 +576,19 @@ hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases,
                      : launch_split_pass<4, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
 }
 
-// The 8-bit draft format on the tile kernel: a.q = q8 [N, K]; shapes as mfma_tile_can_run; two
-// workgroups of four compute waves per compute unit when the LDS allows, else one of eight.
-hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
+// The 8-bit (a.q = q8 [N, K]) and 6-bit (a.q = q6) draft formats on the tile kernel; shapes as
+// mfma_tile_can_run; two workgroups of four compute waves per compute unit when the LDS allows,
+// else one of eight.
+template <int kBits>
+hipError_t launch_tile_fmt(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
 {
     const int n_tiles = (a.n + 15) / 16;
     const size_t widest = tile_lds_bytes(a.k, tile_pass_width(a.m));
-    const bool two = 2 * widest + 2048 <= (size_t)dev.lds_bytes;
+    static const int env_one = [] { const char* e = getenv("MXFP4_TILE_FMT_ONE_WG"); return e ? atoi(e) : -1; }();   // measurement only
+    // Two workgroups of four waves per CU only where the tiles are few (fewer than two per wave of the
+    // wide form): from there on one workgroup of eight waves measured 4-12 % faster in these formats.
+    const bool few = n_tiles < 2 * dev.cus;
+    const bool two = (env_one >= 0 ? env_one == 0 : few) && 2 * widest + 2048 <= (size_t)dev.lds_bytes;
     int blocks = dev.cus * (two ? 2 : 1);
     blocks = blocks > n_tiles ? n_tiles : blocks;
     blocks = blocks > gemv_max_parts(dev) ? gemv_max_parts(dev) : blocks;
@@ -571,18 +600,25 @@ hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* part
         const size_t lds = tile_lds_bytes(a.k, mp, wide ? 8 : kTileNW);
         hipError_t e;
         if (wide)
-            e = mp == 16  ? launch_pass8<16, 8>(a, m0, blocks, lds, dev, stream)
-                : mp == 8 ? launch_pass8<8, 8>(a, m0, blocks, lds, dev, stream)
-                          : launch_pass8<4, 8>(a, m0, blocks, lds, dev, stream);
+            e = mp == 16  ? launch_pass8<16, 8, kBits>(a, m0, blocks, lds, dev, stream)
+                : mp == 8 ? launch_pass8<8, 8, kBits>(a, m0, blocks, lds, dev, stream)
+                          : launch_pass8<4, 8, kBits>(a, m0, blocks, lds, dev, stream);
         else
-            e = mp == 16  ? launch_pass8<16, kTileNW>(a, m0, blocks, lds, dev, stream)
-                : mp == 8 ? launch_pass8<8, kTileNW>(a, m0, blocks, lds, dev, stream)
-                          : launch_pass8<4, kTileNW>(a, m0, blocks, lds, dev, stream);
+            e = mp == 16  ? launch_pass8<16, kTileNW, kBits>(a, m0, blocks, lds, dev, stream)
+                : mp == 8 ? launch_pass8<8, kTileNW, kBits>(a, m0, blocks, lds, dev, stream)
+                          : launch_pass8<4, kTileNW, kBits>(a, m0, blocks, lds, dev, stream);
         if (e != hipSuccess)
             return e;
         m0 += mp;
     }
     return hipSuccess;
+}
+
+hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream, int bits)
+{
+    return bits == 8   ? launch_tile_fmt<8>(a, dev, parts_used, stream)
+           : bits == 6 ? launch_tile_fmt<6>(a, dev, parts_used, stream)
+                       : hipErrorInvalidValue;
 }
 
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,

@@ -89,6 +89,23 @@ def test_product_edge_shapes(n, k, m):
     assert_argmax_ok(idx, val, y_ref, a_ref, "e2m3 argmax N=%d K=%d M=%d" % (n, k, m))
 
 
+@pytest.mark.parametrize("n,k", [(2048, 128), (2500, 4096), (2049, 2176), (2100, 11008)])
+@pytest.mark.parametrize("m", [4, 5, 8, 9, 16, 17])
+def test_product_verification_rows(n, k, m):
+    # three and more rows: the matrix-core tiles where a pass's rows fit the LDS, else passes
+    w = synth.weights_student_t(n, k, seed=500 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=600 + m + k)
+    q, s, q_ref, s_ref = cast_both_ways(w)
+    y_ref, a_ref = oracle.e2m3_woq_gemm(synth.to_bits(x), q_ref, s_ref)
+    xg = x.to(DEV)
+    y = binding.mxfp4_e2m3_woq_gemm(xg, q, s)
+    torch.cuda.synchronize()
+    assert_gemm_close(y, y_ref, a_ref, "e2m3 tiles N=%d K=%d M=%d" % (n, k, m))
+    idx, val = binding.mxfp4_e2m3_woq_gemm_argmax(xg, q, s)
+    torch.cuda.synchronize()
+    assert_argmax_ok(idx, val, y_ref, a_ref, "e2m3 tiles argmax N=%d K=%d M=%d" % (n, k, m))
+
+
 def test_product_llama_shape_refusals_and_nan_block():
     data = synth.llama_linear(synth.LLAMA_7B, "o", m=1, seed=4)
     q, s, q_ref, s_ref = cast_both_ways(data["w"], "o")
