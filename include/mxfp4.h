@@ -225,7 +225,14 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx,
  *              the meaning, layout and alignment rules of the arguments of the same name of
  *              mxfp4_woq_gemm_fused and mxfp4_woq_gemm_argmax; `flags` is 0 or MXFP4_DESC_TILED:
  *              q_packed and scales_e8m0 are then the tile-major pair of mxfp4_tile_repack and the
- *              product is the mxfp4_woq_gemm_tiled_* call of the same kind (other bits: error)
+ *              product is the mxfp4_woq_gemm_tiled_* call of the same kind;
+ *              MXFP4_DESC_INDEPENDENT (ignored together with MXFP4_DESC_TILED): the caller states that
+ *              this product reads no output of the descriptors next to it that carry the flag too
+ *              and that none of them reads or overwrites its outputs; consecutive such
+ *              descriptors may then run in one launch, in any order or at once (taken for up to 8
+ *              products with M = 1, the same K <= 8192, no bias, act or residual, at most one with
+ *              argmax_out, each a shape of the decode kernel; same bits as the single calls;
+ *              otherwise the flag changes nothing).  Other bits: error
  *   workspace  device scratch shared by all products: optional as in mxfp4_woq_gemm_ws when no
  *              descriptor asks for the argmax, required as in mxfp4_woq_gemm_argmax otherwise;
  *              mxfp4_woq_gemm_grouped_workspace_bytes gives the size that serves every
@@ -252,7 +259,7 @@ typedef struct mxfp4_gemm_desc {
     int32_t act;
     int32_t flags;
 } mxfp4_gemm_desc;
-enum { MXFP4_DESC_TILED = 1 };
+enum { MXFP4_DESC_TILED = 1, MXFP4_DESC_INDEPENDENT = 2 };
 size_t mxfp4_woq_gemm_grouped_workspace_bytes(const mxfp4_gemm_desc* descs, int64_t count);
 int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count,
                            void* workspace, size_t workspace_bytes, void* stream);

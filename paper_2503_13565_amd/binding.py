@@ -489,6 +489,7 @@ def mxfp4_woq_gemm_fused(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, bias
 
 
 DESC_TILED = 1
+DESC_INDEPENDENT = 2
 
 
 class GemmGroup:
@@ -498,7 +499,8 @@ class GemmGroup:
     ``argmax=True`` (optionally ``out=(idx int32 [M], val float32 [M])``) for the fused pick, whose
     entry in ``ys`` is the ``(idx, val)`` pair.  The tensors are kept alive by the group; ``ys`` lists
     the outputs in order.  An item with ``w`` (a ``TiledWeights``) in place of ``q`` and ``s`` runs on
-    the tile-major copy."""
+    the tile-major copy.  ``independent=True`` on an item sets ``MXFP4_DESC_INDEPENDENT``: neighbouring
+    items that carry it and do not read each other's outputs may share one launch."""
 
     def __init__(self, items):
         self._keep, self.ys = [], []
@@ -515,6 +517,8 @@ class GemmGroup:
                 q, s = it["q"], it["s"]
                 m, n, k, ldx = _gemm_shapes(x, q, s)
                 d.flags = 0
+            if it.get("independent"):
+                d.flags |= DESC_INDEPENDENT
             d.x_bf16, d.M, d.ldx = x.data_ptr(), m, ldx
             d.q_packed, d.scales_e8m0, d.N, d.K = q.data_ptr(), s.data_ptr(), n, k
             d.act = act

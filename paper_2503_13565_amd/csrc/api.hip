@@ -508,7 +508,7 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx, const void*
 
 static int grouped_one(const mxfp4_gemm_desc& d, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if ((d.flags & ~MXFP4_DESC_TILED) != 0) {
+    if ((d.flags & ~(MXFP4_DESC_TILED | MXFP4_DESC_INDEPENDENT)) != 0) {
         g_err[0] = 0;
         return fail(MXFP4_ERR_ARG, "unknown flags %#x", (unsigned)d.flags);
     }
@@ -539,6 +539,41 @@ static int grouped_one(const mxfp4_gemm_desc& d, void* workspace, size_t workspa
                              workspace_bytes, MXFP4_PATH_AUTO, stream);
 }
 
+// How many descriptors from descs[0] on can share one launch (0 or 1: none).  Only descriptors that
+// have passed the checks of their single call come here.
+static int merged_run(const mxfp4_gemm_desc* descs, int64_t left, const DeviceInfo& dev, void* workspace,
+                      GemmArgs* items)
+{
+    int run = 0;
+    for (int j = 0; j < kMultiMax && j < left; ++j) {
+        const mxfp4_gemm_desc& d = descs[j];
+        if (d.flags != MXFP4_DESC_INDEPENDENT || d.M != 1 || d.K != descs[0].K || d.bias_bf16 || d.residual_bf16 ||
+            d.act != MXFP4_ACT_NONE)
+            break;
+        GemmArgs a{};
+        a.x = static_cast<const uint16_t*>(d.x_bf16);
+        a.ldx = d.ldx;
+        a.q = static_cast<const uint8_t*>(d.q_packed);
+        a.s = static_cast<const uint8_t*>(d.scales_e8m0);
+        a.m = 1;
+        a.n = (int)d.N;
+        a.k = (int)d.K;
+        if (d.argmax_out) {
+            a.parts = gemv_max_parts(dev);
+            a.part_val = static_cast<float*>(workspace);
+            a.part_idx = reinterpret_cast<int32_t*>(a.part_val + a.parts);
+        } else {
+            a.y = static_cast<uint16_t*>(d.y_bf16);
+            a.ldy = d.ldy;
+        }
+        items[j] = a;
+        if (j > 0 && !gemv_multi_can_run(items, j + 1, dev))
+            break;
+        run = j + 1;
+    }
+    return run;
+}
+
 size_t mxfp4_woq_gemm_grouped_workspace_bytes(const mxfp4_gemm_desc* descs, int64_t count)
 {
     size_t need = 0;
@@ -564,8 +599,32 @@ int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count, void* wo
     if (!descs)
         return fail(MXFP4_ERR_NULL, "descs is NULL");
     // first pass: every check of the single calls and nothing launched; second pass: the launches
+    DeviceInfo dev{};
     for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1) {                                    // (the checks have asked for the device already)
+            const int rc = device_info(&dev);
+            if (rc)
+                return rc;
+        }
         for (int64_t i = 0; i < count; ++i) {
+            GemmArgs items[kMultiMax];
+            const int run = pass == 1 ? merged_run(descs + i, count - i, dev, workspace, items) : 0;
+            if (run >= 2) {
+                hipStream_t st = static_cast<hipStream_t>(stream);
+                int parts_used = 0;
+                hipError_t e = launch_gemv_multi(items, run, dev, &parts_used, st);
+                if (e != hipSuccess)
+                    return hip_fail(e, "merged product launch");
+                for (int j = 0; j < run; ++j)
+                    if (descs[i + j].argmax_out) {
+                        e = launch_argmax_finish(items[j].part_val, items[j].part_idx, items[j].parts, parts_used, 1,
+                                                 descs[i + j].argmax_out, descs[i + j].max_out, st);
+                        if (e != hipSuccess)
+                            return hip_fail(e, "argmax finish launch");
+                    }
+                i += run - 1;
+                continue;
+            }
             g_check_only = pass == 0;
             const int rc = grouped_one(descs[i], workspace, workspace_bytes, stream);
             g_check_only = false;

@@ -668,6 +668,231 @@ hipError_t launch_steps6(const GemmArgs& a, int m0, int steps2, int blocks, size
     return hipErrorInvalidValue;
 }
 
+// ---- several independent products in one launch ----------------------------------------------
+//
+// One token, MXFP4 weights, the same K (up to 8192: activations in registers) and up to kMultiMax
+// products that do not read each other's outputs.  The weight rows of all of them form one list
+// (product p owns the virtual rows [first, first + n)); the list is dealt exactly as in the single
+// product, and a wave that crosses from one product to the next only swaps its buffer descriptors
+// and its activation registers: every product's activation row is staged in LDS when the kernel
+// starts, so there is no barrier, no refill of the load pipeline and no launch between products.
+struct MultiProb {
+    const uint16_t* x;
+    const uint8_t* q;
+    const uint8_t* s;
+    void* out;           // y (BF16 [N]), or the partial winners (float [parts], int32 [parts])
+    int n, first, parts, pad;
+};
+struct MultiArgs {
+    int count, k, total, pad;
+    MultiProb p[kMultiMax];      // unused entries: x of entry 0 (it is loaded), n = 0, first = total
+};
+
+template <int STEPS, bool kRagged>
+__global__ __launch_bounds__(1024) void gemv_multi_kernel(const MultiArgs a)
+{
+    constexpr int NW = 16, D = 2, T = NW * 64;
+    static_assert(STEPS % D == 0 && STEPS * 256 <= T, "one 16-byte activation chunk per thread and product");
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int nblk = a.k >> 5, chunks = a.k >> 3, q_row_bytes = nblk * 16;
+
+    u32x4_t xl[kMultiMax];
+#pragma unroll
+    for (int p = 0; p < kMultiMax; ++p)
+        xl[p] = reinterpret_cast<const u32x4_t*>(a.p[p].x)[min(tid, chunks - 1)];
+
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                     // [count][4][nblk] chunks
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int* ctr = reinterpret_cast<int*>(smem + (size_t)a.count * a.k * 2);
+    float* wv = reinterpret_cast<float*>(ctr + 16);                      // the waves' argmax winners
+    int* wi = reinterpret_cast<int*>(wv + NW);
+    const int G = gridDim.x, b = blockIdx.x;
+    auto row_of = [&](int i) { return i * G + b; };
+    if (tid == 0)
+        *ctr = NW;
+
+    struct Set {
+        __amdgpu_buffer_rsrc_t rq, rs;
+        void* out;
+        int first, n, parts, idx;
+    };
+    // the product that owns virtual row v, looking from product `from` on (v only ever grows)
+    auto set_for = [&](int v, int from) {
+        int idx = from;
+        while (idx < a.count - 1 && v >= a.p[idx].first + a.p[idx].n)
+            ++idx;
+        const MultiProb& pr = a.p[idx];
+        Set st;
+        st.rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(pr.q), 0, pr.n * q_row_bytes, 0x00020000);
+        st.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(pr.s), 0, pr.n * nblk, 0x00020000);
+        st.out = pr.out;
+        st.first = pr.first;
+        st.n = pr.n;
+        st.parts = pr.parts;
+        st.idx = idx;
+        return st;
+    };
+
+    u32x4_t bq[D];
+    uint32_t bs[D];
+    // as in the single product: a step always issues the same loads; past the end of the list (or
+    // of a ragged K) the lane offset leaves the descriptor's range and the load returns zero
+    auto issue = [&](const Set& st, int v, int t, int d) {
+        const bool live = v < a.total;
+        const bool vb = !kRagged || t * 64 + lane < nblk;
+        const int row = live ? v - st.first : 0;
+        bq[d] = __builtin_amdgcn_raw_buffer_load_b128(st.rq, (live && vb) ? lane * 16 : 0x7FFFFFF0,
+                                                      row * q_row_bytes + t * 1024, 2);
+        bs[d] = __builtin_amdgcn_raw_buffer_load_b32(st.rs, live ? row * nblk + (lane & 15) * 4 : 0x7FFFFFF0, t * 64,
+                                                     0);
+    };
+    int grp = row_of(wave);
+    Set cur = set_for(grp, 0);
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        issue(cur, grp, d, d);
+
+    {
+        const int c = min(tid, chunks - 1);                 // clamped duplicates rewrite the same data
+#pragma unroll
+        for (int p = 0; p < kMultiMax; ++p)
+            if (p < a.count)
+                xs[(p * 4 + (c & 3)) * nblk + (c >> 2)] = xl[p];
+    }
+    lds_barrier();
+
+    u32x4_t xr[STEPS][4];
+    auto load_x = [&](int idx) {
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xr[t][j] = (!kRagged || t * 64 + lane < nblk) ? xs[(idx * 4 + j) * nblk + t * 64 + lane]
+                                                              : u32x4_t{0, 0, 0, 0};
+    };
+    load_x(cur.idx);
+
+    float best_val = -INFINITY;         // at most one product of a launch takes the argmax form
+    int best_idx = 0x7FFFFFFF;
+    float res = 0.f, acc = 0.f;
+    int rowv = 0, slots = 0;
+    auto flush = [&](void* out) {
+        if (lane < slots)
+            static_cast<uint16_t*>(out)[rowv] = f32_to_bf16_rne(res);
+        slots = 0;
+        drain_vmem();                   // stores and loads share a counter: the loop sees only loads
+    };
+    auto fetch = [&]() {
+        int v = 0;
+        if (lane == 0)
+            v = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+
+    const int sh_top = (3 - (lane & 3)) * 8;
+    int i_next = fetch();
+    while (grp < a.total) {
+        const int grp_n = row_of(i_next);
+        const int i_next2 = fetch();
+        Set nxt = cur;
+        if (grp_n < a.total && grp_n >= cur.first + cur.n)
+            nxt = set_for(grp_n, cur.idx);
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            const int d = t % D;
+            const uint32_t dw = (uint32_t)__builtin_amdgcn_ds_bpermute((lane >> 2) * 4, (int)bs[d]);
+            float sc = __uint_as_float((dw << sh_top) >> 1);
+            if (kRagged)
+                sc = (t * 64 + lane < nblk) ? sc : 1.0f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t qd = bq[d][j];
+                const bf16x2_t w0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0);
+                const bf16x2_t w1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1);
+                const bf16x2_t w2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2);
+                const bf16x2_t w3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3);
+                const uint32_t x0 = xr[t][j][0], x1 = xr[t][j][1], x2 = xr[t][j][2], x3 = xr[t][j][3];
+                acc = __builtin_amdgcn_fdot2_f32_bf16(w0, __builtin_bit_cast(bf16x2_t, x0), acc, false);
+                acc = __builtin_amdgcn_fdot2_f32_bf16(w1, __builtin_bit_cast(bf16x2_t, x1), acc, false);
+                acc = __builtin_amdgcn_fdot2_f32_bf16(w2, __builtin_bit_cast(bf16x2_t, x2), acc, false);
+                acc = __builtin_amdgcn_fdot2_f32_bf16(w3, __builtin_bit_cast(bf16x2_t, x3), acc, false);
+            }
+            const int tn = t + D;
+            if (tn < STEPS)
+                issue(cur, grp, tn, d);
+            else
+                issue(nxt, grp_n, tn - STEPS, d);
+        }
+        const float v = wave_sum(acc);
+        acc = 0.f;
+        const int row = grp - cur.first;
+        if (cur.parts > 0) {
+            if (v > best_val || (v == best_val && row < best_idx)) {
+                best_val = v;
+                best_idx = row;
+            }
+        } else {
+            res = (lane == slots) ? v : res;
+            rowv = (lane == slots) ? row : rowv;
+            if (++slots == 64)
+                flush(cur.out);
+        }
+        if (nxt.idx != cur.idx) {                           // the next row belongs to another product
+            if (cur.parts == 0 && slots > 0)
+                flush(cur.out);
+            cur = nxt;
+            load_x(cur.idx);
+        }
+        grp = grp_n;
+        i_next = i_next2;
+    }
+    if (cur.parts == 0 && slots > 0)
+        flush(cur.out);
+
+    // the argmax product, if there is one: combine the waves, publish the workgroup's winner
+    int am = -1;
+#pragma unroll
+    for (int p = 0; p < kMultiMax; ++p)
+        am = (p < a.count && a.p[p].parts > 0) ? p : am;
+    if (am >= 0) {
+        if (lane == 0) {
+            wv[wave] = best_val;
+            wi[wave] = best_idx;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            float bv = wv[0];
+            int bi = wi[0];
+            for (int w = 1; w < NW; ++w)
+                if (wv[w] > bv || (wv[w] == bv && wi[w] < bi)) {
+                    bv = wv[w];
+                    bi = wi[w];
+                }
+            float* part_val = static_cast<float*>(a.p[am].out);
+            int32_t* part_idx = reinterpret_cast<int32_t*>(part_val + a.p[am].parts);
+            part_val[b] = bv;
+            part_idx[b] = bi;
+        }
+    }
+}
+
+template <int STEPS, bool kRagged>
+hipError_t launch_multi_one(const MultiArgs& ma, int blocks, size_t lds, hipStream_t stream)
+{
+    static bool attr_set = false;
+    if (!attr_set && lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_multi_kernel<STEPS, kRagged>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess)
+            return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemv_multi_kernel<STEPS, kRagged>), dim3(blocks), dim3(1024), lds, stream, ma);
+    return hipGetLastError();
+}
+
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
 bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
 int waves_for(int steps2, int mt) { return wide_group(steps2, mt) ? 8 : 16; }
@@ -690,6 +915,55 @@ bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev)
     if ((size_t)2 * a.k * 2 + 64 > (size_t)dev.lds_bytes)
         return false;
     return a.n >= dev.cus * 8;
+}
+
+// One launch for `count` products of one token: every one must be a shape the single product takes
+// in registers (K <= 8192), all with the same K, their activation rows together within the LDS.
+bool gemv_multi_can_run(const GemmArgs* items, int count, const DeviceInfo& dev)
+{
+    if (count < 2 || count > kMultiMax)
+        return false;
+    int64_t total = 0;
+    int argmaxes = 0;
+    for (int i = 0; i < count; ++i) {
+        const GemmArgs& a = items[i];
+        if (a.m != 1 || a.k != items[0].k || !gemv_reg_can_run(a, dev) || even_steps(a.k) > 4)
+            return false;
+        argmaxes += a.part_val != nullptr;
+        total += a.n;
+    }
+    const size_t lds = (size_t)count * items[0].k * 2 + 64 + 128;
+    return argmaxes <= 1 && total < 0x7FFFFFFF - 64 * 1024 && lds <= (size_t)dev.lds_bytes;
+}
+
+hipError_t launch_gemv_multi(const GemmArgs* items, int count, const DeviceInfo& dev, int* parts_used,
+                             hipStream_t stream)
+{
+    if (!gemv_multi_can_run(items, count, dev))
+        return hipErrorInvalidValue;
+    MultiArgs ma{};
+    ma.count = count;
+    ma.k = items[0].k;
+    int first = 0;
+    for (int i = 0; i < count; ++i) {
+        const GemmArgs& a = items[i];
+        const bool argmax = a.part_val != nullptr;
+        ma.p[i] = MultiProb{a.x, a.q, a.s, argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, first,
+                            argmax ? a.parts : 0, 0};
+        first += a.n;
+    }
+    ma.total = first;
+    for (int i = count; i < kMultiMax; ++i)
+        ma.p[i] = MultiProb{items[0].x, nullptr, nullptr, nullptr, 0, first, 0, 0};
+    const int blocks = min(dev.cus, (first + 15) / 16);     // every product has at least 8 rows per CU
+    if (parts_used)
+        *parts_used = blocks;
+    const int steps2 = even_steps(ma.k);
+    const bool ragged = ma.k != steps2 * 2048;
+    const size_t lds = (size_t)count * ma.k * 2 + 64 + 128;
+    if (steps2 == 2)
+        return ragged ? launch_multi_one<2, true>(ma, blocks, lds, stream) : launch_multi_one<2, false>(ma, blocks, lds, stream);
+    return ragged ? launch_multi_one<4, true>(ma, blocks, lds, stream) : launch_multi_one<4, false>(ma, blocks, lds, stream);
 }
 
 bool gemv_reg_single_pass(const GemmArgs& a) { return a.m == 1 || (a.m == 2 && even_steps(a.k) <= 2); }

@@ -64,6 +64,12 @@ int gemv_max_parts(const DeviceInfo& dev);
 // for the shapes it takes.  The argmax form writes one partial winner per workgroup.
 bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev);
 bool gemv_reg_single_pass(const GemmArgs& a);     // all activation rows in one pass over the weights
+// Several independent one-token products of one K in one launch (y, or part_val/part_idx/parts for
+// at most one of them, per item); see gemv_reg.hip.
+constexpr int kMultiMax = 8;
+bool gemv_multi_can_run(const GemmArgs* items, int count, const DeviceInfo& dev);
+hipError_t launch_gemv_multi(const GemmArgs* items, int count, const DeviceInfo& dev, int* parts_used,
+                             hipStream_t stream);
 // `bits`: 4 (a.q = packed nibbles), 6 (a.q = q6, 24 bytes per block) or 8 (a.q = q8, 32 bytes per
 // block); the fused form exists for 4 only.
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,

@@ -191,3 +191,105 @@ def test_grouped_on_tile_major_weights(m):
     single = binding.mxfp4_woq_gemm_tiled(xg[1], tws[1], workspace=group.workspace)
     torch.cuda.synchronize()
     assert torch.equal(group.ys[1].view(torch.int16), single.view(torch.int16))
+
+
+def _independent_items(shapes, k, seed, argmax_at=None):
+    lins = [make_linear(n, k, seed + i) for i, n in enumerate(shapes)]
+    xs = [synth.activations_outlier_channels(1, k, seed=seed + 50 + i) for i in range(len(shapes))]
+    items = []
+    for i, (lin, x) in enumerate(zip(lins, xs)):
+        it = dict(x=x.to(DEV), q=lin[0], s=lin[1], independent=True)
+        if i == argmax_at:
+            it["argmax"] = True
+        items.append(it)
+    return lins, xs, items
+
+
+def _check_against_single_calls_and_oracle(group, items, lins, xs, what):
+    for i, it in enumerate(items):
+        y_ref, a_ref = oracle.woq_gemm(synth.to_bits(xs[i]), lins[i][2], lins[i][3])
+        if it.get("argmax"):
+            n, k = lins[i][0].shape[0], lins[i][0].shape[1] * 2
+            ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(1, n, k),), dtype=torch.uint8, device=DEV)
+            idx1, val1 = binding.mxfp4_woq_gemm_argmax(it["x"], it["q"], it["s"], workspace=ws)
+            torch.cuda.synchronize()
+            idx, val = group.ys[i]
+            assert torch.equal(idx, idx1) and torch.equal(val.view(torch.int32), val1.view(torch.int32)), (what, i)
+            assert_argmax_ok(idx, val, y_ref, a_ref, "%s pick %d" % (what, i))
+        else:
+            single = binding.mxfp4_woq_gemm(it["x"], it["q"], it["s"])
+            torch.cuda.synchronize()
+            assert torch.equal(group.ys[i].view(torch.int16), single.view(torch.int16)), (what, i)
+            assert_gemm_close(group.ys[i], y_ref, a_ref, "%s product %d" % (what, i))
+
+
+@pytest.mark.parametrize("k", [2048, 4096, 6144, 8192])
+def test_independent_products_in_one_launch(k):
+    # one token, one K (two or four steps, whole and ragged), rows that are odd, a pick in the
+    # middle: the products marked independent share a launch and keep the bits of the single calls
+    shapes = [2048, 4104, 2817, 8192, 2056]
+    lins, xs, items = _independent_items(shapes, k, 12000 + k, argmax_at=3)
+    group = binding.GemmGroup(items)
+    for _ in range(2):                                 # the second run must not depend on what the first left
+        for y in group.ys:
+            if not isinstance(y, tuple):
+                y.fill_(3.0)
+        group.run()
+    torch.cuda.synchronize()
+    _check_against_single_calls_and_oracle(group, items, lins, xs, "one launch K=%d" % k)
+
+
+def test_independent_runs_split_where_the_products_cannot_share_a_launch():
+    # eleven products: the run of independent ones is cut by a second pick, by a product of two
+    # rows, by one with an activation, by another K and by the limit of eight per launch
+    k = 4096
+    shapes = [2048] * 11
+    lins, xs, items = _independent_items(shapes, k, 12100, argmax_at=1)
+    items[2]["argmax"] = True                          # a second pick: starts a new run
+    x2 = synth.activations_outlier_channels(2, k, seed=12190)
+    items[4]["x"] = x2.to(DEV)                         # two rows: runs on its own
+    items[6]["act"] = SWIGLU                           # an epilogue: runs on its own
+    group = binding.GemmGroup(items)
+    group.run()
+    torch.cuda.synchronize()
+    for i in (4, 6):
+        it = items[i]
+        x_cpu = x2 if i == 4 else xs[i]
+        y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x_cpu), lins[i][2], lins[i][3])
+        out_ref, a_out = oracle.epilogue(y_ref, a_ref, None, None, it.get("act", NONE))
+        assert_gemm_close(group.ys[i], out_ref, a_out, "split runs product %d" % i)
+    keep = [i for i in range(11) if i not in (4, 6)]
+    _check_against_single_calls_and_oracle(
+        type("G", (), {"ys": [group.ys[i] for i in keep]}), [items[i] for i in keep], [lins[i] for i in keep],
+        [xs[i] for i in keep], "split runs")
+
+
+def test_independent_decode_step_at_full_7b_sizes_equals_single_calls():
+    # the 7B linears at one row, all marked independent: the four with K = 4096 (the pick among
+    # them) share a launch, the down projection runs on its own
+    shape = synth.LLAMA_7B
+    g = torch.Generator(device=DEV).manual_seed(12200)
+    by_name = {}
+    for name, n, k in shape.linears():
+        q = torch.randint(0, 256, (n, k // 2), dtype=torch.uint8, device=DEV, generator=g)
+        s = torch.randint(112, 130, (n, k // 32), dtype=torch.uint8, device=DEV, generator=g)
+        x = synth.activations_outlier_channels(1, k, seed=12210 + n, device=DEV)
+        by_name[name] = dict(x=x, q=q, s=s, independent=True)
+    by_name["lm_head"]["argmax"] = True
+    order = ["down", "qkv", "o", "gate_up", "lm_head"]
+    group = binding.GemmGroup([by_name[n] for n in order])
+    for _ in range(2):
+        group.run()
+    torch.cuda.synchronize()
+    for name, y in zip(order, group.ys):
+        it = by_name[name]
+        if isinstance(y, tuple):
+            n, k = it["q"].shape[0], it["q"].shape[1] * 2
+            ws = torch.empty((binding.mxfp4_woq_gemm_argmax_workspace_bytes(1, n, k),), dtype=torch.uint8, device=DEV)
+            ref = binding.mxfp4_woq_gemm_argmax(it["x"], it["q"], it["s"], workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(y[0], ref[0]) and torch.equal(y[1].view(torch.int32), ref[1].view(torch.int32))
+        else:
+            ref = binding.mxfp4_woq_gemm(it["x"], it["q"], it["s"])
+            torch.cuda.synchronize()
+            assert torch.equal(y.view(torch.int16), ref.view(torch.int16)), name
