@@ -676,6 +676,8 @@ hipError_t launch_steps6(const GemmArgs& a, int m0, int steps2, int blocks, size
 // product, and a wave that crosses from one product to the next only swaps its buffer descriptors
 // and its activation registers: every product's activation row is staged in LDS when the kernel
 // starts, so there is no barrier, no refill of the load pipeline and no launch between products.
+// The outputs a wave holds (one per lane, each with its own address) are written when 64 have
+// gathered or the list ends, not at the crossing: a store drains the wave's loads in flight.
 struct MultiProb {
     const uint16_t* x;
     const uint8_t* q;
@@ -777,10 +779,11 @@ __global__ __launch_bounds__(1024) void gemv_multi_kernel(const MultiArgs a)
     float best_val = -INFINITY;         // at most one product of a launch takes the argmax form
     int best_idx = 0x7FFFFFFF;
     float res = 0.f, acc = 0.f;
-    int rowv = 0, slots = 0;
-    auto flush = [&](void* out) {
+    uint16_t* dst = nullptr;            // where the output held by this lane goes (any product's y)
+    int slots = 0;
+    auto flush = [&]() {
         if (lane < slots)
-            static_cast<uint16_t*>(out)[rowv] = f32_to_bf16_rne(res);
+            *dst = f32_to_bf16_rne(res);
         slots = 0;
         drain_vmem();                   // stores and loads share a counter: the loop sees only loads
     };
@@ -835,21 +838,19 @@ __global__ __launch_bounds__(1024) void gemv_multi_kernel(const MultiArgs a)
             }
         } else {
             res = (lane == slots) ? v : res;
-            rowv = (lane == slots) ? row : rowv;
+            dst = (lane == slots) ? static_cast<uint16_t*>(cur.out) + row : dst;
             if (++slots == 64)
-                flush(cur.out);
+                flush();
         }
         if (nxt.idx != cur.idx) {                           // the next row belongs to another product
-            if (cur.parts == 0 && slots > 0)
-                flush(cur.out);
             cur = nxt;
             load_x(cur.idx);
         }
         grp = grp_n;
         i_next = i_next2;
     }
-    if (cur.parts == 0 && slots > 0)
-        flush(cur.out);
+    if (slots > 0)
+        flush();
 
     // the argmax product, if there is one: combine the waves, publish the workgroup's winner
     int am = -1;
