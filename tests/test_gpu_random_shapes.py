@@ -100,3 +100,33 @@ def test_random_shapes(kind):
         torch.cuda.synchronize()
         assert_gemm_close(y, y_ref, a_ref, tag)
         assert_argmax_ok(idx, val, y_ref, a_ref, tag)
+
+
+def test_random_independent_groups():
+    # grouped calls of two to ten one-token products of one K, most of them flagged independent (so
+    # that runs of every length up to the limit of eight form and break), at most one pick
+    rng = random.Random(900)
+    for case in range(10):
+        k, count = 128 * rng.randint(1, 64), rng.randint(2, 10)
+        ns = [rng.randint(2048, 3000) for _ in range(count)]
+        pick = rng.choice([None] + list(range(count)))
+        tag = "independent case %d K=%d N=%s pick=%s" % (case, k, ns, pick)
+        seed = rng.randint(0, 10 ** 6)
+        items, refs = [], []
+        for i, n in enumerate(ns):
+            w = synth.weights_student_t(n, k, seed=seed + i)
+            x = synth.activations_outlier_channels(1, k, seed=seed + 100 + i)
+            q, s, q_ref, s_ref = assert_cast_bit_exact(w, tag)
+            refs.append(oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref))
+            item = dict(x=x.to(DEV), q=q, s=s, independent=rng.random() < 0.9)
+            if i == pick:
+                item["argmax"] = True
+            items.append(item)
+        group = binding.GemmGroup(items)
+        group.run()
+        torch.cuda.synchronize()
+        for i, item in enumerate(items):
+            if item.get("argmax"):
+                assert_argmax_ok(group.ys[i][0], group.ys[i][1], refs[i][0], refs[i][1], tag)
+            else:
+                assert_gemm_close(group.ys[i], refs[i][0], refs[i][1], tag)
