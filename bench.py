@@ -483,7 +483,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: this build has no multi-GPU path (the linears shard by "
-              "output rows without collectives; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "output rows without collectives). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import torch
