@@ -114,11 +114,14 @@ def test_grouped_launches_nothing_when_a_descriptor_is_invalid():
     assert bool((y == 7.0).all())                      # the valid first product did not run either
 
 
-def test_grouped_in_a_graph_replays_identically():
+@pytest.mark.parametrize("independent", [False, True])
+def test_grouped_in_a_graph_replays_identically(independent):
+    # (independent: the two products share one launch, captured as one kernel node)
     m, h = 1, 4096
     l0, l1 = make_linear(h, h, 11400), make_linear(h, h, 11401)
     x = synth.activations_outlier_channels(m, h, seed=11410).to(DEV)
-    group = binding.GemmGroup([dict(x=x, q=l0[0], s=l0[1]), dict(x=x, q=l1[0], s=l1[1])])
+    group = binding.GemmGroup([dict(x=x, q=l0[0], s=l0[1], independent=independent),
+                               dict(x=x, q=l1[0], s=l1[1], independent=independent)])
     group.run()
     torch.cuda.synchronize()
     eager = [y.clone() for y in group.ys]
