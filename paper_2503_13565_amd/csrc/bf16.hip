@@ -615,14 +615,9 @@ template <int MP, int NW>
 hipError_t launch_mfma_b(const Bf16Args& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
     auto kern = bf16_mfma_kernel<MP, NW, 2>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), max_lds); e != hipSuccess)
+        return e;
     const bool argmax = a.part_val != nullptr;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.w,
                        argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, (int)a.ldw, a.m,
@@ -850,14 +845,9 @@ template <int MT, int R>
 hipError_t launch_phased(const Bf16Args& a, int m0, int blocks, int phase_steps, int max_lds, hipStream_t stream)
 {
     auto kern = bf16_phased_kernel<MT, R, 16>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), max_lds); e != hipSuccess)
+        return e;
     const size_t lds = (size_t)MT * phase_steps * 1024;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(16 * 64), lds, stream, a, m0, phase_steps);
     return hipGetLastError();
@@ -867,14 +857,9 @@ template <int MT, int R, int NW>
 hipError_t launch_b(const Bf16Args& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
     auto kern = bf16_gemv_kernel<MT, R, NW>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), max_lds); e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0);
     return hipGetLastError();
 }

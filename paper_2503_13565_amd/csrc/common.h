@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace mxfp4 {
 
 constexpr int kWave = 64;
@@ -84,5 +86,27 @@ __device__ __forceinline__ void lds_barrier()
 // other counters untouched; gfx9 encoding).  A real waitcnt instruction rather than inline
 // assembly, so that the compiler's own wait insertion knows nothing is pending afterwards.
 __device__ __forceinline__ void drain_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// Host side: lets a kernel use more than the default 64 KiB of dynamic LDS.  The attribute belongs
+// to the kernel on the current device, so there is one flag per device; each kernel instance keeps a
+// static object of its own.  Threads that race here set the same attribute twice, which is harmless.
+struct LdsLimit {
+    static constexpr int kDevices = 64;
+    std::atomic<bool> done[kDevices] = {};
+    hipError_t raise(const void* kernel, int bytes)
+    {
+        int d = 0;
+        hipError_t e = hipGetDevice(&d);
+        if (e != hipSuccess)
+            return e;
+        const bool tracked = d >= 0 && d < kDevices;
+        if (tracked && done[d].load(std::memory_order_relaxed))
+            return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e == hipSuccess && tracked)
+            done[d].store(true, std::memory_order_relaxed);
+        return e;
+    }
+};
 
 }  // namespace mxfp4

@@ -387,14 +387,9 @@ template <int MT, int R, int NW>
 hipError_t launch_k(const GemmArgs& a, int m0, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
     auto kern = e4m3_gemv_kernel<MT, R, NW>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), max_lds); e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0);
     return hipGetLastError();
 }

@@ -540,14 +540,9 @@ hipError_t launch_one(const GemmArgs& a, int m0, int blocks, size_t lds, int max
                       const Epilogue& epi)
 {
     auto kern = gemv_kernel<MT, R, D, NW, kDecode, kScaleDword, kEpi>;
-    static bool attr_set = false;                   // per instantiation; racing writers set the same value
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), max_lds); e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a, m0, epi);
     return hipGetLastError();
 }

@@ -537,14 +537,12 @@ hipError_t launch_one6(const GemmArgs& g, int m0, int blocks, size_t lds, hipStr
         lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
     if (kBits == 6)
         lds += (size_t)NW * R * 1536;               // the waves' buffers for the lane exchange
-    static bool attr_set = false;
-    if (!attr_set && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged, kBits>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess)
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (lds > 64 * 1024)
+        if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged, kBits>),
+                                           160 * 1024);
+            e != hipSuccess)
             return e;
-        attr_set = true;
-    }
     hipLaunchKernelGGL((gemv_reg6_kernel<MT, R, STEPS, D, NW, kRagged, kBits>), dim3(blocks), dim3(NW * 64), lds, stream,
                        g.x, g.q, g.s, argmax ? static_cast<void*>(g.part_val) : static_cast<void*>(g.y), g.n, g.k,
                        g.m, m0, (int)g.ldx, (int)g.ldy, argmax ? g.parts : 0);
@@ -557,16 +555,14 @@ hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStre
     const bool argmax = g.part_val != nullptr;
     if (MT * STEPS >= 6)
         lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
-    static bool attr_set = false;
-    if (!attr_set && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg_fused_kernel<MT, R, STEPS, D, NW, kRagged>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static LdsLimit lds_limit, lds_limit_fused;     // of these kernel instances
+    if (lds > 64 * 1024) {
+        hipError_t e = lds_limit_fused.raise(
+            reinterpret_cast<const void*>(gemv_reg_fused_kernel<MT, R, STEPS, D, NW, kRagged>), 160 * 1024);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_reg_kernel<MT, R, STEPS, D, NW, kRagged>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            e = lds_limit.raise(reinterpret_cast<const void*>(gemv_reg_kernel<MT, R, STEPS, D, NW, kRagged>), 160 * 1024);
         if (e != hipSuccess)
             return e;
-        attr_set = true;
     }
     if (epi)
         hipLaunchKernelGGL((gemv_reg_fused_kernel<MT, R, STEPS, D, NW, kRagged>), dim3(blocks), dim3(NW * 64), lds,
@@ -882,14 +878,11 @@ __global__ __launch_bounds__(1024) void gemv_multi_kernel(const MultiArgs a)
 template <int STEPS, bool kRagged>
 hipError_t launch_multi_one(const MultiArgs& ma, int blocks, size_t lds, hipStream_t stream)
 {
-    static bool attr_set = false;
-    if (!attr_set && lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_multi_kernel<STEPS, kRagged>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess)
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (lds > 64 * 1024)
+        if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(gemv_multi_kernel<STEPS, kRagged>), 160 * 1024);
+            e != hipSuccess)
             return e;
-        attr_set = true;
-    }
     hipLaunchKernelGGL((gemv_multi_kernel<STEPS, kRagged>), dim3(blocks), dim3(1024), lds, stream, ma);
     return hipGetLastError();
 }

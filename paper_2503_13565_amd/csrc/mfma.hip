@@ -541,14 +541,9 @@ hipError_t launch_one(const GemmArgs& a, int m0, int grid_y, size_t lds, const D
                       hipStream_t stream, const Epilogue& epi)
 {
     auto kern = mfma_kernel<MP, NW, D, kEpi>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), dev.lds_bytes); e != hipSuccess)
+        return e;
     thread_local size_t occ_lds = ~(size_t)0;
     thread_local int occ = 0;
     if (occ_lds != lds) {

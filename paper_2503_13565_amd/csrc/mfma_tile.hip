@@ -451,17 +451,11 @@ hipError_t launch_pass(const GemmArgs& a, int m0, int blocks, size_t lds, const 
 {
     auto kern = mfma_tile_kernel<MP, NW, D, kTiled>;
     auto kern_fused = mfma_tile_fused_kernel<MP, NW, D, kTiled>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_fused),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit, lds_limit_fused;     // of these kernel instances
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), dev.lds_bytes); e != hipSuccess)
+        return e;
+    if (hipError_t e = lds_limit_fused.raise(reinterpret_cast<const void*>(kern_fused), dev.lds_bytes); e != hipSuccess)
+        return e;
     const bool argmax = a.part_val != nullptr;
     if (epi)
         hipLaunchKernelGGL(kern_fused, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
@@ -478,14 +472,9 @@ template <int MP, int NW, int kBits>
 hipError_t launch_pass8(const GemmArgs& a, int m0, int blocks, size_t lds, const DeviceInfo& dev, hipStream_t stream)
 {
     auto kern = mfma_tile8_kernel<MP, NW, 2, kBits>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), dev.lds_bytes); e != hipSuccess)
+        return e;
     const bool argmax = a.part_val != nullptr;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
                        argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, a.m, m0,
@@ -539,14 +528,9 @@ hipError_t launch_split_pass(const GemmArgs& a, int m0, int phases, int phase_st
                              size_t lds, const DeviceInfo& dev, hipStream_t stream)
 {
     auto kern = mfma_tile_split_kernel<MP, NW, D, kTiled>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, dev.lds_bytes);
-        if (e != hipSuccess)
-            return e;
-        attr_set = true;
-    }
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), dev.lds_bytes); e != hipSuccess)
+        return e;
     hipLaunchKernelGGL(kern, dim3(blocks, phases), dim3((NW + 1) * 64), lds, stream, a.x, a.q, a.s,
                        static_cast<void*>(ws), a.n, a.k, a.m, m0, (int)a.ldx, (int)a.ldy, 0, phase_steps);
     return hipGetLastError();
