@@ -818,7 +818,7 @@ static int run_e4m3(const void* x, int64_t M, int64_t ldx, const void* q8, const
     const bool reg = !general_only && aligned(s, 4) && gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a);
     // five and more rows: the matrix-core tiles when a pass's activation rows fit the LDS (up to
     // four rows the vector-ALU kernel is faster: 13.5 against 16.8 us on the 7B qkv shape)
-    const bool tiles = !general_only && !reg && a.m >= 5 && aligned(s, 4) && aligned(q8, 16) && mfma_tile_can_run(a, dev);
+    const bool tiles = !general_only && !reg && a.m >= 5 && aligned(s, 4) && aligned(q8, 16) && mfma_tile_fmt_can_run(a, dev);
     hipError_t e = reg     ? launch_gemv_reg(a, dev, &parts_used, st, nullptr, 8)
                    : tiles ? launch_mfma_tile8(a, dev, &parts_used, st)
                            : launch_e4m3_gemv(a, dev, &parts_used, st);
@@ -968,7 +968,7 @@ static int run_e2m3(const void* x, int64_t M, int64_t ldx, const void* q6, const
     int parts_used = 0;
     // three and more rows: the matrix-core tiles when a pass's activation rows fit the LDS, else
     // passes of the decode kernel over the weights
-    const bool tiles = a.m >= 3 && mfma_tile_can_run(a, dev);
+    const bool tiles = a.m >= 3 && mfma_tile_fmt_can_run(a, dev);
     hipError_t e = tiles ? launch_mfma_tile8(a, dev, &parts_used, st, 6)
                          : launch_gemv_reg(a, dev, &parts_used, st, nullptr, 6);
     if (e != hipSuccess)

@@ -106,6 +106,7 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
 
 // The 8-bit (a.q = q8 [N, K]) and 6-bit (a.q = q6) draft formats on the same tiles; shapes as
 // mfma_tile_can_run; `bits` 8 or 6.
+bool mfma_tile_fmt_can_run(const GemmArgs& a, const DeviceInfo& dev);   // the same with passes of four rows at least
 hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                              int bits = 8);
 

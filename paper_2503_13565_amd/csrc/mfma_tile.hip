@@ -499,6 +499,18 @@ bool mfma_tile_can_run(const GemmArgs& a, const DeviceInfo& dev)
     return tile_lds_bytes(a.k, tile_pass_width(a.m)) <= (size_t)dev.lds_bytes;
 }
 
+// The 6- and 8-bit formats have no K split: where the widest pass does not fit the LDS they take
+// narrower passes (more of them), so a pass of four rows must fit.
+bool mfma_tile_fmt_can_run(const GemmArgs& a, const DeviceInfo& dev)
+{
+    GemmArgs narrow = a;
+    narrow.m = a.m < 4 ? a.m : 4;
+    if (a.part_val && a.part_idx != reinterpret_cast<int32_t*>(a.part_val + (size_t)a.m * a.parts))
+        return false;
+    narrow.part_val = nullptr;
+    return mfma_tile_can_run(narrow, dev);
+}
+
 size_t tile_repack_q_bytes(int64_t n, int64_t k) { return (size_t)((n + 15) / 16) * 16 * (size_t)(k / 2); }
 size_t tile_repack_s_bytes(int64_t n, int64_t k)
 {
@@ -567,7 +579,11 @@ template <int kBits>
 hipError_t launch_tile_fmt(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
 {
     const int n_tiles = (a.n + 15) / 16;
-    const size_t widest = tile_lds_bytes(a.k, tile_pass_width(a.m));
+    int cap = 16;                                           // the widest pass whose rows fit the LDS
+    while (cap > 4 && tile_lds_bytes(a.k, cap) > (size_t)dev.lds_bytes)
+        cap >>= 1;
+    auto width = [&](int left) { const int w = tile_pass_width(left); return w < cap ? w : cap; };
+    const size_t widest = tile_lds_bytes(a.k, width(a.m));
     static const int env_one = [] { const char* e = getenv("MXFP4_TILE_FMT_ONE_WG"); return e ? atoi(e) : -1; }();   // measurement only
     // Two workgroups of four waves per CU only where the tiles are few (fewer than two per wave of the
     // wide form): from there on one workgroup of eight waves measured 4-12 % faster in these formats.
@@ -579,7 +595,7 @@ hipError_t launch_tile_fmt(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     if (parts_used)
         *parts_used = blocks;
     for (int m0 = 0; m0 < a.m;) {
-        const int mp = tile_pass_width(a.m - m0);
+        const int mp = width(a.m - m0);
         const bool wide = !two && tile_lds_bytes(a.k, mp, 8) <= (size_t)dev.lds_bytes;
         const size_t lds = tile_lds_bytes(a.k, mp, wide ? 8 : kTileNW);
         hipError_t e;
