@@ -119,9 +119,10 @@ int mxfp4_e4m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
  *   scales_e8m0  [N, K/32] as for MXFP4 (4-byte aligned for the product)
  * mxfp4_e2m3_direct_cast_bits rounds and packs with integer arithmetic instead of the convert
  * instruction (same bits).  mxfp4_e2m3_woq_gemm and mxfp4_e2m3_woq_gemm_argmax are mxfp4_woq_gemm
- * and mxfp4_woq_gemm_argmax with q6 in place of q_packed, for the shapes the decode GEMV takes:
- * K % 128 == 0, K <= 32768, N >= 8 x compute units (MXFP4_ERR_SHAPE otherwise); any M, one or two
- * rows per pass.  Argmax workspace as for mxfp4_e4m3_woq_gemm_argmax.
+ * and mxfp4_woq_gemm_argmax with q6 in place of q_packed, for K % 128 == 0 and any M, when four
+ * activation rows of K elements fit the LDS (K up to about 19000; any N: the matrix-core tiles,
+ * up to 16 rows per pass) or K <= 32768 and N >= 8 x compute units (the decode kernel, one or two
+ * rows per pass); MXFP4_ERR_SHAPE otherwise.  Argmax workspace as for mxfp4_e4m3_woq_gemm_argmax.
  */
 int mxfp4_e2m3_direct_cast(const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
                            void* q6, void* scales_e8m0, void* stream);

@@ -962,13 +962,16 @@ static int run_e2m3(const void* x, int64_t M, int64_t ldx, const void* q6, const
         a.y = static_cast<uint16_t*>(y);
         a.ldy = ldy;
     }
-    if (!gemv_reg_can_run(a, dev))
-        return fail(MXFP4_ERR_SHAPE, "the 6-bit product needs K %% 128 == 0, K <= 32768 and N >= %d", dev.cus * 8);
+    const bool reg_ok = gemv_reg_can_run(a, dev), tiles_ok = mfma_tile_fmt_can_run(a, dev);
+    if (!reg_ok && !tiles_ok)
+        return fail(MXFP4_ERR_SHAPE, "the 6-bit product needs K %% 128 == 0 and either four activation rows of K "
+                                     "elements within the LDS or K <= 32768 with N >= %d", dev.cus * 8);
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
-    // three and more rows: the matrix-core tiles when a pass's activation rows fit the LDS, else
-    // passes of the decode kernel over the weights
-    const bool tiles = a.m >= 3 && mfma_tile_fmt_can_run(a, dev);
+    // Three and more rows: the matrix-core tiles when four activation rows fit the LDS, else
+    // passes of the decode kernel over the weights.  One and two rows: the decode kernel; the
+    // tiles (any N) for the shapes it does not take.
+    const bool tiles = tiles_ok && (a.m >= 3 || !reg_ok);
     hipError_t e = tiles ? launch_mfma_tile8(a, dev, &parts_used, st, 6)
                          : launch_gemv_reg(a, dev, &parts_used, st, nullptr, 6);
     if (e != hipSuccess)

@@ -89,6 +89,23 @@ def test_product_edge_shapes(n, k, m):
     assert_argmax_ok(idx, val, y_ref, a_ref, "e2m3 argmax N=%d K=%d M=%d" % (n, k, m))
 
 
+@pytest.mark.parametrize("n,k", [(1, 128), (7, 256), (100, 4096), (1000, 2176), (2047, 11008), (300, 18944)])
+@pytest.mark.parametrize("m", [1, 2, 3, 9])
+def test_product_small_n(n, k, m):
+    # fewer weight rows than the decode kernel takes: the tiles, at any row count
+    w = synth.weights_student_t(n, k, seed=700 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=800 + m + k)
+    q, s, q_ref, s_ref = cast_both_ways(w)
+    y_ref, a_ref = oracle.e2m3_woq_gemm(synth.to_bits(x), q_ref, s_ref)
+    xg = x.to(DEV)
+    y = binding.mxfp4_e2m3_woq_gemm(xg, q, s)
+    torch.cuda.synchronize()
+    assert_gemm_close(y, y_ref, a_ref, "e2m3 small N=%d K=%d M=%d" % (n, k, m))
+    idx, val = binding.mxfp4_e2m3_woq_gemm_argmax(xg, q, s)
+    torch.cuda.synchronize()
+    assert_argmax_ok(idx, val, y_ref, a_ref, "e2m3 small N argmax N=%d K=%d M=%d" % (n, k, m))
+
+
 @pytest.mark.parametrize("n,k", [(2048, 128), (2500, 4096), (2049, 2176), (2100, 11008)])
 @pytest.mark.parametrize("m", [4, 5, 8, 9, 16, 17])
 def test_product_verification_rows(n, k, m):
@@ -118,7 +135,7 @@ def test_product_llama_shape_refusals_and_nan_block():
     y2 = binding.mxfp4_e2m3_woq_gemm(data["x"].to(DEV), q, s2).float().cpu().numpy()
     keep = np.arange(4096) != 17
     assert np.isnan(y2[0, 17]) and np.array_equal(y2[:, keep], y.float().cpu().numpy()[:, keep])
-    for n, k in [(100, 4096), (4096, 96)]:                       # too few rows; K % 128
+    for n, k in [(100, 20480), (4096, 96)]:                      # few rows and K beyond the tiles' LDS; K % 128
         x = torch.zeros((1, k), dtype=torch.bfloat16, device=DEV)
         q0 = torch.zeros((n, k // 32 * 24), dtype=torch.uint8, device=DEV)
         s0 = torch.zeros((n, k // 32), dtype=torch.uint8, device=DEV)

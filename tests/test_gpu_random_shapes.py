@@ -21,8 +21,9 @@ KINDS = ["mx", "fused", "tiled", "grouped", "e4m3", "e2m3", "bf16"]
 
 def draw(kind, rng):
     m = rng.choice([1, 1, 2, 3, 4, 5, 7, 8, 9, 16, 17])
-    if kind == "e2m3":                                   # the 6-bit product takes the decode-frame shapes only
-        k, n = 128 * rng.randint(1, 96), rng.randint(2048, 2600)
+    if kind == "e2m3":                                   # the 6-bit product needs K % 128 == 0
+        k = 128 * rng.randint(1, 96)
+        n = rng.choice([rng.randint(1, 300), rng.randint(2040, 2600), rng.randint(300, 5000)])
     elif kind == "tiled":
         k, n = 128 * rng.randint(1, 100), rng.randint(1, 3000)
     else:
