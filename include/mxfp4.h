@@ -231,8 +231,9 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx,
  *              this product reads no output of the descriptors next to it that carry the flag too
  *              and that none of them reads or overwrites its outputs; consecutive such
  *              descriptors may then run in one launch, in any order or at once (taken for up to 8
- *              products with M = 1, the same K <= 8192, no bias, act or residual, at most one with
- *              argmax_out, each a shape of the decode kernel; same bits as the single calls;
+ *              products with M = 1, no bias, act or residual, at most one with argmax_out, each a
+ *              shape of the decode kernel -- K % 128 == 0, K <= 32768, N >= 8 x compute units --
+ *              whose activation rows fit the LDS together; same bits as the single calls;
  *              otherwise the flag changes nothing).  Other bits: error
  *   workspace  device scratch shared by all products: optional as in mxfp4_woq_gemm_ws when no
  *              descriptor asks for the argmax, required as in mxfp4_woq_gemm_argmax otherwise;

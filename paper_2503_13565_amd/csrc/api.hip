@@ -547,7 +547,7 @@ static int merged_run(const mxfp4_gemm_desc* descs, int64_t left, const DeviceIn
     int run = 0;
     for (int j = 0; j < kMultiMax && j < left; ++j) {
         const mxfp4_gemm_desc& d = descs[j];
-        if (d.flags != MXFP4_DESC_INDEPENDENT || d.M != 1 || d.K != descs[0].K || d.bias_bf16 || d.residual_bf16 ||
+        if (d.flags != MXFP4_DESC_INDEPENDENT || d.M != 1 || d.bias_bf16 || d.residual_bf16 ||
             d.act != MXFP4_ACT_NONE)
             break;
         GemmArgs a{};

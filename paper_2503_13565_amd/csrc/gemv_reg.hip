@@ -679,7 +679,7 @@ struct MultiProb {
     const uint8_t* q;
     const uint8_t* s;
     void* out;           // y (BF16 [N]), or the partial winners (float [parts], int32 [parts])
-    int n, first, parts, pad;
+    int n, first, parts, k;
 };
 struct MultiArgs {
     int count, k, total, pad;
@@ -887,6 +887,210 @@ hipError_t launch_multi_one(const MultiArgs& ma, int blocks, size_t lds, hipStre
     return hipGetLastError();
 }
 
+// The same for products of different K (each up to 32768): the activation rows stay in LDS, padded
+// with zeros to a whole (even) number of steps as in the single product's long-K form, and a step
+// reads its 64 bytes per lane from there; the step count of a row is the product's own.
+__global__ __launch_bounds__(1024) void gemv_multi_lds_kernel(const MultiArgs a)
+{
+    constexpr int NW = 16, D = 2, T = NW * 64;
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    auto steps_of = [](int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; };
+
+    // every product's first 1024 chunks of 16 bytes go out before anything else
+    u32x4_t xl[kMultiMax];
+#pragma unroll
+    for (int p = 0; p < kMultiMax; ++p)
+        xl[p] = reinterpret_cast<const u32x4_t*>(a.p[p].x)[min(tid, (a.p[p].k >> 3) - 1)];
+
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);         // per product [4][steps * 64] chunks
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int x_chunks = 0;
+#pragma unroll
+    for (int p = 0; p < kMultiMax; ++p)
+        x_chunks += p < a.count ? steps_of(a.p[p].k) * 256 : 0;
+    int* ctr = reinterpret_cast<int*>(xs + x_chunks);
+    float* wv = reinterpret_cast<float*>(ctr + 16);
+    int* wi = reinterpret_cast<int*>(wv + NW);
+    const int G = gridDim.x, b = blockIdx.x;
+    auto row_of = [&](int i) { return i * G + b; };
+    if (tid == 0)
+        *ctr = NW;
+
+    struct Set {
+        __amdgpu_buffer_rsrc_t rq, rs;
+        void* out;
+        int first, n, parts, idx, nblk, steps, xoff;
+        int fill[3];    // the struct without padding: copying it then moves registers only
+    };
+    auto set_for = [&](Set& st, int v, int from, int from_xoff) __attribute__((always_inline)) {
+        int idx = from, xoff = from_xoff;
+        while (idx < a.count - 1 && v >= a.p[idx].first + a.p[idx].n) {
+            xoff += steps_of(a.p[idx].k) * 256;
+            ++idx;
+        }
+        const MultiProb& pr = a.p[idx];
+        st.nblk = pr.k >> 5;
+        st.steps = steps_of(pr.k);
+        st.xoff = xoff;
+        st.rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(pr.q), 0, pr.n * st.nblk * 16, 0x00020000);
+        st.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(pr.s), 0, pr.n * st.nblk, 0x00020000);
+        st.out = pr.out;
+        st.first = pr.first;
+        st.n = pr.n;
+        st.parts = pr.parts;
+        st.idx = idx;
+        st.fill[0] = st.fill[1] = st.fill[2] = 0;
+    };
+
+    u32x4_t bq[D];
+    uint32_t bs[D];
+    auto issue = [&](const Set& st, int v, int t, int d) {
+        const bool live = v < a.total;
+        const bool vb = t * 64 + lane < st.nblk;
+        const int row = live ? v - st.first : 0;
+        bq[d] = __builtin_amdgcn_raw_buffer_load_b128(st.rq, (live && vb) ? lane * 16 : 0x7FFFFFF0,
+                                                      row * (st.nblk * 16) + t * 1024, 2);
+        bs[d] = __builtin_amdgcn_raw_buffer_load_b32(st.rs, live ? row * st.nblk + (lane & 15) * 4 : 0x7FFFFFF0, t * 64,
+                                                     0);
+    };
+    int grp = row_of(wave);
+    Set cur;
+    set_for(cur, grp, 0, 0);
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        issue(cur, grp, d, d);
+
+    // stage the activation rows: chunk c of a row goes to [c % 4][c / 4]; zeros behind the row's end
+    {
+        int xoff = 0;
+#pragma unroll
+        for (int p = 0; p < kMultiMax; ++p) {
+            if (p < a.count) {
+                const int chunks = a.p[p].k >> 3, nblk = a.p[p].k >> 5, row = steps_of(a.p[p].k) * 64;
+                if (tid < chunks)
+                    xs[xoff + (tid & 3) * row + (tid >> 2)] = xl[p];
+                const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(a.p[p].x);
+                for (int c = tid + T; c < chunks; c += T)        // K > 8192 only
+                    xs[xoff + (c & 3) * row + (c >> 2)] = xp[c];
+                const int pad = row - nblk;
+                for (int e = tid; e < 4 * pad; e += T)
+                    xs[xoff + (e / pad) * row + nblk + e % pad] = u32x4_t{0, 0, 0, 0};
+                xoff += 4 * row;
+            }
+        }
+    }
+    lds_barrier();
+
+    float best_val = -INFINITY;
+    int best_idx = 0x7FFFFFFF;
+    float res = 0.f, acc = 0.f;
+    uint16_t* dst = nullptr;
+    int slots = 0;
+    auto flush = [&]() {
+        if (lane < slots)
+            *dst = f32_to_bf16_rne(res);
+        slots = 0;
+        drain_vmem();
+    };
+    auto fetch = [&]() {
+        int v = 0;
+        if (lane == 0)
+            v = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+
+    const int sh_top = (3 - (lane & 3)) * 8;
+    int i_next = fetch();
+    while (grp < a.total) {
+        const int grp_n = row_of(i_next);
+        const int i_next2 = fetch();
+        Set nxt = cur;
+        if (grp_n < a.total && grp_n >= cur.first + cur.n)
+            set_for(nxt, grp_n, cur.idx, cur.xoff);
+        const u32x4_t* xb = xs + cur.xoff + lane;
+        for (int t = 0; t < cur.steps; t += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const int tt = t + d;
+                __builtin_amdgcn_sched_barrier(0);      // step by step: a step's loads go out when it ends
+                const uint32_t dw = (uint32_t)__builtin_amdgcn_ds_bpermute((lane >> 2) * 4, (int)bs[d]);
+                float sc = __uint_as_float((dw << sh_top) >> 1);
+                sc = (tt * 64 + lane < cur.nblk) ? sc : 1.0f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const u32x4_t xv = xb[(j * cur.steps + tt) * 64];
+                    const uint32_t qd = bq[d][j];
+                    const bf16x2_t w0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 0);
+                    const bf16x2_t w1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 1);
+                    const bf16x2_t w2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 2);
+                    const bf16x2_t w3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, sc, 3);
+                    const uint32_t x0 = xv[0], x1 = xv[1], x2 = xv[2], x3 = xv[3];
+                    acc = __builtin_amdgcn_fdot2_f32_bf16(w0, __builtin_bit_cast(bf16x2_t, x0), acc, false);
+                    acc = __builtin_amdgcn_fdot2_f32_bf16(w1, __builtin_bit_cast(bf16x2_t, x1), acc, false);
+                    acc = __builtin_amdgcn_fdot2_f32_bf16(w2, __builtin_bit_cast(bf16x2_t, x2), acc, false);
+                    acc = __builtin_amdgcn_fdot2_f32_bf16(w3, __builtin_bit_cast(bf16x2_t, x3), acc, false);
+                }
+                // the step two ahead: of this row, or of the next one (perhaps another product's);
+                // chosen with selects, not branches, so that the loads in flight stay countable
+                const int tn = tt + D;
+                const bool same = tn < cur.steps;
+                Set pick;
+                pick.rq = same ? cur.rq : nxt.rq;
+                pick.rs = same ? cur.rs : nxt.rs;
+                pick.first = same ? cur.first : nxt.first;
+                pick.nblk = same ? cur.nblk : nxt.nblk;
+                issue(pick, same ? grp : grp_n, same ? tn : tn - cur.steps, d);
+            }
+        }
+        const float v = wave_sum(acc);
+        acc = 0.f;
+        const int row = grp - cur.first;
+        if (cur.parts > 0) {
+            if (v > best_val || (v == best_val && row < best_idx)) {
+                best_val = v;
+                best_idx = row;
+            }
+        } else {
+            res = (lane == slots) ? v : res;
+            dst = (lane == slots) ? static_cast<uint16_t*>(cur.out) + row : dst;
+            if (++slots == 64)
+                flush();
+        }
+        cur = nxt;
+        grp = grp_n;
+        i_next = i_next2;
+    }
+    if (slots > 0)
+        flush();
+
+    int am = -1;
+#pragma unroll
+    for (int p = 0; p < kMultiMax; ++p)
+        am = (p < a.count && a.p[p].parts > 0) ? p : am;
+    if (am >= 0) {
+        if (lane == 0) {
+            wv[wave] = best_val;
+            wi[wave] = best_idx;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            float bv = wv[0];
+            int bi = wi[0];
+            for (int w = 1; w < NW; ++w)
+                if (wv[w] > bv || (wv[w] == bv && wi[w] < bi)) {
+                    bv = wv[w];
+                    bi = wi[w];
+                }
+            float* part_val = static_cast<float*>(a.p[am].out);
+            int32_t* part_idx = reinterpret_cast<int32_t*>(part_val + a.p[am].parts);
+            part_val[b] = bv;
+            part_idx[b] = bi;
+        }
+    }
+}
+
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
 bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
 int waves_for(int steps2, int mt) { return wide_group(steps2, mt) ? 8 : 16; }
@@ -913,6 +1117,23 @@ bool gemv_reg_can_run(const GemmArgs& a, const DeviceInfo& dev)
 
 // One launch for `count` products of one token: every one must be a shape the single product takes
 // in registers (K <= 8192), all with the same K, their activation rows together within the LDS.
+// One K of at most four steps: the register form (the rows themselves in LDS); else the padded rows.
+static bool multi_in_registers(const GemmArgs* items, int count)
+{
+    for (int i = 1; i < count; ++i)
+        if (items[i].k != items[0].k)
+            return false;
+    return even_steps(items[0].k) <= 4;
+}
+
+static size_t multi_lds_bytes(const GemmArgs* items, int count)
+{
+    size_t x = 0;
+    for (int i = 0; i < count; ++i)
+        x += multi_in_registers(items, count) ? (size_t)items[i].k * 2 : (size_t)even_steps(items[i].k) * 4096;
+    return x + 64 + 128;
+}
+
 bool gemv_multi_can_run(const GemmArgs* items, int count, const DeviceInfo& dev)
 {
     if (count < 2 || count > kMultiMax)
@@ -921,13 +1142,12 @@ bool gemv_multi_can_run(const GemmArgs* items, int count, const DeviceInfo& dev)
     int argmaxes = 0;
     for (int i = 0; i < count; ++i) {
         const GemmArgs& a = items[i];
-        if (a.m != 1 || a.k != items[0].k || !gemv_reg_can_run(a, dev) || even_steps(a.k) > 4)
+        if (a.m != 1 || !gemv_reg_can_run(a, dev))
             return false;
         argmaxes += a.part_val != nullptr;
         total += a.n;
     }
-    const size_t lds = (size_t)count * items[0].k * 2 + 64 + 128;
-    return argmaxes <= 1 && total < 0x7FFFFFFF - 64 * 1024 && lds <= (size_t)dev.lds_bytes;
+    return argmaxes <= 1 && total < 0x7FFFFFFF - 64 * 1024 && multi_lds_bytes(items, count) <= (size_t)dev.lds_bytes;
 }
 
 hipError_t launch_gemv_multi(const GemmArgs* items, int count, const DeviceInfo& dev, int* parts_used,
@@ -943,18 +1163,27 @@ hipError_t launch_gemv_multi(const GemmArgs* items, int count, const DeviceInfo&
         const GemmArgs& a = items[i];
         const bool argmax = a.part_val != nullptr;
         ma.p[i] = MultiProb{a.x, a.q, a.s, argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, first,
-                            argmax ? a.parts : 0, 0};
+                            argmax ? a.parts : 0, a.k};
         first += a.n;
     }
     ma.total = first;
     for (int i = count; i < kMultiMax; ++i)
-        ma.p[i] = MultiProb{items[0].x, nullptr, nullptr, nullptr, 0, first, 0, 0};
+        ma.p[i] = MultiProb{items[0].x, nullptr, nullptr, nullptr, 0, first, 0, items[0].k};
     const int blocks = min(dev.cus, (first + 15) / 16);     // every product has at least 8 rows per CU
     if (parts_used)
         *parts_used = blocks;
     const int steps2 = even_steps(ma.k);
     const bool ragged = ma.k != steps2 * 2048;
-    const size_t lds = (size_t)count * ma.k * 2 + 64 + 128;
+    const size_t lds = multi_lds_bytes(items, count);
+    if (!multi_in_registers(items, count)) {
+        static LdsLimit lds_limit;                  // of this kernel
+        if (lds > 64 * 1024)
+            if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(gemv_multi_lds_kernel), 160 * 1024);
+                e != hipSuccess)
+                return e;
+        hipLaunchKernelGGL(gemv_multi_lds_kernel, dim3(blocks), dim3(1024), lds, stream, ma);
+        return hipGetLastError();
+    }
     if (steps2 == 2)
         return ragged ? launch_multi_one<2, true>(ma, blocks, lds, stream) : launch_multi_one<2, false>(ma, blocks, lds, stream);
     return ragged ? launch_multi_one<4, true>(ma, blocks, lds, stream) : launch_multi_one<4, false>(ma, blocks, lds, stream);

@@ -244,7 +244,7 @@ def test_independent_products_in_one_launch(k):
 
 def test_independent_runs_split_where_the_products_cannot_share_a_launch():
     # eleven products: the run of independent ones is cut by a second pick, by a product of two
-    # rows, by one with an activation, by another K and by the limit of eight per launch
+    # rows, by one with an activation and by the limit of eight per launch
     k = 4096
     shapes = [2048] * 11
     lins, xs, items = _independent_items(shapes, k, 12100, argmax_at=1)
@@ -268,8 +268,8 @@ def test_independent_runs_split_where_the_products_cannot_share_a_launch():
 
 
 def test_independent_decode_step_at_full_7b_sizes_equals_single_calls():
-    # the 7B linears at one row, all marked independent: the four with K = 4096 (the pick among
-    # them) share a launch, the down projection runs on its own
+    # the 7B linears at one row, all marked independent: the five share one launch, the pick
+    # among them
     shape = synth.LLAMA_7B
     g = torch.Generator(device=DEV).manual_seed(12200)
     by_name = {}
@@ -296,3 +296,26 @@ def test_independent_decode_step_at_full_7b_sizes_equals_single_calls():
             ref = binding.mxfp4_woq_gemm(it["x"], it["q"], it["s"])
             torch.cuda.synchronize()
             assert torch.equal(y.view(torch.int16), ref.view(torch.int16)), name
+
+
+@pytest.mark.parametrize("pick", [None, 2, 5])
+def test_independent_products_of_different_k(pick):
+    # one launch for products whose K differ (one step to fourteen, ragged last steps, K beyond
+    # 8192): the activation rows stay in LDS, padded with zeros
+    shapes = [(2048, 4096), (2100, 11008), (2817, 128), (4104, 8192), (2056, 28672), (8192, 4224)]
+    lins = [make_linear(n, k, 12300 + i) for i, (n, k) in enumerate(shapes)]
+    xs = [synth.activations_outlier_channels(1, k, seed=12350 + i) for i, (_, k) in enumerate(shapes)]
+    items = []
+    for i, (lin, x) in enumerate(zip(lins, xs)):
+        item = dict(x=x.to(DEV), q=lin[0], s=lin[1], independent=True)
+        if i == pick:
+            item["argmax"] = True
+        items.append(item)
+    group = binding.GemmGroup(items)
+    for _ in range(2):
+        for y in group.ys:
+            if not isinstance(y, tuple):
+                y.fill_(3.0)
+        group.run()
+    torch.cuda.synchronize()
+    _check_against_single_calls_and_oracle(group, items, lins, xs, "different K pick=%s" % pick)
