@@ -104,17 +104,19 @@ def test_random_shapes(kind):
 
 
 def test_random_independent_groups():
-    # grouped calls of two to ten one-token products of one K, most of them flagged independent (so
-    # that runs of every length up to the limit of eight form and break), at most one pick
+    # grouped calls of two to ten one-token products, of one K or each of its own, most of them
+    # flagged independent (so that runs of every length up to the limit of eight form and break,
+    # also where the activation rows no longer fit the LDS together), at most one pick
     rng = random.Random(900)
-    for case in range(10):
+    for case in range(12):
         k, count = 128 * rng.randint(1, 64), rng.randint(2, 10)
+        ks = [k] * count if case % 2 == 0 else [128 * rng.randint(1, 100) for _ in range(count)]
         ns = [rng.randint(2048, 3000) for _ in range(count)]
         pick = rng.choice([None] + list(range(count)))
-        tag = "independent case %d K=%d N=%s pick=%s" % (case, k, ns, pick)
+        tag = "independent case %d K=%s N=%s pick=%s" % (case, ks, ns, pick)
         seed = rng.randint(0, 10 ** 6)
         items, refs = [], []
-        for i, n in enumerate(ns):
+        for i, (n, k) in enumerate(zip(ns, ks)):
             w = synth.weights_student_t(n, k, seed=seed + i)
             x = synth.activations_outlier_channels(1, k, seed=seed + 100 + i)
             q, s, q_ref, s_ref = assert_cast_bit_exact(w, tag)
