@@ -23,6 +23,7 @@ EXPORTS = [
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
     "mxfp4_woq_gemm_fused", "mxfp4_woq_gemm_grouped_workspace_bytes", "mxfp4_woq_gemm_grouped",
+    "mxfp4_woq_gemm_chain_workspace_bytes", "mxfp4_woq_gemm_chain_init", "mxfp4_woq_gemm_chain",
     "mxfp4_e4m3_direct_cast", "mxfp4_e4m3_direct_cast_bits", "mxfp4_e4m3_dequant", "mxfp4_e4m3_woq_gemm",
     "mxfp4_e4m3_woq_gemm_argmax",
     "mxfp4_e2m3_direct_cast", "mxfp4_e2m3_direct_cast_bits", "mxfp4_e2m3_dequant", "mxfp4_e2m3_woq_gemm",
@@ -44,6 +45,14 @@ class GemmDesc(ctypes.Structure):
                 ("ldr", ctypes.c_int64), ("y_bf16", ctypes.c_void_p), ("ldy", ctypes.c_int64),
                 ("argmax_out", ctypes.c_void_p), ("max_out", ctypes.c_void_p),
                 ("act", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+class ChainOpts(ctypes.Structure):
+    """``mxfp4_chain_opts`` of the header."""
+    _fields_ = [("wait_us", ctypes.c_int64), ("phantom_workgroups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+CHAIN_STATUS_OFFSET = 4224
 
 
 class Mxfp4Error(RuntimeError):
@@ -128,6 +137,12 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_grouped_workspace_bytes.restype = sz
     lib.mxfp4_woq_gemm_grouped.argtypes = [ctypes.POINTER(GemmDesc), i64, vp, sz, vp]
     lib.mxfp4_woq_gemm_grouped.restype = i32
+    lib.mxfp4_woq_gemm_chain_workspace_bytes.argtypes = []
+    lib.mxfp4_woq_gemm_chain_workspace_bytes.restype = sz
+    lib.mxfp4_woq_gemm_chain_init.argtypes = [vp, sz, vp]
+    lib.mxfp4_woq_gemm_chain_init.restype = i32
+    lib.mxfp4_woq_gemm_chain.argtypes = [ctypes.POINTER(GemmDesc), i64, vp, sz, ctypes.POINTER(ChainOpts), vp]
+    lib.mxfp4_woq_gemm_chain.restype = i32
     lib.mxfp4_diag_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mxfp4_diag_stream_copy.argtypes = [vp, vp, sz, vp]
     for name in ("mxfp4_direct_cast", "mxfp4_direct_cast_bits", "mxfp4_dequant", "mxfp4_dequant_hwcvt", "mxfp4_woq_gemm",
@@ -500,9 +515,12 @@ class GemmGroup:
     entry in ``ys`` is the ``(idx, val)`` pair.  The tensors are kept alive by the group; ``ys`` lists
     the outputs in order.  An item with ``w`` (a ``TiledWeights``) in place of ``q`` and ``s`` runs on
     the tile-major copy.  ``independent=True`` on an item sets ``MXFP4_DESC_INDEPENDENT``: neighbouring
-    items that carry it and do not read each other's outputs may share one launch."""
+    items that carry it and do not read each other's outputs may share one launch.
+    ``chained=True``: ``run()`` is ``mxfp4_woq_gemm_chain`` (one persistent launch for the whole
+    dependent sequence; one-token products on canonical tensors only); the group then owns a chain
+    workspace, prepared once, and ``chain_status()`` reads its status word (synchronises)."""
 
-    def __init__(self, items):
+    def __init__(self, items, chained: bool = False, wait_us: int = 0, phantom_workgroups: int = 0):
         self._keep, self.ys = [], []
         self._descs = (GemmDesc * max(1, len(items)))()
         self.count = len(items)
@@ -550,11 +568,35 @@ class GemmGroup:
             self._keep.append((x, q, s, bias, residual, y))
             self.ys.append(y)
         self.device = items[0]["x"].device if items else None
+        self.chained = chained
+        if chained:
+            self._opts = ChainOpts(int(wait_us), int(phantom_workgroups), 0)
+            self.workspace = None
+            self.chain_ws = None
+            if self.count:
+                nbytes = int(load().mxfp4_woq_gemm_chain_workspace_bytes())
+                self.chain_ws = torch.empty((nbytes,), dtype=torch.uint8, device=self.device)
+                self.chain_reset()
+            return
         need = int(load().mxfp4_woq_gemm_grouped_workspace_bytes(self._descs, self.count))
         self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.device) if need else None
 
+    def chain_reset(self) -> None:
+        """Prepare the chain workspace again (after a wait that was given up)."""
+        with torch.cuda.device(self.device):
+            _check(load().mxfp4_woq_gemm_chain_init(_ptr(self.chain_ws), self.chain_ws.numel(), _stream()))
+
+    def chain_status(self) -> int:
+        """The chain workspace's status word (0: every wait so far was met); synchronises."""
+        return int(self.chain_ws[CHAIN_STATUS_OFFSET:CHAIN_STATUS_OFFSET + 4].view(torch.int32).item())
+
     def run(self) -> None:
         if self.count == 0:
+            return
+        if self.chained:
+            with torch.cuda.device(self.device):
+                _check(load().mxfp4_woq_gemm_chain(self._descs, self.count, _ptr(self.chain_ws),
+                                                   self.chain_ws.numel(), ctypes.byref(self._opts), _stream()))
             return
         with torch.cuda.device(self.device):
             _check(load().mxfp4_woq_gemm_grouped(

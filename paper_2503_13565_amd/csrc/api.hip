@@ -7,6 +7,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <vector>
+
 #include "common.h"
 #include "kernels.h"
 #include "../../include/mxfp4.h"
@@ -635,6 +637,114 @@ int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count, void* wo
             }
         }
     }
+    return MXFP4_OK;
+}
+
+// ---- a chain of dependent one-token products in one persistent launch ------------------------
+
+size_t mxfp4_woq_gemm_chain_workspace_bytes(void) { return chain_workspace_bytes(); }
+
+int mxfp4_woq_gemm_chain_init(void* chain_ws, size_t chain_ws_bytes, void* stream)
+{
+    g_err[0] = 0;
+    if (!chain_ws)
+        return fail(MXFP4_ERR_NULL, "chain_ws is NULL");
+    if (chain_ws_bytes < chain_workspace_bytes())
+        return fail(MXFP4_ERR_WORKSPACE, "chain workspace of %zu bytes needed, %zu given", chain_workspace_bytes(),
+                    chain_ws_bytes);
+    if (!aligned(chain_ws, 256))
+        return fail(MXFP4_ERR_ALIGN, "chain_ws must be 256-byte aligned");
+    hipError_t e = launch_chain_ws_init(chain_ws, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "chain workspace init launch");
+}
+
+int mxfp4_woq_gemm_chain(const mxfp4_gemm_desc* descs, int64_t count, void* chain_ws, size_t chain_ws_bytes,
+                         const mxfp4_chain_opts* opts, void* stream)
+{
+    g_err[0] = 0;
+    if (count < 0 || count > MXFP4_CHAIN_MAX_LINKS)
+        return fail(MXFP4_ERR_SHAPE, "count=%lld out of range [0, %d]", (long long)count, MXFP4_CHAIN_MAX_LINKS);
+    if (count == 0)
+        return MXFP4_OK;
+    if (!descs)
+        return fail(MXFP4_ERR_NULL, "descs is NULL");
+    if (!chain_ws)
+        return fail(MXFP4_ERR_NULL, "chain_ws is NULL");
+    if (chain_ws_bytes < chain_workspace_bytes())
+        return fail(MXFP4_ERR_WORKSPACE, "chain workspace of %zu bytes needed, %zu given", chain_workspace_bytes(),
+                    chain_ws_bytes);
+    if (!aligned(chain_ws, 256))
+        return fail(MXFP4_ERR_ALIGN, "chain_ws must be 256-byte aligned");
+    int64_t wait_us = 2000000;
+    int phantom = 0;
+    if (opts) {
+        if (opts->wait_us < 0 || opts->wait_us > 20000000 || opts->phantom_workgroups < 0 ||
+            opts->phantom_workgroups > 64 || opts->reserved != 0)
+            return fail(MXFP4_ERR_ARG, "chain options out of range");
+        if (opts->wait_us > 0)
+            wait_us = opts->wait_us;
+        phantom = opts->phantom_workgroups;
+    }
+    std::vector<ChainItem> items((size_t)count);
+    for (int64_t i = 0; i < count; ++i) {
+        const mxfp4_gemm_desc& d = descs[i];
+        auto bad = [&](int code, const char* what) {
+            return fail(code, "descriptor %lld: %s", (long long)i, what);
+        };
+        if (d.flags != 0)
+            return bad(MXFP4_ERR_ARG, "a chained product takes no flags (canonical tensors only)");
+        if (d.M != 1)
+            return bad(MXFP4_ERR_ARG, "a chained product has one activation row (M == 1)");
+        int rc = check_weights(d.q_packed, d.scales_e8m0, d.N, d.K);
+        if (rc == MXFP4_OK)
+            rc = check_x(d.x_bf16, d.M, d.ldx, d.K);
+        if (rc != MXFP4_OK) {
+            char text[sizeof g_err];
+            snprintf(text, sizeof text, "%s", g_err);
+            return bad(rc, text);
+        }
+        if (d.act != MXFP4_ACT_NONE && d.act != MXFP4_ACT_SWIGLU)
+            return bad(MXFP4_ERR_ARG, "unknown act");
+        if (d.act == MXFP4_ACT_SWIGLU && d.N % 2 != 0)
+            return bad(MXFP4_ERR_SHAPE, "the gate pairs rows 2c and 2c + 1: N must be even");
+        if (d.argmax_out) {
+            if (d.y_bf16 || d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE)
+                return bad(MXFP4_ERR_ARG, "a descriptor with argmax_out takes no y, bias, residual or act");
+            if (i != count - 1)
+                return bad(MXFP4_ERR_ARG, "only the last product of a chain may carry argmax_out");
+            if (!aligned(d.argmax_out, 4) || !aligned(d.max_out, 4))
+                return bad(MXFP4_ERR_ALIGN, "argmax_out and max_out must be 4-byte aligned");
+        } else {
+            if (!d.y_bf16)
+                return bad(MXFP4_ERR_NULL, "y_bf16 is NULL");
+            if (!aligned(d.y_bf16, 2) || !aligned(d.bias_bf16, 2) || !aligned(d.residual_bf16, 2))
+                return bad(MXFP4_ERR_ALIGN, "y_bf16, bias_bf16 and residual_bf16 must be 2-byte aligned");
+        }
+        ChainItem& it = items[(size_t)i];
+        it.x = static_cast<const uint16_t*>(d.x_bf16);
+        it.q = static_cast<const uint8_t*>(d.q_packed);
+        it.s = static_cast<const uint8_t*>(d.scales_e8m0);
+        it.y = static_cast<uint16_t*>(d.y_bf16);
+        it.bias = static_cast<const uint16_t*>(d.bias_bf16);
+        it.residual = static_cast<const uint16_t*>(d.residual_bf16);
+        it.n = (int)d.N;
+        it.k = (int)d.K;
+        it.act = d.act;
+        it.argmax_out = d.argmax_out;
+        it.max_out = d.max_out;
+    }
+    DeviceInfo dev;
+    int rc = device_info(&dev);
+    if (rc)
+        return rc;
+    if (!chain_can_run(items.data(), (int)count, dev))
+        return fail(MXFP4_ERR_ARG, "not a chain the persistent launch takes: every K %% 128 == 0, at most %d weight "
+                                   "rows per compute unit and product, an activation row that fits the LDS",
+                    kChainMaxChunk);
+    hipError_t e = launch_chain(items.data(), (int)count, dev, chain_ws, (int)(wait_us * 100), phantom,
+                                static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return hip_fail(e, "chained product launch");
     return MXFP4_OK;
 }
 

@@ -158,6 +158,32 @@ hipError_t launch_verify_finish(const float* part_val, const int32_t* part_idx, 
                                 int m, const int32_t* draft, int32_t* argmax_out, float* max_out,
                                 int32_t* accept_out, hipStream_t stream);
 
+// A chain of dependent one-token products in one persistent launch (chain.hip): link i reads what
+// the links before it wrote; a grid-wide barrier sits between neighbours and the weights of the
+// next link are already streaming while it is crossed.  y == nullptr: the fused pick (last item
+// only; argmax_out / max_out).  The workspace holds the barrier's flags (zeroed once by
+// launch_chain_ws_init, then only ever advanced by the launches).  `wait_ticks`: bound of one wait
+// in 10 ns ticks; `phantom`: workgroups the barrier waits for that do not exist (tests of the
+// give-up path only).
+constexpr int kChainMaxLinks = 48;       // per launch; longer chains take several launches
+constexpr int kChainMaxChunk = 1024;     // weight rows of one link per workgroup
+struct ChainItem {
+    const uint16_t* x;
+    const uint8_t* q;
+    const uint8_t* s;
+    uint16_t* y;
+    const uint16_t* bias;
+    const uint16_t* residual;
+    int n, k, act;
+    int32_t* argmax_out;
+    float* max_out;
+};
+size_t chain_workspace_bytes();
+hipError_t launch_chain_ws_init(void* ws, hipStream_t stream);
+bool chain_can_run(const ChainItem* items, int count, const DeviceInfo& dev);
+hipError_t launch_chain(const ChainItem* items, int count, const DeviceInfo& dev, void* ws, int wait_ticks,
+                        int phantom, hipStream_t stream);
+
 // Plain streaming kernels used to measure what the memory system delivers.
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, const DeviceInfo& dev,
                               hipStream_t stream);
