@@ -19,6 +19,15 @@ static thread_local char g_err[512] = "";
 // Set while a grouped call checks its descriptors: run_gemm then does everything but launch.
 static thread_local bool g_check_only = false;
 
+// Every entry point starts here: no error text yet, and a HIP error left behind by earlier calls of
+// the caller (the runtime keeps the last one until somebody reads it) must not be reported as the
+// status of the launches that follow.
+static void begin_call()
+{
+    g_err[0] = 0;
+    (void)hipGetLastError();
+}
+
 static int fail(int code, const char* fmt, ...)
 {
     va_list ap;
@@ -37,14 +46,14 @@ static int hip_fail(hipError_t e, const char* what)
 static int device_info(DeviceInfo* out)
 {
     static DeviceInfo cache[64];
-    static bool have[64];
+    static std::atomic<bool> have[64];              // set after the entry is complete (racing threads write the same values)
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess)
         return hip_fail(e, "hipGetDevice");
     if (dev < 0 || dev >= 64)
         return fail(MXFP4_ERR_HIP, "device ordinal %d out of range", dev);
-    if (!have[dev]) {
+    if (!have[dev].load(std::memory_order_acquire)) {
         int cus = 0, lds = 0;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess)
@@ -54,7 +63,7 @@ static int device_info(DeviceInfo* out)
             return hip_fail(e, "hipDeviceGetAttribute(lds)");
         cache[dev].cus = cus > 0 ? cus : 256;
         cache[dev].lds_bytes = lds > 0 ? lds : 64 * 1024;
-        have[dev] = true;
+        have[dev].store(true, std::memory_order_release);
     }
     *out = cache[dev];
     return MXFP4_OK;
@@ -141,7 +150,7 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
                     size_t workspace_bytes, bool argmax, int path, void* stream, const Verify* verify = nullptr,
                     bool tiled = false, const Epilogue* epi = nullptr)
 {
-    g_err[0] = 0;
+    begin_call();
     int rc = check_verify(verify, M);
     if (rc)
         return rc;
@@ -277,7 +286,7 @@ static int run_bf16(const void* x, int64_t M, int64_t ldx, const void* w, int64_
                     void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
                     size_t workspace_bytes, bool argmax, void* stream, const Verify* verify = nullptr)
 {
-    g_err[0] = 0;
+    begin_call();
     if (int vrc = check_verify(verify, M))
         return vrc;
     if (!w)
@@ -405,7 +414,7 @@ extern "C" {
 static int cast_impl(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q_packed, void* scales_e8m0,
                      bool integer_rule, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (N < 0 || N > 0x7FFFFFFF)
         return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
     if (K < 32 || K % 32 != 0 || K > (1 << 24))
@@ -440,7 +449,7 @@ int mxfp4_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_t ldw
 static int dequant_impl(const void* q, const void* s, int64_t N, int64_t K, void* w, int64_t ldw, bool hw,
                         void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (N == 0)
         return MXFP4_OK;
     int rc = check_weights(q, s, N, K);
@@ -480,7 +489,7 @@ int mxfp4_woq_gemm_ws(const void* x_bf16, int64_t M, int64_t ldx, const void* q_
                       void* workspace, size_t workspace_bytes, int path, void* stream)
 {
     if (workspace && !aligned(workspace, 8)) {
-        g_err[0] = 0;
+        begin_call();
         return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
     }
     return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, workspace,
@@ -492,7 +501,7 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx, const void*
                          const void* residual_bf16, int64_t ldr, void* y_bf16, int64_t ldy, void* workspace,
                          size_t workspace_bytes, int path, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (workspace && !aligned(workspace, 8))
         return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
     Epilogue epi{static_cast<const uint16_t*>(bias_bf16), static_cast<const uint16_t*>(residual_bf16), 0, act};
@@ -511,13 +520,13 @@ int mxfp4_woq_gemm_fused(const void* x_bf16, int64_t M, int64_t ldx, const void*
 static int grouped_one(const mxfp4_gemm_desc& d, void* workspace, size_t workspace_bytes, void* stream)
 {
     if ((d.flags & ~(MXFP4_DESC_TILED | MXFP4_DESC_INDEPENDENT)) != 0) {
-        g_err[0] = 0;
+        begin_call();
         return fail(MXFP4_ERR_ARG, "unknown flags %#x", (unsigned)d.flags);
     }
     const bool tiled = (d.flags & MXFP4_DESC_TILED) != 0;
     if (d.argmax_out) {
         if (d.y_bf16 || d.bias_bf16 || d.residual_bf16 || d.act != MXFP4_ACT_NONE) {
-            g_err[0] = 0;
+            begin_call();
             return fail(MXFP4_ERR_ARG, "a descriptor with argmax_out takes no y, bias, residual or act");
         }
         if (tiled)
@@ -593,7 +602,7 @@ size_t mxfp4_woq_gemm_grouped_workspace_bytes(const mxfp4_gemm_desc* descs, int6
 int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count, void* workspace, size_t workspace_bytes,
                            void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (count < 0 || count > (1 << 20))
         return fail(MXFP4_ERR_SHAPE, "count=%lld out of range", (long long)count);
     if (count == 0)
@@ -646,7 +655,7 @@ size_t mxfp4_woq_gemm_chain_workspace_bytes(void) { return chain_workspace_bytes
 
 int mxfp4_woq_gemm_chain_init(void* chain_ws, size_t chain_ws_bytes, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (!chain_ws)
         return fail(MXFP4_ERR_NULL, "chain_ws is NULL");
     if (chain_ws_bytes < chain_workspace_bytes())
@@ -661,7 +670,7 @@ int mxfp4_woq_gemm_chain_init(void* chain_ws, size_t chain_ws_bytes, void* strea
 int mxfp4_woq_gemm_chain(const mxfp4_gemm_desc* descs, int64_t count, void* chain_ws, size_t chain_ws_bytes,
                          const mxfp4_chain_opts* opts, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (count < 0 || count > MXFP4_CHAIN_MAX_LINKS)
         return fail(MXFP4_ERR_SHAPE, "count=%lld out of range [0, %d]", (long long)count, MXFP4_CHAIN_MAX_LINKS);
     if (count == 0)
@@ -752,7 +761,7 @@ int mxfp4_woq_gemm_tiled_fused(const void* x_bf16, int64_t M, int64_t ldx, const
                                const void* s_tiled, int64_t N, int64_t K, const void* bias_bf16, int act,
                                const void* residual_bf16, int64_t ldr, void* y_bf16, int64_t ldy, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     Epilogue epi{static_cast<const uint16_t*>(bias_bf16), static_cast<const uint16_t*>(residual_bf16), 0, act};
     if (residual_bf16) {
         const int64_t C = act == MXFP4_ACT_SWIGLU ? N / 2 : N;
@@ -779,7 +788,7 @@ static DeviceInfo size_query_device()
     if (device_info(&dev) != MXFP4_OK) {
         dev.cus = 256;
         dev.lds_bytes = 160 * 1024;
-        g_err[0] = 0;
+        begin_call();
     }
     return dev;
 }
@@ -822,7 +831,7 @@ static int e4m3_check_weights(const void* q8, const void* s, int64_t N, int64_t 
 static int e4m3_cast_impl(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q8, void* scales_e8m0,
                           bool integer_rule, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (N < 0 || N > 0x7FFFFFFF)
         return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
     if (K < 32 || K % 32 != 0 || K > (1 << 24))
@@ -857,7 +866,7 @@ int mxfp4_e4m3_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_
 int mxfp4_e4m3_dequant(const void* q8, const void* scales_e8m0, int64_t N, int64_t K, void* w_bf16, int64_t ldw,
                        void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (N == 0)
         return MXFP4_OK;
     int rc = e4m3_check_weights(q8, scales_e8m0, N, K);
@@ -877,7 +886,7 @@ static int run_e4m3(const void* x, int64_t M, int64_t ldx, const void* q8, const
                     void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
                     size_t workspace_bytes, bool argmax, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     int rc = e4m3_check_weights(q8, s, N, K);
     if (rc)
         return rc;
@@ -976,7 +985,7 @@ static int e2m3_check_weights(const void* q6, const void* s, int64_t N, int64_t 
 static int e2m3_cast_impl(const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q6, void* scales_e8m0,
                           bool integer_rule, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (N < 0 || N > 0x7FFFFFFF)
         return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
     if (K < 32 || K % 32 != 0 || K > (1 << 24))
@@ -1011,7 +1020,7 @@ int mxfp4_e2m3_direct_cast_bits(const void* w_bf16, int64_t N, int64_t K, int64_
 int mxfp4_e2m3_dequant(const void* q6, const void* scales_e8m0, int64_t N, int64_t K, void* w_bf16, int64_t ldw,
                        void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (N == 0)
         return MXFP4_OK;
     int rc = e2m3_check_weights(q6, scales_e8m0, N, K);
@@ -1031,7 +1040,7 @@ static int run_e2m3(const void* x, int64_t M, int64_t ldx, const void* q6, const
                     void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
                     size_t workspace_bytes, bool argmax, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     int rc = e2m3_check_weights(q6, s, N, K);
     if (rc)
         return rc;
@@ -1161,7 +1170,7 @@ size_t mxfp4_tile_repack_s_bytes(int64_t N, int64_t K)
 int mxfp4_tile_repack(const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K, void* q_tiled,
                       void* s_tiled, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     int rc = check_weights(q_packed, scales_e8m0, (N + 15) / 16 * 16, K);
     if (rc)
         return rc;
@@ -1188,7 +1197,7 @@ int mxfp4_woq_gemm_tiled_ws(const void* x_bf16, int64_t M, int64_t ldx, const vo
                             size_t workspace_bytes, void* stream)
 {
     if (workspace && !aligned(workspace, 8)) {
-        g_err[0] = 0;
+        begin_call();
         return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
     }
     return run_gemm(x_bf16, M, ldx, q_tiled, s_tiled, N, K, y_bf16, ldy, nullptr, nullptr, workspace,
@@ -1235,7 +1244,7 @@ int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx, const voi
 
 int mxfp4_diag_stream_read(const void* src, size_t bytes, void* sink4, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (!src || !sink4)
         return fail(MXFP4_ERR_NULL, "src or sink is NULL");
     if (!aligned(src, 16) || bytes % 16 != 0)
@@ -1250,7 +1259,7 @@ int mxfp4_diag_stream_read(const void* src, size_t bytes, void* sink4, void* str
 
 int mxfp4_diag_stream_copy(const void* src, void* dst, size_t bytes, void* stream)
 {
-    g_err[0] = 0;
+    begin_call();
     if (!src || !dst)
         return fail(MXFP4_ERR_NULL, "src or dst is NULL");
     if (!aligned(src, 16) || !aligned(dst, 16) || bytes % 16 != 0)

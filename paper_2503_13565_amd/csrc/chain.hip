@@ -42,8 +42,13 @@ namespace {
 
 constexpr int kWaves = 16;                // of a workgroup
 constexpr int kCompute = kWaves - 1;      // waves that stream weights
-constexpr int kD = 8;                     // weight steps in flight per compute wave
+#ifndef MXFP4_CHAIN_D
+#define MXFP4_CHAIN_D 8
+#endif
+constexpr int kD = MXFP4_CHAIN_D;         // weight steps in flight per compute wave
 constexpr int kSc1 = 16;                  // cache policy of buffer instructions: device scope
+constexpr int kGroup = 16;                // consecutive weight rows dealt to a workgroup at a time
+constexpr int kBatch = 24;                // 16-byte loads in flight per lane when an activation row is fetched
 constexpr int kOut = 0x7FFFFFF0;          // a lane offset beyond every descriptor: touches no memory
 
 // workspace (32-bit words): flags, then the go word and the status word in lines of their own,
@@ -65,7 +70,7 @@ struct ChainLink {
     int n, k;
     int act;
     int rot;                    // weight rows dealt to the waves before this link, modulo kCompute
-    int chunk;                  // weight rows per workgroup
+    int chunk;                  // most weight rows of the link in one workgroup
     int pad;
 };
 static_assert(sizeof(ChainLink) == 72, "kernel argument layout");
@@ -83,9 +88,9 @@ struct ChainArgs {
 };
 
 struct Cursor {
-    int p, row, t;              // link, weight row within the workgroup's chunk, step within the row
-    int steps, nblk, cnt, row0;
-    bool pick;
+    int p, row, t;              // link, index of the weight row among the workgroup's, step within the row
+    int steps, nblk, cnt;       // cnt: weight rows of the link that belong to this workgroup
+    bool pick, gated;
     __amdgpu_buffer_rsrc_t rq, rs;
 };
 
@@ -103,13 +108,28 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
     int* wbi = reinterpret_cast<int*>(wbv + kWaves);
     int* abort_mark = wbi + kWaves;
 
+    // Weight rows are dealt to the workgroups in groups of kGroup consecutive rows, round robin (group
+    // g G + b is the g-th of workgroup b): all workgroups sweep through a link's weights side by side,
+    // and a workgroup's outputs, bias and residual values come in runs of kGroup.  (One contiguous run
+    // of all its rows per workgroup: the workgroups finished a link up to 4 us apart and the stream
+    // ran at half the speed.  Single rows round robin: every 2-byte access of the service wave hits a
+    // cache line of its own, 1.4 us to store a link's outputs.)  A gate pair never straddles groups.
+    auto rows_of = [&](int n, bool) {
+        const int groups = (n + kGroup - 1) / kGroup;
+        if (b >= groups)
+            return 0;
+        const int mine = (groups - b + G - 1) / G;
+        const bool owns_last = (groups - 1) % G == b;
+        return mine * kGroup - (owns_last ? groups * kGroup - n : 0);
+    };
+    auto global_row = [&](int r, bool) { return ((r / kGroup) * G + b) * kGroup + r % kGroup; };
     auto load_link = [&](Cursor& c, int p) {
         const ChainLink& L = a.links[p];
         c.p = p;
         c.nblk = L.k >> 5;
         c.steps = (c.nblk + 63) >> 6;
-        c.row0 = b * L.chunk;
-        c.cnt = max(0, min(L.chunk, L.n - c.row0));
+        c.gated = L.act == MXFP4_ACT_SWIGLU;
+        c.cnt = rows_of(L.n, c.gated);
         c.pick = L.y == nullptr;
         const int r = wave - L.rot;
         c.row = r < 0 ? r + kCompute : r;
@@ -141,7 +161,7 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
         auto issue = [&](int d) {
             const bool live = I.p < a.count;
             const bool vb = I.t * 64 + lane < I.nblk;
-            const int grow = I.row0 + I.row;
+            const int grow = global_row(I.row, I.gated);
             asm volatile("buffer_load_dwordx4 %0, %2, %4, %5 offen nt\n\t"
                          "buffer_load_dword %1, %3, %6, %7 offen"
                          : "=&v"(bq[d]), "=&v"(bs[d])
@@ -225,7 +245,7 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
                     const float v = wave_sum(acc);
                     acc = 0.f;
                     if (C.pick) {
-                        const int grow = C.row0 + C.row;             // the lower index wins among equal values
+                        const int grow = global_row(C.row, false);      // the lower index wins among equal values
                         if (v > best_val || (v == best_val && grow < best_idx)) {
                             best_val = v;
                             best_idx = grow;
@@ -257,19 +277,20 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
         const __amdgpu_buffer_rsrc_t rx =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(L.x), 0, L.k * 2, 0x00020000);
         auto slot = [](int c) { return (((c >> 8) * 4 + (c & 3)) << 6) + ((c >> 2) & 63); };
-        for (int c0 = 0; c0 < chunks; c0 += 64 * 8) {
-            u32x4_t v[8];
+        constexpr int kB = kBatch;                  // loads in flight per lane: a row of 12288 elements at once
+        for (int c0 = 0; c0 < chunks; c0 += 64 * kB) {
+            u32x4_t v[kB];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)             // past the end: zero
+            for (int u = 0; u < kB; ++u)            // past the end: zero
                 v[u] = __builtin_amdgcn_raw_buffer_load_b128(rx, (c0 + u * 64 + lane) * 16, 0, kSc1);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kB; ++u) {
                 const int c = c0 + u * 64 + lane;
                 if (c < steps * 256)
                     xs[slot(c)] = v[u];
             }
         }
-        for (int c = (chunks + 511) / 512 * 512 + lane; c < steps * 256; c += 64)
+        for (int c = (chunks + 64 * kBatch - 1) / (64 * kBatch) * (64 * kBatch) + lane; c < steps * 256; c += 64)
             xs[slot(c)] = u32x4_t{0, 0, 0, 0};
     };
     // wait until every workgroup has published `epoch` (workgroup 0: all flags, then the go word;
@@ -297,6 +318,16 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
         }
     };
 
+#ifdef MXFP4_CHAIN_TRACE
+    // measurement build only: time stamps (10 ns ticks) of the service wave's stages per link, in
+    // the memory behind the workspace proper: [workgroup][link][8]
+    auto stamp = [&](int p, int i) {
+        if (lane == 0)
+            a.ws[kWorkspaceBytes / 4 + (b * kChainMaxLinks + p) * 8 + i] = (uint32_t)__builtin_amdgcn_s_memrealtime();
+    };
+#else
+    auto stamp = [](int, int) {};
+#endif
     bool aborted = status0 != 0;                    // an earlier launch on this workspace gave up
     if (lane == 0)
         *abort_mark = aborted ? 1 : 0;
@@ -308,42 +339,64 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
 
     for (int p = 0; p < a.count; ++p) {
         const ChainLink& L = a.links[p];
-        const int row0 = b * L.chunk;
-        const int cnt = max(0, min(L.chunk, L.n - row0));
-        const bool last = p + 1 == a.count;
         const bool gated = L.act == MXFP4_ACT_SWIGLU;
+        const int cnt = rows_of(L.n, gated);
+        const bool last = p + 1 == a.count;
         const bool epi = gated || L.bias || L.residual;
-        // a link's bias and residual do not depend on its row sums: fetched ahead of the barrier
         const int cols = gated ? L.n >> 1 : L.n;
+        const int units = gated ? cnt >> 1 : cnt;   // outputs of this workgroup
+        // column of the workgroup's u-th output (a gated output is a pair of rows)
+        auto col_of = [&](int u) { return gated ? global_row(2 * u, true) >> 1 : global_row(u, false); };
         const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint16_t*>(L.bias), 0, L.bias ? L.n * 2 : 0, 0x00020000);
         const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint16_t*>(L.residual), 0, L.residual ? cols * 2 : 0, 0x00020000);
         const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(L.y, 0, L.y ? cols * 2 : 0, 0x00020000);
+        // a link's bias and residual do not depend on its row sums: those of the first kPre outputs
+        // per lane are fetched before the link's rows are awaited (absent operands: descriptors of
+        // size zero, the loads return zero)
+        constexpr int kPre = 4;
+        uint32_t e_b0[kPre], e_b1[kPre], e_r[kPre];
+        auto fetch_operands = [&](int u, uint32_t& b0, uint32_t& b1, uint32_t& r) {
+            const int col = col_of(u);
+            const int row = gated ? 2 * col : col;
+            b0 = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, u < units ? row * 2 : kOut, 0, kSc1);
+            b1 = gated ? (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, u < units ? row * 2 + 2 : kOut, 0, kSc1) : 0u;
+            r = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rr, u < units ? col * 2 : kOut, 0, kSc1);
+        };
+        if (epi) {
+#pragma unroll
+            for (int i = 0; i < kPre; ++i)
+                fetch_operands(lane + 64 * i, e_b0[i], e_b1[i], e_r[i]);
+        }
 
+        stamp(p, 0);
         lds_barrier();                              // this workgroup's part of link p is in LDS
+        stamp(p, 1);
         if (L.y) {
-            if (!gated) {
-                for (int r = lane; r < cnt; r += 64) {
-                    const int col = row0 + r;
-                    float v = ybuf[r];
-                    if (epi) {
-                        const float bias = bf16_bits_to_f32((uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, col * 2, 0, kSc1));
-                        const float res = bf16_bits_to_f32((uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rr, col * 2, 0, kSc1));
-                        v = (v + bias) + res;
-                    }
-                    __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16_rne(v), ry, col * 2, 0, kSc1);
+            auto finish = [&](int u, uint32_t b0, uint32_t b1, uint32_t r) {
+                if (u >= units)
+                    return;
+                const int col = col_of(u);
+                float v;
+                if (gated) {
+                    const float g = ybuf[2 * u] + bf16_bits_to_f32(b0), up = ybuf[2 * u + 1] + bf16_bits_to_f32(b1);
+                    v = silu_gate(g, up) + bf16_bits_to_f32(r);
+                } else {
+                    v = ybuf[u];
+                    if (epi)
+                        v = (v + bf16_bits_to_f32(b0)) + bf16_bits_to_f32(r);
                 }
-            } else {
-                for (int r = lane; r < (cnt >> 1); r += 64) {
-                    const int row = row0 + 2 * r, col = row >> 1;
-                    const float bg = bf16_bits_to_f32((uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, row * 2, 0, kSc1));
-                    const float bu = bf16_bits_to_f32((uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rb, row * 2 + 2, 0, kSc1));
-                    const float res = bf16_bits_to_f32((uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rr, col * 2, 0, kSc1));
-                    const float g = ybuf[2 * r] + bg, u = ybuf[2 * r + 1] + bu;
-                    const float v = silu_gate(g, u) + res;
-                    __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16_rne(v), ry, col * 2, 0, kSc1);
-                }
+                __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16_rne(v), ry, col * 2, 0, kSc1);
+            };
+#pragma unroll
+            for (int i = 0; i < kPre; ++i)
+                finish(lane + 64 * i, epi ? e_b0[i] : 0u, epi ? e_b1[i] : 0u, epi ? e_r[i] : 0u);
+            for (int u = lane + 64 * kPre; u < units; u += 64) {
+                uint32_t b0 = 0, b1 = 0, r = 0;
+                if (epi)
+                    fetch_operands(u, b0, b1, r);
+                finish(u, b0, b1, r);
             }
         } else {
             // the fused pick: this workgroup's winner among its waves
@@ -363,7 +416,9 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
                 __builtin_amdgcn_raw_buffer_store_b32((uint32_t)bi, rws, (kPartIdxWord + b) * 4, 0, kSc1);
             }
         }
+        stamp(p, 2);
         drain_vmem();                               // the outputs have left before the flag does
+        stamp(p, 3);
         const uint32_t epoch = base + (uint32_t)p + 1u;
         if (lane == 0)
             __builtin_amdgcn_raw_buffer_store_b32(epoch, rws, b * 4, 0, kSc1);
@@ -405,6 +460,7 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
         bool ok = wait_epoch(epoch, b == 0);
         if (ok && b == 0 && lane == 0)
             __builtin_amdgcn_raw_buffer_store_b32(epoch, rws, kGoWord * 4, 0, kSc1);
+        stamp(p, 4);
         if (!ok) {
             if (lane == 0) {
                 __builtin_amdgcn_raw_buffer_store_b32(0x100u + (uint32_t)p, rws, kStatusWord * 4, 0, kSc1);
@@ -413,7 +469,9 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
         } else {
             stage_x(p + 1);
         }
+        stamp(p, 5);
         lds_barrier();                              // the next activation row is staged (or the abort mark set)
+        stamp(p, 6);
         if (!ok)
             return;
     }
@@ -438,6 +496,13 @@ hipError_t launch_chain_ws_init(void* ws, hipStream_t stream)
 
 static int chain_steps(int k) { return ((k >> 5) + 63) >> 6; }
 
+// most weight rows of a link that one workgroup gets (whole groups of kGroup rows)
+static int chain_rows_per_workgroup(int n, int, int workgroups)
+{
+    const int groups = (n + kGroup - 1) / kGroup;
+    return (groups + workgroups - 1) / workgroups * kGroup;
+}
+
 bool chain_can_run(const ChainItem* items, int count, const DeviceInfo& dev)
 {
     if (count < 1 || dev.cus > kFlagWords)
@@ -451,9 +516,7 @@ bool chain_can_run(const ChainItem* items, int count, const DeviceInfo& dev)
             return false;                           // the pick ends a chain and takes no epilogue
         if (it.act == MXFP4_ACT_SWIGLU && it.n % 2 != 0)
             return false;
-        int chunk = (it.n + dev.cus - 1) / dev.cus;
-        if (it.act == MXFP4_ACT_SWIGLU)
-            chunk += chunk & 1;                     // a gate pair stays in one workgroup
+        const int chunk = chain_rows_per_workgroup(it.n, it.act, dev.cus);
         if (chunk > kChainMaxChunk)
             return false;
         x_bytes = max(x_bytes, (size_t)chain_steps(it.k) * 4096);
@@ -503,9 +566,7 @@ hipError_t launch_chain(const ChainItem* items, int count, const DeviceInfo& dev
             L.n = it.n;
             L.k = it.k;
             L.act = it.act;
-            L.chunk = (it.n + dev.cus - 1) / dev.cus;
-            if (it.act == MXFP4_ACT_SWIGLU)
-                L.chunk += L.chunk & 1;
+            L.chunk = chain_rows_per_workgroup(it.n, it.act, dev.cus);
             L.rot = rot;
             rot = (rot + L.chunk) % kCompute;
             if (!it.y) {
