@@ -335,6 +335,23 @@ int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx,
                                void* workspace, size_t workspace_bytes, int path, void* stream);
 
 /*
+ * mxfp4_woq_gemm_argmax for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same product,
+ * same pick, same bits; the scratch is a buffer of the library's own in device memory
+ * (mxfp4_woq_gemm_argmax_noalloc_max_bytes() = 4 MiB per device, held from the time the library is
+ * loaded until the process ends).  The call allocates and frees nothing.
+ *   - MXFP4_ERR_WORKSPACE when mxfp4_woq_gemm_argmax_workspace_bytes(M, N, K) exceeds that size
+ *     (large M with a K that has to be split): use the workspace form then.
+ *   - All calls on one device share the one buffer, whose contents are whatever the last call left;
+ *     nothing in it needs to start at zero.  Calls that overlap in time on one device (two streams,
+ *     two threads) race on it and give unspecified picks: serialise them, or use the workspace form.
+ */
+size_t mxfp4_woq_gemm_argmax_noalloc_max_bytes(void);
+int mxfp4_woq_gemm_argmax_noalloc(const void* x_bf16, int64_t M, int64_t ldx,
+                                  const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                                  int32_t* argmax_out, float* max_out, void* stream);
+
+/*
  * The unquantised counterpart, y = x * W^T with BF16 weights: the linear layer as the target
  * model runs it when it verifies draft tokens (section 3.2), and the 2-bytes-per-weight yardstick
  * of the 3.76x in section 3.4.3.  FP32 accumulation, BF16 RNE output, or the fused greedy pick

@@ -23,6 +23,7 @@ EXPORTS = [
     "mxfp4_bf16_gemm", "mxfp4_bf16_gemm_argmax_workspace_bytes", "mxfp4_bf16_gemm_argmax",
     "mxfp4_woq_gemm_verify", "mxfp4_bf16_gemm_verify",
     "mxfp4_woq_gemm_fused", "mxfp4_woq_gemm_grouped_workspace_bytes", "mxfp4_woq_gemm_grouped",
+    "mxfp4_woq_gemm_argmax_noalloc_max_bytes", "mxfp4_woq_gemm_argmax_noalloc",
     "mxfp4_woq_gemm_chain_workspace_bytes", "mxfp4_woq_gemm_chain_init", "mxfp4_woq_gemm_chain",
     "mxfp4_e4m3_direct_cast", "mxfp4_e4m3_direct_cast_bits", "mxfp4_e4m3_dequant", "mxfp4_e4m3_woq_gemm",
     "mxfp4_e4m3_woq_gemm_argmax",
@@ -137,6 +138,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_woq_gemm_grouped_workspace_bytes.restype = sz
     lib.mxfp4_woq_gemm_grouped.argtypes = [ctypes.POINTER(GemmDesc), i64, vp, sz, vp]
     lib.mxfp4_woq_gemm_grouped.restype = i32
+    lib.mxfp4_woq_gemm_argmax_noalloc_max_bytes.argtypes = []
+    lib.mxfp4_woq_gemm_argmax_noalloc_max_bytes.restype = sz
+    lib.mxfp4_woq_gemm_argmax_noalloc.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp]
+    lib.mxfp4_woq_gemm_argmax_noalloc.restype = i32
     lib.mxfp4_woq_gemm_chain_workspace_bytes.argtypes = []
     lib.mxfp4_woq_gemm_chain_workspace_bytes.restype = sz
     lib.mxfp4_woq_gemm_chain_init.argtypes = [vp, sz, vp]
@@ -266,6 +271,21 @@ def mxfp4_woq_gemm_argmax(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor,
         _check(load().mxfp4_woq_gemm_argmax_path(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(idx), _ptr(val),
                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                 path, _stream()))
+    return idx, val
+
+
+def mxfp4_woq_gemm_argmax_noalloc(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor,
+                                  out: Tuple[torch.Tensor, torch.Tensor]) -> Tuple[torch.Tensor, torch.Tensor]:
+    """The fused pick on the library's own scratch: nothing is allocated here either, so the caller
+    brings ``out = (idx int32 [M], val float32 [M])``."""
+    m, n, k, ldx = _gemm_shapes(x, q, s)
+    idx, val = out
+    if (idx.dtype != torch.int32 or val.dtype != torch.float32 or idx.shape != (m,) or val.shape != (m,)
+            or not idx.is_contiguous() or not val.is_contiguous()):
+        raise ValueError("out must be (int32 [M], float32 [M]), contiguous")
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_argmax_noalloc(_ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(idx), _ptr(val),
+                                                    _stream()))
     return idx, val
 
 

@@ -1148,6 +1148,55 @@ int mxfp4_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const void
                     workspace_bytes, true, MXFP4_PATH_AUTO, stream);
 }
 
+// The fused pick for callers that cannot allocate: the scratch of mxfp4_woq_gemm_argmax lives in
+// device memory of the library's own, one array per device, which the device holds from the moment
+// the library is loaded until the process ends.  In host code the array's name is only a handle for
+// the symbol; its address on the current device comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static int static_scratch(void** out)
+{
+    static void* ptr[64];
+    static std::atomic<bool> have[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64)
+        return fail(MXFP4_ERR_HIP, "device ordinal %d out of range", dev);
+    if (!have[dev].load(std::memory_order_acquire)) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        ptr[dev] = p;                               // (racing threads store the same address)
+        have[dev].store(true, std::memory_order_release);
+    }
+    *out = ptr[dev];
+    return MXFP4_OK;
+}
+
+size_t mxfp4_woq_gemm_argmax_noalloc_max_bytes(void) { return kStaticScratchBytes; }
+
+int mxfp4_woq_gemm_argmax_noalloc(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
+                                  const void* scales_e8m0, int64_t N, int64_t K, int32_t* argmax_out,
+                                  float* max_out, void* stream)
+{
+    begin_call();
+    const size_t need = mxfp4_woq_gemm_argmax_workspace_bytes(M, N, K);
+    if (need > kStaticScratchBytes)
+        return fail(MXFP4_ERR_WORKSPACE, "this shape needs %zu bytes of scratch, the library's own buffer holds %zu: "
+                                         "use mxfp4_woq_gemm_argmax with a workspace", need, kStaticScratchBytes);
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws))
+        return rc;
+    // nothing in the buffer has to start at zero: every partial winner that the second stage
+    // reads has been written by this call's product kernel
+    return run_gemm(x_bf16, M, ldx, q_packed, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, ws,
+                    kStaticScratchBytes, true, MXFP4_PATH_AUTO, stream);
+}
+
 int mxfp4_woq_gemm_argmax_path(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed,
                                const void* scales_e8m0, int64_t N, int64_t K, int32_t* argmax_out,
                                float* max_out, void* workspace, size_t workspace_bytes, int path,
