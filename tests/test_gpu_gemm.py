@@ -36,7 +36,7 @@ def test_verification_sweep_config0_shape(m):
     run_gemm_case(w, x, [AUTO], "cfg2 4096x4096 M=%d" % m)
 
 
-@pytest.mark.parametrize("m", [2, 8, 32])
+@pytest.mark.parametrize("m", [2, 4, 8, 16, 32])
 def test_verification_sweep_lm_head_argmax(m):
     data = synth.llama_linear(synth.LLAMA_7B, "lm_head", m=m, seed=0)
     run_gemm_case(data["w"], data["x"], [AUTO], "cfg2 lm_head M=%d" % m, argmax=True)
