@@ -20,6 +20,24 @@
  *   - Return value: MXFP4_OK or an error code; on error nothing was enqueued and
  *     mxfp4_last_error() (host, thread-local) describes it.  No call aborts the process.
  *   - Results are deterministic: the same inputs and shapes give bit-identical outputs.
+ *
+ * Which calls are what
+ *   The contract (the paper's problem statement: cast once, then products per step):
+ *     mxfp4_direct_cast, mxfp4_woq_gemm, mxfp4_woq_gemm_argmax (+ _workspace_bytes), mxfp4_last_error.
+ *   The same product with more said about it -- one family, pick by what the caller has:
+ *     mxfp4_woq_gemm_ws (a workspace), mxfp4_woq_gemm_fused (bias, gate, residual),
+ *     mxfp4_woq_gemm_verify (draft acceptance behind the pick), mxfp4_woq_gemm_grouped (a step's
+ *     products in one call), mxfp4_woq_gemm_chain (a step's dependent products in one launch),
+ *     mxfp4_woq_gemm_argmax_noalloc (no workspace), mxfp4_woq_gemm_tiled* with mxfp4_tile_repack (the
+ *     same calls on the tile-major copy of the weights).
+ *   Next to the method: mxfp4_bf16_gemm* (the unquantised target's linear), mxfp4_e4m3_* and
+ *     mxfp4_e2m3_* (8- and 6-bit element formats as drafts).
+ *   Diagnostics, for tests and measurements only: mxfp4_*_path (a kernel family forced),
+ *     mxfp4_direct_cast_bits / mxfp4_*_direct_cast_bits (the integer rounding rule in place of the
+ *     convert instruction), mxfp4_dequant*, mxfp4_diag_stream_*.
+ *   The library reads one environment variable, MXFP4_FORCE_PATH (a MXFP4_PATH_* number in place of
+ *   AUTO for every product call; tests only).  The launch-shape switches used while measuring exist
+ *   only in builds with -DMXFP4_MEASUREMENT_KNOBS.
  */
 #ifndef MXFP4_H
 #define MXFP4_H

@@ -31,9 +31,9 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def _compile(src: str, verbose: bool) -> str:
+def _compile(src: str, verbose: bool, defines=()) -> str:
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *EXTRA.get(src, []), *defines, "-c", os.path.join(CSRC, src), "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -45,10 +45,13 @@ def _compile(src: str, verbose: bool) -> str:
     return obj
 
 
-def build(verbose: bool = True, jobs: int = 4) -> str:
+def build(verbose: bool = True, jobs: int = 4, knobs: bool = False) -> str:
+    """knobs: a measurement build in which the launch-shape switches (environment variables) exist;
+    the library as shipped is built without them."""
     os.makedirs(BUILD, exist_ok=True)
+    defines = ("-DMXFP4_MEASUREMENT_KNOBS",) if knobs else ()
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, verbose), SOURCES))
+        objs = list(ex.map(lambda s: _compile(s, verbose, defines), SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
@@ -59,4 +62,4 @@ def build(verbose: bool = True, jobs: int = 4) -> str:
 
 
 if __name__ == "__main__":
-    print(build())
+    print(build(knobs="--knobs" in sys.argv[1:]))

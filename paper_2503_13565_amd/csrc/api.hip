@@ -931,7 +931,7 @@ static int run_e4m3(const void* x, int64_t M, int64_t ldx, const void* q8, const
     int parts_used = 0;
     // one or two rows in one pass over the weights: the decode-step frame; else the general kernel
     static const bool general_only = [] {
-        const char* e = getenv("MXFP4_E4M3_GENERAL");              // measurement only
+        const char* e = knob("MXFP4_E4M3_GENERAL");              // measurement only
         return e && atoi(e) != 0;
     }();
     const bool reg = !general_only && aligned(s, 4) && gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a);

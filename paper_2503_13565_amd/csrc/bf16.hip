@@ -887,7 +887,7 @@ bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev) { return (size_t)a.k
 hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
 {
     static const bool general_only = [] {
-        const char* e = getenv("MXFP4_BF16_GENERAL");                // measurement only
+        const char* e = knob("MXFP4_BF16_GENERAL");                // measurement only
         return e && atoi(e) != 0;
     }();
     if (!general_only && bf16_reg_can_run(a, dev))
@@ -896,7 +896,7 @@ hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts
     // 20.1 / 33.0 / 46.3 against 21.2 / 36.8 / 48.6 at four rows, equal at eight); from nine rows on
     // it needs two passes and the matrix cores one.
     static const int mfma_from = [] {
-        const char* e = getenv("MXFP4_BF16_MFMA_FROM");             // measurement only
+        const char* e = knob("MXFP4_BF16_MFMA_FROM");             // measurement only
         return e ? atoi(e) : 9;
     }();
     if (!general_only && a.m >= mfma_from && bf16_mfma_can_run(a, dev))

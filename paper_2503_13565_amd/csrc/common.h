@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include <atomic>
 
@@ -86,6 +87,19 @@ __device__ __forceinline__ void lds_barrier()
 // other counters untouched; gfx9 encoding).  A real waitcnt instruction rather than inline
 // assembly, so that the compiler's own wait insertion knows nothing is pending afterwards.
 __device__ __forceinline__ void drain_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// Host side: a measurement switch (an environment variable that picks a launch shape or a kernel so
+// that two of them can be timed in one run).  The library as shipped reads none of them; they exist
+// only in builds with -DMXFP4_MEASUREMENT_KNOBS.
+inline const char* knob(const char* name)
+{
+#ifdef MXFP4_MEASUREMENT_KNOBS
+    return getenv(name);
+#else
+    (void)name;
+    return nullptr;
+#endif
+}
 
 // Host side: lets a kernel use more than the default 64 KiB of dynamic LDS.  The attribute belongs
 // to the kernel on the current device, so there is one flag per device; each kernel instance keeps a

@@ -449,7 +449,7 @@ hipError_t launch_e4m3_gemv(const GemmArgs& a, const DeviceInfo& dev, int* parts
     for (int m0 = 0; m0 < a.m;) {
         const int left = a.m - m0;
         static const int max_mt = [] {
-            const char* e = getenv("MXFP4_E4M3_MAX_ROWS");           // measurement only
+            const char* e = knob("MXFP4_E4M3_MAX_ROWS");           // measurement only
             return e ? atoi(e) : 8;
         }();
         int mt = left > 4 && max_mt >= 8 ? 8 : (left > 2 ? 4 : (left > 1 ? 2 : 1));

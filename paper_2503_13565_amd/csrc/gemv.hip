@@ -521,7 +521,7 @@ bool env_tune(Tune* out)
 {
     static Tune t;
     static const bool have = [] {
-        if (const char* e = getenv("MXFP4_GEMV_TUNE")) {
+        if (const char* e = knob("MXFP4_GEMV_TUNE")) {
             int r, d, nw, w, b = 0;
             if (sscanf(e, "%d,%d,%d,%d,%d", &r, &d, &nw, &w, &b) >= 4) {
                 t = Tune{r, d, nw, w, b != 0};

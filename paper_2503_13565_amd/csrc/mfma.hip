@@ -556,7 +556,7 @@ hipError_t launch_one(const GemmArgs& a, int m0, int grid_y, size_t lds, const D
         occ_lds = lds;
     }
     static const int max_per_cu = [] {                             // MXFP4_MFMA_WGS: measurement only
-        const char* e = getenv("MXFP4_MFMA_WGS");
+        const char* e = knob("MXFP4_MFMA_WGS");
         const int v = e ? atoi(e) : 0;
         return v >= 1 && v <= 4 ? v : 1;
     }();
@@ -589,7 +589,7 @@ size_t lds_need(int steps, int mp)
 size_t lds_target(const DeviceInfo& dev)
 {
     static const int env = [] {
-        const char* e = getenv("MXFP4_MFMA_LDS_TARGET");
+        const char* e = knob("MXFP4_MFMA_LDS_TARGET");
         return e ? atoi(e) : 0;
     }();
     return env > 0 ? (size_t)env : (size_t)dev.lds_bytes;
@@ -701,7 +701,7 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
     if (tiled && (!splitk_ws || !mfma_tiled_split_can_run(a_in, dev)))
         return hipErrorInvalidValue;
     static const bool legacy = [] {
-        const char* e = getenv("MXFP4_MFMA_LEGACY");
+        const char* e = knob("MXFP4_MFMA_LEGACY");
         return e && atoi(e) != 0;
     }();
     if (!tiled && !legacy && !general_only && mfma_tile_can_run(a_in, dev))
@@ -765,7 +765,7 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
         a.phases = phases;
         a.phase_steps = steps;
         static const int depth = [] {                             // MXFP4_MFMA_DEPTH: measurement only
-            const char* e = getenv("MXFP4_MFMA_DEPTH");
+            const char* e = knob("MXFP4_MFMA_DEPTH");
             const int v = e ? atoi(e) : 0;
             return v >= 2 && v <= 4 ? v : 2;
         }();

@@ -584,7 +584,7 @@ hipError_t launch_tile_fmt(const GemmArgs& a, const DeviceInfo& dev, int* parts_
         cap >>= 1;
     auto width = [&](int left) { const int w = tile_pass_width(left); return w < cap ? w : cap; };
     const size_t widest = tile_lds_bytes(a.k, width(a.m));
-    static const int env_one = [] { const char* e = getenv("MXFP4_TILE_FMT_ONE_WG"); return e ? atoi(e) : -1; }();   // measurement only
+    static const int env_one = [] { const char* e = knob("MXFP4_TILE_FMT_ONE_WG"); return e ? atoi(e) : -1; }();   // measurement only
     // Two workgroups of four waves per CU only where the tiles are few (fewer than two per wave of the
     // wide form): from there on one workgroup of eight waves measured 4-12 % faster in these formats.
     const bool few = n_tiles < 2 * dev.cus;
@@ -635,13 +635,13 @@ hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts
     // three items in flight also for 16-row passes over many tiles (7B gate+up and LM head: 5 %)
     bool deep = long_k || (tile_pass_width(a.m) == 16 && n_tiles >= 4 * dev.cus);
     // MXFP4_TILE_WGS (1 to 4), MXFP4_TILE_D (2, 3) and MXFP4_TILE_NW (4, 8): measurement only
-    static const int env_wgs = [] { const char* e = getenv("MXFP4_TILE_WGS"); return e ? atoi(e) : 0; }();
-    static const int env_d = [] { const char* e = getenv("MXFP4_TILE_D"); return e ? atoi(e) : 0; }();
+    static const int env_wgs = [] { const char* e = knob("MXFP4_TILE_WGS"); return e ? atoi(e) : 0; }();
+    static const int env_d = [] { const char* e = knob("MXFP4_TILE_D"); return e ? atoi(e) : 0; }();
     if (env_wgs >= 1 && env_wgs <= 4 && env_wgs * widest + 2048 <= (size_t)dev.lds_bytes)
         per_cu = env_wgs;
     if (env_d == 2 || env_d == 3)
         deep = env_d == 3;
-    static const int env_nw = [] { const char* e = getenv("MXFP4_TILE_NW"); return e ? atoi(e) : 0; }();
+    static const int env_nw = [] { const char* e = knob("MXFP4_TILE_NW"); return e ? atoi(e) : 0; }();
     int blocks = dev.cus * per_cu;
     if (blocks > n_tiles)
         blocks = n_tiles;
