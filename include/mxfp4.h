@@ -285,20 +285,29 @@ int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * A chain of dependent one-token products in ONE persistent launch (section 3.2: a decode step is
- * bound by streaming the model's weights in; sections 3.1 and 3.4: one forward pass is a fixed
- * chain of contractions, each reading what the one before it wrote).  Same results as
- * mxfp4_woq_gemm_grouped on the same descriptors, bit for bit, but the products do not pay a launch
- * each: one workgroup per compute unit stays resident, a grid-wide barrier separates neighbouring
- * products, and the weights of the next product are already streaming while the barrier is
- * crossed and the new activation row is fetched.  Every product is ordered after ALL products
- * before it in the array, so a descriptor may read (x, residual) any earlier output, also in place.
+ * A chain of dependent one-token products, run the fastest way the device allows (section 3.2: a
+ * decode step is bound by streaming the model's weights in; sections 3.1 and 3.4: one forward pass
+ * is a fixed chain of contractions, each reading what the one before it wrote).  Same results as
+ * mxfp4_woq_gemm_grouped on the same descriptors, bit for bit.  Every product is ordered after ALL
+ * products before it in the array, so a descriptor may read (x, residual) any earlier output, also
+ * in place.
+ *
+ * The persistent launch.  One workgroup per compute unit stays resident for a run of products; a
+ * grid-wide barrier separates neighbours; the weights of the next product are already streaming
+ * while the barrier is crossed and the new activation row is fetched; a pick at the end of the
+ * chain is finished inside the same launch.  Measured on this device a barrier costs more than a
+ * launch (the barrier's own memory operations queue behind the weight loads of their compute
+ * unit), so opts.mode decides how much of the chain uses it:
+ *   MXFP4_CHAIN_AUTO        (default) the fastest form measured for the shapes at hand; on this device
+ *                           that is MXFP4_CHAIN_SEPARATE for every chain tried (7B and 70B shapes)
+ *   MXFP4_CHAIN_PERSISTENT  the whole chain in persistent launches (up to 48 products each)
+ *   MXFP4_CHAIN_SEPARATE    every product a launch of its own (what mxfp4_woq_gemm_grouped does)
+ *
  *   descs     HOST array, read during the call only.  Every descriptor: M == 1, flags == 0,
  *             K % 128 == 0, at most 1024 weight rows per compute unit (N <= 1024 x compute units);
  *             bias, act, residual as in mxfp4_woq_gemm_fused; argmax_out (with optional max_out)
- *             only on the last descriptor.  count <= MXFP4_CHAIN_MAX_LINKS (longer chains run as
- *             several launches of up to 48 products).  Shapes outside this: MXFP4_ERR_ARG, nothing
- *             launched (use mxfp4_woq_gemm_grouped).
+ *             only on the last descriptor.  count <= MXFP4_CHAIN_MAX_LINKS.  Shapes outside this:
+ *             MXFP4_ERR_ARG, nothing launched (use mxfp4_woq_gemm_grouped).
  *   chain_ws  device memory of mxfp4_woq_gemm_chain_workspace_bytes() bytes, 256-byte aligned,
  *             prepared ONCE by mxfp4_woq_gemm_chain_init and from then on owned by the chained
  *             calls: it carries the barrier's epoch counters from one call to the next (nothing is
@@ -308,21 +317,24 @@ int mxfp4_woq_gemm_grouped(const mxfp4_gemm_desc* descs, int64_t count,
  *   opts      NULL, or: wait_us = bound of a single barrier wait in microseconds (0: the default
  *             of 2 s; at most 20 s); phantom_workgroups = number of workgroups the barrier waits
  *             for that do not exist (0 in production; > 0 makes every wait expire and is how the
- *             give-up path is exercised from the host); reserved = 0.
- * The launch needs all its workgroups resident together (one per compute unit).  Other work on
- * the device only delays it; a wait that outlasts wait_us is given up: every wave then ends
- * normally, the outputs of the call are unspecified, and the 32-bit word at byte offset
- * MXFP4_CHAIN_STATUS_OFFSET of chain_ws becomes non-zero (0x100 + index of the product whose
- * barrier expired).  The status is sticky: later calls on that workspace launch, see it and do
- * nothing, until mxfp4_woq_gemm_chain_init prepares the workspace again.  The call itself never
- * synchronises; the caller reads the status word after synchronising the stream.
+ *             give-up path is exercised from the host; it implies the persistent kernel for the
+ *             whole chain); mode as above.
+ * The persistent launch needs all its workgroups resident together (one per compute unit).  Other
+ * work on the device only delays it; a wait that outlasts wait_us is given up: every wave then
+ * ends normally, the outputs of the call are unspecified, and the 32-bit word at byte offset
+ * MXFP4_CHAIN_STATUS_OFFSET of chain_ws becomes non-zero (0x100 + index, within its launch, of the
+ * product whose barrier expired).  The status is sticky: later persistent launches on that
+ * workspace see it and do nothing, until mxfp4_woq_gemm_chain_init prepares the workspace again.
+ * The call itself never synchronises; the caller reads the status word after synchronising the
+ * stream.
  */
 #define MXFP4_CHAIN_MAX_LINKS 4096
 #define MXFP4_CHAIN_STATUS_OFFSET 4224
+enum { MXFP4_CHAIN_AUTO = 0, MXFP4_CHAIN_PERSISTENT = 1, MXFP4_CHAIN_SEPARATE = 2 };
 typedef struct mxfp4_chain_opts {
     int64_t wait_us;
     int32_t phantom_workgroups;
-    int32_t reserved;
+    int32_t mode;
 } mxfp4_chain_opts;
 size_t mxfp4_woq_gemm_chain_workspace_bytes(void);
 int mxfp4_woq_gemm_chain_init(void* chain_ws, size_t chain_ws_bytes, void* stream);

@@ -50,10 +50,11 @@ class GemmDesc(ctypes.Structure):
 
 class ChainOpts(ctypes.Structure):
     """``mxfp4_chain_opts`` of the header."""
-    _fields_ = [("wait_us", ctypes.c_int64), ("phantom_workgroups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+    _fields_ = [("wait_us", ctypes.c_int64), ("phantom_workgroups", ctypes.c_int32), ("mode", ctypes.c_int32)]
 
 
 CHAIN_STATUS_OFFSET = 4224
+CHAIN_AUTO, CHAIN_PERSISTENT, CHAIN_SEPARATE = 0, 1, 2
 
 
 class Mxfp4Error(RuntimeError):
@@ -536,11 +537,13 @@ class GemmGroup:
     the outputs in order.  An item with ``w`` (a ``TiledWeights``) in place of ``q`` and ``s`` runs on
     the tile-major copy.  ``independent=True`` on an item sets ``MXFP4_DESC_INDEPENDENT``: neighbouring
     items that carry it and do not read each other's outputs may share one launch.
-    ``chained=True``: ``run()`` is ``mxfp4_woq_gemm_chain`` (one persistent launch for the whole
-    dependent sequence; one-token products on canonical tensors only); the group then owns a chain
-    workspace, prepared once, and ``chain_status()`` reads its status word (synchronises)."""
+    ``chained=True``: ``run()`` is ``mxfp4_woq_gemm_chain`` (a dependent sequence of one-token
+    products on canonical tensors, ``mode`` = ``CHAIN_AUTO``, ``CHAIN_PERSISTENT`` or
+    ``CHAIN_SEPARATE``); the group then owns a chain workspace, prepared once, and
+    ``chain_status()`` reads its status word (synchronises)."""
 
-    def __init__(self, items, chained: bool = False, wait_us: int = 0, phantom_workgroups: int = 0):
+    def __init__(self, items, chained: bool = False, wait_us: int = 0, phantom_workgroups: int = 0,
+                 mode: int = 0):
         self._keep, self.ys = [], []
         self._descs = (GemmDesc * max(1, len(items)))()
         self.count = len(items)
@@ -590,7 +593,7 @@ class GemmGroup:
         self.device = items[0]["x"].device if items else None
         self.chained = chained
         if chained:
-            self._opts = ChainOpts(int(wait_us), int(phantom_workgroups), 0)
+            self._opts = ChainOpts(int(wait_us), int(phantom_workgroups), int(mode))
             self.workspace = None
             self.chain_ws = None
             if self.count:

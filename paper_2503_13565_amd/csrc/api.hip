@@ -685,14 +685,15 @@ int mxfp4_woq_gemm_chain(const mxfp4_gemm_desc* descs, int64_t count, void* chai
     if (!aligned(chain_ws, 256))
         return fail(MXFP4_ERR_ALIGN, "chain_ws must be 256-byte aligned");
     int64_t wait_us = 2000000;
-    int phantom = 0;
+    int phantom = 0, mode = MXFP4_CHAIN_AUTO;
     if (opts) {
         if (opts->wait_us < 0 || opts->wait_us > 20000000 || opts->phantom_workgroups < 0 ||
-            opts->phantom_workgroups > 64 || opts->reserved != 0)
+            opts->phantom_workgroups > 64 || opts->mode < MXFP4_CHAIN_AUTO || opts->mode > MXFP4_CHAIN_SEPARATE)
             return fail(MXFP4_ERR_ARG, "chain options out of range");
         if (opts->wait_us > 0)
             wait_us = opts->wait_us;
         phantom = opts->phantom_workgroups;
+        mode = opts->mode;
     }
     std::vector<ChainItem> items((size_t)count);
     for (int64_t i = 0; i < count; ++i) {
@@ -750,10 +751,36 @@ int mxfp4_woq_gemm_chain(const mxfp4_gemm_desc* descs, int64_t count, void* chai
         return fail(MXFP4_ERR_ARG, "not a chain the persistent launch takes: every K %% 128 == 0, at most %d weight "
                                    "rows per compute unit and product, an activation row that fits the LDS",
                     kChainMaxChunk);
-    hipError_t e = launch_chain(items.data(), (int)count, dev, chain_ws, (int)(wait_us * 100), phantom,
-                                static_cast<hipStream_t>(stream));
-    if (e != hipSuccess)
-        return hip_fail(e, "chained product launch");
+    // How many leading products run as launches of their own.  A grid barrier costs more here than
+    // a launch does (4 to 5.5 us against 3 to 3.5 us per product, measured on the 7B shapes: the
+    // barrier's memory operations queue behind the weight loads of their compute unit), and the LM
+    // head with its pick in one persistent launch takes 20 us against 17 for the two ordinary
+    // launches (the persistent kernel starts more slowly), so AUTO keeps every product apart.
+    const int64_t apart = (phantom == 0 && mode != MXFP4_CHAIN_PERSISTENT) ? count : 0;
+    for (int pass = 0; pass < 2 && apart > 0; ++pass) {
+        // first every check of the single calls with nothing launched, then the launches
+        for (int64_t i = 0; i < apart; ++i) {
+            g_check_only = pass == 0;
+            const int rc1 = descs[i].argmax_out
+                                ? mxfp4_woq_gemm_argmax(descs[i].x_bf16, 1, descs[i].ldx, descs[i].q_packed,
+                                                        descs[i].scales_e8m0, descs[i].N, descs[i].K, descs[i].argmax_out,
+                                                        descs[i].max_out, static_cast<char*>(chain_ws) + chain_pick_area_offset(),
+                                                        chain_workspace_bytes() - chain_pick_area_offset(), stream)
+                                : grouped_one(descs[i], nullptr, 0, stream);
+            g_check_only = false;
+            if (rc1 != MXFP4_OK) {
+                char text[sizeof g_err];
+                snprintf(text, sizeof text, "%s", g_err);
+                return fail(rc1, "descriptor %lld: %s", (long long)i, text);
+            }
+        }
+    }
+    if (apart < count) {
+        hipError_t e = launch_chain(items.data() + apart, (int)(count - apart), dev, chain_ws, (int)(wait_us * 100),
+                                    phantom, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess)
+            return hip_fail(e, "chained product launch");
+    }
     return MXFP4_OK;
 }
 

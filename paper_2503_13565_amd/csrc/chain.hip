@@ -52,13 +52,15 @@ constexpr int kBatch = 24;                // 16-byte loads in flight per lane wh
 constexpr int kOut = 0x7FFFFFF0;          // a lane offset beyond every descriptor: touches no memory
 
 // workspace (32-bit words): flags, then the go word and the status word in lines of their own,
-// then the partial winners of the fused pick
+// then the partial winners of the fused pick; behind these 16 KB, scratch for a pick that the
+// caller's mode sends to the ordinary two-launch form
 constexpr int kFlagWords = 1024;
 constexpr int kGoWord = 1024;
 constexpr int kStatusWord = 1056;
 constexpr int kPartValWord = 2048;
 constexpr int kPartIdxWord = 3072;
-constexpr size_t kWorkspaceBytes = 16384;
+constexpr size_t kSyncBytes = 16384;       // flags, go and status words, partial winners
+constexpr size_t kWorkspaceBytes = 65536;  // + the scratch of a pick that runs as launches of its own
 
 struct ChainLink {
     const uint8_t* q;
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(kWaves * 64) void chain_kernel(const ChainArgs a)
 
     // ---- service wave --------------------------------------------------------------------------
     __builtin_amdgcn_s_setprio(3);
-    const __amdgpu_buffer_rsrc_t rws = __builtin_amdgcn_make_buffer_rsrc(a.ws, 0, (int)kWorkspaceBytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rws = __builtin_amdgcn_make_buffer_rsrc(a.ws, 0, (int)kSyncBytes, 0x00020000);
     const int n_flags = G + a.phantom;
     const uint32_t base = __builtin_amdgcn_raw_buffer_load_b32(rws, b * 4, 0, kSc1);
     const uint32_t status0 = __builtin_amdgcn_raw_buffer_load_b32(rws, kStatusWord * 4, 0, kSc1);
@@ -486,11 +488,12 @@ __global__ __launch_bounds__(256) void chain_ws_init_kernel(uint32_t* ws, int wo
 }  // namespace
 
 size_t chain_workspace_bytes() { return kWorkspaceBytes; }
+size_t chain_pick_area_offset() { return kSyncBytes; }
 
 hipError_t launch_chain_ws_init(void* ws, hipStream_t stream)
 {
     hipLaunchKernelGGL(chain_ws_init_kernel, dim3(4), dim3(256), 0, stream, static_cast<uint32_t*>(ws),
-                       (int)(kWorkspaceBytes / 4));
+                       (int)(kSyncBytes / 4));
     return hipGetLastError();
 }
 

@@ -179,6 +179,7 @@ struct ChainItem {
     float* max_out;
 };
 size_t chain_workspace_bytes();
+size_t chain_pick_area_offset();       // where the scratch of a pick run as ordinary launches starts
 hipError_t launch_chain_ws_init(void* ws, hipStream_t stream);
 bool chain_can_run(const ChainItem* items, int count, const DeviceInfo& dev);
 hipError_t launch_chain(const ChainItem* items, int count, const DeviceInfo& dev, void* ws, int wait_ticks,

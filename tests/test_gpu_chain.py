@@ -62,11 +62,11 @@ def clone_items(items, remap):
     return out
 
 
-def run_both(items, chained_tensors):
+def run_both(items, chained_tensors, mode=binding.CHAIN_PERSISTENT):
     """Run `items` chained and as single launches on twin buffers; compare every output's bits."""
     remap = {t.data_ptr(): t.clone() for t in chained_tensors}
     twin = clone_items(items, remap)
-    chain = binding.GemmGroup(items, chained=True)
+    chain = binding.GemmGroup(items, chained=True, mode=mode)
     chain.run()
     single = binding.GemmGroup(twin)
     single.run()
@@ -138,10 +138,11 @@ def oracle_chain(lins, inputs, f):
     return (out0, tol0), (out1, tol1), (out2, tol2), (y3, tol3)
 
 
+@pytest.mark.parametrize("mode", [binding.CHAIN_PERSISTENT, binding.CHAIN_AUTO, binding.CHAIN_SEPARATE])
 @pytest.mark.parametrize("h,f,vocab,bias", [(1024, 1408, 4096, False), (2048, 2816, 8192, True)])
-def test_real_chain_equals_single_launches_and_the_oracle_chain(h, f, vocab, bias):
+def test_real_chain_equals_single_launches_and_the_oracle_chain(h, f, vocab, bias, mode):
     items, chained, lins, inputs = decoder_chain(h, f, vocab, 21000 + h, with_bias=bias)
-    chain, single = run_both(items, chained)
+    chain, single = run_both(items, chained, mode)
     y_o, y_g = chained
     (out0, tol0), (out1, tol1), (out2, tol2), (y3, tol3) = oracle_chain(lins, inputs, f)
     # y_o holds link 2's output (link 0's was updated in place); the twin run keeps no copy either
@@ -205,6 +206,7 @@ def test_llama7b_decode_step_equals_single_launches():
         dict(x=y_g, q=ld[0], s=ld[1], residual=y_o, y=y_o),
         dict(x=y_o, q=lh[0], s=lh[1], argmax=True),
     ]
+    run_both(items, [y_q, y_o, y_g], binding.CHAIN_AUTO)
     chain, _ = run_both(items, [y_q, y_o, y_g])
     # replays of the same chain (new epochs every time) give the same bits
     first = [y.clone() if not isinstance(y, tuple) else (y[0].clone(), y[1].clone()) for y in chain.ys]
@@ -252,7 +254,7 @@ def test_give_up_is_reported_and_nothing_hangs():
     torch.cuda.synchronize()
     assert chain.chain_status() == 0x100
     # after a reset the same workspace serves a proper chain again
-    good = binding.GemmGroup(items, chained=True)
+    good = binding.GemmGroup(items, chained=True, mode=binding.CHAIN_PERSISTENT)
     good.chain_ws = chain.chain_ws
     good.chain_reset()
     good.run()
@@ -266,7 +268,7 @@ def test_give_up_is_reported_and_nothing_hangs():
 def test_chain_in_a_graph_replays():
     h, f = 1024, 1408
     items, chained, _, _ = decoder_chain(h, f, 4096, 26000)
-    chain = binding.GemmGroup(items, chained=True)
+    chain = binding.GemmGroup(items, chained=True, mode=binding.CHAIN_PERSISTENT)
     chain.run()
     torch.cuda.synchronize()
     want = [chained[1].clone(), chained[0].clone(), chain.ys[3][0].clone()]

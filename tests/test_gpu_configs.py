@@ -137,7 +137,7 @@ def test_llama70b_stack_chained_equals_single_launches(stack70b):
             items.append(dict(x=xs[key], q=t["q"], s=t["s"], argmax=True))
         else:
             items.append(dict(x=xs[key], q=t["q"], s=t["s"]))
-    chain = binding.GemmGroup(items, chained=True)
+    chain = binding.GemmGroup(items, chained=True, mode=binding.CHAIN_PERSISTENT)
     chain.run()
     torch.cuda.synchronize()
     assert chain.chain_status() == 0
