@@ -330,12 +330,13 @@ def config_verify_sweep_lm_head(clock, sets, dev, reps):
     return out
 
 
-def stack_step_times(clock, ops, xs, m, reps, with_chain):
+def stack_step_times(clock, ops, xs, m, reps, with_chain, tiled=False):
     """One linear-only decode step over a resident stack at M rows: a graph replay of all launches,
-    one grouped library call, and (M = 1) chained persistent launches."""
+    one grouped library call, and (M = 1) chained persistent launches.  tiled: every product on the
+    tile-major copy of its weights (ops then carry `tw`)."""
     import torch
     from paper_2503_13565_amd import binding
-    dev = ops[0]["q"].device
+    dev = xs[(m, "lm_head")][0].device
     head = ops[-1]
     idx = torch.empty((m,), dtype=torch.int32, device=dev)
     val = torch.empty((m,), dtype=torch.float32, device=dev)
@@ -347,11 +348,19 @@ def stack_step_times(clock, ops, xs, m, reps, with_chain):
     def step():
         for t in ops[:-1]:
             x, y = xs[(m, t["name"])]
-            binding.mxfp4_woq_gemm(x, t["q"], t["s"], y=y, workspace=sk)
-        binding.mxfp4_woq_gemm_argmax(xs[(m, "lm_head")][0], head["q"], head["s"], workspace=ws, out=(idx, val))
+            if tiled:
+                binding.mxfp4_woq_gemm_tiled(x, t["tw"], y=y, workspace=sk)
+            else:
+                binding.mxfp4_woq_gemm(x, t["q"], t["s"], y=y, workspace=sk)
+        if tiled:
+            binding.mxfp4_woq_gemm_tiled_argmax(xs[(m, "lm_head")][0], head["tw"], workspace=ws, out=(idx, val))
+        else:
+            binding.mxfp4_woq_gemm_argmax(xs[(m, "lm_head")][0], head["q"], head["s"], workspace=ws, out=(idx, val))
 
-    items = [dict(x=xs[(m, t["name"])][0], q=t["q"], s=t["s"], y=xs[(m, t["name"])][1]) for t in ops[:-1]]
-    items.append(dict(x=xs[(m, "lm_head")][0], q=head["q"], s=head["s"], argmax=True, out=(idx, val)))
+    def weights_of(t):
+        return dict(w=t["tw"]) if tiled else dict(q=t["q"], s=t["s"])
+    items = [dict(x=xs[(m, t["name"])][0], y=xs[(m, t["name"])][1], **weights_of(t)) for t in ops[:-1]]
+    items.append(dict(x=xs[(m, "lm_head")][0], argmax=True, out=(idx, val), **weights_of(head)))
     nbytes = sum(algorithmic_bytes(m, t["n"], t["k"]) for t in ops)
     res = {}
     us, graphs = clock.us_per_call_graphs([step], reps, 1)
@@ -359,7 +368,7 @@ def stack_step_times(clock, ops, xs, m, reps, with_chain):
     del graphs
     group = binding.GemmGroup(items)
     res["grouped_call"] = rate(nbytes, clock.us_per_call([group.run], reps, 1))
-    if with_chain and m == 1:
+    if with_chain and m == 1 and not tiled:
         chain = binding.GemmGroup(items, chained=True, mode=binding.CHAIN_PERSISTENT)
         res["chained_persistent_launches"] = rate(nbytes, clock.us_per_call([chain.run], reps, 1))
         if chain.chain_status() != 0:
@@ -370,13 +379,23 @@ def stack_step_times(clock, ops, xs, m, reps, with_chain):
     return res
 
 
-def config_stack(clock, shape, m_list, reps, dev, with_chain=True, layers=0):
-    from paper_2503_13565_amd import synth  # noqa: F401
+def config_stack(clock, shape, m_list, reps, dev, with_chain=True, layers=0, tiled=False, tiled_m=()):
+    """tiled: the stack only as tile-major copies (a pure verifier); tiled_m: rows for which the step
+    is timed on the tile-major copy too, beside the canonical tensors (both copies resident)."""
+    from paper_2503_13565_amd import binding
     ops, xs, cast_acc = build_stack(shape, m_list, dev, layers)
     out = {"weights_GB": round(sum(t["n"] * t["k"] * 0.53125 for t in ops) / 1e9, 3),
            "layers": (len(ops) - 1) // 4}
+    if tiled or tiled_m:
+        for t in ops:
+            t["tw"] = binding.mxfp4_tile_repack(t["q"], t["s"])
+            if tiled:
+                t["q"] = t["s"] = None
     for m in m_list:
-        out["M=%d" % m] = stack_step_times(clock, ops, xs, m, reps, with_chain)
+        if not tiled:
+            out["M=%d" % m] = stack_step_times(clock, ops, xs, m, reps, with_chain)
+        if tiled or m in tiled_m:
+            out["M=%d on the tile-major copy" % m] = stack_step_times(clock, ops, xs, m, reps, False, tiled=True)
     gbps = cast_acc["bytes"] / (cast_acc["ms"] * 1e-3) / 1e9
     out["direct_cast_all_weights"] = {
         "weights": cast_acc["weights"], "ms": round(cast_acc["ms"], 3), "GBps_moved": round(gbps, 1),
@@ -399,8 +418,8 @@ def run_stack_only(args) -> int:
     reps = max(2, args.steps // 24)
     if args.weights == "bf16":
         return run_stack_bf16(args, clock, shape, dev, reps)
-    res = config_stack(clock, shape, [args.m], reps, dev, layers=args.layers)
-    best = res["M=%d" % args.m]["best"]
+    res = config_stack(clock, shape, [args.m], reps, dev, layers=args.layers, tiled=args.tiled)
+    best = res["M=%d on the tile-major copy" % args.m if args.tiled else "M=%d" % args.m]["best"]
     print(json.dumps({
         "metric": METRIC, "value": best["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": reps, "warmup": 1,
         "ms_per_step": round(best["us"] * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -472,6 +491,8 @@ def main() -> int:
                     help="decode7b (default): the five 7B decode linears over rotating weight sets, with the "
                          "other configurations beside them; stack7b / stack70b: only that stack at --m rows")
     ap.add_argument("--layers", type=int, default=0, help="stack workloads: layers to build (0 = the model's)")
+    ap.add_argument("--tiled", action="store_true",
+                    help="stack workloads: every product on the tile-major copy of its weights")
     ap.add_argument("--weights", default="mxfp4", choices=["mxfp4", "bf16"],
                     help="stack workloads: bf16 runs the unquantised reference stack")
     args = ap.parse_args()
@@ -678,7 +699,7 @@ def main() -> int:
         sets.clear()
         torch.cuda.empty_cache()
         stack_reps = max(5, steps // 24)
-        configs["config_4_llama7b_stack"] = config_stack(clock, synth.LLAMA_7B, [1, 8], stack_reps, dev)
+        configs["config_4_llama7b_stack"] = config_stack(clock, synth.LLAMA_7B, [1, 8], stack_reps, dev, tiled_m=(1, 8))
         torch.cuda.empty_cache()
         if not args.no_70b:
             configs["config_5_llama70b_stack"] = config_stack(clock, synth.LLAMA_70B, [1, 4, 16], max(2, stack_reps // 2), dev)

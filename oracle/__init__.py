@@ -79,6 +79,16 @@ def _load():
         lib.oracle_e2m3_woq_gemm.restype = i32
         lib.oracle_e2m3_magnitude.argtypes = [i32]
         lib.oracle_e2m3_magnitude.restype = ctypes.c_double
+        lib.oracle_mx_block_bytes.argtypes = [i32]
+        lib.oracle_mx_block_bytes.restype = i32
+        lib.oracle_mx_magnitude.argtypes = [i32, i32]
+        lib.oracle_mx_magnitude.restype = ctypes.c_double
+        lib.oracle_mx_direct_cast.argtypes = [i32, vp, i64, i64, i64, vp, vp, i32]
+        lib.oracle_mx_direct_cast.restype = i32
+        lib.oracle_mx_dequant.argtypes = [i32, vp, vp, i64, i64, vp]
+        lib.oracle_mx_dequant.restype = i32
+        lib.oracle_mx_woq_gemm.argtypes = [i32, vp, i64, i64, vp, vp, i64, i64, vp, vp, i32]
+        lib.oracle_mx_woq_gemm.restype = i32
         lib.oracle_epilogue.argtypes = [vp, vp, i64, i64, vp, vp, i64, i32, vp, vp]
         lib.oracle_epilogue.restype = i32
         lib.oracle_argmax.argtypes = [vp, i64, i64, vp, vp]
@@ -284,6 +294,66 @@ def e2m3_woq_gemm(x_bits, q6, s, threads: int = 0, want_abs: bool = True):
                                       _ptr(a) if want_abs else None, threads)
     if rc:
         raise RuntimeError("oracle_e2m3_woq_gemm failed: %d" % rc)
+    return (y, a) if want_abs else y
+
+
+FMT_E5M2, FMT_E3M2, FMT_T2 = 1, 2, 3
+
+
+def mx_block_bytes(fmt: int) -> int:
+    return int(_load().oracle_mx_block_bytes(int(fmt)))
+
+
+def mx_magnitude(fmt: int, code: int) -> float:
+    return float(_load().oracle_mx_magnitude(int(fmt), int(code)))
+
+
+def mx_direct_cast(fmt: int, w_bits, threads: int = 0):
+    """BF16 bit patterns ``[N, K]`` -> (``q [N, K/32 * block bytes]`` packed codes, ``s [N, K/32]`` scale
+    bytes) in one of the generic formats (``FMT_E5M2``, ``FMT_E3M2``, ``FMT_T2``)."""
+    w = _as(w_bits, np.uint16, 2)
+    n, k = w.shape
+    bb = mx_block_bytes(fmt)
+    if k % BLOCK or not bb:
+        raise ValueError("K must be a multiple of 32 and fmt a known format")
+    q = np.empty((n, k // BLOCK * bb), np.uint8)
+    s = np.empty((n, k // BLOCK), np.uint8)
+    rc = _load().oracle_mx_direct_cast(int(fmt), _ptr(w), n, k, k, _ptr(q), _ptr(s), threads)
+    if rc:
+        raise RuntimeError("oracle_mx_direct_cast failed: %d" % rc)
+    return q, s
+
+
+def mx_dequant(fmt: int, q, s) -> np.ndarray:
+    q = _as(q, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    n, nblk = s.shape
+    bb = mx_block_bytes(fmt)
+    if q.shape != (n, nblk * bb):
+        raise ValueError("shape mismatch: q %r s %r" % (q.shape, s.shape))
+    out = np.empty((n, nblk * BLOCK), np.float64)
+    rc = _load().oracle_mx_dequant(int(fmt), _ptr(q), _ptr(s), n, nblk * BLOCK, _ptr(out))
+    if rc:
+        raise RuntimeError("oracle_mx_dequant failed: %d" % rc)
+    return out
+
+
+def mx_woq_gemm(fmt: int, x_bits, q, s, threads: int = 0, want_abs: bool = True):
+    """FP64 product with weights in a generic format and the sum of absolute products."""
+    x = _as(x_bits, np.uint16, 2)
+    q = _as(q, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    m, k = x.shape
+    n = q.shape[0]
+    bb = mx_block_bytes(fmt)
+    if q.shape[1] != k // BLOCK * bb or s.shape != (n, k // BLOCK):
+        raise ValueError("shape mismatch: x %r q %r s %r" % (x.shape, q.shape, s.shape))
+    y = np.empty((m, n), np.float64)
+    a = np.empty((m, n), np.float64) if want_abs else None
+    rc = _load().oracle_mx_woq_gemm(int(fmt), _ptr(x), m, k, _ptr(q), _ptr(s), n, k, _ptr(y),
+                                    _ptr(a) if want_abs else None, threads)
+    if rc:
+        raise RuntimeError("oracle_mx_woq_gemm failed: %d" % rc)
     return (y, a) if want_abs else y
 
 

@@ -38,7 +38,11 @@
  * point, saturation, and a library FP64 matmul (tests/test_oracle_e4m3.py); the
  * 6-bit (E2M3) cast, packing and product against a grid and a bit string written
  * out in the test, exact midpoints, round trips, and a library FP64 matmul
- * (tests/test_oracle_e2m3.py).
+ * (tests/test_oracle_e2m3.py); the generic formats (E5M2, E3M2, the 2-bit ternary
+ * T2) against grids built from the field widths in exact rationals, a library
+ * float8 conversion (E5M2), brute-force nearest search, closed-form intervals
+ * (T2), a bit string written out in the test and a library FP64 matmul
+ * (tests/test_oracle_mx.py).
  */
 #include <math.h>
 #include <stdint.h>
@@ -623,6 +627,215 @@ int oracle_e2m3_woq_gemm(const uint16_t *x, int64_t M, int64_t ldx,
 }
 
 double oracle_e2m3_magnitude(int code) { return e2m3_magnitude(code & 31); }
+
+/* ------------------------------------------------------------------------------
+ * Further element formats as drafts, by one generic rule (sections 1, 3.2 and 5 name
+ * 8-bit and lower-bit drafts -- 3, 2, 1.58 and 1 bit -- as drop-ins for the 4-bit
+ * one without fixing their formats).  Each is "sign + magnitude code" with the MX
+ * block scale (one E8M0 byte per 32 elements) and the two-step cast of section
+ * 3.4.3: X = 2^(floor(log2 amax) - emax), emax the exponent of the largest power of
+ * two the element format holds; elements rounded to the nearest magnitude, ties
+ * to the even code, beyond the largest finite magnitude saturated to it; zero
+ * blocks, tiny scales, non-finite inputs and the sign of zero as in the 4-bit cast.
+ *   format 1, E5M2 (the second OCP 8-bit format): 5 exponent bits (bias 15), 2
+ *     mantissa bits; exponent field 31 is Inf/NaN and never produced; largest
+ *     finite magnitude 1.75 * 2^15 = 57344, emax = 15; one byte per element.
+ *   format 2, E3M2 (the second OCP 6-bit format): 3 exponent bits (bias 3), 2
+ *     mantissa bits, no Inf/NaN; largest magnitude 1.75 * 2^4 = 28, emax = 4.
+ *   format 3, T2: a 2-bit element, sign and one magnitude bit, values -1, -0, +0, +1
+ *     (ternary: the 1.58-bit draft stored in two bits); emax = 0, so X is the
+ *     largest power of two not above amax; |v| / X above 1/2 rounds to 1, exactly
+ *     1/2 is a tie and goes to the even code 0, everything from 1 up saturates to 1.
+ * Packing for every format: the 32 codes (sign << (bits - 1) | magnitude code) of a
+ * block as a little-endian bit string, code i in bits bits*i .. bits*i + bits - 1:
+ * 32, 24 and 8 bytes per block; q[N, K/32 * block bytes]; scales [N, K/32]. */
+typedef struct {
+    int bits, ebits, mbits, bias, emax, ncodes;     /* ncodes: finite magnitude codes 0 .. ncodes - 1 */
+} mx_fmt;
+
+static int mx_format(int id, mx_fmt *f)
+{
+    switch (id) {
+    case 1: *f = (mx_fmt){8, 5, 2, 15, 15, 31 * 4}; return 0;
+    case 2: *f = (mx_fmt){6, 3, 2, 3, 4, 32}; return 0;
+    case 3: *f = (mx_fmt){2, 0, 1, 0, 0, 2}; return 0;
+    }
+    return 2;
+}
+
+static double mx_magnitude(const mx_fmt *f, int code)
+{
+    if (f->ebits == 0)
+        return (double)code;                          /* T2: 0 or 1 */
+    int e = code >> f->mbits;
+    int m = code & ((1 << f->mbits) - 1);
+    double frac = (double)m / (double)(1 << f->mbits);
+    if (e == 0)
+        return ldexp(frac, 1 - f->bias);              /* subnormal */
+    return ldexp(1.0 + frac, e - f->bias);            /* normal */
+}
+
+static int mx_round_code(const mx_fmt *f, double r)
+{
+    int best = 0;
+    double best_d = fabs(r - mx_magnitude(f, 0));
+    for (int c = 1; c < f->ncodes; ++c) {
+        double d = fabs(r - mx_magnitude(f, c));
+        if (d < best_d || (d == best_d && (c & 1) == 0)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return best;
+}
+
+static void mx_put(uint8_t *blk, int bits, int i, int code)
+{
+    for (int b = 0; b < bits; ++b) {
+        int bit = bits * i + b;
+        if ((code >> b) & 1)
+            blk[bit >> 3] |= (uint8_t)(1u << (bit & 7));
+    }
+}
+
+static int mx_get(const uint8_t *blk, int bits, int i)
+{
+    int code = 0;
+    for (int b = 0; b < bits; ++b) {
+        int bit = bits * i + b;
+        code |= ((blk[bit >> 3] >> (bit & 7)) & 1) << b;
+    }
+    return code;
+}
+
+static uint8_t mx_cast_block(const mx_fmt *f, const uint16_t *w, uint8_t *blk)
+{
+    double v[ORACLE_BLOCK];
+    double amax = 0.0;
+    int nonfinite = 0;
+    memset(blk, 0, (size_t)f->bits * 4);
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        v[i] = bf16_to_double(w[i]);
+        if (isnan(v[i]) || isinf(v[i]))
+            nonfinite = 1;
+        else if (fabs(v[i]) > amax)
+            amax = fabs(v[i]);
+    }
+    if (nonfinite)
+        return 0xFF;
+    int E;
+    if (amax == 0.0) {
+        E = -127;
+    } else {
+        int ex;
+        (void)frexp(amax, &ex);
+        E = (ex - 1) - f->emax;                   /* floor(log2 amax) - emax */
+    }
+    if (E < -127)
+        E = -127;
+    if (E > 127)
+        E = 127;
+    for (int i = 0; i < ORACLE_BLOCK; ++i) {
+        double r = ldexp(fabs(v[i]), -E);
+        int sign = (w[i] >> 15) & 1;
+        mx_put(blk, f->bits, i, (sign << (f->bits - 1)) | mx_round_code(f, r));
+    }
+    return (uint8_t)(E + 127);
+}
+
+int oracle_mx_block_bytes(int fmt)
+{
+    mx_fmt f;
+    return mx_format(fmt, &f) ? 0 : f.bits * 4;
+}
+
+double oracle_mx_magnitude(int fmt, int code)
+{
+    mx_fmt f;
+    if (mx_format(fmt, &f) || code < 0 || code >= f.ncodes)
+        return NAN;
+    return mx_magnitude(&f, code);
+}
+
+int oracle_mx_direct_cast(int fmt, const uint16_t *w, int64_t N, int64_t K, int64_t ldw,
+                          uint8_t *q, uint8_t *s, int threads)
+{
+    mx_fmt f;
+    if (mx_format(fmt, &f) || N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldw < K)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+    int bb = f.bits * 4;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t b = 0; b < nblk; ++b)
+            s[n * nblk + b] = mx_cast_block(&f, w + n * ldw + b * ORACLE_BLOCK, q + (n * nblk + b) * bb);
+    (void)threads;
+    return 0;
+}
+
+static double mx_dequant_one(const mx_fmt *f, int code, uint8_t scale_byte)
+{
+    int mag = code & ((1 << (f->bits - 1)) - 1);
+    if (scale_byte == 0xFF || mag >= f->ncodes)
+        return NAN;                                  /* NaN block; Inf/NaN codes of E5M2 */
+    double val = ldexp(mx_magnitude(f, mag), (int)scale_byte - 127);
+    return (code >> (f->bits - 1)) ? -val : val;
+}
+
+int oracle_mx_dequant(int fmt, const uint8_t *q, const uint8_t *s, int64_t N, int64_t K, double *w_hat)
+{
+    mx_fmt f;
+    if (mx_format(fmt, &f) || N < 0 || K < 0 || K % ORACLE_BLOCK != 0)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+    int bb = f.bits * 4;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t b = k / ORACLE_BLOCK;
+            w_hat[n * K + k] = mx_dequant_one(&f, mx_get(q + (n * nblk + b) * bb, f.bits, (int)(k % ORACLE_BLOCK)),
+                                              s[n * nblk + b]);
+        }
+    return 0;
+}
+
+/* y[m][n] = sum_k x[m][k] * w_hat[n][k] in FP64, k ascending, and the sum of absolute products. */
+int oracle_mx_woq_gemm(int fmt, const uint16_t *x, int64_t M, int64_t ldx,
+                       const uint8_t *q, const uint8_t *s, int64_t N, int64_t K,
+                       double *y_ref, double *a_ref, int threads)
+{
+    mx_fmt f;
+    if (mx_format(fmt, &f) || M < 0 || N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldx < K)
+        return 2;
+    int64_t nblk = K / ORACLE_BLOCK;
+    int bb = f.bits * 4;
+#ifdef _OPENMP
+    if (threads > 0)
+        omp_set_num_threads(threads);
+#pragma omp parallel for schedule(static)
+#endif
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t m = 0; m < M; ++m) {
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                int64_t b = k / ORACLE_BLOCK;
+                double wv = mx_dequant_one(&f, mx_get(q + (n * nblk + b) * bb, f.bits, (int)(k % ORACLE_BLOCK)),
+                                           s[n * nblk + b]);
+                double p = bf16_to_double(x[m * ldx + k]) * wv;
+                acc += p;
+                aacc += fabs(p);
+            }
+            y_ref[m * N + n] = acc;
+            if (a_ref)
+                a_ref[m * N + n] = aacc;
+        }
+    }
+    (void)threads;
+    return 0;
+}
 
 /* What the linear layer's backend fuses around the contraction (section 3.4: bias
  * and residual add applied to the product's output while it is at hand) and, for
