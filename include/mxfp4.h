@@ -30,8 +30,8 @@
  *     products in one call), mxfp4_woq_gemm_chain (a step's dependent products in one launch),
  *     mxfp4_woq_gemm_argmax_noalloc (no workspace), mxfp4_woq_gemm_tiled* with mxfp4_tile_repack (the
  *     same calls on the tile-major copy of the weights).
- *   Next to the method: mxfp4_bf16_gemm* (the unquantised target's linear), mxfp4_e4m3_* and
- *     mxfp4_e2m3_* (8- and 6-bit element formats as drafts).
+ *   Next to the method: mxfp4_bf16_gemm* (the unquantised target's linear), mxfp4_e4m3_*,
+ *     mxfp4_e2m3_* and mxfp4_fmt_* (8-, 6- and 2-bit element formats as drafts).
  *   Diagnostics, for tests and measurements only: mxfp4_*_path (a kernel family forced),
  *     mxfp4_direct_cast_bits / mxfp4_*_direct_cast_bits (the integer rounding rule in place of the
  *     convert instruction), mxfp4_dequant*, mxfp4_diag_stream_*.
@@ -155,6 +155,50 @@ int mxfp4_e2m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx,
                                const void* q6, const void* scales_e8m0, int64_t N, int64_t K,
                                int32_t* argmax_out, float* max_out,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Further block formats on the same path, chosen by id (sections 1, 3.2 and 5: 8-bit and lower-bit
+ * drafts, down to ternary, as drop-ins for the 4-bit draft; the cast is the two-step rule of
+ * section 3.4.3 with the element format named, the product is Eq. 2 with FP32 accumulation):
+ *   MXFP4_FMT_E5M2  OCP 8-bit E5M2: 1 sign, 5 exponent bits (bias 15), 2 mantissa bits; largest
+ *                   finite magnitude 57344; X = 2^(floor(log2 amax) - 15).  The cast never writes the
+ *                   Inf and NaN codes (S.11111.xx); beyond 57344 saturates.  32 bytes per block.
+ *   MXFP4_FMT_E3M2  OCP 6-bit E3M2: 1 sign, 3 exponent bits (bias 3), 2 mantissa bits; largest 28, no
+ *                   Inf, no NaN; X = 2^(floor(log2 amax) - 4).  24 bytes per block.
+ *   MXFP4_FMT_T2    2 bits, sign << 1 | magnitude: values {0, +1, -1} (and -0), a ternary draft;
+ *                   X = 2^floor(log2 amax), so |v| / X < 2: up to 1/2 rounds to 0 (the tie goes to the
+ *                   even code 0), above it to 1.  8 bytes per block, 2.25 bits per weight.
+ * Elements are rounded to nearest, ties to the even code; zero blocks, the clamp of X at 2^-127,
+ * non-finite inputs (scale byte 0xFF, zero codes) and the sign of zero as in mxfp4_direct_cast.
+ *   q            [N, K/32 * B] bytes, B = mxfp4_fmt_block_bytes(fmt): the 32 codes of a block (sign
+ *                in the top bit of a code) are a little-endian bit string, code i in bits b i ..
+ *                b i + b - 1 with b the element width; 8-byte aligned; N * K/32 * B below 2 GiB - 256
+ *   scales_e8m0  [N, K/32] as for MXFP4
+ * mxfp4_fmt_block_bytes is 0 for an unknown id; every other call then returns MXFP4_ERR_SHAPE.
+ * mxfp4_fmt_direct_cast_bits rounds by an ALU rule on the bit patterns instead of the convert
+ * instructions (same bits; T2 has only that rule).  mxfp4_fmt_dequant writes scale * element as BF16
+ * (E5M2, E3M2: exact while that is a normal BF16 number; T2: always exact).  mxfp4_fmt_woq_gemm and
+ * mxfp4_fmt_woq_gemm_argmax are mxfp4_woq_gemm and mxfp4_woq_gemm_argmax with q in place of
+ * q_packed (same arguments, same error codes, same tie rule) for any M, any N and every K up to
+ * MXFP4_MAX_K whose BF16 row fits the LDS (on gfx950 all of them); rows of K <= 1024 with K/32 a power of two (the
+ * rows of a quantised attention cache, section 5) are processed 64 / (K/32) at a time per wave.
+ * Argmax workspace as for mxfp4_e4m3_woq_gemm_argmax.
+ */
+enum { MXFP4_FMT_E5M2 = 1, MXFP4_FMT_E3M2 = 2, MXFP4_FMT_T2 = 3 };
+int mxfp4_fmt_block_bytes(int fmt);
+int mxfp4_fmt_direct_cast(int fmt, const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                          void* q, void* scales_e8m0, void* stream);
+int mxfp4_fmt_direct_cast_bits(int fmt, const void* w_bf16, int64_t N, int64_t K, int64_t ldw,
+                               void* q, void* scales_e8m0, void* stream);
+int mxfp4_fmt_dequant(int fmt, const void* q, const void* scales_e8m0, int64_t N, int64_t K,
+                      void* w_bf16, int64_t ldw, void* stream);
+int mxfp4_fmt_woq_gemm(int fmt, const void* x_bf16, int64_t M, int64_t ldx,
+                       const void* q, const void* scales_e8m0, int64_t N, int64_t K,
+                       void* y_bf16, int64_t ldy, void* stream);
+int mxfp4_fmt_woq_gemm_argmax(int fmt, const void* x_bf16, int64_t M, int64_t ldx,
+                              const void* q, const void* scales_e8m0, int64_t N, int64_t K,
+                              int32_t* argmax_out, float* max_out,
+                              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Dequantise to BF16 (exact whenever 2^(scale-127) * 6 is a normal BF16 number): the inverse

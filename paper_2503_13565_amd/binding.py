@@ -29,6 +29,8 @@ EXPORTS = [
     "mxfp4_e4m3_woq_gemm_argmax",
     "mxfp4_e2m3_direct_cast", "mxfp4_e2m3_direct_cast_bits", "mxfp4_e2m3_dequant", "mxfp4_e2m3_woq_gemm",
     "mxfp4_e2m3_woq_gemm_argmax",
+    "mxfp4_fmt_block_bytes", "mxfp4_fmt_direct_cast", "mxfp4_fmt_direct_cast_bits", "mxfp4_fmt_dequant",
+    "mxfp4_fmt_woq_gemm", "mxfp4_fmt_woq_gemm_argmax",
     "mxfp4_tile_repack_q_bytes", "mxfp4_tile_repack_s_bytes", "mxfp4_tile_repack", "mxfp4_woq_gemm_tiled",
     "mxfp4_woq_gemm_tiled_ws",
     "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify", "mxfp4_woq_gemm_tiled_fused",
@@ -117,6 +119,17 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_e2m3_woq_gemm.restype = i32
     lib.mxfp4_e2m3_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     lib.mxfp4_e2m3_woq_gemm_argmax.restype = i32
+    lib.mxfp4_fmt_block_bytes.argtypes = [i32]
+    lib.mxfp4_fmt_block_bytes.restype = i32
+    for name in ("mxfp4_fmt_direct_cast", "mxfp4_fmt_direct_cast_bits"):
+        getattr(lib, name).argtypes = [i32, vp, i64, i64, i64, vp, vp, vp]
+        getattr(lib, name).restype = i32
+    lib.mxfp4_fmt_dequant.argtypes = [i32, vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_fmt_dequant.restype = i32
+    lib.mxfp4_fmt_woq_gemm.argtypes = [i32, vp, i64, i64, vp, vp, i64, i64, vp, i64, vp]
+    lib.mxfp4_fmt_woq_gemm.restype = i32
+    lib.mxfp4_fmt_woq_gemm_argmax.argtypes = [i32, vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
+    lib.mxfp4_fmt_woq_gemm_argmax.restype = i32
     lib.mxfp4_woq_gemm_fused.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i32, vp, i64, vp, i64, vp, sz, i32, vp]
     lib.mxfp4_woq_gemm_fused.restype = i32
     lib.mxfp4_tile_repack_q_bytes.argtypes = [i64, i64]
@@ -492,6 +505,82 @@ def mxfp4_e2m3_woq_gemm_argmax(x: torch.Tensor, q6: torch.Tensor, s: torch.Tenso
         _check(load().mxfp4_e2m3_woq_gemm_argmax(_ptr(x), m, ldx, _ptr(q6), _ptr(s), n, k, _ptr(idx), _ptr(val),
                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                 _stream()))
+    return idx, val
+
+
+FMT_E5M2, FMT_E3M2, FMT_T2 = 1, 2, 3
+
+
+def mxfp4_fmt_block_bytes(fmt: int) -> int:
+    """Bytes of one 32-element block of the format (32, 24, 8); 0 for an unknown id."""
+    return int(load().mxfp4_fmt_block_bytes(fmt))
+
+
+def mxfp4_fmt_direct_cast(fmt: int, w: torch.Tensor, integer_rule: bool = False) -> Tuple[torch.Tensor, torch.Tensor]:
+    """BF16 ``[N, K]`` -> (``q [N, K/32 * block_bytes]`` packed codes, ``s [N, K/32]`` E8M0 scale bytes)."""
+    _dev(w)
+    if w.dtype != torch.bfloat16 or w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be a 2-D BF16 tensor with a contiguous last dimension")
+    n, k = w.shape
+    q = torch.empty((n, k // 32 * max(mxfp4_fmt_block_bytes(fmt), 1)), dtype=torch.uint8, device=w.device)
+    s = torch.empty((n, k // 32), dtype=torch.uint8, device=w.device)
+    fn = load().mxfp4_fmt_direct_cast_bits if integer_rule else load().mxfp4_fmt_direct_cast
+    with torch.cuda.device(w.device):
+        _check(fn(fmt, _ptr(w), n, k, w.stride(0) if n > 1 else k, _ptr(q), _ptr(s), _stream()))
+    return q, s
+
+
+def mxfp4_fmt_dequant(fmt: int, q: torch.Tensor, s: torch.Tensor) -> torch.Tensor:
+    _dev(q)
+    n, k = s.shape[0], s.shape[1] * 32
+    w = torch.empty((n, k), dtype=torch.bfloat16, device=q.device)
+    with torch.cuda.device(q.device):
+        _check(load().mxfp4_fmt_dequant(fmt, _ptr(q), _ptr(s), n, k, _ptr(w), k, _stream()))
+    return w
+
+
+def _fmt_shapes(fmt, x, q, s):
+    _dev(x)
+    if x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D BF16 tensor with a contiguous last dimension")
+    if q.dtype != torch.uint8 or s.dtype != torch.uint8 or not q.is_contiguous() or not s.is_contiguous():
+        raise ValueError("q and s must be contiguous uint8 tensors")
+    m, k = x.shape
+    n = q.shape[0]
+    bb = mxfp4_fmt_block_bytes(fmt)
+    if bb and (q.shape[1] != k // 32 * bb or tuple(s.shape) != (n, k // 32)):
+        raise ValueError("shape mismatch: x %r q %r s %r" % (tuple(x.shape), tuple(q.shape), tuple(s.shape)))
+    return m, n, k, (x.stride(0) if m > 1 else k)
+
+
+def mxfp4_fmt_woq_gemm(fmt: int, x: torch.Tensor, q: torch.Tensor, s: torch.Tensor,
+                       y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    m, n, k, ldx = _fmt_shapes(fmt, x, q, s)
+    if y is None:
+        y = torch.empty((m, n), dtype=torch.bfloat16, device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_fmt_woq_gemm(fmt, _ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(y),
+                                        y.stride(0) if m > 1 else n, _stream()))
+    return y
+
+
+def mxfp4_fmt_woq_gemm_argmax(fmt: int, x: torch.Tensor, q: torch.Tensor, s: torch.Tensor,
+                              workspace: Optional[torch.Tensor] = None,
+                              out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None
+                              ) -> Tuple[torch.Tensor, torch.Tensor]:
+    m, n, k, ldx = _fmt_shapes(fmt, x, q, s)
+    if workspace is None:
+        workspace = torch.empty((mxfp4_woq_gemm_argmax_workspace_bytes(m, n, k),), dtype=torch.uint8,
+                                device=x.device)
+    if out is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=x.device)
+        val = torch.empty((m,), dtype=torch.float32, device=x.device)
+    else:
+        idx, val = out
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_fmt_woq_gemm_argmax(fmt, _ptr(x), m, ldx, _ptr(q), _ptr(s), n, k, _ptr(idx), _ptr(val),
+                                               _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                               _stream()))
     return idx, val
 
 

@@ -1144,6 +1144,157 @@ int mxfp4_e2m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const
                     workspace_bytes, true, stream);
 }
 
+// ---- further block formats by id (E5M2, E3M2, 2-bit ternary) ---------------------------------
+
+int mxfp4_fmt_block_bytes(int fmt) { return mxfmt_block_bytes(fmt); }
+
+static int fmt_check_weights(int fmt, const void* q, const void* s, int64_t N, int64_t K)
+{
+    const int bb = mxfmt_block_bytes(fmt);
+    if (bb == 0)
+        return fail(MXFP4_ERR_SHAPE, "format id %d is none of MXFP4_FMT_E5M2, _E3M2, _T2", fmt);
+    if (!q || !s)
+        return fail(MXFP4_ERR_NULL, "q or scales_e8m0 is NULL");
+    if (N < 1 || N > 0x7FFFFFFF / 8)
+        return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
+    if (K < 32 || K % 32 != 0 || K > MXFP4_MAX_K)
+        return fail(MXFP4_ERR_SHAPE, "K=%lld must be a multiple of 32 in [32, %d]", (long long)K, MXFP4_MAX_K);
+    if (N * (K / 32) * bb > 0x7FFFFF00)
+        return fail(MXFP4_ERR_SHAPE, "%lld bytes of weights exceed 2 GiB - 256", (long long)(N * (K / 32) * bb));
+    if (!aligned(q, 8))
+        return fail(MXFP4_ERR_ALIGN, "q must be 8-byte aligned");
+    return MXFP4_OK;
+}
+
+static int fmt_cast_impl(int fmt, const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q, void* scales_e8m0,
+                         bool integer_rule, void* stream)
+{
+    begin_call();
+    if (mxfmt_block_bytes(fmt) == 0)
+        return fail(MXFP4_ERR_SHAPE, "format id %d is none of MXFP4_FMT_E5M2, _E3M2, _T2", fmt);
+    if (N < 0 || N > 0x7FFFFFFF)
+        return fail(MXFP4_ERR_SHAPE, "N=%lld out of range", (long long)N);
+    if (K < 32 || K % 32 != 0 || K > (1 << 24))
+        return fail(MXFP4_ERR_SHAPE, "K=%lld must be a positive multiple of 32", (long long)K);
+    if (ldw < K)
+        return fail(MXFP4_ERR_SHAPE, "ldw=%lld < K=%lld", (long long)ldw, (long long)K);
+    if (N == 0)
+        return MXFP4_OK;
+    if (!w_bf16 || !q || !scales_e8m0)
+        return fail(MXFP4_ERR_NULL, "w_bf16, q or scales_e8m0 is NULL");
+    if (ldw % 8 != 0 || !aligned(w_bf16, 16))
+        return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
+    if (!aligned(q, 8))
+        return fail(MXFP4_ERR_ALIGN, "q must be 8-byte aligned");
+    hipError_t e = launch_mxfmt_cast(fmt, w_bf16, N, K, ldw, q, scales_e8m0, integer_rule,
+                                     static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "block-format cast launch");
+}
+
+int mxfp4_fmt_direct_cast(int fmt, const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q,
+                          void* scales_e8m0, void* stream)
+{
+    return fmt_cast_impl(fmt, w_bf16, N, K, ldw, q, scales_e8m0, false, stream);
+}
+
+int mxfp4_fmt_direct_cast_bits(int fmt, const void* w_bf16, int64_t N, int64_t K, int64_t ldw, void* q,
+                               void* scales_e8m0, void* stream)
+{
+    return fmt_cast_impl(fmt, w_bf16, N, K, ldw, q, scales_e8m0, true, stream);
+}
+
+int mxfp4_fmt_dequant(int fmt, const void* q, const void* scales_e8m0, int64_t N, int64_t K, void* w_bf16,
+                      int64_t ldw, void* stream)
+{
+    begin_call();
+    if (N == 0 && mxfmt_block_bytes(fmt) != 0)
+        return MXFP4_OK;
+    int rc = fmt_check_weights(fmt, q, scales_e8m0, N, K);
+    if (rc)
+        return rc;
+    if (!w_bf16)
+        return fail(MXFP4_ERR_NULL, "w_bf16 is NULL");
+    if (ldw < K)
+        return fail(MXFP4_ERR_SHAPE, "ldw=%lld < K=%lld", (long long)ldw, (long long)K);
+    if (ldw % 8 != 0 || !aligned(w_bf16, 16))
+        return fail(MXFP4_ERR_ALIGN, "w_bf16 must be 16-byte aligned with ldw %% 8 == 0");
+    hipError_t e = launch_mxfmt_dequant(fmt, q, scales_e8m0, N, K, w_bf16, ldw, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "block-format dequant launch");
+}
+
+static int run_fmt(int fmt, const void* x, int64_t M, int64_t ldx, const void* q, const void* s, int64_t N,
+                   int64_t K, void* y, int64_t ldy, int32_t* argmax_out, float* max_out, void* workspace,
+                   size_t workspace_bytes, bool argmax, void* stream)
+{
+    begin_call();
+    int rc = fmt_check_weights(fmt, q, s, N, K);
+    if (rc)
+        return rc;
+    rc = check_x(x, M, ldx, K);
+    if (rc)
+        return rc;
+    DeviceInfo dev;
+    rc = device_info(&dev);
+    if (rc)
+        return rc;
+    GemmArgs a{};
+    a.x = static_cast<const uint16_t*>(x);
+    a.ldx = ldx;
+    a.q = static_cast<const uint8_t*>(q);
+    a.s = static_cast<const uint8_t*>(s);
+    a.m = (int)M;
+    a.n = (int)N;
+    a.k = (int)K;
+    if (!mxfmt_can_run(a, dev))
+        return fail(MXFP4_ERR_SHAPE, "K=%lld does not fit the LDS copy of one activation row", (long long)K);
+    if (argmax) {
+        if (!argmax_out)
+            return fail(MXFP4_ERR_NULL, "argmax_out is NULL");
+        const size_t need = (size_t)M * gemv_max_parts(dev) * 8;
+        if (!workspace || workspace_bytes < need)
+            return fail(MXFP4_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                        workspace ? workspace_bytes : (size_t)0);
+        if (!aligned(workspace, 8))
+            return fail(MXFP4_ERR_ALIGN, "workspace must be 8-byte aligned");
+        a.parts = gemv_max_parts(dev);
+        a.part_val = static_cast<float*>(workspace);
+        a.part_idx = reinterpret_cast<int32_t*>(a.part_val + (size_t)M * a.parts);
+    } else {
+        if (!y)
+            return fail(MXFP4_ERR_NULL, "y_bf16 is NULL");
+        if (ldy < N)
+            return fail(MXFP4_ERR_SHAPE, "ldy=%lld < N=%lld", (long long)ldy, (long long)N);
+        a.y = static_cast<uint16_t*>(y);
+        a.ldy = ldy;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int parts_used = 0;
+    hipError_t e = launch_mxfmt_gemv(fmt, a, dev, &parts_used, st);
+    if (e != hipSuccess)
+        return hip_fail(e, "block-format product launch");
+    if (argmax) {
+        e = launch_argmax_finish(a.part_val, a.part_idx, a.parts, parts_used, a.m, argmax_out, max_out, st);
+        if (e != hipSuccess)
+            return hip_fail(e, "argmax finish launch");
+    }
+    return MXFP4_OK;
+}
+
+int mxfp4_fmt_woq_gemm(int fmt, const void* x_bf16, int64_t M, int64_t ldx, const void* q,
+                       const void* scales_e8m0, int64_t N, int64_t K, void* y_bf16, int64_t ldy, void* stream)
+{
+    return run_fmt(fmt, x_bf16, M, ldx, q, scales_e8m0, N, K, y_bf16, ldy, nullptr, nullptr, nullptr, 0, false,
+                   stream);
+}
+
+int mxfp4_fmt_woq_gemm_argmax(int fmt, const void* x_bf16, int64_t M, int64_t ldx, const void* q,
+                              const void* scales_e8m0, int64_t N, int64_t K, int32_t* argmax_out, float* max_out,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_fmt(fmt, x_bf16, M, ldx, q, scales_e8m0, N, K, nullptr, 0, argmax_out, max_out, workspace,
+                   workspace_bytes, true, stream);
+}
+
 int mxfp4_bf16_gemm(const void* x_bf16, int64_t M, int64_t ldx, const void* w_bf16, int64_t N, int64_t K,
                     int64_t ldw, void* y_bf16, int64_t ldy, void* stream)
 {

@@ -138,6 +138,16 @@ struct Bf16Args {
 bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev);
 hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
 
+// Further block formats by id (1 E5M2, 2 E3M2, 3 the 2-bit ternary T2; a.q holds 32, 24 or 8 bytes
+// per block); mxfmt.hip.  mxfmt_block_bytes is 0 for an unknown id.
+int mxfmt_block_bytes(int fmt);
+hipError_t launch_mxfmt_cast(int fmt, const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q, void* s,
+                             bool integer_rule, hipStream_t stream);
+hipError_t launch_mxfmt_dequant(int fmt, const void* q, const void* s, int64_t n_rows, int64_t k, void* w,
+                                int64_t ldw, hipStream_t stream);
+bool mxfmt_can_run(const GemmArgs& a, const DeviceInfo& dev);
+hipError_t launch_mxfmt_gemv(int fmt, const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+
 // The 8-bit draft format (E4M3 elements, one byte each: a.q is q8 [N, K]; a.s as before); e4m3.hip.
 hipError_t launch_e4m3_cast(const void* w, int64_t n_rows, int64_t k, int64_t ldw, void* q8, void* s,
                             bool integer_rule, hipStream_t stream);
