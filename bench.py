@@ -616,6 +616,8 @@ def main() -> int:
             for name, t in lin.items():
                 t["q8"], t["s8"] = binding.mxfp4_e4m3_direct_cast(t["w"])
                 t["q6"], t["s6"] = binding.mxfp4_e2m3_direct_cast(t["w"])
+                for fmt in (binding.FMT_E5M2, binding.FMT_E3M2, binding.FMT_T2):
+                    t["qf%d" % fmt], t["sf%d" % fmt] = binding.mxfp4_fmt_direct_cast(fmt, t["w"])
                 t["w"] = None
                 if name in ("qkv", "o", "gate_up"):
                     t["x8"] = synth.activations_outlier_channels(8, t["k"], seed=t["n"], device=dev)
@@ -636,6 +638,16 @@ def main() -> int:
                 binding.mxfp4_e2m3_woq_gemm(t["x"], t["q6"], t["s6"], y=t["y"])
             t = lin["lm_head"]
             binding.mxfp4_e2m3_woq_gemm_argmax(t["x"], t["q6"], t["s6"], workspace=ws, out=(t["idx"], t["val"]))
+
+        def by_id(fmt):
+            def run(lin):
+                for name in STEP_LINEARS:
+                    t = lin[name]
+                    binding.mxfp4_fmt_woq_gemm(fmt, t["x"], t["qf%d" % fmt], t["sf%d" % fmt], y=t["y"])
+                t = lin["lm_head"]
+                binding.mxfp4_fmt_woq_gemm_argmax(fmt, t["x"], t["qf%d" % fmt], t["sf%d" % fmt], workspace=ws,
+                                                  out=(t["idx"], t["val"]))
+            return run
 
         def layer_plain(lin):
             for name in STEP_LINEARS:
@@ -663,6 +675,9 @@ def main() -> int:
 
         variants = {}
         for key, fn in (("e4m3_weights_us_per_step", e4m3), ("e2m3_weights_us_per_step", e2m3),
+                        ("e5m2_weights_us_per_step", by_id(binding.FMT_E5M2)),
+                        ("e3m2_weights_us_per_step", by_id(binding.FMT_E3M2)),
+                        ("ternary_2bit_weights_us_per_step", by_id(binding.FMT_T2)),
                         ("layer_4_linears_us", layer_plain), ("layer_4_linears_fused_epilogues_us", layer_fused),
                         ("verify_m8_qkv_o_gateup_us", verify8), ("verify_m8_qkv_o_gateup_tile_major_us", verify8_tiled)):
             us, g = clock.us_per_call_graphs([(lambda lin=lin, fn=fn: fn(lin)) for lin in bsets], nb, n_bf16)
@@ -671,7 +686,7 @@ def main() -> int:
         extra["variants"] = variants
         for lin in bsets:
             for t in lin.values():
-                for key in ("q8", "s8", "q6", "s6", "x8", "y8", "x5", "y5", "tw", "h"):
+                for key in ("q8", "s8", "q6", "s6", "x8", "y8", "x5", "y5", "tw", "h", "qf1", "sf1", "qf2", "sf2", "qf3", "sf3"):
                     t.pop(key, None)
 
     # --- what a plain 128-bit read stream gets on this device, over 4 GiB (context for frac), and one

@@ -79,6 +79,8 @@ def _load():
         lib.oracle_e2m3_woq_gemm.restype = i32
         lib.oracle_e2m3_magnitude.argtypes = [i32]
         lib.oracle_e2m3_magnitude.restype = ctypes.c_double
+        lib.oracle_woq_gemm_t.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp]
+        lib.oracle_woq_gemm_t.restype = i32
         lib.oracle_mx_block_bytes.argtypes = [i32]
         lib.oracle_mx_block_bytes.restype = i32
         lib.oracle_mx_magnitude.argtypes = [i32, i32]
@@ -182,6 +184,24 @@ def bf16_gemm(x_bits, w_bits, threads: int = 0, want_abs: bool = True):
                                   threads)
     if rc:
         raise RuntimeError("oracle_bf16_gemm failed: %d" % rc)
+    return (y, a) if want_abs else y
+
+
+def woq_gemm_t(x_bits, q, s, want_abs: bool = True):
+    """FP64 product along the rows of the stored tensor, ``y[m,k] = sum_n x[m,n] * w_hat[n,k]``, and the
+    sum of absolute products.  ``x_bits`` is uint16 ``[M,N]``."""
+    x = _as(x_bits, np.uint16, 2)
+    q = _as(q, np.uint8, 2)
+    s = _as(s, np.uint8, 2)
+    m, n = x.shape
+    k = q.shape[1] * 2
+    if q.shape[0] != n or s.shape != (n, k // BLOCK) or k % BLOCK:
+        raise ValueError("shape mismatch: x %r q %r s %r" % (x.shape, q.shape, s.shape))
+    y = np.empty((m, k), np.float64)
+    a = np.empty((m, k), np.float64) if want_abs else None
+    rc = _load().oracle_woq_gemm_t(_ptr(x), m, n, _ptr(q), _ptr(s), n, k, _ptr(y), _ptr(a) if want_abs else None)
+    if rc:
+        raise RuntimeError("oracle_woq_gemm_t failed: %d" % rc)
     return (y, a) if want_abs else y
 
 

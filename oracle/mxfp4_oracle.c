@@ -42,7 +42,9 @@
  * T2) against grids built from the field widths in exact rationals, a library
  * float8 conversion (E5M2), brute-force nearest search, closed-form intervals
  * (T2), a bit string written out in the test and a library FP64 matmul
- * (tests/test_oracle_mx.py).
+ * (tests/test_oracle_mx.py); the product along the rows (oracle_woq_gemm_t)
+ * against one-hot activations, a library FP64 matmul on the transpose of the
+ * pinned product, and loops written out in the test (tests/test_oracle_kv.py).
  */
 #include <math.h>
 #include <stdint.h>
@@ -254,6 +256,42 @@ int oracle_woq_gemm(const uint16_t *x, int64_t M, int64_t ldx,
     free(xd);
     (void)threads;
     return failed ? 6 : 0;
+}
+
+/* The product along the other axis of the same stored tensor (section 5 names a
+ * quantised attention cache as the next step; with one token per weight row,
+ * blocks along the head dimension, the value side of attention contracts over
+ * the rows):  y_ref[m,k] = sum_n x[m,n] * w_hat[n,k] in FP64, n ascending, and
+ * a_ref[m,k] = sum_n |x[m,n] * w_hat[n,k]|.  x holds BF16 bit patterns [M,N] with
+ * row stride ldx; outputs are [M,K] row-major doubles.  a_ref may be NULL. */
+int oracle_woq_gemm_t(const uint16_t *x, int64_t M, int64_t ldx,
+                      const uint8_t *q, const uint8_t *s, int64_t N, int64_t K,
+                      double *y_ref, double *a_ref)
+{
+    if (M < 0 || N < 0 || K < 0 || K % ORACLE_BLOCK != 0 || ldx < N)
+        return 2;
+    double *wrow = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+    if (!wrow)
+        return 6;
+    for (int64_t i = 0; i < M * K; ++i) {
+        y_ref[i] = 0.0;
+        if (a_ref)
+            a_ref[i] = 0.0;
+    }
+    for (int64_t n = 0; n < N; ++n) {
+        dequant_row(q + n * (K / 2), s + n * (K / ORACLE_BLOCK), K, wrow);
+        for (int64_t m = 0; m < M; ++m) {
+            double xv = bf16_to_double(x[m * ldx + n]);
+            for (int64_t k = 0; k < K; ++k) {
+                double p = xv * wrow[k];
+                y_ref[m * K + k] += p;
+                if (a_ref)
+                    a_ref[m * K + k] += fabs(p);
+            }
+        }
+    }
+    free(wrow);
+    return 0;
 }
 
 /* The same product with the scale applied once per 32-block partial sum (the
