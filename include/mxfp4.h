@@ -31,7 +31,8 @@
  *     mxfp4_woq_gemm_argmax_noalloc (no workspace), mxfp4_woq_gemm_tiled* with mxfp4_tile_repack (the
  *     same calls on the tile-major copy of the weights).
  *   Next to the method: mxfp4_bf16_gemm* (the unquantised target's linear), mxfp4_e4m3_*,
- *     mxfp4_e2m3_* and mxfp4_fmt_* (8-, 6- and 2-bit element formats as drafts).
+ *     mxfp4_e2m3_* and mxfp4_fmt_* (8-, 6- and 2-bit element formats as drafts), mxfp4_woq_gemm_t
+ *     (the value side of attention over a cache held in the same format).
  *   Diagnostics, for tests and measurements only: mxfp4_*_path (a kernel family forced),
  *     mxfp4_direct_cast_bits / mxfp4_*_direct_cast_bits (the integer rounding rule in place of the
  *     convert instruction), mxfp4_dequant*, mxfp4_diag_stream_*.
@@ -199,6 +200,30 @@ int mxfp4_fmt_woq_gemm_argmax(int fmt, const void* x_bf16, int64_t M, int64_t ld
                               const void* q, const void* scales_e8m0, int64_t N, int64_t K,
                               int32_t* argmax_out, float* max_out,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The product along the rows of a stored MXFP4 tensor (section 5 names a quantised attention cache
+ * as the next step of the method and gives no procedure; the reading taken here: one token per row
+ * of q_packed / scales_e8m0, the 32-element blocks of section 3.4.3 along the head dimension K, so
+ * that a new token is cast on its own by mxfp4_direct_cast(N = 1) into row T of the cache; the score
+ * side  scores[M, T] = query[M, K] * dequant(K-cache)^T  is mxfp4_woq_gemm with N = T; the value side
+ * contracts over the rows and is this call):
+ *   y[m, k] = sum_n x[m, n] * dequant(W)[n, k],   FP32 accumulation, BF16 result
+ *   x_bf16     [M, N] (the attention weights of M query rows that share the cache), row stride ldx
+ *              >= N, 2-byte aligned; 1 <= M <= 64
+ *   q_packed, scales_e8m0   the stored tensor [N, K/2], [N, K/32] as for mxfp4_woq_gemm; K a multiple
+ *              of 32, at most 2048 (a head dimension), else MXFP4_ERR_SHAPE
+ *   y_bf16     [M, K], row stride ldy >= K
+ *   workspace  mxfp4_woq_gemm_t_workspace_bytes(M, N, K) bytes of device memory (FP32 partial sums
+ *              of the workgroups, added in index order: the result is the same on every call),
+ *              4-byte aligned; the size query returns 0 for shapes the call refuses
+ * A scale byte 0xFF makes the 32 outputs of its block NaN for every row m, also where x[m, n] = 0.
+ */
+size_t mxfp4_woq_gemm_t_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int mxfp4_woq_gemm_t(const void* x_bf16, int64_t M, int64_t ldx,
+                     const void* q_packed, const void* scales_e8m0, int64_t N, int64_t K,
+                     void* y_bf16, int64_t ldy,
+                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Dequantise to BF16 (exact whenever 2^(scale-127) * 6 is a normal BF16 number): the inverse

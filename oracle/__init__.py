@@ -453,12 +453,12 @@ def sd_speedup_two_level(alpha_mid, n_mid, s_mid, alpha_last, n_last, s_last) ->
 
 
 def bf16_ulp(y) -> np.ndarray:
-    """Spacing of BF16 numbers at |y|: 2^(floor(log2|y|) - 7); the smallest normal
-    spacing for zero.  This is the '+1 BF16 ulp of |y_ref|' term of the output
-    tolerance."""
+    """Spacing of BF16 numbers at |y|: 2^(floor(log2|y|) - 7) for normal numbers, 2^-133 for
+    zero and throughout the subnormal range (the format has no finer step there).  This is
+    the '+1 BF16 ulp of |y_ref|' term of the output tolerance."""
     y = np.abs(np.asarray(y, np.float64))
     _, ex = np.frexp(y)                       # y = f * 2^ex, f in [0.5, 1)
-    ulp = np.ldexp(1.0, ex - 1 - 7)
+    ulp = np.ldexp(1.0, np.maximum(ex - 1, -126) - 7)
     return np.where(y == 0.0, np.ldexp(1.0, -126 - 7), ulp)
 
 

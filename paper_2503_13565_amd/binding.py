@@ -31,6 +31,7 @@ EXPORTS = [
     "mxfp4_e2m3_woq_gemm_argmax",
     "mxfp4_fmt_block_bytes", "mxfp4_fmt_direct_cast", "mxfp4_fmt_direct_cast_bits", "mxfp4_fmt_dequant",
     "mxfp4_fmt_woq_gemm", "mxfp4_fmt_woq_gemm_argmax",
+    "mxfp4_woq_gemm_t_workspace_bytes", "mxfp4_woq_gemm_t",
     "mxfp4_tile_repack_q_bytes", "mxfp4_tile_repack_s_bytes", "mxfp4_tile_repack", "mxfp4_woq_gemm_tiled",
     "mxfp4_woq_gemm_tiled_ws",
     "mxfp4_woq_gemm_tiled_argmax", "mxfp4_woq_gemm_tiled_verify", "mxfp4_woq_gemm_tiled_fused",
@@ -119,6 +120,10 @@ def load() -> ctypes.CDLL:
     lib.mxfp4_e2m3_woq_gemm.restype = i32
     lib.mxfp4_e2m3_woq_gemm_argmax.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     lib.mxfp4_e2m3_woq_gemm_argmax.restype = i32
+    lib.mxfp4_woq_gemm_t_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.mxfp4_woq_gemm_t_workspace_bytes.restype = sz
+    lib.mxfp4_woq_gemm_t.argtypes = [vp, i64, i64, vp, vp, i64, i64, vp, i64, vp, sz, vp]
+    lib.mxfp4_woq_gemm_t.restype = i32
     lib.mxfp4_fmt_block_bytes.argtypes = [i32]
     lib.mxfp4_fmt_block_bytes.restype = i32
     for name in ("mxfp4_fmt_direct_cast", "mxfp4_fmt_direct_cast_bits"):
@@ -506,6 +511,34 @@ def mxfp4_e2m3_woq_gemm_argmax(x: torch.Tensor, q6: torch.Tensor, s: torch.Tenso
                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                 _stream()))
     return idx, val
+
+
+def mxfp4_woq_gemm_t_workspace_bytes(m: int, n: int, k: int) -> int:
+    return int(load().mxfp4_woq_gemm_t_workspace_bytes(m, n, k))
+
+
+def mxfp4_woq_gemm_t(x: torch.Tensor, q: torch.Tensor, s: torch.Tensor, y: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """``y[M, K] = x[M, N] @ dequant(q, s)[N, K]``: the product along the rows of the stored tensor."""
+    _dev(x)
+    if x.dtype != torch.bfloat16 or x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be a 2-D BF16 tensor with a contiguous last dimension")
+    if q.dtype != torch.uint8 or s.dtype != torch.uint8 or not q.is_contiguous() or not s.is_contiguous():
+        raise ValueError("q and s must be contiguous uint8 tensors")
+    m, n = x.shape
+    k = q.shape[1] * 2
+    if q.shape[0] != n or tuple(s.shape) != (n, k // 32):
+        raise ValueError("shape mismatch: x %r q %r s %r" % (tuple(x.shape), tuple(q.shape), tuple(s.shape)))
+    if y is None:
+        y = torch.empty((m, k), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty((max(mxfp4_woq_gemm_t_workspace_bytes(m, n, k), 4),), dtype=torch.uint8,
+                                device=x.device)
+    with torch.cuda.device(x.device):
+        _check(load().mxfp4_woq_gemm_t(_ptr(x), m, x.stride(0) if m > 1 else n, _ptr(q), _ptr(s), n, k, _ptr(y),
+                                      y.stride(0) if m > 1 else k, _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream()))
+    return y
 
 
 FMT_E5M2, FMT_E3M2, FMT_T2 = 1, 2, 3

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmxfp4_hip.so")
-SOURCES = ["api.hip", "cast.hip", "gemv.hip", "gemv_reg.hip", "chain.hip", "mfma.hip", "mfma_tile.hip", "bf16.hip", "e4m3.hip", "e2m3.hip", "mxfmt.hip"]
+SOURCES = ["api.hip", "cast.hip", "gemv.hip", "gemv_reg.hip", "chain.hip", "mfma.hip", "mfma_tile.hip", "bf16.hip", "e4m3.hip", "e2m3.hip", "mxfmt.hip", "gemm_t.hip"]
 # packed FP32 instructions are disabled on purpose: see the build notes of this project
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

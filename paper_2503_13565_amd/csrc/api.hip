@@ -1144,6 +1144,59 @@ int mxfp4_e2m3_woq_gemm_argmax(const void* x_bf16, int64_t M, int64_t ldx, const
                     workspace_bytes, true, stream);
 }
 
+// ---- the product along the rows (value side of attention over a quantised cache) --------------
+
+size_t mxfp4_woq_gemm_t_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M < 1 || M > 64 || N < 1 || N > 0x7FFFFFFF / 8 || !gemm_t_can_run((int)(K > 0x7FFFFFFF ? 0 : K)))
+        return 0;
+    return gemm_t_workspace_bytes((int)M, (int)N, (int)K, size_query_device());
+}
+
+int mxfp4_woq_gemm_t(const void* x_bf16, int64_t M, int64_t ldx, const void* q_packed, const void* scales_e8m0,
+                     int64_t N, int64_t K, void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                     void* stream)
+{
+    begin_call();
+    int rc = check_weights(q_packed, scales_e8m0, N, K);
+    if (rc)
+        return rc;
+    if (!gemm_t_can_run((int)K))
+        return fail(MXFP4_ERR_SHAPE, "K=%lld: the product along the rows takes K up to 2048", (long long)K);
+    if (!x_bf16 || !y_bf16)
+        return fail(MXFP4_ERR_NULL, "x_bf16 or y_bf16 is NULL");
+    if (M < 1 || M > 64)
+        return fail(MXFP4_ERR_SHAPE, "M=%lld out of range [1, 64]", (long long)M);
+    if (ldx < N)
+        return fail(MXFP4_ERR_SHAPE, "ldx=%lld < N=%lld", (long long)ldx, (long long)N);
+    if (ldy < K)
+        return fail(MXFP4_ERR_SHAPE, "ldy=%lld < K=%lld", (long long)ldy, (long long)K);
+    if (!aligned(x_bf16, 2) || !aligned(y_bf16, 2))
+        return fail(MXFP4_ERR_ALIGN, "x_bf16 and y_bf16 must be 2-byte aligned");
+    DeviceInfo dev;
+    rc = device_info(&dev);
+    if (rc)
+        return rc;
+    const size_t need = gemm_t_workspace_bytes((int)M, (int)N, (int)K, dev);
+    if (!workspace || workspace_bytes < need)
+        return fail(MXFP4_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : (size_t)0);
+    if (!aligned(workspace, 4))
+        return fail(MXFP4_ERR_ALIGN, "workspace must be 4-byte aligned");
+    GemmArgs a{};
+    a.x = static_cast<const uint16_t*>(x_bf16);
+    a.ldx = ldx;
+    a.q = static_cast<const uint8_t*>(q_packed);
+    a.s = static_cast<const uint8_t*>(scales_e8m0);
+    a.m = (int)M;
+    a.n = (int)N;
+    a.k = (int)K;
+    a.y = static_cast<uint16_t*>(y_bf16);
+    a.ldy = ldy;
+    hipError_t e = launch_gemm_t(a, dev, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MXFP4_OK : hip_fail(e, "product-along-rows launch");
+}
+
 // ---- further block formats by id (E5M2, E3M2, 2-bit ternary) ---------------------------------
 
 int mxfp4_fmt_block_bytes(int fmt) { return mxfmt_block_bytes(fmt); }

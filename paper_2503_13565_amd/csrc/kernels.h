@@ -138,6 +138,12 @@ struct Bf16Args {
 bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev);
 hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
 
+// y[M, K] = x[M, N] * dequant(W)[N, K]: the product along the rows of the stored tensor (gemm_t.hip).
+// `part` holds gemm_t_workspace_bytes of FP32 partial sums.
+bool gemm_t_can_run(int k);
+size_t gemm_t_workspace_bytes(int m, int n, int k, const DeviceInfo& dev);
+hipError_t launch_gemm_t(const GemmArgs& a, const DeviceInfo& dev, float* part, hipStream_t stream);
+
 // Further block formats by id (1 E5M2, 2 E3M2, 3 the 2-bit ternary T2; a.q holds 32, 24 or 8 bytes
 // per block); mxfmt.hip.  mxfmt_block_bytes is 0 for an unknown id.
 int mxfmt_block_bytes(int fmt);

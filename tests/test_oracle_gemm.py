@@ -158,6 +158,11 @@ def test_tolerance_terms():
     assert oracle.bf16_ulp(-2.0) == 2.0 ** -6
     assert oracle.bf16_ulp(0.75) == 2.0 ** -8
     assert oracle.bf16_ulp(0.0) == 2.0 ** -133
+    # BF16 subnormals m * 2^-133, m = 1 .. 127, are 2^-133 apart; the first normal binade too
+    assert oracle.bf16_ulp(2.0 ** -133) == 2.0 ** -133 and oracle.bf16_ulp(1.5e-40) == 2.0 ** -133
+    assert oracle.bf16_ulp(127 * 2.0 ** -133) == 2.0 ** -133 and oracle.bf16_ulp(2.0 ** -126) == 2.0 ** -133
+    assert oracle.bf16_ulp(2.0 ** -125) == 2.0 ** -132
+    assert torch.tensor([1.5 * 2.0 ** -133], dtype=torch.float64).to(torch.bfloat16).double().item() == 2.0 ** -132
     t = oracle.tolerance(np.array([1.0]), np.array([10.0]))
     assert t[0] == 1e-2 + 2.0 ** -7
 
