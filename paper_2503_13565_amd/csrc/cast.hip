@@ -4,7 +4,7 @@
 // Four lanes share one 32-element block: each lane loads 16 bytes (8 elements), the block maximum
 // is taken across the quad with DPP on the integer magnitudes, the scale byte is integer
 // arithmetic on the BF16 exponent, and each lane writes one packed dword; a wave therefore reads
-// 1 KiB and writes 256 B, contiguous.  The elements are rounded by the gfx950 scaled BF16->FP4
+// 1 KiB and writes 256 B, contiguous, per piece, and the 64 scale bytes of four pieces as one run.  The elements are rounded by the gfx950 scaled BF16->FP4
 // convert, or by an integer-only rule on the bit patterns that gives the same bits.
 #include "common.h"
 #include "kernels.h"
@@ -79,9 +79,12 @@ __device__ __forceinline__ void cast_group(const u32x4_t v, uint32_t* packed_out
     *scale_out = scale_byte;
 }
 
-// Persistent grid-stride walk over the groups, kU independent loads in flight per lane.  kFlat:
-// rows are contiguous (ldw == K), so a group's address needs no division.  The grid's stride is a
-// multiple of 4 groups, so quads are never split.
+// Persistent walk over chunks of 256 groups (4 KiB of BF16, 64 blocks): wave w of the grid takes
+// chunks w, w + waves, ...; its four loads per lane are the chunk's four consecutive 1 KiB pieces.
+// A chunk's 64 scale bytes are contiguous in s: the quads leave them in 64 bytes of LDS of the
+// wave's own and lanes 0..3 store them as one 64-byte run (byte stores, 16 per wave instruction,
+// cost the memory system a partial write each).  A wave's LDS operations run in order, so no barrier
+// is needed.  kFlat: rows are contiguous (ldw == K), so a group's address needs no division.
 template <bool kHw, bool kFlat>
 __global__ __launch_bounds__(256) void direct_cast_kernel(const uint16_t* __restrict__ w,
                                                           int64_t n_rows, int k, int64_t ldw,
@@ -89,15 +92,20 @@ __global__ __launch_bounds__(256) void direct_cast_kernel(const uint16_t* __rest
                                                           uint8_t* __restrict__ s)
 {
     constexpr int kU = 4;
+    __shared__ __align__(16) uint8_t sbytes[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int groups_per_row = k >> 3;               // 8-element groups; a multiple of 4
     const int64_t total = n_rows * groups_per_row;   // a multiple of 4
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < total; g0 += kU * stride) {
+    const int64_t chunks = (total + 255) >> 8;
+    const int64_t waves = (int64_t)gridDim.x * 4;
+    const bool s_aligned = (reinterpret_cast<uintptr_t>(s) & 15) == 0;       // else byte stores throughout
+    for (int64_t c = (int64_t)blockIdx.x * 4 + wave; c < chunks; c += waves) {
+        const int64_t g0 = c * 256 + lane;
         u32x4_t v[kU];
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-            int64_t gid = g0 + u * stride;
-            gid = gid < total ? gid : g0;            // surplus slots repeat the first (never stored)
+            int64_t gid = g0 + u * 64;
+            gid = gid < total ? gid : c * 256;       // surplus slots repeat the chunk's first group (never stored)
             int64_t off = gid * 8;
             if constexpr (!kFlat) {
                 const int64_t row = gid / groups_per_row;
@@ -105,17 +113,26 @@ __global__ __launch_bounds__(256) void direct_cast_kernel(const uint16_t* __rest
             }
             v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w + off));
         }
+        const bool whole = s_aligned && c * 256 + 256 <= total;
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-            const int64_t gid = g0 + u * stride;
+            const int64_t gid = g0 + u * 64;
             uint32_t packed;
             int scale_byte;
             cast_group<kHw>(v[u], &packed, &scale_byte);   // whole quads take part in the DPP steps
             if (gid < total) {
-                q[gid] = packed;
-                if ((gid & 3) == 0)
-                    s[gid >> 2] = (uint8_t)scale_byte;
+                __builtin_nontemporal_store(packed, q + gid);
+                if ((lane & 3) == 0) {
+                    if (whole)
+                        sbytes[wave][u * 16 + (lane >> 2)] = (uint8_t)scale_byte;
+                    else
+                        s[gid >> 2] = (uint8_t)scale_byte;
+                }
             }
+        }
+        if (whole && lane < 4) {
+            const u32x4_t line = *reinterpret_cast<const u32x4_t*>(&sbytes[wave][lane * 16]);
+            __builtin_nontemporal_store(line, reinterpret_cast<u32x4_t*>(s + c * 64) + lane);
         }
     }
 }
@@ -166,8 +183,12 @@ hipError_t launch_direct_cast(const void* w, int64_t n_rows, int64_t k, int64_t 
     const int64_t total = n_rows * (k / 8);
     if (total == 0)
         return hipSuccess;
-    int64_t blocks = (total + 255) / 256;
-    const int64_t resident = 256 * 8;                // 8 workgroups of 4 waves per CU on the target part
+    int64_t blocks = (total + 1023) / 1024;          // a workgroup's four waves take a chunk of 256 groups each
+    static const int per_cu = [] {
+        const char* e = knob("MXFP4_CAST_WGS");      // measurement only
+        return e && atoi(e) > 0 ? atoi(e) : 8;
+    }();
+    const int64_t resident = 256 * per_cu;           // 8 workgroups of 4 waves per CU on the target part
     if (blocks > resident)
         blocks = resident;
     const bool flat = ldw == k;
