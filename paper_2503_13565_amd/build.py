@@ -15,13 +15,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmxfp4_hip.so")
-SOURCES = ["api.hip", "cast.hip", "gemv.hip", "gemv_reg.hip", "chain.hip", "mfma.hip", "mfma_tile.hip", "bf16.hip", "e4m3.hip", "e2m3.hip", "mxfmt.hip", "gemm_t.hip"]
+SOURCES = ["api.hip", "cast.hip", "gemv.hip", "gemv_reg.hip", "chain.hip", "mfma.hip", "mfma_tile.hip", "bf16.hip", "e4m3.hip", "e2m3.hip", "mxfmt.hip", "gemm_t.hip", "gemv_tile.hip"]
 # packed FP32 instructions are disabled on purpose: see the build notes of this project
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # per file: the leading scalar kernel arguments arrive in scalar registers when a wave starts
 PRELOAD = ["-mllvm", "-amdgpu-kernarg-preload-count=16"]
-EXTRA = {"gemv_reg.hip": PRELOAD, "chain.hip": PRELOAD, "mfma_tile.hip": PRELOAD, "gemv.hip": PRELOAD, "bf16.hip": PRELOAD}
+EXTRA = {"gemv_reg.hip": PRELOAD, "gemv_tile.hip": PRELOAD, "chain.hip": PRELOAD, "mfma_tile.hip": PRELOAD, "gemv.hip": PRELOAD, "bf16.hip": PRELOAD}
 
 
 def _hipcc() -> str:

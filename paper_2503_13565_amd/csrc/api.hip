@@ -225,8 +225,18 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
     hipError_t e = hipSuccess;
     const bool go = !g_check_only;
     switch (chosen) {
-    case -1:
-        if (mfma_tile_can_run(a, dev)) {
+    case -1: {
+        // One row: the decode kernel of the tile-major layout (the tiles' matrix-core kernel takes 7 %
+        // longer over the four linears of a 7B layer).  Two rows: the tiles where they run (equal or
+        // up to 8 % faster on the 7B shapes), else the decode kernel (K = 28672: 28.1 against 29.6 us).
+        static const bool tiled_decode = [] {
+            const char* e = knob("MXFP4_TILED_DECODE");              // measurement only
+            return !e || atoi(e) != 0;
+        }();
+        if (tiled_decode && !epi && gemv_tile_can_run(a, dev) && (a.m == 1 || !mfma_tile_can_run(a, dev))) {
+            if (go)
+                e = launch_gemv_tile(a, dev, &parts_used, st);
+        } else if (mfma_tile_can_run(a, dev)) {
             if (go)
                 e = launch_mfma_tile(a, dev, &parts_used, st, true, epi);
         } else if (splitk_ws && mfma_tiled_split_can_run(a, dev)) {
@@ -239,6 +249,7 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
                         (long long)(M > 16 ? 16 : M), (long long)K);
         }
         break;
+    }
     case MXFP4_PATH_VALU_BITS:
     case MXFP4_PATH_VALU_CVT:
     case MXFP4_PATH_VALU_LUT:

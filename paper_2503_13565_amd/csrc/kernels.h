@@ -138,6 +138,11 @@ struct Bf16Args {
 bool bf16_can_run(const Bf16Args& a, const DeviceInfo& dev);
 hipError_t launch_bf16_gemv(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
 
+// The decode step (one or two activation rows) on the tile-major tensors (a.q = q_tiled, a.s =
+// s_tiled); gemv_tile.hip.  The argmax form writes one partial winner per workgroup.
+bool gemv_tile_can_run(const GemmArgs& a, const DeviceInfo& dev);
+hipError_t launch_gemv_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream);
+
 // y[M, K] = x[M, N] * dequant(W)[N, K]: the product along the rows of the stored tensor (gemm_t.hip).
 // `part` holds gemm_t_workspace_bytes of FP32 partial sums.
 bool gemm_t_can_run(int k);

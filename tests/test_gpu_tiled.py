@@ -46,7 +46,7 @@ def test_tile_repack_is_the_stated_permutation(n, k):
 
 @pytest.mark.parametrize("n,k", [(16, 128), (17, 256), (250, 11008), (1000, 4096), (48, 8192), (2050, 2048),
                                  (31, 12288), (4100, 11008), (530, 28672)])
-@pytest.mark.parametrize("m", [1, 3, 4, 5, 8, 16, 17, 33])
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 16, 17, 33])
 def test_tiled_product_edge_shapes(n, k, m):
     w = synth.weights_student_t(n, k, seed=7000 + n + k)
     x = synth.activations_outlier_channels(m, k, seed=8000 + m + k)
@@ -57,7 +57,12 @@ def test_tiled_product_edge_shapes(n, k, m):
     width = 16 if m > 8 else (8 if m > 4 else 4)
     y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref)
     ws_bytes = binding.mxfp4_woq_gemm_workspace_bytes(m, n, k)
-    if (k + 511) // 512 * 1024 * width + 8192 > 160 * 1024:
+    # one and two rows run the decode kernel of this layout: the rows and 1 KiB of partial sums per row
+    # and tile of a workgroup in the LDS
+    tiles = (n + 15) // 16
+    slots = -(-tiles // min(tiles, 256))
+    decode = m <= 2 and m * k * 2 + slots * (1088 * m + 4) + 512 <= 160 * 1024
+    if not decode and (k + 511) // 512 * 1024 * width + 8192 > 160 * 1024:
         # no workspace: refused; with one, K is split over grid rows
         with pytest.raises(binding.Mxfp4Error) as e:
             binding.mxfp4_woq_gemm_tiled(xg, tw)
@@ -125,3 +130,33 @@ def test_tiled_refuses_what_does_not_fit_and_bad_k():
     with pytest.raises(binding.Mxfp4Error) as e:
         binding.mxfp4_tile_repack(q96, s96)
     assert e.value.code == 2
+
+
+@pytest.mark.parametrize("n,k", [(1, 128), (15, 128), (16, 256), (4096, 4096), (4097, 4096), (12288, 4096),
+                                 (22016, 4096), (4096, 11008), (32000, 4096), (2050, 3072), (777, 8192),
+                                 (5000, 2176), (300, 28672), (9000, 6144), (128256, 2048), (66000, 1024)])
+@pytest.mark.parametrize("m", [1, 2])
+def test_tiled_decode_rows(n, k, m):
+    """One and two rows on the tile-major copy: every count of steps per wave (K = 128 .. 28672: in
+    registers up to four, from LDS beyond), waves beyond K, ragged N, one to 32 tiles per workgroup;
+    the same pick as from the row-major tensors."""
+    w = synth.weights_student_t(n, k, seed=9000 + n + k)
+    x = synth.activations_outlier_channels(m, k, seed=9100 + m + k)
+    q, s, q_ref, s_ref = assert_cast_bit_exact(w)
+    tw = binding.mxfp4_tile_repack(q, s)
+    xg = x.to(DEV)
+    y_ref, a_ref = oracle.woq_gemm(synth.to_bits(x), q_ref, s_ref)
+    y = binding.mxfp4_woq_gemm_tiled(xg, tw)
+    torch.cuda.synchronize()
+    assert_gemm_close(y, y_ref, a_ref, "tiled decode N=%d K=%d M=%d" % (n, k, m))
+    again = binding.mxfp4_woq_gemm_tiled(xg, tw)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), again.view(torch.int16))          # the same bits on every call
+    idx, val = binding.mxfp4_woq_gemm_tiled_argmax(xg, tw)
+    torch.cuda.synchronize()
+    assert_argmax_ok(idx, val, y_ref, a_ref, "tiled decode argmax N=%d K=%d M=%d" % (n, k, m))
+    s2 = s.clone()
+    s2[n // 2, 0] = 0xFF                                                       # a NaN block stays in its row
+    y2 = binding.mxfp4_woq_gemm_tiled(xg, binding.mxfp4_tile_repack(q, s2)).float().cpu().numpy()
+    keep = np.arange(n) != n // 2
+    assert np.isnan(y2[:, n // 2]).all() and np.array_equal(y2[:, keep], y.float().cpu().numpy()[:, keep])
