@@ -52,6 +52,8 @@ struct RegArgs {
 // wave instruction with misaligned, gapped accesses and costs 16 to 21 % of the kernel's time;
 // instead the wave loads the 1536 bytes lane-contiguous (16 bytes per lane, then 8), passes them
 // through 1536 bytes of LDS of its own and reads back bytes [24 lane, 24 lane + 24).
+// Format codes 22 and 24 are the second element formats of those widths (E3M2, E5M2): the same frame
+// with the other convert instruction.
 // kBits 8 (E4M3 bytes, 32 bytes per block, 2048 bytes per wave step): loaded lane-contiguous too
 // (16 bytes per lane, twice), and no exchange is needed: a lane keeps what it loaded, two half
 // blocks -- elements [16 lane, 16 lane + 16) of the step, block lane / 2, and the same 1024
@@ -62,10 +64,15 @@ typedef __attribute__((ext_vector_type(6))) unsigned int u32x6_t;
 typedef __attribute__((ext_vector_type(16))) unsigned int u32x16_t;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
 
-template <int MT, int R, int STEPS, int D, int NW, bool kRagged, class Epi, int kBits = 4>
+template <int MT, int R, int STEPS, int D, int NW, bool kRagged, class Epi, int kFmt = 4>
 __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
 {
+    // kFmt: the element width, + 16 for the second element format of that width (22: E3M2 in place of
+    // E2M3, 24: E5M2 in place of E4M3): same loads and lane mapping, the other convert instruction
+    constexpr bool kAlt = kFmt > 16;
+    constexpr int kBits = kAlt ? kFmt - 16 : kFmt;
     static_assert(kBits == 4 || kBits == 6 || kBits == 8, "element width");
+    static_assert(!kAlt || kBits != 4, "the 4-bit format has one element format");
     constexpr int kBlkBytes = kBits == 8 ? 32 : (kBits == 6 ? 24 : 16);
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     const int m0 = a.m0;
@@ -350,10 +357,17 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                         for (int jj = 0; jj < 2; ++jj) {
                             const uint32_t qd0 = piece[2 * jj], qd1 = piece[2 * jj + 1];
                             bf16x2_t w[4];
-                            w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd0, sc2[p], false);
-                            w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd0, sc2[p], true);
-                            w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd1, sc2[p], false);
-                            w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd1, sc2[p], true);
+                            if constexpr (kAlt) {
+                                w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(qd0, sc2[p], false);
+                                w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(qd0, sc2[p], true);
+                                w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(qd1, sc2[p], false);
+                                w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(qd1, sc2[p], true);
+                            } else {
+                                w[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd0, sc2[p], false);
+                                w[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd0, sc2[p], true);
+                                w[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd1, sc2[p], false);
+                                w[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(qd1, sc2[p], true);
+                            }
 #pragma unroll
                             for (int m = 0; m < MT; ++m) {
                                 const u32x4_t xv = xq[m][2 * p + jj];
@@ -392,7 +406,10 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                     const u32x6_t packed = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1]};
-                    w6 = __builtin_bit_cast(u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(packed, sc));
+                    if constexpr (kAlt)
+                        w6 = __builtin_bit_cast(u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_bf6(packed, sc));
+                    else
+                        w6 = __builtin_bit_cast(u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(packed, sc));
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -535,7 +552,7 @@ hipError_t launch_one6(const GemmArgs& g, int m0, int blocks, size_t lds, hipStr
     const bool argmax = g.part_val != nullptr;
     if (MT * STEPS >= 6)
         lds = (size_t)MT * STEPS * 4096 + 64;       // padded activation rows
-    if (kBits == 6)
+    if ((kBits & 15) == 6)
         lds += (size_t)NW * R * 1536;               // the waves' buffers for the lane exchange
     static LdsLimit lds_limit;                      // of this kernel instance
     if (lds > 64 * 1024)
@@ -1194,7 +1211,7 @@ bool gemv_reg_single_pass(const GemmArgs& a) { return a.m == 1 || (a.m == 2 && e
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                            const Epilogue* epi, int bits)
 {
-    if (bits != 4 && ((bits != 6 && bits != 8) || epi))
+    if (bits != 4 && ((bits != 6 && bits != 8 && bits != 22 && bits != 24) || epi))
         return hipErrorInvalidValue;
     const int steps2 = even_steps(a.k);
     const bool ragged = a.k != steps2 * 2048;
@@ -1212,13 +1229,17 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     for (int m0 = 0; m0 < a.m;) {
         hipError_t e;
         if (a.m - m0 >= 2 && steps2 <= 2) {
-            e = bits == 6   ? launch_steps6<2, 6>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
-                : bits == 8 ? launch_steps6<2, 8>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+            e = bits == 6    ? launch_steps6<2, 6>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+                : bits == 8  ? launch_steps6<2, 8>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+                : bits == 22 ? launch_steps6<2, 22>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+                : bits == 24 ? launch_steps6<2, 24>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                             : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi);
             m0 += 2;
         } else {
-            e = bits == 6   ? launch_steps6<1, 6>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
-                : bits == 8 ? launch_steps6<1, 8>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+            e = bits == 6    ? launch_steps6<1, 6>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+                : bits == 8  ? launch_steps6<1, 8>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+                : bits == 22 ? launch_steps6<1, 22>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+                : bits == 24 ? launch_steps6<1, 24>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                             : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi);
             m0 += 1;
         }

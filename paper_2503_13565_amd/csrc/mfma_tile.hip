@@ -64,13 +64,18 @@ typedef __attribute__((ext_vector_type(2))) unsigned int t_u32x2_t;
 typedef __attribute__((ext_vector_type(6))) unsigned int t_u32x6_t;
 typedef __attribute__((ext_vector_type(16))) unsigned int t_u32x16_t;
 
-template <int MP, int NW, int D, bool kTiled, class Epi, int kBits = 4>
+template <int MP, int NW, int D, bool kTiled, class Epi, int kFmt = 4>
 __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, const uint8_t* __restrict__ q,
                                                const uint8_t* __restrict__ s, void* out, int n, int k, int m,
                                                int m0, int ldx, int ldy, int parts, const Epi& epi,
                                                int phase_steps = 0)
 {
+    // kFmt: the element width, + 16 for the second element format of that width (22: E3M2, 24: E5M2):
+    // the same frame with the other convert instruction
+    constexpr bool kAlt = kFmt > 16;
+    constexpr int kBits = kAlt ? kFmt - 16 : kFmt;
     static_assert(kBits == 4 || ((kBits == 8 || kBits == 6) && !kTiled), "element width");
+    static_assert(!kAlt || kBits != 4, "the 4-bit format has one element format");
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     constexpr int T = (NW + 1) * 64;
     extern __shared__ __align__(16) uint8_t smem[];
@@ -322,7 +327,10 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                         const u32x4_t lo = it.q[u];
                         const t_u32x2_t hi = it.qh[u];
                         const t_u32x6_t packed = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1]};
-                        w6 = __builtin_bit_cast(t_u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(packed, scl));
+                        if constexpr (kAlt)
+                            w6 = __builtin_bit_cast(t_u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_bf6(packed, scl));
+                        else
+                            w6 = __builtin_bit_cast(t_u32x16_t, __builtin_amdgcn_cvt_scalef32_pk32_bf16_fp6(packed, scl));
                     }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
@@ -333,10 +341,17 @@ __device__ __forceinline__ void mfma_tile_body(const uint16_t* __restrict__ x, c
                         } else if constexpr (kBits == 8) {
                             const uint32_t q0 = it.q[2 * u + (j >> 1)][2 * (j & 1)];
                             const uint32_t q1 = it.q[2 * u + (j >> 1)][2 * (j & 1) + 1];
-                            w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q0, scl, false));
-                            w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q0, scl, true));
-                            w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q1, scl, false));
-                            w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q1, scl, true));
+                            if constexpr (kAlt) {
+                                w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(q0, scl, false));
+                                w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(q0, scl, true));
+                                w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(q1, scl, false));
+                                w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_bf8(q1, scl, true));
+                            } else {
+                                w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q0, scl, false));
+                                w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q0, scl, true));
+                                w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q1, scl, false));
+                                w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(q1, scl, true));
+                            }
                         } else {
                             const uint32_t qd = it.q[u][j];
                             w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 0));
@@ -616,9 +631,11 @@ hipError_t launch_tile_fmt(const GemmArgs& a, const DeviceInfo& dev, int* parts_
 
 hipError_t launch_mfma_tile8(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream, int bits)
 {
-    return bits == 8   ? launch_tile_fmt<8>(a, dev, parts_used, stream)
-           : bits == 6 ? launch_tile_fmt<6>(a, dev, parts_used, stream)
-                       : hipErrorInvalidValue;
+    return bits == 8    ? launch_tile_fmt<8>(a, dev, parts_used, stream)
+           : bits == 6  ? launch_tile_fmt<6>(a, dev, parts_used, stream)
+           : bits == 24 ? launch_tile_fmt<24>(a, dev, parts_used, stream)
+           : bits == 22 ? launch_tile_fmt<22>(a, dev, parts_used, stream)
+                        : hipErrorInvalidValue;
 }
 
 hipError_t launch_mfma_tile(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
