@@ -10,8 +10,8 @@
 //
 // One workgroup of 16 waves per compute unit walks the tiles b, b + G, ...; inside a tile the waves
 // split K: wave w takes the steps [w spw, (w + 1) spw), the same for every tile, so the 32 spw
-// activations a lane meets never change and sit in registers (spw <= 4: K <= 8192; else they are read
-// from the LDS copy every step).  A wave's steps of one tile are in flight (32 KiB per compute unit at
+// activations a lane meets never change and sit in registers (one row: up to four steps per wave, K <=
+// 8192; two rows: two; else they are read from the LDS copy every step).  A wave's steps of one tile are in flight (32 KiB per compute unit at
 // K = 4096); each buffer is refilled with the next tile's step as soon as it has been used.  A
 // lane accumulates its row over its blocks; at a tile's end the four lanes of a row are added, the wave
 // leaves 16 partial sums in LDS and counts itself in at the tile's LDS counter; the wave that completes
@@ -80,10 +80,11 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
     };
     // Always the same two loads per step: past the wave's last position the lane offset is out of the
     // descriptor's range (no memory touched, zero back).
-    // Register form: buffer s holds step s of the current tile and is refilled with step s of the next
-    // tile as soon as it has been used (SPW KiB of a wave in flight); steps beyond the wave's range
-    // load nothing and count as zero weights.  Else: two buffers walk the wave's positions.
-    constexpr int kBufs = kRegs ? SPW : 2;
+    // Register form: two buffers (SPW odd: SPW) hold the next steps of the wave's sequence; a buffer is
+    // refilled with the step that many ahead, of this tile or the next, as soon as it has been used
+    // (2 KiB of a wave in flight); steps beyond the wave's range load nothing and count as zero
+    // weights.  Else: two buffers walk the wave's positions.
+    constexpr int kBufs = kRegs ? (SPW % 2 == 0 ? 2 : SPW) : 2;     // divides SPW: step s always uses buffer s % kBufs
     u32x4_t bq[kBufs];
     uint32_t bs[kBufs];
     auto issue_at = [&](const bool live, const int j, const int s, const int d) {
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
     TPos load{0, 0};
     if constexpr (kRegs) {
 #pragma unroll
-        for (int s = 0; s < SPW; ++s) {
+        for (int s = 0; s < kBufs; ++s) {
             issue_at(s < nsteps && tiles_wg > 0, 0, s, s);
             __builtin_amdgcn_sched_barrier(0);       // the loop's order of loads: the waits then count alike
         }
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
         }
     };
 
-    // step `s` of the wave's range from buffer d (register form: s == d, a constant)
+    // step `s` of the wave's range from buffer d (register form: both constants, d = s % kBufs)
     auto compute = [&](const int s, const int d) {
         const u32x4_t wq = bq[d];
         // the convert reads only the exponent field of its scale operand (as E8M0)
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
             for (int r = 0; r < MT; ++r)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    xv[r][c] = xr[r][d][c];
+                    xv[r][c] = xr[r][s][c];
         } else {
             const int blk = 4 * (s_begin + s) + g;
 #pragma unroll
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
         for (int j = 0; j < tiles_wg; ++j) {
 #pragma unroll
             for (int s = 0; s < SPW; ++s) {
-                compute(s, s);
+                compute(s, s % kBufs);
                 if (s == 0 && j > 0)
                     complete(j - 1, pending);
                 // the refill leaves right behind the step that freed the buffer, not after the tile's
@@ -255,7 +256,10 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
                 for (int r = 0; r < MT; ++r)
                     asm volatile("" : "+v"(acc[r])::"memory");
                 __builtin_amdgcn_sched_barrier(0);
-                issue_at(s < nsteps && j + 1 < tiles_wg, j + 1, s, s);
+                // the step kBufs ahead: of this tile, or of the next
+                const int sn = s + kBufs < SPW ? s + kBufs : s + kBufs - SPW;
+                const int jn = s + kBufs < SPW ? j : j + 1;
+                issue_at(sn < nsteps && jn < tiles_wg, jn, sn, s % kBufs);
                 __builtin_amdgcn_sched_barrier(0);
             }
             pending = post(j);
@@ -370,12 +374,14 @@ hipError_t launch_mt(const GemmArgs& a, int blocks, size_t lds, int max_lds, hip
     case 2:
         return launch_k<MT, 2, true>(a, blocks, lds, spw, max_lds, stream);
     case 3:
-        return launch_k<MT, 3, true>(a, blocks, lds, spw, max_lds, stream);
+        if constexpr (MT == 1)                      // two rows of three steps spill
+            return launch_k<MT, 3, true>(a, blocks, lds, spw, max_lds, stream);
+        break;
     case 4:
         if constexpr (MT == 1)
             return launch_k<MT, 4, true>(a, blocks, lds, spw, max_lds, stream);
         break;
-    }
+    }                                                // (six steps in registers spill: 11.3 against 8.2 us on the 7B down projection)
     return launch_k<MT, 1, false>(a, blocks, lds, spw, max_lds, stream);
 }
 
