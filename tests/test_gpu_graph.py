@@ -17,7 +17,9 @@ def make_case(n, k, m, seed):
     q, s = binding.mxfp4_direct_cast(w)
     q8, s8 = binding.mxfp4_e4m3_direct_cast(w)
     x = synth.activations_outlier_channels(m, k, seed=seed + 1).to(DEV)
-    return dict(n=n, k=k, m=m, q=q, s=s, q8=q8, s8=s8, w=w, x=x, tw=binding.mxfp4_tile_repack(q, s))
+    fmts = {f: binding.mxfp4_fmt_direct_cast(f, w) for f in (binding.FMT_E5M2, binding.FMT_E3M2, binding.FMT_T2)}
+    p = synth.activations_outlier_channels(min(m, 8), n, seed=seed + 2).to(DEV)      # for the product along the rows
+    return dict(n=n, k=k, m=m, q=q, s=s, q8=q8, s8=s8, w=w, x=x, tw=binding.mxfp4_tile_repack(q, s), fmts=fmts, p=p)
 
 
 def test_replays_match_eager_calls():
@@ -41,7 +43,13 @@ def test_replays_match_eager_calls():
             yb=torch.empty((m, n), dtype=torch.bfloat16, device=DEV),
             idx=torch.empty((m,), dtype=torch.int32, device=DEV), val=torch.empty((m,), dtype=torch.float32, device=DEV),
             acc=torch.empty((2,), dtype=torch.int32, device=DEV), vidx=torch.empty((m,), dtype=torch.int32, device=DEV),
+            yf1=torch.empty((m, n), dtype=torch.bfloat16, device=DEV), yf2=torch.empty((m, n), dtype=torch.bfloat16, device=DEV),
+            yf3=torch.empty((m, n), dtype=torch.bfloat16, device=DEV),
+            yt1=torch.empty((1, n), dtype=torch.bfloat16, device=DEV),
+            yrows=torch.empty((min(m, 8), k), dtype=torch.bfloat16, device=DEV),
         )
+        c["wst"] = torch.empty((max(binding.mxfp4_woq_gemm_t_workspace_bytes(min(m, 8), n, k), 8),), dtype=torch.uint8,
+                               device=DEV)
         outs.append(c["out"])
 
     def step():
@@ -56,6 +64,11 @@ def test_replays_match_eager_calls():
             binding.mxfp4_bf16_gemm(c["x"], c["w"], y=o["yb"])
             if c["m"] >= 3 and c["k"] <= 4096:         # eight rows of K = 11008 do not fit the tile-major form
                 binding.mxfp4_woq_gemm_tiled(c["x"], c["tw"], y=o["yt"])
+            for f, name in ((binding.FMT_E5M2, "yf1"), (binding.FMT_E3M2, "yf2"), (binding.FMT_T2, "yf3")):
+                binding.mxfp4_fmt_woq_gemm(f, c["x"], c["fmts"][f][0], c["fmts"][f][1], y=o[name])
+            binding.mxfp4_woq_gemm_tiled(c["x"][:1], c["tw"], y=o["yt1"])          # the decode kernel of that layout
+            if c["k"] <= 2048:
+                binding.mxfp4_woq_gemm_t(c["p"], c["q"], c["s"], y=o["yrows"], workspace=c["wst"])
 
     def snapshot():
         torch.cuda.synchronize()
@@ -85,6 +98,6 @@ def test_replays_match_eager_calls():
             for name in g:
                 if name == "yt" and not (cases[ci]["m"] >= 3 and cases[ci]["k"] <= 4096):
                     continue
-                if name in ("acc", "vidx"):
+                if name in ("acc", "vidx") or (name == "yrows" and cases[ci]["k"] > 2048):
                     continue
                 assert torch.equal(g[name].view(torch.uint8), e[name].view(torch.uint8)), (rep, ci, name)

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 from helpers import DEV, assert_argmax_ok, assert_cast_bit_exact, assert_gemm_close  # noqa: E402
 
-KINDS = ["mx", "fused", "tiled", "grouped", "e4m3", "e2m3", "bf16"]
+KINDS = ["mx", "fused", "tiled", "grouped", "e4m3", "e2m3", "bf16", "e5m2", "e3m2", "t2", "rows"]
 
 
 def draw(kind, rng):
@@ -26,6 +26,8 @@ def draw(kind, rng):
         n = rng.choice([rng.randint(1, 300), rng.randint(2040, 2600), rng.randint(300, 5000)])
     elif kind == "tiled":
         k, n = 128 * rng.randint(1, 100), rng.randint(1, 3000)
+    elif kind == "rows":                                 # the product along the rows: K is a head dimension
+        k, n, m = 32 * rng.randint(1, 64), rng.randint(1, 9000), min(m, 9)
     else:
         k = 32 * rng.randint(1, 400) if rng.random() < 0.5 else 128 * rng.randint(1, 100)
         n = rng.choice([rng.randint(1, 300), rng.randint(2040, 2600), rng.randint(300, 5000)])
@@ -46,7 +48,23 @@ def test_random_shapes(kind):
         w = synth.weights_student_t(n, k, seed=seed)
         x = synth.activations_outlier_channels(m, k, seed=seed + 1)
         xg = x.to(DEV)
-        if kind == "bf16":
+        if kind == "rows":
+            q, s, q_ref, s_ref = assert_cast_bit_exact(w, tag)
+            p = synth.activations_outlier_channels(m, n, seed=seed + 2)
+            y_ref, a_ref = oracle.woq_gemm_t(synth.to_bits(p), q_ref, s_ref)
+            y = binding.mxfp4_woq_gemm_t(p.to(DEV), q, s)
+            torch.cuda.synchronize()
+            assert_gemm_close(y, y_ref, a_ref, tag)
+            continue
+        if kind in ("e5m2", "e3m2", "t2"):
+            fmt = {"e5m2": binding.FMT_E5M2, "e3m2": binding.FMT_E3M2, "t2": binding.FMT_T2}[kind]
+            q_ref, s_ref = oracle.mx_direct_cast(fmt, synth.to_bits(w))
+            q, s = binding.mxfp4_fmt_direct_cast(fmt, w.to(DEV))
+            assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref), tag
+            y_ref, a_ref = oracle.mx_woq_gemm(fmt, synth.to_bits(x), q_ref, s_ref)
+            y = binding.mxfp4_fmt_woq_gemm(fmt, xg, q, s)
+            idx, val = binding.mxfp4_fmt_woq_gemm_argmax(fmt, xg, q, s)
+        elif kind == "bf16":
             y_ref, a_ref = oracle.bf16_gemm(synth.to_bits(x), synth.to_bits(w))
             y = binding.mxfp4_bf16_gemm(xg, w.to(DEV))
             idx, val = binding.mxfp4_bf16_gemm_argmax(xg, w.to(DEV))
