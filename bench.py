@@ -683,6 +683,26 @@ def main() -> int:
             us, g = clock.us_per_call_graphs([(lambda lin=lin, fn=fn: fn(lin)) for lin in bsets], nb, n_bf16)
             variants[key] = round(us, 2)
             del g
+        # attention over a cache held in MXFP4: one head, 4096 tokens of dimension 128, four query rows
+        # (64 heads' caches in rotation: 36 MB, more than the L2s hold)
+        heads = []
+        for h in range(64):
+            kq, ks = binding.mxfp4_direct_cast(synth.weights_student_t(4096, 128, seed=900 + h, device=dev))
+            vq, vs = binding.mxfp4_direct_cast(synth.weights_student_t(4096, 128, seed=1900 + h, device=dev))
+            heads.append(dict(kq=kq, ks=ks, vq=vq, vs=vs))
+        qx = synth.activations_outlier_channels(4, 128, seed=77, device=dev)
+        px = synth.activations_outlier_channels(4, 4096, seed=78, device=dev)
+        sc = torch.empty((4, 4096), dtype=torch.bfloat16, device=dev)
+        ov = torch.empty((4, 128), dtype=torch.bfloat16, device=dev)
+        wst = torch.empty((binding.mxfp4_woq_gemm_t_workspace_bytes(4, 4096, 128),), dtype=torch.uint8, device=dev)
+        us, g = clock.us_per_call_graphs([(lambda h=h: binding.mxfp4_woq_gemm(qx, h["kq"], h["ks"], y=sc)) for h in heads],
+                                         4 * len(heads), len(heads))
+        variants["cache_head_4096x128_scores_4_rows_us"] = round(us, 2)
+        del g
+        us, g = clock.us_per_call_graphs([(lambda h=h: binding.mxfp4_woq_gemm_t(px, h["vq"], h["vs"], y=ov, workspace=wst))
+                                          for h in heads], 4 * len(heads), len(heads))
+        variants["cache_head_4096x128_values_4_rows_us"] = round(us, 2)
+        del g, heads
         extra["variants"] = variants
         for lin in bsets:
             for t in lin.values():

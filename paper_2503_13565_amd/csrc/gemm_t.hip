@@ -100,8 +100,19 @@ __global__ __launch_bounds__(kThreads) void gemm_t_finish_kernel(const float* __
     const int o = (int)blockIdx.x * kThreads + threadIdx.x;
     if (o >= m * k)
         return;
+    // index order; eight loads in flight at a time (one by one, each add waits a memory round trip)
     float v = 0.f;
-    for (int g = 0; g < groups; ++g)
+    int g = 0;
+    for (; g + 8 <= groups; g += 8) {
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            p[u] = part[(size_t)(g + u) * m * k + o];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            v += p[u];
+    }
+    for (; g < groups; ++g)
         v += part[(size_t)g * m * k + o];
     const int i = o / k, col = o - i * k;
     y[(int64_t)i * ldy + col] = f32_to_bf16_rne(v);
