@@ -496,12 +496,13 @@ int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Tile-major weights for verification passes (an internal layout, made once from the canonical
- * tensors; bit-exactness is defined on the canonical ones).  The MFMA tile kernel of the
- * M >= 3 path loads 16 rows x 64 bytes per wave instruction from the row-major tensors; from this
- * copy the same fragment is 1 KiB contiguous, which is worth 10 to 14 % on such a pass.  A model
- * that is used for single-row decoding too keeps both copies (the decode kernels want rows
- * contiguous): +0.53 bytes per weight of the 288 GB.
+ * Tile-major weights (an internal layout, made once from the canonical tensors; bit-exactness is
+ * defined on the canonical ones).  The MFMA tile kernel of the M >= 3 path loads 16 rows x 64 bytes
+ * per wave instruction from the row-major tensors; from this copy the same fragment is 1 KiB
+ * contiguous, which is worth 10 to 14 % on a verification pass.  The copy serves single rows too
+ * (section 3.3: one quantised model drafts and verifies): one row runs a decode kernel of this
+ * layout, 4 to 8 % behind the row-major decode kernel on the 7B shapes, so a model can keep this
+ * copy alone, or both (+0.53 bytes per weight of the 288 GB) for the fastest of each.
  *   q_tiled out uint8, mxfp4_tile_repack_q_bytes(N, K) bytes, 16-byte aligned:
  *           [tile = ceil(N/16)][step = K/128][lane = i + 16 g][16 bytes] = block 4 step + g of row
  *           16 tile + i (rows past N are zero)
@@ -515,8 +516,8 @@ int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
  * (mxfp4_woq_gemm_workspace_bytes(M, N, K) bytes for mxfp4_woq_gemm_tiled_ws; the argmax and
  * verify workspaces of mxfp4_woq_gemm_argmax_workspace_bytes include them); a call without one
  * (mxfp4_woq_gemm_tiled, a NULL or short workspace) returns MXFP4_ERR_ARG for such a shape, which
- * then goes through the canonical tensors.  Any M >= 1 works (single rows too, but the decode
- * kernels on the canonical tensors are faster there).
+ * then goes through the canonical tensors.  Any M >= 1 works; one row (and two, where the tiles
+ * cannot run) needs no workspace at any K whose activation rows fit the LDS.
  */
 size_t mxfp4_tile_repack_q_bytes(int64_t N, int64_t K);
 size_t mxfp4_tile_repack_s_bytes(int64_t N, int64_t K);
