@@ -261,8 +261,10 @@ int mxfp4_woq_gemm_path(const void* x_bf16, int64_t M, int64_t ldx,
  * `workspace` the phases run side by side on different compute units and a second kernel adds
  * their FP32 partial products, which live in the workspace, in a fixed order: the fast form.
  * Without it (NULL, or smaller than mxfp4_woq_gemm_workspace_bytes, which is 0 when no split is
- * needed) the call still works: the phases then run one after the other inside the kernel, or,
- * for matrices with very many output rows per compute unit, in narrower passes over the weights.
+ * needed) the call still works: the phases then run one after the other inside the kernel (up to
+ * eight rows: about as fast as the split for matrices with one tile of 16 output rows per compute
+ * unit, such as a down projection), or, for wider passes over matrices with very many output rows
+ * per compute unit, in narrower passes over the weights.
  * workspace: 8-byte aligned, contents unspecified before and after; calls that overlap in time
  * must not share it.  `path` as in mxfp4_woq_gemm_path.
  */
@@ -514,10 +516,11 @@ int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
  * mxfp4_woq_gemm_verify.  When the activation rows of a pass (min(M, 16) x K BF16) do not fit the
  * LDS of a compute unit next to 8 KB, K is split through the workspace as in mxfp4_woq_gemm_ws
  * (mxfp4_woq_gemm_workspace_bytes(M, N, K) bytes for mxfp4_woq_gemm_tiled_ws; the argmax and
- * verify workspaces of mxfp4_woq_gemm_argmax_workspace_bytes include them); a call without one
- * (mxfp4_woq_gemm_tiled, a NULL or short workspace) returns MXFP4_ERR_ARG for such a shape, which
- * then goes through the canonical tensors.  Any M >= 1 works; one row (and two, where the tiles
- * cannot run) needs no workspace at any K whose activation rows fit the LDS.
+ * verify workspaces of mxfp4_woq_gemm_argmax_workspace_bytes include them); a call of more than
+ * eight rows without one (mxfp4_woq_gemm_tiled, a NULL or short workspace) returns MXFP4_ERR_ARG
+ * for such a shape, which then goes through the canonical tensors.  Up to eight rows need no
+ * workspace at any K (the workgroup walks K in phases); one row (and two, where the tiles cannot
+ * run) at any K whose activation rows fit the LDS.
  */
 size_t mxfp4_tile_repack_q_bytes(int64_t N, int64_t K);
 size_t mxfp4_tile_repack_s_bytes(int64_t N, int64_t K);

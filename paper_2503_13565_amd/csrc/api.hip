@@ -239,6 +239,9 @@ static int run_gemm(const void* x, int64_t M, int64_t ldx, const void* q, const 
         } else if (mfma_tile_can_run(a, dev)) {
             if (go)
                 e = launch_mfma_tile(a, dev, &parts_used, st, true, epi);
+        } else if (!epi && mfma_tile_phased_preferred(a, dev, splitk_ws != nullptr && mfma_tiled_split_can_run(a, dev))) {
+            if (go)
+                e = launch_mfma_tile_phased(a, dev, st, true);
         } else if (splitk_ws && mfma_tiled_split_can_run(a, dev)) {
             if (go)
                 e = launch_mfma(a, dev, splitk_ws, &parts_used, st, false, epi, true);

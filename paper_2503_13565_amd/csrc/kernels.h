@@ -116,6 +116,15 @@ bool mfma_tile_split_fits(int phase_steps, int mp, const DeviceInfo& dev);
 hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases, int phase_steps, float* ws,
                                   const DeviceInfo& dev, hipStream_t stream, bool tiled = false);
 
+// The tile kernel with K in phases inside the workgroup, for passes whose activation rows do not
+// fit the LDS: no workspace, no second launch; plain product (no pick, no fused epilogue), passes
+// of four or eight rows.  Faster than the split in space where a workgroup has few tiles.
+bool mfma_tile_phased_can_run(const GemmArgs& a, const DeviceInfo& dev);
+hipError_t launch_mfma_tile_phased(const GemmArgs& a, const DeviceInfo& dev, hipStream_t stream, bool tiled);
+// Whether a call whose rows do not fit the LDS should take it: `split_available` says that the
+// split in space could run too (the caller gave a workspace).
+bool mfma_tile_phased_preferred(const GemmArgs& a, const DeviceInfo& dev, bool split_available);
+
 // Tile-major copy of the weights for the tile kernel (`tiled`: a.q / a.s are that copy): what a
 // wave instruction loads is contiguous.  Sizes in bytes; K % 128 == 0.
 size_t tile_repack_q_bytes(int64_t n, int64_t k);

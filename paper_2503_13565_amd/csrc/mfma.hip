@@ -706,6 +706,8 @@ hipError_t launch_mfma(const GemmArgs& a_in, const DeviceInfo& dev, float* split
     }();
     if (!tiled && !legacy && !general_only && mfma_tile_can_run(a_in, dev))
         return launch_mfma_tile(a_in, dev, parts_used, stream, false, epi);
+    if (!tiled && !legacy && !general_only && !epi && mfma_tile_phased_preferred(a_in, dev, splitk_ws != nullptr))
+        return launch_mfma_tile_phased(a_in, dev, stream, false);
     if (!mfma_can_run(a_in, dev, splitk_ws != nullptr))
         return hipErrorInvalidValue;
     GemmArgs a = a_in;

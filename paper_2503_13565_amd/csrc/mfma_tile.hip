@@ -426,6 +426,207 @@ __global__ __launch_bounds__((NW + 1) * 64) void mfma_tile_split_kernel(const ui
     mfma_tile_body<MP, NW, D, kTiled>(x, q, s, out, n, k, m, m0, ldx, ldy, parts, NoEpilogue{}, phase_steps);
 }
 
+// ---- Activation rows that do not fit the LDS whole: K in phases inside the workgroup ----------
+// (7B down projection from five rows, K = 28672 at any width.)  The split in space above needs a
+// workspace and a second launch that adds the partial products; for the few-tile shapes that have
+// this problem (a down projection has N / 16 tiles, about one per compute unit) that launch costs
+// a third of the product.  Here a workgroup keeps its tile's accumulators in registers and walks K
+// in phases of kPhaseSteps steps; the LDS holds the activation rows of two phases.  One workgroup
+// of eight compute waves per unit; a phase is eight items, one per wave.  A wave's share of a
+// phase's activation rows (chunk `tid` of each row) travels with the wave's weight item of that
+// phase: loaded right in front of it, D phases ahead, so that waiting for it waits for nothing
+// younger; it is written to the other LDS buffer at the end of the phase before, and one barrier
+// per phase both publishes that buffer and retires the one just read.  The ninth wave, as in the
+// kernel above, sums the eight partial tiles of a finished tile and stores them.
+constexpr int kPhaseSteps = 32;
+constexpr int kPhaseNW = 8;
+constexpr size_t phased_lds_bytes(int mp) { return (size_t)2 * kPhaseSteps * 256 * mp + (size_t)2 * kPhaseNW * 1024; }
+
+template <int MP, int D, bool kTiled>
+__global__ __launch_bounds__((kPhaseNW + 1) * 64) void mfma_tile_phased_kernel(
+    const uint16_t* __restrict__ x, const uint8_t* __restrict__ q, const uint8_t* __restrict__ s,
+    uint16_t* __restrict__ y, int n, int k, int m, int m0, int ldx, int ldy)
+{
+    constexpr int NW = kPhaseNW, P = kPhaseSteps;
+    constexpr int kXBuf = P * 16 * MP;                                  // 16-byte chunks of one LDS buffer
+    extern __shared__ __align__(16) uint8_t smem[];
+    u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);
+    f32x4_t* red = reinterpret_cast<f32x4_t*>(smem + (size_t)2 * kXBuf * 16);   // [2][NW][64]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int steps_all = k >> 7;
+    const int n_items_all = (steps_all + 3) >> 2;
+    const int phases = (steps_all + P - 1) / P;
+    const int nblk = k >> 5;
+    const int q_row_bytes = k >> 1;
+    const int n_tiles = (n + 15) >> 4;
+    const int G = gridDim.x, b = blockIdx.x;
+    const int pairs = (n_tiles - b + G - 1) / G * phases;               // (tile, phase) pairs of this workgroup
+    const int trips = (pairs + D - 1) / D * D;
+
+    if (wave == NW) {
+        // one barrier per phase, like the compute waves; a tile is complete after its last phase
+        const int m_valid = min(MP, m - m0);
+        lds_barrier();
+        int tile = b, ph = 0, done = 0;
+        for (int u = 0; u < trips; ++u) {
+            lds_barrier();
+            if (tile < n_tiles && ph == phases - 1) {
+                const f32x4_t* slot = red + (size_t)(done & 1) * NW * 64;
+                f32x4_t sum = slot[lane];
+#pragma unroll
+                for (int w = 1; w < NW; ++w)
+                    sum += slot[w * 64 + lane];
+                // lane (li, lg) holds rows 4 lg + r of the tile for activation row li
+                if (li < m_valid) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = tile * 16 + 4 * lg + r;
+                        if (row < n)
+                            y[(int64_t)(m0 + li) * ldy + row] = f32_to_bf16_rne(sum[r]);
+                    }
+                }
+                ++done;
+            }
+            if (++ph == phases) {
+                ph = 0;
+                tile += G;
+            }
+        }
+        return;
+    }
+
+    // (tile-major tensors hold whole tiles and whole items: rows past N and steps past K are there)
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(q), 0, kTiled ? n_tiles * 16 * q_row_bytes : n * q_row_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(s), 0, kTiled ? n_tiles * n_items_all * 256 : n * nblk, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(x), 0, ((m - 1) * ldx + k) * 2, 0x00020000);
+
+    struct Slot {
+        u32x4_t xl[MP];     // chunk `tid` of the phase of every activation row of the pass
+        u32x4_t q[4];
+        u32x4_t sc;
+    };
+    Slot buf[D];
+    // Always MP + 5 loads per pair; what does not exist (a pair past the workgroup's last, a step
+    // past K, an item past the last) reads nothing and returns zero.
+    int ld_tile = b, ld_ph = 0;
+    auto issue = [&](Slot& sl) {
+        const int live = (int)(ld_tile < n_tiles);
+        const int tile = ld_tile * live;
+        {
+            const int mk = -(live & (int)(ld_ph * P + (tid >> 4) < steps_all));
+            const int at = (ld_ph * (P * 16) + tid) * 16;
+#pragma unroll
+            for (int mm = 0; mm < MP; ++mm) {
+                const int msrc = min(m0 + mm, m - 1);                   // ragged M: repeat the last row
+                sl.xl[mm] = __builtin_amdgcn_raw_buffer_load_b128(rx, ((msrc * ldx * 2 + at) & mk) | (kOob & ~mk), 0, 0);
+            }
+        }
+        const int item = ld_ph * (P / 4) + wave;
+        const int have = live & (int)(item < n_items_all);
+        if constexpr (kTiled) {
+            const int vq = lane * 16;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int mk = -(have & (int)(item * 4 + u < steps_all));
+                sl.q[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rq, (vq & mk) | (kOob & ~mk), (((tile * steps_all + item * 4 + u) * 1024) & mk) | ((u * 16) & ~mk), 2);
+            }
+            const int mk = -have;
+            sl.sc = __builtin_amdgcn_raw_buffer_load_b128(rs, ((li * 16) & mk) | (kOob & ~mk),
+                                                          ((tile * n_items_all + item) * 256) & mk, 0);
+        } else {
+            const int row = min(tile * 16 + li, n - 1);                 // ragged N: repeat the last row
+            const int vq = row * q_row_bytes + lg * 16;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int mk = -(have & (int)(item * 4 + u < steps_all));
+                sl.q[u] = __builtin_amdgcn_raw_buffer_load_b128(rq, (vq & mk) | (kOob & ~mk),
+                                                                (((item * 4 + u) * 64) & mk) | ((u * 16) & ~mk), 0);
+            }
+            const int mk = -have;
+            sl.sc = __builtin_amdgcn_raw_buffer_load_b128(rs, ((row * nblk) & mk) | (kOob & ~mk), (item * 16) & mk, 0);
+        }
+        const int wrap = (int)(ld_ph + 1 == phases);
+        ld_ph = (ld_ph + 1) * (1 - wrap);
+        ld_tile += G * wrap;
+    };
+    // chunk kc = 16 T + 4 g + j of row mm goes to slot (16 T + 4 j + g) * MP + (mm ^ (kc % MP)), as above
+    auto x_store = [&](const Slot& sl, u32x4_t* xb) {
+        const int Tl = tid >> 4, cs = tid & 15, g = cs >> 2, j = cs & 3;
+#pragma unroll
+        for (int mm = 0; mm < MP; ++mm)
+            xb[(Tl * 16 + 4 * j + g) * MP + (mm ^ (cs & (MP - 1)))] = sl.xl[mm];
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        issue(buf[d]);
+        __builtin_amdgcn_sched_barrier(0);                              // keep the slots' loads in issue order
+    }
+    x_store(buf[0], xs);
+    lds_barrier();
+
+    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};       // two chains: even and odd j
+    const int col = li & (MP - 1);
+    int c_tile = b, c_ph = 0, done = 0;
+    for (int u0 = 0; u0 < trips; u0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const Slot& sl = buf[d];
+            const u32x4_t* xb_now = xs + (size_t)((u0 + d) & 1) * kXBuf;
+            const int item = c_ph * (P / 4) + wave;
+            const int have = (int)(c_tile < n_tiles) & (int)(item < n_items_all);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int Tl = wave * 4 + u;
+                const uint32_t mk = (uint32_t)-(have & (int)(item * 4 + u < steps_all));
+                const uint32_t sbyte = (((sl.sc[u] >> (8 * lg)) & 0xFFu) & mk) | (0x7Fu & ~mk);
+                const float scl = __uint_as_float(sbyte << 23);
+                u32x4_t xb[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    xb[j] = xb_now[(Tl * 16 + 4 * j + lg) * MP + (col ^ ((4 * lg + j) & (MP - 1)))];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t qd = sl.q[u][j];
+                    u32x4_t w;
+                    w[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 0));
+                    w[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 1));
+                    w[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 2));
+                    w[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(qd, scl, 3));
+                    if (j & 1)
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
+                                                                       __builtin_bit_cast(bf16x8_t, xb[j]), acc1, 0, 0, 0);
+                    else
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w),
+                                                                       __builtin_bit_cast(bf16x8_t, xb[j]), acc0, 0, 0, 0);
+                }
+            }
+            if (c_tile < n_tiles && c_ph == phases - 1) {
+                // end of the tile: leave the partial tile for the ninth wave
+                f32x4_t* slot = red + (size_t)(done & 1) * NW * 64;
+                slot[wave * 64 + lane] = acc0 + acc1;
+                acc0 = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                acc1 = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                ++done;
+            }
+            if (++c_ph == phases) {
+                c_ph = 0;
+                c_tile += G;
+            }
+            // the next phase's activation rows go to the buffer that the phase before this one read
+            x_store(buf[(d + 1) % D], xs + (size_t)((u0 + d + 1) & 1) * kXBuf);
+            issue(buf[d]);
+            lds_barrier();
+        }
+    }
+}
+
 // Make the tile-major copy: one thread per 16 bytes of either output.  q_t unit (tile, T, lane =
 // i + 16 g) is block 4T + g of row 16 tile + i; s_t unit (tile, item, i) holds the scale bytes of
 // blocks 16 item .. 16 item + 15 of that row.  Rows past N get zero nibbles, blocks past K and rows
@@ -585,6 +786,66 @@ hipError_t launch_mfma_tile_split(const GemmArgs& a, int m0, int mp, int phases,
     return mp == 16  ? launch_split_pass<16, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
            : mp == 8 ? launch_split_pass<8, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream)
                      : launch_split_pass<4, kTileNW, 3, false>(a, m0, phases, phase_steps, ws, blocks, lds, dev, stream);
+}
+
+// K in phases inside the workgroup: any K % 128 == 0, no workspace, plain product only.  Passes of
+// four or eight rows (more rows take several passes).
+bool mfma_tile_phased_can_run(const GemmArgs& a, const DeviceInfo& dev)
+{
+    if (a.k % 128 != 0 || a.m < 1 || a.part_val != nullptr || a.y == nullptr)
+        return false;
+    if (a.ldx > 0x7FFFFFFF || a.ldy > 0x7FFFFFFF)
+        return false;
+    if (((int64_t)(a.m - 1) * a.ldx + a.k) * 2 > 0x7FFFFFF0LL)          // the activation rows behind one 32-bit offset
+        return false;
+    return phased_lds_bytes(a.m > 4 ? 8 : 4) <= (size_t)dev.lds_bytes;
+}
+
+bool mfma_tile_phased_preferred(const GemmArgs& a, const DeviceInfo& dev, bool split_available)
+{
+    static const int env = [] { const char* e = knob("MXFP4_TILE_PHASED"); return e ? atoi(e) : -1; }();   // measurement only
+    if (env == 0 || a.m > 8 || !mfma_tile_phased_can_run(a, dev))
+        return false;
+    if (!split_available || env == 1)
+        return true;
+    // Against the split in space (measured at 8 rows, tile-major / row-major): one tile per workgroup
+    // 11.3 against 11.7 us / 12.4 against 12.8 (7B down projection); two tiles and seven phases (70B
+    // down projection) 34.5 against 27.8 / 42.4 against 34.5, because every tile fetches the rows again.
+    return (a.n + 15) / 16 <= dev.cus;
+}
+
+template <int MP, int D, bool kTiled>
+hipError_t launch_phased_pass(const GemmArgs& a, int m0, int blocks, const DeviceInfo& dev, hipStream_t stream)
+{
+    auto kern = mfma_tile_phased_kernel<MP, D, kTiled>;
+    static LdsLimit lds_limit;                      // of this kernel instance
+    if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), dev.lds_bytes); e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3((kPhaseNW + 1) * 64), phased_lds_bytes(MP), stream, a.x, a.q, a.s,
+                       a.y, a.n, a.k, a.m, m0, (int)a.ldx, (int)a.ldy);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_tile_phased(const GemmArgs& a, const DeviceInfo& dev, hipStream_t stream, bool tiled)
+{
+    if (!mfma_tile_phased_can_run(a, dev))
+        return hipErrorInvalidValue;
+    const int n_tiles = (a.n + 15) / 16;
+    const int blocks = n_tiles < dev.cus ? n_tiles : dev.cus;
+    for (int m0 = 0; m0 < a.m;) {
+        const int mp = a.m - m0 > 4 ? 8 : 4;
+        hipError_t e;
+        if (mp == 8)
+            e = tiled ? launch_phased_pass<8, 2, true>(a, m0, blocks, dev, stream)
+                      : launch_phased_pass<8, 2, false>(a, m0, blocks, dev, stream);
+        else
+            e = tiled ? launch_phased_pass<4, 3, true>(a, m0, blocks, dev, stream)
+                      : launch_phased_pass<4, 3, false>(a, m0, blocks, dev, stream);
+        if (e != hipSuccess)
+            return e;
+        m0 += mp;
+    }
+    return hipSuccess;
 }
 
 // The 8-bit (a.q = q8 [N, K]) and 6-bit (a.q = q6) draft formats on the tile kernel; shapes as

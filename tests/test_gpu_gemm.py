@@ -145,11 +145,13 @@ def test_mfma_needs_k_multiple_of_128():
 
 
 @pytest.mark.parametrize("n,k,m", [(130, 11008, 8), (130, 11008, 16), (75, 11008, 20), (40, 28672, 3),
-                                   (40, 28672, 16), (100, 8192, 32), (20, 65536, 5), (4200, 11008, 9)])
+                                   (40, 28672, 16), (100, 8192, 32), (20, 65536, 5), (4200, 11008, 9),
+                                   (4200, 11008, 7), (9000, 5120 * 3, 6)])
 def test_mfma_split_k(n, k, m):
-    """K cut into phases: inside the kernel (running sums in LDS) when there is no workspace, across
-    workgroups through the workspace when there is; rows in passes of unequal width; several tiles
-    per workgroup.  The fused argmax always has its workspace and so takes the second form."""
+    """K cut into phases: inside the kernel when there is no workspace (up to eight rows: accumulators in
+    registers, the activation rows of two phases in LDS; wider passes: running sums in LDS), across
+    workgroups through the workspace when there is (or the first form again where a workgroup has one
+    tile); rows in passes of unequal width; several tiles per workgroup.  The fused argmax always has its workspace and so takes the second form."""
     assert binding.mxfp4_woq_gemm_workspace_bytes(m, n, k) > 0
     w = synth.weights_gaussian_outliers(n, k, seed=31 + n + k)
     x = synth.activations_outlier_channels(m, k, seed=32 + m)

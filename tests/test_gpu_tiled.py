@@ -45,7 +45,7 @@ def test_tile_repack_is_the_stated_permutation(n, k):
 
 
 @pytest.mark.parametrize("n,k", [(16, 128), (17, 256), (250, 11008), (1000, 4096), (48, 8192), (2050, 2048),
-                                 (31, 12288), (4100, 11008), (530, 28672)])
+                                 (31, 12288), (4100, 11008), (530, 28672), (8300, 11008)])
 @pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 16, 17, 33])
 def test_tiled_product_edge_shapes(n, k, m):
     w = synth.weights_student_t(n, k, seed=7000 + n + k)
@@ -63,12 +63,19 @@ def test_tiled_product_edge_shapes(n, k, m):
     slots = -(-tiles // min(tiles, 256))
     decode = m <= 2 and m * k * 2 + slots * (1088 * m + 4) + 512 <= 160 * 1024
     if not decode and (k + 511) // 512 * 1024 * width + 8192 > 160 * 1024:
-        # no workspace: refused; with one, K is split over grid rows
-        with pytest.raises(binding.Mxfp4Error) as e:
-            binding.mxfp4_woq_gemm_tiled(xg, tw)
-        assert e.value.code == 6
         assert ws_bytes > 0
         ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=DEV)
+        if m > 8:
+            # no workspace: refused; with one, K is split over grid rows
+            with pytest.raises(binding.Mxfp4Error) as e:
+                binding.mxfp4_woq_gemm_tiled(xg, tw)
+            assert e.value.code == 6
+        else:
+            # up to eight rows walk K in phases inside the workgroup, no workspace needed; with one, the
+            # same kernel where a workgroup has few tiles, else K split over grid rows
+            y0 = binding.mxfp4_woq_gemm_tiled(xg, tw)
+            torch.cuda.synchronize()
+            assert_gemm_close(y0, y_ref, a_ref, "tiled, K in phases, N=%d K=%d M=%d" % (n, k, m))
         y = binding.mxfp4_woq_gemm_tiled(xg, tw, workspace=ws)
     else:
         y = binding.mxfp4_woq_gemm_tiled(xg, tw)
@@ -119,12 +126,13 @@ def test_tiled_refuses_what_does_not_fit_and_bad_k():
     q = torch.zeros((64, 11008 // 2), dtype=torch.uint8, device=DEV)
     s = torch.zeros((64, 11008 // 32), dtype=torch.uint8, device=DEV)
     tw = binding.mxfp4_tile_repack(q, s)
-    x = torch.zeros((8, 11008), dtype=torch.bfloat16, device=DEV)      # 8 x 11008 BF16 = 176 KB
+    x = torch.zeros((16, 11008), dtype=torch.bfloat16, device=DEV)     # 16 x 11008 BF16 = 352 KB
     with pytest.raises(binding.Mxfp4Error) as e:
         binding.mxfp4_woq_gemm_tiled(x, tw)
     assert e.value.code == 6
-    y = binding.mxfp4_woq_gemm_tiled(x[:4], tw)
-    assert not y.float().abs().sum().item()
+    for rows in (4, 8):                                                 # whole in the LDS; K in phases
+        y = binding.mxfp4_woq_gemm_tiled(x[:rows], tw)
+        assert not y.float().abs().sum().item()
     q96 = torch.zeros((16, 48), dtype=torch.uint8, device=DEV)
     s96 = torch.zeros((16, 3), dtype=torch.uint8, device=DEV)
     with pytest.raises(binding.Mxfp4Error) as e:
