@@ -618,8 +618,12 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
                           : launch_one<MT, 1, 4, 2, 16, false>(a, m0, blocks, lds, stream, epi);
         break;
     case 6:
+        // 8 waves with three steps in flight (24 KiB per unit): a 7B down projection has one row per wave
+        // of the 16-wave form, whose six steps then pass two at a time.  Measured 6.32 against 6.75 us
+        // (4096 x 11008), 6.86 / 6.96 (4096 x 12288), 10.31 / 10.56 (8192 x 11008); six in flight, or two
+        // rows per step, are slower.  The same choice loses at 4 steps (K = 8192) and at 14 (K = 28672).
         if constexpr (MT == 1)
-            return launch_one<MT, 1, 6, 2, 16, true>(a, m0, blocks, lds, stream, epi);
+            return launch_one<MT, 1, 6, 3, 8, true>(a, m0, blocks, lds, stream, epi);
         break;
     case 8:
         if constexpr (MT == 1)
@@ -1110,7 +1114,8 @@ __global__ __launch_bounds__(1024) void gemv_multi_lds_kernel(const MultiArgs a)
 
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
 bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
-int waves_for(int steps2, int mt) { return wide_group(steps2, mt) ? 8 : 16; }
+// (the 4-bit six-step instance runs 8 waves of one row: see launch_steps)
+int waves_for(int steps2, int mt, int bits = 4) { return wide_group(steps2, mt) || (bits == 4 && steps2 == 6 && mt == 1) ? 8 : 16; }
 int rows_per_step(int steps2, int mt) { return wide_group(steps2, mt) ? 2 : 1; }
 
 }  // namespace
@@ -1218,7 +1223,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     // one workgroup per compute unit; the argmax form writes one partial winner per workgroup, so
     // every pass must use the same number of workgroups: the count of the narrowest pass
     auto blocks_for = [&](int mt) {
-        const int r = rows_per_step(steps2, mt), nw = waves_for(steps2, mt);
+        const int r = rows_per_step(steps2, mt), nw = waves_for(steps2, mt, bits);
         const int n_groups = (a.n + r - 1) / r;
         return min(dev.cus, (n_groups + nw - 1) / nw);
     };
