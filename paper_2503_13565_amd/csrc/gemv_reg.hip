@@ -6,7 +6,7 @@
 //   - A lane always works on the same scale blocks of a row (block t*64 + lane in step t), so
 //     its 32 activations per step never change.  They are staged through LDS once (one global
 //     read per workgroup) and then live in registers: the streaming loop has no LDS reads.
-//   - One workgroup per compute unit, 8 or 16 waves.  The rows of a workgroup are handed to its
+//   - One workgroup per compute unit, 8, 12 or 16 waves.  The rows of a workgroup are handed to its
 //     waves through an LDS counter, one row at a time: the memory system serves the waves of a
 //     compute unit very unevenly (the first data reaches them 2 to 6 us after the launch), and
 //     with a fixed share per wave the slowest wave set the kernel time.
@@ -595,7 +595,7 @@ hipError_t launch_one(const GemmArgs& g, int m0, int blocks, size_t lds, hipStre
 
 template <int MT>
 hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int blocks, size_t lds,
-                        hipStream_t stream, const Epilogue* epi)
+                        hipStream_t stream, const Epilogue* epi, int nw)
 {
     // 16 waves hold at most 128 registers each: enough for four steps of one activation row.
     // From six steps on (K > 8192) the activations stay in the LDS copy: registers are free
@@ -606,16 +606,20 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
     // every such instance.)
     switch (steps2) {
     case 2:
-        if constexpr (MT == 1)
+        // (`nw` is waves_for's answer: 12 waves where a compute unit has at most 40 rows)
+        if constexpr (MT == 1) {
+            if (nw == 12)
+                return ragged ? launch_one<MT, 1, 2, 2, 12, true>(a, m0, blocks, lds, stream, epi)
+                              : launch_one<MT, 1, 2, 2, 12, false>(a, m0, blocks, lds, stream, epi);
             return ragged ? launch_one<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream, epi)
                           : launch_one<MT, 1, 2, 2, 16, false>(a, m0, blocks, lds, stream, epi);
-        else                                       // two activation rows need more registers: 8 waves
+        } else                                       // two activation rows need more registers: 8 waves
             return ragged ? launch_one<MT, 2, 2, 2, 8, true>(a, m0, blocks, lds, stream, epi)
                           : launch_one<MT, 2, 2, 2, 8, false>(a, m0, blocks, lds, stream, epi);
     case 4:
         if constexpr (MT == 1)
-            return ragged ? launch_one<MT, 1, 4, 2, 16, true>(a, m0, blocks, lds, stream, epi)
-                          : launch_one<MT, 1, 4, 2, 16, false>(a, m0, blocks, lds, stream, epi);
+            return ragged ? launch_one<MT, 1, 4, 2, 12, true>(a, m0, blocks, lds, stream, epi)
+                          : launch_one<MT, 1, 4, 2, 12, false>(a, m0, blocks, lds, stream, epi);
         break;
     case 6:
         // 8 waves with three steps in flight (24 KiB per unit): a 7B down projection has one row per wave
@@ -1114,8 +1118,26 @@ __global__ __launch_bounds__(1024) void gemv_multi_lds_kernel(const MultiArgs a)
 
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
 bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
-// (the 4-bit six-step instance runs 8 waves of one row: see launch_steps)
-int waves_for(int steps2, int mt, int bits = 4) { return wide_group(steps2, mt) || (bits == 4 && steps2 == 6 && mt == 1) ? 8 : 16; }
+// Waves per workgroup of the instance that launch_steps picks.  The 4-bit form at one activation row,
+// from a sweep of 4 to 16 waves per step count (us per launch, 16 waves -> the choice): two steps
+// (K <= 4096) 12 waves while a compute unit has at most 40 rows -- N = 2048: 3.81 -> 3.53, 4096: 4.52 ->
+// 3.84, 8192: 5.71 -> 5.52, 10240: 6.21 -> 5.98, but 12288: 7.07 -> 7.20 and no gain beyond; four steps
+// (K <= 8192) 12 waves at any N -- 8192 x 8192 8.14 -> 7.65, 10240 x 8192 9.43 -> 9.27, 57344 x 8192
+// 39.9 -> 38.9; six steps 8 waves (see launch_steps); from eight steps on 16.
+int waves_for(int steps2, int mt, int bits, int n, int cus)
+{
+    if (wide_group(steps2, mt))
+        return 8;
+    if (bits == 4 && mt == 1) {
+        if (steps2 == 2)
+            return n <= 40 * cus ? 12 : 16;
+        if (steps2 == 4)
+            return 12;
+        if (steps2 == 6)
+            return 8;
+    }
+    return 16;
+}
 int rows_per_step(int steps2, int mt) { return wide_group(steps2, mt) ? 2 : 1; }
 
 }  // namespace
@@ -1223,7 +1245,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     // one workgroup per compute unit; the argmax form writes one partial winner per workgroup, so
     // every pass must use the same number of workgroups: the count of the narrowest pass
     auto blocks_for = [&](int mt) {
-        const int r = rows_per_step(steps2, mt), nw = waves_for(steps2, mt, bits);
+        const int r = rows_per_step(steps2, mt), nw = waves_for(steps2, mt, bits, a.n, dev.cus);
         const int n_groups = (a.n + r - 1) / r;
         return min(dev.cus, (n_groups + nw - 1) / nw);
     };
@@ -1238,14 +1260,16 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
                 : bits == 8  ? launch_steps6<2, 8>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                 : bits == 22 ? launch_steps6<2, 22>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                 : bits == 24 ? launch_steps6<2, 24>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
-                            : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi);
+                            : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi,
+                                              waves_for(steps2, 2, bits, a.n, dev.cus));
             m0 += 2;
         } else {
             e = bits == 6    ? launch_steps6<1, 6>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                 : bits == 8  ? launch_steps6<1, 8>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                 : bits == 22 ? launch_steps6<1, 22>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                 : bits == 24 ? launch_steps6<1, 24>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
-                            : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi);
+                            : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi,
+                                              waves_for(steps2, 1, bits, a.n, dev.cus));
             m0 += 1;
         }
         if (e != hipSuccess)
