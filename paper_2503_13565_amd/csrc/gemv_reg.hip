@@ -613,9 +613,9 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
                               : launch_one<MT, 1, 2, 2, 12, false>(a, m0, blocks, lds, stream, epi);
             return ragged ? launch_one<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream, epi)
                           : launch_one<MT, 1, 2, 2, 16, false>(a, m0, blocks, lds, stream, epi);
-        } else                                       // two activation rows need more registers: 8 waves
-            return ragged ? launch_one<MT, 2, 2, 2, 8, true>(a, m0, blocks, lds, stream, epi)
-                          : launch_one<MT, 2, 2, 2, 8, false>(a, m0, blocks, lds, stream, epi);
+        } else                                       // two activation rows need more registers: 12 waves
+            return ragged ? launch_one<MT, 1, 2, 2, 12, true>(a, m0, blocks, lds, stream, epi)
+                          : launch_one<MT, 1, 2, 2, 12, false>(a, m0, blocks, lds, stream, epi);
     case 4:
         if constexpr (MT == 1)
             return ragged ? launch_one<MT, 1, 4, 2, 12, true>(a, m0, blocks, lds, stream, epi)
@@ -657,12 +657,12 @@ hipError_t launch_steps6(const GemmArgs& a, int m0, int steps2, int blocks, size
     switch (steps2) {
     case 2:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 2, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 2, 2, 12, true, kBits>(a, m0, blocks, lds, stream);
         else
             return launch_one6<MT, 2, 2, 2, 8, true, kBits>(a, m0, blocks, lds, stream);
     case 4:
         if constexpr (MT == 1)
-            return launch_one6<MT, 1, 4, 2, 16, true, kBits>(a, m0, blocks, lds, stream);
+            return launch_one6<MT, 1, 4, 2, 12, true, kBits>(a, m0, blocks, lds, stream);
         break;
     case 6:
         if constexpr (MT == 1)
@@ -1117,7 +1117,8 @@ __global__ __launch_bounds__(1024) void gemv_multi_lds_kernel(const MultiArgs a)
 }
 
 int even_steps(int k) { return ((((k >> 5) + 63) >> 6) + 1) & ~1; }
-bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
+// two activation rows in the 6- and 8-bit forms: two weight rows per wave step, 8 waves
+bool wide_group(int steps2, int mt, int bits) { return mt == 2 && steps2 == 2 && bits != 4; }
 // Waves per workgroup of the instance that launch_steps picks.  The 4-bit form at one activation row,
 // from a sweep of 4 to 16 waves per step count (us per launch, 16 waves -> the choice): two steps
 // (K <= 4096) 12 waves while a compute unit has at most 40 rows -- N = 2048: 3.81 -> 3.53, 4096: 4.52 ->
@@ -1126,8 +1127,12 @@ bool wide_group(int steps2, int mt) { return mt == 2 && steps2 == 2; }
 // 39.9 -> 38.9; six steps 8 waves (see launch_steps); from eight steps on 16.
 int waves_for(int steps2, int mt, int bits, int n, int cus)
 {
-    if (wide_group(steps2, mt))
+    if (wide_group(steps2, mt, bits))
         return 8;
+    // two activation rows, 4-bit: 12 waves of one weight row against the 8 waves of two rows it ran before --
+    // 4096 x 4096 4.70 -> 4.31 us, 12288 x 4096 8.16 -> 7.81, 22016 x 4096 11.80 -> 11.13, 32000 x 4096 15.63 -> 14.71
+    if (bits == 4 && mt == 2)
+        return 12;
     if (bits == 4 && mt == 1) {
         if (steps2 == 2)
             return n <= 40 * cus ? 12 : 16;
@@ -1136,9 +1141,13 @@ int waves_for(int steps2, int mt, int bits, int n, int cus)
         if (steps2 == 6)
             return 8;
     }
+    // the 6- and 8-bit forms: 12 waves up to four steps at any N (E5M2 / E3M2, 16 -> 12 waves: 4096 x 4096
+    // 5.50 -> 5.24 / 4.85 -> 4.63 us, 22016 x 4096 16.8 -> 16.6 / 13.4 -> 13.3, 8192 x 8192 13.0 -> 12.9 / 10.8 -> 10.6)
+    if (bits != 4 && mt == 1 && steps2 <= 4)
+        return 12;
     return 16;
 }
-int rows_per_step(int steps2, int mt) { return wide_group(steps2, mt) ? 2 : 1; }
+int rows_per_step(int steps2, int mt, int bits) { return wide_group(steps2, mt, bits) ? 2 : 1; }
 
 }  // namespace
 
@@ -1245,7 +1254,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     // one workgroup per compute unit; the argmax form writes one partial winner per workgroup, so
     // every pass must use the same number of workgroups: the count of the narrowest pass
     auto blocks_for = [&](int mt) {
-        const int r = rows_per_step(steps2, mt), nw = waves_for(steps2, mt, bits, a.n, dev.cus);
+        const int r = rows_per_step(steps2, mt, bits), nw = waves_for(steps2, mt, bits, a.n, dev.cus);
         const int n_groups = (a.n + r - 1) / r;
         return min(dev.cus, (n_groups + nw - 1) / nw);
     };
