@@ -34,8 +34,8 @@ struct TPos {
 };
 
 // kRegs: the wave's activations in registers (SPW steps of 16 dwords per row), else from LDS.
-template <int MT, int SPW, bool kRegs>
-__global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t* __restrict__ x,
+template <int MT, int SPW, bool kRegs, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_tile_kernel(const uint16_t* __restrict__ x,
                                                                  const uint8_t* __restrict__ qt,
                                                                  const uint8_t* __restrict__ st, void* out, int n,
                                                                  int k, int m, int ldx, int ldy, int parts,
@@ -58,13 +58,13 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
     const int nsteps = min(s_begin + spw, steps) - s_begin;          // 0 for the waves beyond K
     // waves that count themselves in at a tile's end: in the register form all of them (those beyond
     // K add zeros), else those that hold steps
-    const int active = kRegs ? kWavesT : (steps + spw - 1) / spw;
+    const int active = kRegs ? NW : (steps + spw - 1) / spw;
     const bool argmax = parts > 0;
 
     u32x4_t* xs = reinterpret_cast<u32x4_t*>(smem);                  // [MT][K / 8] chunks, natural order
     float* part = reinterpret_cast<float*>(smem + (size_t)MT * k * 2);      // [tile][MT][row 16][wave 16]
     const int tiles_cap = (n_tiles + G - 1) / G;
-    float* fin = part + (size_t)tiles_cap * kWavesT * MT * 16;              // finished outputs [tile][MT][16]
+    float* fin = part + (size_t)tiles_cap * NW * MT * 16;              // finished outputs [tile][MT][16]
     int* cnt = reinterpret_cast<int*>(fin + (size_t)tiles_cap * MT * 16);
 
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(qt), 0,
@@ -114,14 +114,14 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
             advance(load);
         }
     }
-    for (int c = tid; c < xchunks; c += kWavesT * 64) {
+    for (int c = tid; c < xchunks; c += NW * 64) {
 #pragma unroll
         for (int r = 0; r < MT; ++r) {
             const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(x + (int64_t)min(r, m - 1) * ldx);
             xs[r * xchunks + c] = xp[c];
         }
     }
-    for (int t = tid; t < tiles_cap; t += kWavesT * 64)
+    for (int t = tid; t < tiles_cap; t += NW * 64)
         cnt[t] = 0;
     lds_barrier();
 
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
             v += dpp_f32<0xB1>(v);                   // quad_perm [1,0,3,2]
             v += dpp_f32<0x4E>(v);                   // quad_perm [2,3,0,1]: the row's sum in its four lanes
             if (g == 0)
-                part[((size_t)(j * MT + r) * 16 + i) * kWavesT + wave] = v;
+                part[((size_t)(j * MT + r) * 16 + i) * NW + wave] = v;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         int arrived = 0;
@@ -180,14 +180,15 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
         if (lane < 16) {
 #pragma unroll
             for (int r = 0; r < MT; ++r) {
-                const f32x4_t* pp = reinterpret_cast<const f32x4_t*>(part + ((size_t)(j * MT + r) * 16 + lane) * kWavesT);
-                const f32x4_t p0 = pp[0], p1 = pp[1], p2 = pp[2], p3 = pp[3];
-                const float pv[16] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3],
-                                      p2[0], p2[1], p2[2], p2[3], p3[0], p3[1], p3[2], p3[3]};
+                const f32x4_t* pp = reinterpret_cast<const f32x4_t*>(part + ((size_t)(j * MT + r) * 16 + lane) * NW);
+                f32x4_t pq[NW / 4];
+#pragma unroll
+                for (int c = 0; c < NW / 4; ++c)
+                    pq[c] = pp[c];
                 float v = 0.f;
 #pragma unroll
-                for (int w = 0; w < kWavesT; ++w)
-                    v += w < active ? pv[w] : 0.f;      // a wave that holds no steps never wrote its slot
+                for (int w = 0; w < NW; ++w)
+                    v += w < active ? pq[w >> 2][w & 3] : 0.f;      // a wave that holds no steps never wrote its slot
                 if (argmax) {
                     if (row < n && (v > best_val[r] || (v == best_val[r] && row < best_idx[r]))) {
                         best_val[r] = v;
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
     if (!argmax) {
         // every tile of the workgroup has been finished by one of its waves: store them all
         __syncthreads();
-        for (int o = tid; o < tiles_wg * MT * 16; o += kWavesT * 64) {
+        for (int o = tid; o < tiles_wg * MT * 16; o += NW * 64) {
             const int j = o / (MT * 16), r = (o >> 4) % MT, row = (b + j * G) * 16 + (o & 15);
             if (row < n)
                 static_cast<uint16_t*>(out)[(int64_t)r * ldy + row] = f32_to_bf16_rne(fin[o]);
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
         }
         __syncthreads();
         float* wval = reinterpret_cast<float*>(smem);
-        int* widx = reinterpret_cast<int*>(smem) + kWavesT * MT;
+        int* widx = reinterpret_cast<int*>(smem) + NW * MT;
         if (lane == 0) {
 #pragma unroll
             for (int r = 0; r < MT; ++r) {
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
         if (tid < MT && tid < m) {
             float bv = wval[tid];
             int bi = widx[tid];
-            for (int w = 1; w < kWavesT; ++w) {
+            for (int w = 1; w < NW; ++w) {
                 const float v = wval[w * MT + tid];
                 const int ix = widx[w * MT + tid];
                 if (v > bv || (v == bv && ix < bi)) {
@@ -336,11 +337,11 @@ __global__ __launch_bounds__(kWavesT * 64) void gemv_tile_kernel(const uint16_t*
     }
 }
 
-size_t gemv_tile_lds(int mt, int n, int k, int blocks)
+size_t gemv_tile_lds(int mt, int n, int k, int blocks, int nw = kWavesT)
 {
     const int n_tiles = (n + 15) / 16;
     const int tiles_cap = (n_tiles + blocks - 1) / blocks;
-    return (size_t)mt * k * 2 + (size_t)tiles_cap * (kWavesT * mt * 16 * 4 + mt * 64 + 4);
+    return (size_t)mt * k * 2 + (size_t)tiles_cap * (nw * mt * 16 * 4 + mt * 64 + 4);
 }
 
 int gemv_tile_blocks(int n, const DeviceInfo& dev)
@@ -349,16 +350,16 @@ int gemv_tile_blocks(int n, const DeviceInfo& dev)
     return n_tiles < dev.cus ? n_tiles : dev.cus;
 }
 
-template <int MT, int SPW, bool kRegs>
+template <int MT, int SPW, bool kRegs, int NW = kWavesT>
 hipError_t launch_k(const GemmArgs& a, int blocks, size_t lds, int spw, int max_lds, hipStream_t stream)
 {
-    auto kern = gemv_tile_kernel<MT, SPW, kRegs>;
+    auto kern = gemv_tile_kernel<MT, SPW, kRegs, NW>;
     static LdsLimit lds_limit;                      // of this kernel instance
     if (lds > 64 * 1024)
         if (hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), max_lds); e != hipSuccess)
             return e;
     const bool argmax = a.part_val != nullptr;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(kWavesT * 64), lds, stream, a.x, a.q, a.s,
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a.x, a.q, a.s,
                        argmax ? static_cast<void*>(a.part_val) : static_cast<void*>(a.y), a.n, a.k, a.m, (int)a.ldx,
                        (int)a.ldy, argmax ? a.parts : 0, spw);
     return hipGetLastError();
@@ -367,6 +368,13 @@ hipError_t launch_k(const GemmArgs& a, int blocks, size_t lds, int spw, int max_
 template <int MT>
 hipError_t launch_mt(const GemmArgs& a, int blocks, size_t lds, int max_lds, hipStream_t stream)
 {
+    // K of 61 to 72 steps (K = 8192): 12 waves of six steps in registers, 9.94 -> 9.67 us on 8192 x 8192 and
+    // 47.8 -> 44.3 on 57344 x 8192 against 16 waves of four; at K = 4096 16 waves stay ahead of 12 and 8
+    // (7.4 / 7.8 / 8.9 us on the 7B qkv projection).
+    if constexpr (MT == 1) {
+        if ((a.k / 128 + 11) / 12 == 6)
+            return launch_k<MT, 6, true, 12>(a, blocks, lds, 6, max_lds, stream);
+    }
     const int spw = (a.k / 128 + kWavesT - 1) / kWavesT;
     switch (spw) {
     case 1:
