@@ -30,8 +30,8 @@ METRIC = "MXFP4 WOQ GEMV effective HBM GB/s (% peak) at M=1; us per 7B-shaped de
 HBM_PEAK_GBPS = 8000.0
 DTYPE = "bf16 x mxfp4 (e2m1 + e8m0 per 32) -> f32 accumulate, bf16 out"
 STEP_LINEARS = ("qkv", "o", "gate_up", "down")
-DOMINANT = ("qkv", "gate_up", "lm_head")      # the o projection (16 rows per compute unit) runs the 12-wave instance
-DOMINANT_KERNEL = "mxfp4::(anonymous namespace)::gemv_reg_kernel<1, 1, 2, 2, 16, false>"
+DOMINANT = ("qkv", "gate_up", "lm_head")      # two workgroups of 8 waves per unit; the o projection (16 rows per unit) runs the 12-wave instance
+DOMINANT_KERNEL = "mxfp4::(anonymous namespace)::gemv_reg_kernel<1, 1, 2, 2, 8, false>"
 
 
 def algorithmic_bytes(m: int, n: int, k: int) -> float:

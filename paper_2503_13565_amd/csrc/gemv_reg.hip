@@ -606,8 +606,12 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
     // every such instance.)
     switch (steps2) {
     case 2:
-        // (`nw` is waves_for's answer: 12 waves where a compute unit has at most 40 rows)
+        // (`nw` is waves_for's answer: 12 waves where a compute unit has at most 40 rows, beyond that two
+        // workgroups of 8 per unit, or one of 16 when the call also has passes of two rows)
         if constexpr (MT == 1) {
+            if (nw == 8)
+                return ragged ? launch_one<MT, 1, 2, 2, 8, true>(a, m0, blocks, lds, stream, epi)
+                              : launch_one<MT, 1, 2, 2, 8, false>(a, m0, blocks, lds, stream, epi);
             if (nw == 12)
                 return ragged ? launch_one<MT, 1, 2, 2, 12, true>(a, m0, blocks, lds, stream, epi)
                               : launch_one<MT, 1, 2, 2, 12, false>(a, m0, blocks, lds, stream, epi);
@@ -1125,8 +1129,18 @@ bool wide_group(int steps2, int mt, int bits) { return mt == 2 && steps2 == 2 &&
 // 3.84, 8192: 5.71 -> 5.52, 10240: 6.21 -> 5.98, but 12288: 7.07 -> 7.20 and no gain beyond; four steps
 // (K <= 8192) 12 waves at any N -- 8192 x 8192 8.14 -> 7.65, 10240 x 8192 9.43 -> 9.27, 57344 x 8192
 // 39.9 -> 38.9; six steps 8 waves (see launch_steps); from eight steps on 16.
-int waves_for(int steps2, int mt, int bits, int n, int cus)
+// `alone`: the call has no passes of two rows (whose grid every pass must share).
+bool two_workgroups(int steps2, int mt, int bits, int n, int cus, bool alone)
 {
+    // K <= 4096, one row, more than 40 rows per unit: two workgroups of 8 waves per compute unit against
+    // one of 16 -- qkv 7.10 -> 6.89 us, gate+up 10.19 -> 9.96, LM head 13.30 -> 13.06 (two of 12: 7.10,
+    // 9.92, 13.04; two or three of 6: slower)
+    return alone && bits == 4 && mt == 1 && steps2 == 2 && n > 40 * cus;
+}
+int waves_for(int steps2, int mt, int bits, int n, int cus, bool alone)
+{
+    if (two_workgroups(steps2, mt, bits, n, cus, alone))
+        return 8;
     if (wide_group(steps2, mt, bits))
         return 8;
     // two activation rows, 4-bit: 12 waves of one weight row against the 8 waves of two rows it ran before --
@@ -1253,12 +1267,12 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     const bool ragged = a.k != steps2 * 2048;
     // one workgroup per compute unit; the argmax form writes one partial winner per workgroup, so
     // every pass must use the same number of workgroups: the count of the narrowest pass
-    auto blocks_for = [&](int mt) {
-        const int r = rows_per_step(steps2, mt, bits), nw = waves_for(steps2, mt, bits, a.n, dev.cus);
-        const int n_groups = (a.n + r - 1) / r;
-        return min(dev.cus, (n_groups + nw - 1) / nw);
-    };
     const bool pairs = a.m >= 2 && steps2 <= 2;
+    auto blocks_for = [&](int mt) {
+        const int r = rows_per_step(steps2, mt, bits), nw = waves_for(steps2, mt, bits, a.n, dev.cus, !pairs);
+        const int n_groups = (a.n + r - 1) / r;
+        return min(dev.cus * (two_workgroups(steps2, mt, bits, a.n, dev.cus, !pairs) ? 2 : 1), (n_groups + nw - 1) / nw);
+    };
     const int blocks = pairs ? min(blocks_for(1), blocks_for(2)) : blocks_for(1);
     if (parts_used)
         *parts_used = blocks;
@@ -1270,7 +1284,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
                 : bits == 22 ? launch_steps6<2, 22>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                 : bits == 24 ? launch_steps6<2, 24>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                             : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi,
-                                              waves_for(steps2, 2, bits, a.n, dev.cus));
+                                              waves_for(steps2, 2, bits, a.n, dev.cus, !pairs));
             m0 += 2;
         } else {
             e = bits == 6    ? launch_steps6<1, 6>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
@@ -1278,7 +1292,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
                 : bits == 22 ? launch_steps6<1, 22>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                 : bits == 24 ? launch_steps6<1, 24>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                             : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi,
-                                              waves_for(steps2, 1, bits, a.n, dev.cus));
+                                              waves_for(steps2, 1, bits, a.n, dev.cus, !pairs));
             m0 += 1;
         }
         if (e != hipSuccess)
