@@ -380,10 +380,9 @@ __global__ __launch_bounds__(NW * 64) void bf16_reg_kernel(const uint16_t* __res
     }
 }
 
-template <int NS, int D>
+template <int NS, int D, int NW>
 hipError_t launch_reg_b(const Bf16Args& a, int blocks, hipStream_t stream)
 {
-    constexpr int NW = 16;
     const bool argmax = a.part_val != nullptr;
     const size_t lds = (size_t)NS * 1024 + 64;
     hipLaunchKernelGGL((bf16_reg_kernel<NS, D, NW>), dim3(blocks), dim3(NW * 64), lds, stream, a.x, a.w,
@@ -409,12 +408,18 @@ bool bf16_reg_can_run(const Bf16Args& a, const DeviceInfo& dev)
 
 hipError_t launch_bf16_reg(const Bf16Args& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream)
 {
-    const int blocks = dev.cus < (a.n + 15) / 16 ? dev.cus : (a.n + 15) / 16;
+    const int steps = (a.k + 511) / 512;
+    // 12 waves per workgroup beyond K = 4096 and, up to there, beyond 40 rows per compute unit; else 16
+    // (us per launch, 16 -> 12 waves: 8192 x 8192 26.9 -> 24.7, 12288 x 4096 18.0 -> 17.8, 32000 x 4096 42.9 ->
+    // 42.2, but 4096 x 4096 7.4 -> 8.0; two workgroups of 8 or 12 per unit, or one of 8: slower)
+    const int nw = steps > 8 || a.n > 40 * dev.cus ? 12 : 16;
+    const int blocks = dev.cus < (a.n + nw - 1) / nw ? dev.cus : (a.n + nw - 1) / nw;
     if (parts_used)
         *parts_used = blocks;
-    const int steps = (a.k + 511) / 512;
     // (four steps in flight: 2 % faster on the largest matrices, 5 % slower on the smallest; one: 7 to 20 % slower)
-    return steps <= 8 ? launch_reg_b<8, 2>(a, blocks, stream) : launch_reg_b<16, 2>(a, blocks, stream);
+    if (steps > 8)
+        return launch_reg_b<16, 2, 12>(a, blocks, stream);
+    return nw == 12 ? launch_reg_b<8, 2, 12>(a, blocks, stream) : launch_reg_b<8, 2, 16>(a, blocks, stream);
 }
 
 // Verification passes (three and more activation rows) on the matrix cores: the frame of the
