@@ -1336,16 +1336,16 @@ static int run_fmt(int fmt, const void* x, int64_t M, int64_t ldx, const void* q
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     int parts_used = 0;
-    // E5M2 and E3M2, one or two rows in one pass over the weights: the decode-step frame of their
+    // One or two rows in one pass over the weights: the decode-step frame -- E5M2 and E3M2 that of their
     // sibling formats with the other convert instruction (a lane's 24 bytes of a 6-bit block need the
-    // scale bytes 4-byte aligned there); everything else: the general kernel
-    const bool reg = fmt != MXFP4_FMT_T2 && aligned(s, 4) && aligned(q, 16) && gemv_reg_can_run(a, dev) &&
-                     gemv_reg_single_pass(a);
+    // scale bytes 4-byte aligned there), the 2-bit codes with their own decode; everything else: the
+    // general kernel
+    const bool reg = aligned(s, 4) && aligned(q, 16) && gemv_reg_can_run(a, dev) && gemv_reg_single_pass(a);
     // three and more rows when a pass's activation rows fit the LDS: the matrix-core tiles of the
     // sibling formats (E5M2 at four rows on the 7B qkv shape: 16.8 us there, 20.9 in the general kernel)
     const bool tiles = fmt != MXFP4_FMT_T2 && !reg && a.m >= 3 && a.k % 128 == 0 &&
                        aligned(s, 4) && aligned(q, 16) && mfma_tile_fmt_can_run(a, dev);
-    const int code = fmt == MXFP4_FMT_E5M2 ? 24 : 22;
+    const int code = fmt == MXFP4_FMT_E5M2 ? 24 : (fmt == MXFP4_FMT_E3M2 ? 22 : 2);
     hipError_t e = reg     ? launch_gemv_reg(a, dev, &parts_used, st, nullptr, code)
                    : tiles ? launch_mfma_tile8(a, dev, &parts_used, st, code)
                            : launch_mxfmt_gemv(fmt, a, dev, &parts_used, st);

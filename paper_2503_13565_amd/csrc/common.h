@@ -83,6 +83,26 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+typedef __attribute__((ext_vector_type(2))) unsigned short u16x2_t;
+
+// Sixteen codes of the 2-bit format (one dword, code j in bits 2j, 2j + 1) -> eight BF16 pairs.  A
+// code is sign << 1 | magnitude, which are the top two bits of the BF16 number +-2.0 or +-0: a
+// pair of codes moves to bits 15:14 and 31:30 of a dword by one packed 16-bit shift of the half that
+// holds them, and a mask.  The product then carries 2 X per unit and is scaled by X / 2 afterwards.
+__device__ __forceinline__ void decode_t2(uint32_t c, uint32_t* out8)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(c, c, 0x01000100u);   // codes 0..7 in both halves
+    const uint32_t hi = __builtin_amdgcn_perm(c, c, 0x03020302u);   // codes 8..15 in both halves
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const u16x2_t sh = {(unsigned short)(14 - 4 * p), (unsigned short)(12 - 4 * p)};
+        const u16x2_t a = __builtin_bit_cast(u16x2_t, lo) << sh;
+        const u16x2_t b = __builtin_bit_cast(u16x2_t, hi) << sh;
+        out8[p] = __builtin_bit_cast(uint32_t, a) & 0xC000C000u;
+        out8[4 + p] = __builtin_bit_cast(uint32_t, b) & 0xC000C000u;
+    }
+}
+
 // Wait until every vector-memory operation of this wave has completed (s_waitcnt vmcnt(0),
 // other counters untouched; gfx9 encoding).  A real waitcnt instruction rather than inline
 // assembly, so that the compiler's own wait insertion knows nothing is pending afterwards.

@@ -53,7 +53,8 @@ struct RegArgs {
 // instead the wave loads the 1536 bytes lane-contiguous (16 bytes per lane, then 8), passes them
 // through 1536 bytes of LDS of its own and reads back bytes [24 lane, 24 lane + 24).
 // Format codes 22 and 24 are the second element formats of those widths (E3M2, E5M2): the same frame
-// with the other convert instruction.
+// with the other convert instruction.  Format code 2: the 2-bit ternary codes (8 bytes per block, one
+// 64-bit load per lane and step, bit-move decode, late scaling by X / 2).
 // kBits 8 (E4M3 bytes, 32 bytes per block, 2048 bytes per wave step): loaded lane-contiguous too
 // (16 bytes per lane, twice), and no exchange is needed: a lane keeps what it loaded, two half
 // blocks -- elements [16 lane, 16 lane + 16) of the step, block lane / 2, and the same 1024
@@ -71,9 +72,12 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     // E2M3, 24: E5M2 in place of E4M3): same loads and lane mapping, the other convert instruction
     constexpr bool kAlt = kFmt > 16;
     constexpr int kBits = kAlt ? kFmt - 16 : kFmt;
-    static_assert(kBits == 4 || kBits == 6 || kBits == 8, "element width");
-    static_assert(!kAlt || kBits != 4, "the 4-bit format has one element format");
-    constexpr int kBlkBytes = kBits == 8 ? 32 : (kBits == 6 ? 24 : 16);
+    static_assert(kBits == 4 || kBits == 6 || kBits == 8 || kBits == 2, "element width");
+    static_assert(!kAlt || (kBits != 4 && kBits != 2), "the 4-bit and 2-bit formats have one element format");
+    // kBits 2: the 2-bit ternary codes, 8 bytes per block, 512 bytes of a row per wave step (one 64-bit load
+    // per lane); the activations in registers are what this frame gives the format: in the general
+    // kernel a block's 8 bytes of weights pull 64 bytes of activations out of the LDS.
+    constexpr int kBlkBytes = kBits == 8 ? 32 : (kBits == 6 ? 24 : (kBits == 2 ? 8 : 16));
     constexpr bool kEpi = !__is_same(Epi, NoEpilogue);
     const int m0 = a.m0;
     static_assert(STEPS % D == 0, "the buffer of a step must be known at compile time");
@@ -147,7 +151,7 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
     const __amdgpu_buffer_rsrc_t rr0 = residual_row(0), rr1 = residual_row(MT - 1);
 
     u32x4_t bq[D][R];
-    u32x2_t bq2[D][kBits == 6 ? R : 1];             // bytes 16..23 of a 6-bit block
+    u32x2_t bq2[D][kBits == 6 || kBits == 2 ? R : 1];   // bytes 16..23 of a 6-bit block; the 8 bytes of a 2-bit one
     u32x4_t bqb[D][kBits == 8 ? R : 1];             // 8-bit form: the lane's second 16 bytes
     uint32_t bs[D];
     const int n_groups = (a.n + R - 1) / R;
@@ -180,6 +184,9 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                 bqb[d][r] = __builtin_amdgcn_raw_buffer_load_b128(
                     rq, (live && 1024 + lane * 16 < valid8) ? 1024 + lane * 16 : 0x7FFFFFF0,
                     row * q_row_bytes + t * 2048, 2);
+            } else if constexpr (kBits == 2) {
+                bq2[d][r] = __builtin_amdgcn_raw_buffer_load_b64(rq, (live && vb) ? lane * kBlkBytes : 0x7FFFFFF0,
+                                                                 row * q_row_bytes + t * (64 * kBlkBytes), 2);
             } else {
                 bq[d][r] = __builtin_amdgcn_raw_buffer_load_b128(rq, (live && vb) ? lane * kBlkBytes : 0x7FFFFFF0,
                                                                  row * q_row_bytes + t * (64 * kBlkBytes), 2);
@@ -390,6 +397,31 @@ __device__ __forceinline__ void gemv_reg_body(const RegArgs& a, const Epi& epi)
                 float sc = __uint_as_float((dw << sh_top) >> 1);
                 if (kRagged)
                     sc = (t * 64 + lane < nblk) ? sc : 1.0f;         // no NaN from a neighbour's scale byte
+                if constexpr (kBits == 2) {
+                    // codes -> BF16 +-2.0 / +-0 by bit moves, the block's sum scaled by X / 2 = 2^(byte - 128)
+                    // afterwards (Eq. 2); bytes 0 and 1 give FP32 subnormals, 0xFF gives NaN
+                    const uint32_t sb = (dw << sh_top) >> 24;
+                    uint32_t bits = sb >= 2u ? (sb - 1u) << 23 : 0x00200000u << sb;
+                    bits = sb == 0xFFu ? 0x7FC00000u : bits;
+                    float late = __uint_as_float(bits);
+                    if (kRagged)
+                        late = (t * 64 + lane < nblk) ? late : 0.f;
+                    uint32_t wv[16];
+                    decode_t2(bq2[d][r][0], wv);
+                    decode_t2(bq2[d][r][1], wv + 8);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        float v = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const uint32_t xd = xq[m][i >> 2][i & 3];
+                            v = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, wv[i]),
+                                                                __builtin_bit_cast(bf16x2_t, xd), v, false);
+                        }
+                        acc[r][m] = __builtin_fmaf(v, late, acc[r][m]);
+                    }
+                    continue;
+                }
                 u32x16_t w6 = {};
                 if constexpr (kBits == 6) {
                     // lane-contiguous bytes -> the lane's own block.  The buffer is the wave's alone
@@ -1261,7 +1293,7 @@ bool gemv_reg_single_pass(const GemmArgs& a) { return a.m == 1 || (a.m == 2 && e
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                            const Epilogue* epi, int bits)
 {
-    if (bits != 4 && ((bits != 6 && bits != 8 && bits != 22 && bits != 24) || epi))
+    if (bits != 4 && ((bits != 6 && bits != 8 && bits != 22 && bits != 24 && bits != 2) || epi))
         return hipErrorInvalidValue;
     const int steps2 = even_steps(a.k);
     const bool ragged = a.k != steps2 * 2048;
@@ -1283,6 +1315,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
                 : bits == 8  ? launch_steps6<2, 8>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                 : bits == 22 ? launch_steps6<2, 22>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                 : bits == 24 ? launch_steps6<2, 24>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
+                : bits == 2  ? launch_steps6<2, 2>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                             : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi,
                                               waves_for(steps2, 2, bits, a.n, dev.cus, !pairs));
             m0 += 2;
@@ -1291,6 +1324,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
                 : bits == 8  ? launch_steps6<1, 8>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                 : bits == 22 ? launch_steps6<1, 22>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                 : bits == 24 ? launch_steps6<1, 24>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
+                : bits == 2  ? launch_steps6<1, 2>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                             : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi,
                                               waves_for(steps2, 1, bits, a.n, dev.cus, !pairs));
             m0 += 1;

@@ -71,7 +71,8 @@ bool gemv_multi_can_run(const GemmArgs* items, int count, const DeviceInfo& dev)
 hipError_t launch_gemv_multi(const GemmArgs* items, int count, const DeviceInfo& dev, int* parts_used,
                              hipStream_t stream);
 // `bits`: 4 (a.q = packed nibbles), 6 (a.q = q6, 24 bytes per block) or 8 (a.q = q8, 32 bytes per
-// block); 22 and 24: the same widths with E3M2 and E5M2 elements; the fused form exists for 4 only.
+// block); 22 and 24: the same widths with E3M2 and E5M2 elements; 2: the 2-bit ternary codes (8 bytes per
+// block); the fused form exists for 4 only.
 hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_used, hipStream_t stream,
                            const Epilogue* epi = nullptr, int bits = 4);
 

@@ -27,7 +27,6 @@ namespace {
 
 typedef __attribute__((ext_vector_type(32))) __bf16 bf16x32_t;
 typedef __attribute__((ext_vector_type(2))) short s16x2_t;
-typedef __attribute__((ext_vector_type(2))) unsigned short u16x2_t;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
 typedef __attribute__((ext_vector_type(6))) unsigned int u32x6_t;
 typedef __attribute__((ext_vector_type(16))) unsigned int u32x16_t;
@@ -154,24 +153,6 @@ __global__ __launch_bounds__(256) void mx_cast_kernel(const uint16_t* __restrict
         for (int i = 0; i < kDw / 2; ++i)
             dst[i] = u32x2_t{out[2 * i], out[2 * i + 1]};
         s[blk] = (uint8_t)scale_byte;
-    }
-}
-
-// Sixteen codes of the 2-bit format (one dword, code j in bits 2j, 2j + 1) -> eight BF16 pairs.  A
-// code is sign << 1 | magnitude, which are the top two bits of the BF16 number +-2.0 or +-0: a
-// pair of codes moves to bits 15:14 and 31:30 of a dword by one packed 16-bit shift of the half that
-// holds them, and a mask.  The product then carries 2 X per unit and is scaled by X / 2 afterwards.
-__device__ __forceinline__ void decode_t2(uint32_t c, uint32_t* out8)
-{
-    const uint32_t lo = __builtin_amdgcn_perm(c, c, 0x01000100u);   // codes 0..7 in both halves
-    const uint32_t hi = __builtin_amdgcn_perm(c, c, 0x03020302u);   // codes 8..15 in both halves
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const u16x2_t sh = {(unsigned short)(14 - 4 * p), (unsigned short)(12 - 4 * p)};
-        const u16x2_t a = __builtin_bit_cast(u16x2_t, lo) << sh;
-        const u16x2_t b = __builtin_bit_cast(u16x2_t, hi) << sh;
-        out8[p] = __builtin_bit_cast(uint32_t, a) & 0xC000C000u;
-        out8[4 + p] = __builtin_bit_cast(uint32_t, b) & 0xC000C000u;
     }
 }
 
