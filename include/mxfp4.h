@@ -71,7 +71,7 @@ enum {
     MXFP4_PATH_MFMA_GENERAL = 6, /* the general MFMA kernel (K split in time or space) also where the
                                  leaner tile kernel, which MXFP4_PATH_MFMA prefers, could run      */
     MXFP4_PATH_VALU_REG = 5   /* decode-step GEMV: converts + dot2 with the activations in registers,
-                                 one workgroup per compute unit; K % 128 == 0, K <= 12288 (one row)
+                                 one or two workgroups per compute unit; K % 128 == 0, K <= 12288 (one row)
                                  or 4096 (two rows at a time), N >= 8 * compute units              */
 };
 
@@ -503,7 +503,7 @@ int mxfp4_bf16_gemm_verify(const void* x_bf16, int64_t M, int64_t ldx,
  * per wave instruction from the row-major tensors; from this copy the same fragment is 1 KiB
  * contiguous, which is worth 10 to 14 % on a verification pass.  The copy serves single rows too
  * (section 3.3: one quantised model drafts and verifies): one row runs a decode kernel of this
- * layout, 4 to 8 % behind the row-major decode kernel on the 7B shapes, so a model can keep this
+ * layout, about 13 % behind the row-major decode kernels over a 7B stack, so a model can keep this
  * copy alone, or both (+0.53 bytes per weight of the 288 GB) for the fastest of each.
  *   q_tiled out uint8, mxfp4_tile_repack_q_bytes(N, K) bytes, 16-byte aligned:
  *           [tile = ceil(N/16)][step = K/128][lane = i + 16 g][16 bytes] = block 4 step + g of row
