@@ -57,11 +57,13 @@ REG = binding.PATH_VALU_REG
 
 @pytest.mark.parametrize("n,k", [(2048, 128), (2100, 256), (2049, 2176), (2500, 4096), (2111, 6144),
                                  (2300, 8192), (2222, 10240), (2100, 11008), (2050, 12288), (2049, 14336),
-                                 (2060, 16384), (2111, 20480), (2050, 28672), (2048, 32768)])
+                                 (2060, 16384), (2111, 20480), (2050, 28672), (2048, 32768),
+                                 (10241, 4096), (12001, 3968), (11000, 1024), (10240, 2176), (10500, 6144)])
 @pytest.mark.parametrize("m", [1, 2, 3])
 def test_register_gemv_edge_shapes(n, k, m):
     """The decode-step kernel: full, ragged and padded step counts, rows that do not fill the last
-    round of a workgroup, one and two activation rows per pass, the fused argmax."""
+    round of a workgroup, one and two activation rows per pass, the fused argmax; few and many rows
+    per compute unit (12 waves, or two workgroups of 8, up to K = 4096)."""
     w = synth.weights_student_t(n, k, seed=5000 + n + k)
     x = synth.activations_outlier_channels(m, k, seed=6000 + m + k)
     run_gemm_case(w, x, [REG, binding.PATH_VALU_CVT], "REG N=%d K=%d M=%d" % (n, k, m), argmax=True)
