@@ -649,9 +649,13 @@ hipError_t launch_steps(const GemmArgs& a, int m0, int steps2, bool ragged, int 
                               : launch_one<MT, 1, 2, 2, 12, false>(a, m0, blocks, lds, stream, epi);
             return ragged ? launch_one<MT, 1, 2, 2, 16, true>(a, m0, blocks, lds, stream, epi)
                           : launch_one<MT, 1, 2, 2, 16, false>(a, m0, blocks, lds, stream, epi);
-        } else                                       // two activation rows need more registers: 12 waves
+        } else {                                      // two activation rows need more registers: 12 waves (or 8, twice)
+            if (nw == 8)
+                return ragged ? launch_one<MT, 1, 2, 2, 8, true>(a, m0, blocks, lds, stream, epi)
+                              : launch_one<MT, 1, 2, 2, 8, false>(a, m0, blocks, lds, stream, epi);
             return ragged ? launch_one<MT, 1, 2, 2, 12, true>(a, m0, blocks, lds, stream, epi)
                           : launch_one<MT, 1, 2, 2, 12, false>(a, m0, blocks, lds, stream, epi);
+        }
     case 4:
         if constexpr (MT == 1)
             return ragged ? launch_one<MT, 1, 4, 2, 12, true>(a, m0, blocks, lds, stream, epi)
@@ -1161,9 +1165,14 @@ bool wide_group(int steps2, int mt, int bits) { return mt == 2 && steps2 == 2 &&
 // 3.84, 8192: 5.71 -> 5.52, 10240: 6.21 -> 5.98, but 12288: 7.07 -> 7.20 and no gain beyond; four steps
 // (K <= 8192) 12 waves at any N -- 8192 x 8192 8.14 -> 7.65, 10240 x 8192 9.43 -> 9.27, 57344 x 8192
 // 39.9 -> 38.9; six steps 8 waves (see launch_steps); from eight steps on 16.
-// `alone`: the call has no passes of two rows (whose grid every pass must share).
+// `alone`: every pass of the call has this many rows (a call of one row, or of exactly two), so no
+// other pass has to share the grid.
 bool two_workgroups(int steps2, int mt, int bits, int n, int cus, bool alone)
 {
+    // the same for a call of exactly two rows: 12288 x 4096 7.91 -> 7.64 us, 22016 x 4096 11.17 -> 11.01,
+    // 32000 x 4096 14.68 -> 14.37 against one workgroup of 12 waves
+    if (alone && bits == 4 && mt == 2 && steps2 == 2 && n > 40 * cus)
+        return true;
     // K <= 4096, one row, more than 40 rows per unit: two workgroups of 8 waves per compute unit against
     // one of 16 -- qkv 7.10 -> 6.89 us, gate+up 10.19 -> 9.96, LM head 13.30 -> 13.06 (two of 12: 7.10,
     // 9.92, 13.04; two or three of 6: slower)
@@ -1300,12 +1309,14 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
     // one workgroup per compute unit; the argmax form writes one partial winner per workgroup, so
     // every pass must use the same number of workgroups: the count of the narrowest pass
     const bool pairs = a.m >= 2 && steps2 <= 2;
+    // every pass alike: one row per pass (no pairs), or the call is one pass of two rows
+    auto alone = [&](int mt) { return mt == 2 ? pairs && a.m == 2 : !pairs; };
     auto blocks_for = [&](int mt) {
-        const int r = rows_per_step(steps2, mt, bits), nw = waves_for(steps2, mt, bits, a.n, dev.cus, !pairs);
+        const int r = rows_per_step(steps2, mt, bits), nw = waves_for(steps2, mt, bits, a.n, dev.cus, alone(mt));
         const int n_groups = (a.n + r - 1) / r;
-        return min(dev.cus * (two_workgroups(steps2, mt, bits, a.n, dev.cus, !pairs) ? 2 : 1), (n_groups + nw - 1) / nw);
+        return min(dev.cus * (two_workgroups(steps2, mt, bits, a.n, dev.cus, alone(mt)) ? 2 : 1), (n_groups + nw - 1) / nw);
     };
-    const int blocks = pairs ? min(blocks_for(1), blocks_for(2)) : blocks_for(1);
+    const int blocks = !pairs ? blocks_for(1) : (a.m == 2 ? blocks_for(2) : min(blocks_for(1), blocks_for(2)));
     if (parts_used)
         *parts_used = blocks;
     for (int m0 = 0; m0 < a.m;) {
@@ -1317,7 +1328,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
                 : bits == 24 ? launch_steps6<2, 24>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                 : bits == 2  ? launch_steps6<2, 2>(a, m0, steps2, blocks, (size_t)2 * a.k * 2 + 64, stream)
                             : launch_steps<2>(a, m0, steps2, ragged, blocks, (size_t)2 * a.k * 2 + 64, stream, epi,
-                                              waves_for(steps2, 2, bits, a.n, dev.cus, !pairs));
+                                              waves_for(steps2, 2, bits, a.n, dev.cus, alone(2)));
             m0 += 2;
         } else {
             e = bits == 6    ? launch_steps6<1, 6>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
@@ -1326,7 +1337,7 @@ hipError_t launch_gemv_reg(const GemmArgs& a, const DeviceInfo& dev, int* parts_
                 : bits == 24 ? launch_steps6<1, 24>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                 : bits == 2  ? launch_steps6<1, 2>(a, m0, steps2, blocks, (size_t)a.k * 2 + 64, stream)
                             : launch_steps<1>(a, m0, steps2, ragged, blocks, (size_t)a.k * 2 + 64, stream, epi,
-                                              waves_for(steps2, 1, bits, a.n, dev.cus, !pairs));
+                                              waves_for(steps2, 1, bits, a.n, dev.cus, alone(1)));
             m0 += 1;
         }
         if (e != hipSuccess)
